@@ -1,0 +1,147 @@
+/*
+ * qalora.h -- C ABI of the MI355X (gfx950) QA-LoRA adapted linear layer.
+ *
+ * The layer (arXiv 2309.14717, Sec. 3.3, Alg. 1, App. B), 0-based indices:
+ *
+ *   W~[i,j] = alpha[i/g, j] * code[i,j] + beta[i/g, j]            (Eq. 1 per group)
+ *   y       = x W~ + s * (pool_g(x) A) B                          (Alg. 1 forward)
+ *   pool_g(x)[t,l] = (1/g) * sum_{q<g} x[t, l*g+q]                (group AVERAGE)
+ *
+ * W is [d_in x d_out]; every column is cut into L = d_in/g groups of g consecutive
+ * input rows, each with its own scaling factor alpha and zero factor beta.  A is
+ * [L x rank], B is [rank x d_out].  The paper pools by SUM; a caller who wants that
+ * passes s*g as s.  beta is Eq. 1's zero FACTOR in weight units (beta = group
+ * minimum after quantize), not the zero point of Alg. 1 / App. B.1; the two are
+ * related by z = -beta/alpha.
+ *
+ * Conventions for every entry point
+ *   - All pointers are DEVICE pointers unless marked "host".  All matrices are dense
+ *     row-major with no padding.  The descriptor is a host struct, read during the call.
+ *   - The caller owns every buffer.  The library allocates nothing, frees nothing,
+ *     keeps no state between calls and never synchronises: work is enqueued on
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream) and the
+ *     results are ready when that stream reaches the end of the enqueued work.
+ *   - Scratch memory comes from the caller through (ws, ws_bytes); ask
+ *     qalora_workspace_bytes for the size.  ws contents are undefined afterwards.
+ *   - Inputs are read-only.  Outputs must not alias inputs unless stated.
+ *   - Device pointers must be 16-byte aligned (QALORA_EALIGN otherwise).
+ *   - Every entry returns a status (0 = QALORA_OK, negative = error).  Argument errors
+ *     are detected on the host before anything is launched; no partial work is
+ *     enqueued in that case.  Nothing throws.
+ *   - Supported shapes: bits in {2,3,4}; group a multiple of 8 that divides d_in;
+ *     d_out a multiple of 8; rank a multiple of 8 (or 0), at most 512.  Anything else
+ *     that is well-formed returns QALORA_EUNSUPPORTED -- there is no fallback path.
+ *   - Results are deterministic: a rerun on the same inputs is bit-identical.
+ */
+#ifndef QALORA_H_
+#define QALORA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* One QA-LoRA linear layer (header of Alg. 1).  Plain data, caller-owned, host. */
+typedef struct qalora_desc {
+  int32_t d_in;  /* input features  D_in  (rows of W)                      */
+  int32_t d_out; /* output features D_out (columns of W)                   */
+  int32_t bits;  /* N, code width: codes are in {0 .. 2^N - 1}   (Eq. 1)   */
+  int32_t group; /* g = D_in / L, rows per quantization group (Sec. 3.3)   */
+  int32_t rank;  /* D_int, adapter rank; 0 = no adapter                    */
+  float s;       /* adapter coefficient (Sec. 3.1), with average pooling   */
+} qalora_desc;
+
+enum qalora_status {
+  QALORA_OK = 0,
+  QALORA_EINVAL = -1,       /* null pointer, bad enum, bits/group/rank/tokens out of range,
+                               group does not divide d_in, exactly one of A/B null */
+  QALORA_EALIGN = -2,       /* a device pointer is not 16-byte aligned              */
+  QALORA_EWORKSPACE = -3,   /* ws is null or smaller than qalora_workspace_bytes    */
+  QALORA_EUNSUPPORTED = -4, /* well-formed, but outside the supported shapes        */
+  QALORA_EHIP = -5          /* a launch failed; hipGetLastError() is left in place  */
+};
+
+enum qalora_dtype { QALORA_F32 = 0, QALORA_BF16 = 1 };
+
+enum qalora_op {
+  QALORA_OP_QUANTIZE = 0,
+  QALORA_OP_FORWARD = 1,
+  QALORA_OP_BACKWARD = 2,
+  QALORA_OP_MERGE = 3
+};
+
+/* Human-readable name of a status code (static string, host). */
+const char* qalora_status_string(int status);
+
+/* Validate a descriptor on the host.  Returns QALORA_OK, QALORA_EINVAL or
+ * QALORA_EUNSUPPORTED exactly as the compute entry points would. */
+int qalora_check_desc(const qalora_desc* desc);
+
+/* Size in bytes of the packed-code buffer for this layer (0 if the descriptor is
+ * invalid).  The packed format is private to the library (codes are bit-packed
+ * N bits each, eight consecutive input rows of one column per field); its meaning is
+ * defined by qalora_unpack. */
+size_t qalora_packed_bytes(const qalora_desc* desc);
+
+/* Scratch bytes the given operation needs for `tokens` tokens (tokens is ignored by
+ * QUANTIZE and MERGE).  Returns 0 for an invalid descriptor or op. */
+size_t qalora_workspace_bytes(const qalora_desc* desc, int tokens, int op);
+
+/* Group-wise min-max quantization: Eq. 1 applied to each group of g consecutive rows
+ * of each column (Sec. 3.3).  In fp32, in this order:
+ *   beta = min, alpha = (max - min) / (2^N - 1)   (one subtract, one IEEE divide),
+ *   code = clamp(rint((w - beta) / alpha), 0, 2^N - 1)   (ties to even);
+ *   a group whose alpha is not > 0 (constant group) gets alpha = 1 and codes 0.
+ * in : W      fp32 [d_in, d_out]
+ * out: packed  qalora_packed_bytes(desc) bytes
+ *      alpha, beta  fp32 [L, d_out]
+ * rank and s of the descriptor are ignored.  Non-finite W gives unspecified codes. */
+int qalora_quantize(const qalora_desc* desc, const float* W, void* packed, float* alpha,
+                    float* beta, void* ws, size_t ws_bytes, void* stream);
+
+/* packed -> canonical codes, uint8 [d_in, d_out] row-major, one code per byte.
+ * This is the definition of the packed format ("bit-exact codes" means equal here). */
+int qalora_unpack(const qalora_desc* desc, const void* packed, uint8_t* codes, void* stream);
+
+/* canonical codes -> packed; imports codes chosen by any other quantizer (the layer
+ * accepts any (codes, alpha, beta) triple).  Codes above 2^N - 1 are masked to N bits. */
+int qalora_pack(const qalora_desc* desc, const uint8_t* codes, void* packed, void* stream);
+
+/* Adapted forward, Alg. 1 / App. B.2:   y = x W~ + s (pool_g(x) A) B.
+ * in : x bf16 [tokens, d_in]; packed; alpha, beta fp32 [L, d_out];
+ *      A fp32 [L, rank], B fp32 [rank, d_out] -- both NULL (or rank 0) for the
+ *      adapter-free layer, e.g. after qalora_merge (then s is ignored).
+ * out: y [tokens, d_out], fp32 or bf16 per y_dtype (bf16 = round-to-nearest-even of the
+ *      fp32 result).
+ * W~ is rounded to bf16 before the matrix units for tokens > 16; accumulation is fp32. */
+int qalora_forward(const qalora_desc* desc, int tokens, const void* x, const void* packed,
+                   const float* alpha, const float* beta, const float* A, const float* B,
+                   void* y, int y_dtype, void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of qalora_forward with W~ frozen: only A and B are parameters (Alg. 1),
+ * so with G = dy, P = pool_g(x), U = P A:
+ *   dU = s G B^T,  dB = s U^T G,  dA = P^T dU,
+ *   dx[t,i] = sum_j G[t,j] W~[i,j] + (dU A^T)[t, i/g] / g.
+ * in : dy bf16 [tokens, d_out]; x bf16 [tokens, d_in]; packed, alpha, beta, A, B as above
+ *      (A = B = NULL: only dx is produced, dA and dB are not touched).
+ * out: dx [tokens, d_in] fp32 or bf16 per dx_dtype, or NULL to skip it;
+ *      dA fp32 [L, rank], dB fp32 [rank, d_out]; accumulate = 0 overwrites them,
+ *      accumulate = 1 adds to their current contents (gradient accumulation). */
+int qalora_backward(const qalora_desc* desc, int tokens, const void* dy, const void* x,
+                    const void* packed, const float* alpha, const float* beta,
+                    const float* A, const float* B, void* dx, int dx_dtype, float* dA,
+                    float* dB, int accumulate, void* ws, size_t ws_bytes, void* stream);
+
+/* Merge the adapter into the zero factors (Alg. 1 merge, App. B.3, in Eq. 1's
+ * convention):  beta_out[l,j] = beta[l,j] + (s/g) * sum_k A[l,k] B[k,j].
+ * Codes and alpha are untouched, so the merged layer is still N-bit.
+ * beta_out may alias beta.  Needs no workspace. */
+int qalora_merge(const qalora_desc* desc, const float* beta, const float* A, const float* B,
+                 float* beta_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QALORA_H_ */

@@ -1,0 +1,180 @@
+"""Thin Python binding of the C-ABI library (include/qalora.h).
+
+Argument marshalling only: every step of the layer runs in the HIP kernels behind the
+C ABI.  PyTorch supplies device memory and the stream.  There is no fallback: if the
+shared library has not been built, or a call returns an error status, this raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqalora_hip.so")
+
+OK, EINVAL, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5
+F32, BF16 = 0, 1
+OP_QUANTIZE, OP_FORWARD, OP_BACKWARD, OP_MERGE = 0, 1, 2, 3
+
+EXPORTS = (
+    "qalora_status_string", "qalora_check_desc", "qalora_packed_bytes", "qalora_workspace_bytes",
+    "qalora_quantize", "qalora_unpack", "qalora_pack", "qalora_forward", "qalora_backward",
+    "qalora_merge",
+)
+
+
+class Desc(ctypes.Structure):
+    """Mirror of ``qalora_desc``."""
+    _fields_ = [("d_in", ctypes.c_int32), ("d_out", ctypes.c_int32), ("bits", ctypes.c_int32),
+                ("group", ctypes.c_int32), ("rank", ctypes.c_int32), ("s", ctypes.c_float)]
+
+
+class QaloraError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load the in-tree shared library; fail loudly when it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} not found: build the HIP library first "
+            "(python -m paper_2309_14717_amd.build); there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, cp, i, sz = ctypes.c_void_p, ctypes.POINTER(Desc), ctypes.c_int, ctypes.c_size_t
+    lib.qalora_status_string.restype = ctypes.c_char_p
+    lib.qalora_status_string.argtypes = [i]
+    lib.qalora_check_desc.argtypes = [cp]
+    lib.qalora_packed_bytes.restype = sz
+    lib.qalora_packed_bytes.argtypes = [cp]
+    lib.qalora_workspace_bytes.restype = sz
+    lib.qalora_workspace_bytes.argtypes = [cp, i, i]
+    lib.qalora_quantize.argtypes = [cp, vp, vp, vp, vp, vp, sz, vp]
+    lib.qalora_unpack.argtypes = [cp, vp, vp, vp]
+    lib.qalora_pack.argtypes = [cp, vp, vp, vp]
+    lib.qalora_forward.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
+    lib.qalora_backward.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, vp, i, vp, vp, i, vp, sz, vp]
+    lib.qalora_merge.argtypes = [cp, vp, vp, vp, vp, vp]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().qalora_status_string(int(status)).decode()
+
+
+def make_desc(d_in, d_out, bits=4, group=32, rank=0, s=0.0) -> Desc:
+    return Desc(int(d_in), int(d_out), int(bits), int(group), int(rank), float(s))
+
+
+def check_desc(desc: Desc) -> int:
+    return int(load().qalora_check_desc(ctypes.byref(desc)))
+
+
+def packed_bytes(desc: Desc) -> int:
+    return int(load().qalora_packed_bytes(ctypes.byref(desc)))
+
+
+def workspace_bytes(desc: Desc, tokens: int, op: int) -> int:
+    return int(load().qalora_workspace_bytes(ctypes.byref(desc), int(tokens), int(op)))
+
+
+def _p(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc, where):
+    if rc != OK:
+        raise QaloraError(int(rc), where)
+
+
+def _workspace(desc, tokens, op, ws):
+    need = workspace_bytes(desc, tokens, op)
+    if ws is None:
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    return ws, ws.numel()
+
+
+def quantize(desc: Desc, W: torch.Tensor):
+    """W fp32 [d_in, d_out] (device) -> (packed uint8, alpha fp32 [L, d_out], beta fp32 [L, d_out])."""
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous()
+    L = desc.d_in // desc.group
+    packed = torch.empty(packed_bytes(desc), dtype=torch.uint8, device=W.device)
+    alpha = torch.empty((L, desc.d_out), dtype=torch.float32, device=W.device)
+    beta = torch.empty_like(alpha)
+    rc = load().qalora_quantize(ctypes.byref(desc), _p(W), _p(packed), _p(alpha), _p(beta), None, 0,
+                                _stream())
+    _check(rc, "qalora_quantize")
+    return packed, alpha, beta
+
+
+def unpack(desc: Desc, packed: torch.Tensor) -> torch.Tensor:
+    codes = torch.empty((desc.d_in, desc.d_out), dtype=torch.uint8, device=packed.device)
+    _check(load().qalora_unpack(ctypes.byref(desc), _p(packed), _p(codes), _stream()), "qalora_unpack")
+    return codes
+
+
+def pack(desc: Desc, codes: torch.Tensor) -> torch.Tensor:
+    assert codes.is_cuda and codes.dtype == torch.uint8 and codes.is_contiguous()
+    packed = torch.empty(packed_bytes(desc), dtype=torch.uint8, device=codes.device)
+    _check(load().qalora_pack(ctypes.byref(desc), _p(codes), _p(packed), _stream()), "qalora_pack")
+    return packed
+
+
+def forward(desc: Desc, x, packed, alpha, beta, A=None, B=None, out_dtype=torch.float32, ws=None,
+            y=None):
+    """y = x W~ + s (pool(x) A) B.  x bf16 [T, d_in]; returns y [T, d_out]."""
+    assert x.dtype == torch.bfloat16 and x.is_contiguous()
+    T = x.shape[0]
+    if y is None:
+        y = torch.empty((T, desc.d_out), dtype=out_dtype, device=x.device)
+    ws, ws_bytes = _workspace(desc, T, OP_FORWARD, ws)
+    rc = load().qalora_forward(ctypes.byref(desc), T, _p(x), _p(packed), _p(alpha), _p(beta), _p(A),
+                               _p(B), _p(y), BF16 if y.dtype == torch.bfloat16 else F32, _p(ws),
+                               ws_bytes, _stream())
+    _check(rc, "qalora_forward")
+    return y
+
+
+def backward(desc: Desc, dy, x, packed, alpha, beta, A=None, B=None, want_dx=True,
+             dx_dtype=torch.float32, dA=None, dB=None, accumulate=False, ws=None, dx=None):
+    """Returns (dx, dA, dB).  dy bf16 [T, d_out], x bf16 [T, d_in]."""
+    assert dy.dtype == torch.bfloat16 and dy.is_contiguous()
+    T = dy.shape[0]
+    if want_dx and dx is None:
+        dx = torch.empty((T, desc.d_in), dtype=dx_dtype, device=dy.device)
+    if A is not None:
+        if dA is None:
+            dA = torch.zeros_like(A)
+        if dB is None:
+            dB = torch.zeros_like(B)
+    ws, ws_bytes = _workspace(desc, T, OP_BACKWARD, ws)
+    dxd = BF16 if (dx is not None and dx.dtype == torch.bfloat16) else F32
+    rc = load().qalora_backward(ctypes.byref(desc), T, _p(dy), _p(x), _p(packed), _p(alpha),
+                                _p(beta), _p(A), _p(B), _p(dx), dxd, _p(dA), _p(dB),
+                                1 if accumulate else 0, _p(ws), ws_bytes, _stream())
+    _check(rc, "qalora_backward")
+    return dx, dA, dB
+
+
+def merge(desc: Desc, beta, A, B, out=None):
+    """beta' = beta + (s/g) A B; ``out`` may be ``beta`` itself."""
+    if out is None:
+        out = torch.empty_like(beta)
+    _check(load().qalora_merge(ctypes.byref(desc), _p(beta), _p(A), _p(B), _p(out), _stream()),
+           "qalora_merge")
+    return out

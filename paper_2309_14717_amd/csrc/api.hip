@@ -1,0 +1,324 @@
+// extern "C" entry points of the QA-LoRA library: host-side argument validation,
+// workspace carving and kernel sequencing.  No allocation, no synchronisation, no state.
+#include "../../include/qalora.h"
+
+#include "common.hpp"
+#include "kernels.hpp"
+
+using namespace qalora;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int row_align_for_bits(int bits) { return bits == 4 ? 8 : (bits == 2 ? 16 : 32); }
+
+// Workspace plans.  Offsets are a pure function of (desc, tokens), so the size query and
+// the compute call always agree.
+struct FwdPlan {
+  int ktail;
+  size_t u_ext, b_ext_t, total;
+};
+struct BwdPlan {
+  int ktail, rp, t_pad, ksplit, tsplit_b, tsplit_a;
+  size_t P, us_t, b_hl, a_ext_t, du_raw, dU, du_ext, db_part, da_part, total;
+};
+
+FwdPlan plan_forward(const qalora_desc& d, int T) {
+  FwdPlan p{};
+  p.ktail = adapter_ktail(d.rank);
+  size_t off = 0;
+  p.u_ext = off;
+  off += align_up((size_t)T * p.ktail * 2);
+  p.b_ext_t = off;
+  off += align_up((size_t)d.d_out * p.ktail * 2);
+  p.total = d.rank > 0 ? off : 0;
+  return p;
+}
+
+BwdPlan plan_backward(const qalora_desc& d, int T) {
+  BwdPlan p{};
+  const int L = d.d_in / d.group;
+  p.ktail = adapter_ktail(d.rank);
+  p.rp = rank_pad32(d.rank);
+  p.t_pad = round_up(T, 64);
+  // dU product: [T, 2rp] output tiles of 64 x 128; split K = d_out to fill the chip.
+  {
+    const int tiles = ceil_div(T, 64) * ceil_div(2 * p.rp, 128);
+    const int nk = ceil_div(d.d_out, 64);
+    int ks = ceil_div(256, tiles);
+    ks = ks < 1 ? 1 : (ks > 16 ? 16 : ks);
+    p.ksplit = ks > nk ? nk : ks;
+  }
+  {
+    const int blocks = ceil_div(d.d_out, 128);
+    int ts = ceil_div(512, blocks);
+    ts = ts > 32 ? 32 : ts;
+    const int steps = p.t_pad / 64;
+    p.tsplit_b = ts > steps ? steps : ts;
+  }
+  {
+    const int blocks = ceil_div(L, 64);
+    int ts = ceil_div(256, blocks);
+    ts = ts > 64 ? 64 : ts;
+    const int steps = ceil_div(T, 16);
+    p.tsplit_a = ts > steps ? steps : ts;
+  }
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t o = off;
+    off += align_up(bytes);
+    return o;
+  };
+  p.P = take((size_t)T * L * 4);
+  p.us_t = take((size_t)2 * p.rp * p.t_pad * 2);
+  p.b_hl = take((size_t)2 * p.rp * d.d_out * 2);
+  p.a_ext_t = take((size_t)L * p.ktail * 2);
+  p.du_raw = take((size_t)p.ksplit * T * 2 * p.rp * 4);
+  p.dU = take((size_t)T * d.rank * 4);
+  p.du_ext = take((size_t)T * p.ktail * 2);
+  p.db_part = take((size_t)p.tsplit_b * d.rank * d.d_out * 4);
+  p.da_part = take((size_t)p.tsplit_a * L * d.rank * 4);
+  p.total = d.rank > 0 ? off : 0;
+  return p;
+}
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+}  // namespace
+
+extern "C" {
+
+const char* qalora_status_string(int status) {
+  switch (status) {
+    case QALORA_OK: return "QALORA_OK";
+    case QALORA_EINVAL: return "QALORA_EINVAL: invalid argument";
+    case QALORA_EALIGN: return "QALORA_EALIGN: device pointer not 16-byte aligned";
+    case QALORA_EWORKSPACE: return "QALORA_EWORKSPACE: workspace missing or too small";
+    case QALORA_EUNSUPPORTED: return "QALORA_EUNSUPPORTED: shape outside the supported set";
+    case QALORA_EHIP: return "QALORA_EHIP: kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+int qalora_check_desc(const qalora_desc* d) {
+  if (!d) return QALORA_EINVAL;
+  if (d->d_in <= 0 || d->d_out <= 0) return QALORA_EINVAL;
+  if (d->bits < 2 || d->bits > 4) return QALORA_EINVAL;
+  if (d->group <= 0 || d->d_in % d->group != 0) return QALORA_EINVAL;
+  if (d->rank < 0) return QALORA_EINVAL;
+  if (d->group % row_align_for_bits(d->bits) != 0) return QALORA_EUNSUPPORTED;
+  if (d->d_out % 8 != 0) return QALORA_EUNSUPPORTED;
+  if (d->rank > 128) return QALORA_EUNSUPPORTED;
+  return QALORA_OK;
+}
+
+size_t qalora_packed_bytes(const qalora_desc* d) {
+  if (qalora_check_desc(d) != QALORA_OK) return 0;
+  return 4 * (plane0_words(d->bits, d->d_in, d->d_out) + plane1_words(d->bits, d->d_in, d->d_out));
+}
+
+size_t qalora_workspace_bytes(const qalora_desc* d, int tokens, int op) {
+  if (qalora_check_desc(d) != QALORA_OK) return 0;
+  switch (op) {
+    case QALORA_OP_QUANTIZE:
+    case QALORA_OP_MERGE: return 0;
+    case QALORA_OP_FORWARD: return tokens > 0 ? plan_forward(*d, tokens).total : 0;
+    case QALORA_OP_BACKWARD: return tokens > 0 ? plan_backward(*d, tokens).total : 0;
+    default: return 0;
+  }
+}
+
+int qalora_quantize(const qalora_desc* d, const float* W, void* packed, float* alpha, float* beta,
+                    void* ws, size_t ws_bytes, void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  const int rc = qalora_check_desc(d);
+  if (rc != QALORA_OK) return rc;
+  if (!W || !packed || !alpha || !beta) return QALORA_EINVAL;
+  if (misaligned(W) || misaligned(packed) || misaligned(alpha) || misaligned(beta))
+    return QALORA_EALIGN;
+  launch_quantize(d->bits, W, packed, alpha, beta, d->d_in, d->d_out, d->group, as_stream(stream));
+  return hipGetLastError() == hipSuccess ? QALORA_OK : QALORA_EHIP;
+}
+
+int qalora_unpack(const qalora_desc* d, const void* packed, uint8_t* codes, void* stream) {
+  const int rc = qalora_check_desc(d);
+  if (rc != QALORA_OK) return rc;
+  if (!packed || !codes) return QALORA_EINVAL;
+  if (misaligned(packed) || misaligned(codes)) return QALORA_EALIGN;
+  launch_unpack(d->bits, packed, codes, d->d_in, d->d_out, as_stream(stream));
+  return hipGetLastError() == hipSuccess ? QALORA_OK : QALORA_EHIP;
+}
+
+int qalora_pack(const qalora_desc* d, const uint8_t* codes, void* packed, void* stream) {
+  const int rc = qalora_check_desc(d);
+  if (rc != QALORA_OK) return rc;
+  if (!packed || !codes) return QALORA_EINVAL;
+  if (misaligned(packed) || misaligned(codes)) return QALORA_EALIGN;
+  launch_pack(d->bits, codes, packed, d->d_in, d->d_out, as_stream(stream));
+  return hipGetLastError() == hipSuccess ? QALORA_OK : QALORA_EHIP;
+}
+
+int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* packed,
+                   const float* alpha, const float* beta, const float* A, const float* B, void* y,
+                   int y_dtype, void* ws, size_t ws_bytes, void* stream) {
+  const int rc = qalora_check_desc(d);
+  if (rc != QALORA_OK) return rc;
+  if (tokens <= 0 || !x || !packed || !alpha || !beta || !y) return QALORA_EINVAL;
+  if ((A == nullptr) != (B == nullptr)) return QALORA_EINVAL;
+  if (y_dtype != QALORA_F32 && y_dtype != QALORA_BF16) return QALORA_EINVAL;
+  if (misaligned(x) || misaligned(packed) || misaligned(alpha) || misaligned(beta) ||
+      misaligned(A) || misaligned(B) || misaligned(y) || misaligned(ws))
+    return QALORA_EALIGN;
+  const bool adapter = A && B && d->rank > 0;
+  FwdPlan plan = plan_forward(*d, tokens);
+  if (adapter && (!ws || ws_bytes < plan.total)) return QALORA_EWORKSPACE;
+  hipStream_t st = as_stream(stream);
+  char* w = static_cast<char*>(ws);
+
+  GemmArgs g{};
+  g.a_main = static_cast<const uint16_t*>(x);
+  g.lda_main = d->d_in;
+  g.plane0 = static_cast<const uint32_t*>(packed);
+  g.plane1 = g.plane0 + plane0_words(d->bits, d->d_in, d->d_out);
+  g.alpha = alpha;
+  g.beta = beta;
+  g.out = y;
+  g.out_bf16 = (y_dtype == QALORA_BF16);
+  g.M = tokens;
+  g.N = d->d_out;
+  g.K_main = d->d_in;
+  g.d_in = d->d_in;
+  g.d_out = d->d_out;
+  g.group = d->group;
+  if (adapter) {
+    uint16_t* u_ext = reinterpret_cast<uint16_t*>(w + plan.u_ext);
+    uint16_t* b_ext_t = reinterpret_cast<uint16_t*>(w + plan.b_ext_t);
+    if (launch_pool_down(static_cast<const uint16_t*>(x), A, d->s, tokens, d->d_in, d->group,
+                         d->rank, nullptr, u_ext, plan.ktail, nullptr, 0, st) != hipSuccess)
+      return QALORA_EHIP;
+    if (launch_prep_b_fwd(B, d->rank, d->d_out, b_ext_t, plan.ktail, st) != hipSuccess)
+      return QALORA_EHIP;
+    g.a_tail = u_ext;
+    g.lda_tail = plan.ktail;
+    g.b_tail = b_ext_t;
+    g.K_tail = plan.ktail;
+  }
+  return launch_gemm_dq(d->bits, false, g, st) == hipSuccess ? QALORA_OK : QALORA_EHIP;
+}
+
+int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void* x,
+                    const void* packed, const float* alpha, const float* beta, const float* A,
+                    const float* B, void* dx, int dx_dtype, float* dA, float* dB, int accumulate,
+                    void* ws, size_t ws_bytes, void* stream) {
+  const int rc = qalora_check_desc(d);
+  if (rc != QALORA_OK) return rc;
+  if (tokens <= 0 || !dy || !packed || !alpha || !beta) return QALORA_EINVAL;
+  if ((A == nullptr) != (B == nullptr)) return QALORA_EINVAL;
+  const bool adapter = A && B && d->rank > 0;
+  if (adapter && (!x || !dA || !dB)) return QALORA_EINVAL;
+  if (dx && dx_dtype != QALORA_F32 && dx_dtype != QALORA_BF16) return QALORA_EINVAL;
+  if (accumulate != 0 && accumulate != 1) return QALORA_EINVAL;
+  if (misaligned(dy) || misaligned(x) || misaligned(packed) || misaligned(alpha) ||
+      misaligned(beta) || misaligned(A) || misaligned(B) || misaligned(dx) || misaligned(dA) ||
+      misaligned(dB) || misaligned(ws))
+    return QALORA_EALIGN;
+  BwdPlan plan = plan_backward(*d, tokens);
+  if (adapter && (!ws || ws_bytes < plan.total)) return QALORA_EWORKSPACE;
+  hipStream_t st = as_stream(stream);
+  char* w = static_cast<char*>(ws);
+  const int L = d->d_in / d->group;
+  const uint16_t* dy16 = static_cast<const uint16_t*>(dy);
+
+  uint16_t* du_ext = nullptr;
+  uint16_t* a_ext_t = nullptr;
+  if (adapter) {
+    float* P = reinterpret_cast<float*>(w + plan.P);
+    uint16_t* us_t = reinterpret_cast<uint16_t*>(w + plan.us_t);
+    uint16_t* b_hl = reinterpret_cast<uint16_t*>(w + plan.b_hl);
+    a_ext_t = reinterpret_cast<uint16_t*>(w + plan.a_ext_t);
+    float* du_raw = reinterpret_cast<float*>(w + plan.du_raw);
+    float* dU = reinterpret_cast<float*>(w + plan.dU);
+    du_ext = reinterpret_cast<uint16_t*>(w + plan.du_ext);
+    float* db_part = reinterpret_cast<float*>(w + plan.db_part);
+    float* da_part = reinterpret_cast<float*>(w + plan.da_part);
+
+    // P = pool(x), sU = s P A (transposed hi/lo for the dB product)
+    if (launch_pool_down(static_cast<const uint16_t*>(x), A, d->s, tokens, d->d_in, d->group,
+                         d->rank, P, nullptr, 0, us_t, plan.t_pad, st) != hipSuccess)
+      return QALORA_EHIP;
+    if (launch_prep_bwd(A, B, L, d->rank, d->d_out, d->group, b_hl, a_ext_t, plan.ktail, st) !=
+        hipSuccess)
+      return QALORA_EHIP;
+    // dU = s dy B^T : plain bf16 product against the hi/lo rows of B, split over K = d_out
+    GemmArgs g{};
+    g.a_tail = dy16;
+    g.lda_tail = d->d_out;
+    g.b_tail = b_hl;
+    g.K_tail = d->d_out;
+    g.out = du_raw;
+    g.M = tokens;
+    g.N = 2 * plan.rp;
+    g.group = 1;
+    if (launch_gemm_plain(g, plan.ksplit, st) != hipSuccess) return QALORA_EHIP;
+    if (launch_du_finalize(du_raw, plan.ksplit, tokens, d->rank, d->s, dU, du_ext, plan.ktail,
+                           st) != hipSuccess)
+      return QALORA_EHIP;
+    // dB = (sU)^T dy
+    if (launch_db_partial(us_t, plan.t_pad, dy16, tokens, d->d_out, d->rank, plan.tsplit_b,
+                          db_part, st) != hipSuccess)
+      return QALORA_EHIP;
+    if (launch_reduce_partials(db_part, plan.tsplit_b, (size_t)d->rank * d->d_out, dB, accumulate,
+                               st) != hipSuccess)
+      return QALORA_EHIP;
+    // dA = P^T dU
+    if (launch_da_partial(P, dU, tokens, L, d->rank, plan.tsplit_a, da_part, st) != hipSuccess)
+      return QALORA_EHIP;
+    if (launch_reduce_partials(da_part, plan.tsplit_a, (size_t)L * d->rank, dA, accumulate, st) !=
+        hipSuccess)
+      return QALORA_EHIP;
+  }
+  if (dx) {
+    GemmArgs g{};
+    g.a_main = dy16;
+    g.lda_main = d->d_out;
+    g.plane0 = static_cast<const uint32_t*>(packed);
+    g.plane1 = g.plane0 + plane0_words(d->bits, d->d_in, d->d_out);
+    g.alpha = alpha;
+    g.beta = beta;
+    g.out = dx;
+    g.out_bf16 = (dx_dtype == QALORA_BF16);
+    g.M = tokens;
+    g.N = d->d_in;
+    g.K_main = d->d_out;
+    g.d_in = d->d_in;
+    g.d_out = d->d_out;
+    g.group = d->group;
+    if (adapter) {
+      g.a_tail = du_ext;
+      g.lda_tail = plan.ktail;
+      g.b_tail = a_ext_t;
+      g.K_tail = plan.ktail;
+    }
+    if (launch_gemm_dq(d->bits, true, g, st) != hipSuccess) return QALORA_EHIP;
+  }
+  return QALORA_OK;
+}
+
+int qalora_merge(const qalora_desc* d, const float* beta, const float* A, const float* B,
+                 float* beta_out, void* stream) {
+  const int rc = qalora_check_desc(d);
+  if (rc != QALORA_OK) return rc;
+  if (!beta || !A || !B || !beta_out || d->rank <= 0) return QALORA_EINVAL;
+  if (misaligned(beta) || misaligned(A) || misaligned(B) || misaligned(beta_out))
+    return QALORA_EALIGN;
+  return launch_merge(beta, A, B, d->d_in / d->group, d->d_out, d->rank, d->group, d->s, beta_out,
+                      as_stream(stream)) == hipSuccess
+             ? QALORA_OK
+             : QALORA_EHIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,73 @@
+// Host-side launchers of the gfx950 kernels.  Everything here takes raw device pointers
+// and a stream; argument validation and workspace carving happen in api.hip.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace qalora {
+
+// --- quantize.hip -------------------------------------------------------------------
+void launch_quantize(int bits, const float* W, void* packed, float* alpha, float* beta, int d_in,
+                     int d_out, int g, hipStream_t st);
+void launch_unpack(int bits, const void* packed, uint8_t* codes, int d_in, int d_out,
+                   hipStream_t st);
+void launch_pack(int bits, const uint8_t* codes, void* packed, int d_in, int d_out,
+                 hipStream_t st);
+
+// --- gemm_dq.hip --------------------------------------------------------------------
+struct GemmArgs {
+  const uint16_t* a_main;  // bf16 [M, K_main]: x (forward) or dy (backward)
+  int lda_main;
+  const uint16_t* a_tail;  // bf16 [M, K_tail]: hi/lo split of s*U (forward) or dU (backward)
+  int lda_tail;
+  const uint32_t* plane0;  // packed codes
+  const uint32_t* plane1;
+  const float* alpha;      // [L, d_out]
+  const float* beta;       // [L, d_out]
+  const uint16_t* b_tail;  // bf16: forward [d_out, K_tail] (B~^T); backward [L, K_tail] (A~/g)
+  void* out;               // [ksplit][M, N] fp32, or [M, N] bf16
+  int out_bf16;
+  int M, N;                // tokens; d_out (forward) or d_in (backward)
+  int K_main;              // d_in (forward) or d_out (backward); 0 for a plain product
+  int K_tail;              // multiple of 64 (zero padded), may be 0
+  int d_in, d_out, group;
+};
+hipError_t launch_gemm_dq(int bits, bool bwd, const GemmArgs& a, hipStream_t st);
+hipError_t launch_gemm_plain(const GemmArgs& a, int ksplit, hipStream_t st);
+
+// --- adapter.hip --------------------------------------------------------------------
+// Tail width of the adapter operands: three bf16 sections of `rank` columns, zero padded
+// to a multiple of 64.
+__host__ __device__ inline int adapter_ktail(int rank) { return rank > 0 ? ((3 * rank + 63) / 64) * 64 : 0; }
+// Rows of the hi (and of the lo) section of a bf16 hi/lo split of a [rank, *] matrix.
+__host__ __device__ inline int rank_pad32(int rank) { return ((rank + 31) / 32) * 32; }
+
+// x -> P = pool_g(x) (optional, fp32 [T, L]) and U = P A, written as
+//   u_ext   bf16 [T, ktail]      = [hi(sU) | lo(sU) | hi(sU) | 0]   (forward tail operand), and/or
+//   us_t    bf16 [2*rp, t_pad]   = rows hi(sU)^T then lo(sU)^T      (dB operand, t contiguous)
+hipError_t launch_pool_down(const uint16_t* x, const float* A, float s, int T, int d_in, int g,
+                            int rank, float* P_out, uint16_t* u_ext, int ktail, uint16_t* us_t,
+                            int t_pad, hipStream_t st);
+// B fp32 [rank, d_out] -> b_ext_t bf16 [d_out, ktail] = [hi | hi | lo | 0] per output column
+hipError_t launch_prep_b_fwd(const float* B, int rank, int d_out, uint16_t* b_ext_t, int ktail,
+                             hipStream_t st);
+// B -> b_hl bf16 [2*rp, d_out] (hi rows then lo rows);  A -> a_ext_t bf16 [L, ktail] = [hi|hi|lo]/g
+hipError_t launch_prep_bwd(const float* A, const float* B, int L, int rank, int d_out, int g,
+                           uint16_t* b_hl, uint16_t* a_ext_t, int ktail, hipStream_t st);
+// dU = s * sum_z (raw[z][:, :rp] + raw[z][:, rp:]) -> dU fp32 [T, rank], du_ext bf16 [T, ktail]
+hipError_t launch_du_finalize(const float* raw, int ksplit, int T, int rank, float s, float* dU,
+                              uint16_t* du_ext, int ktail, hipStream_t st);
+// dB partials over token slices: part[z][rank][d_out] = sum_{t in slice z} sU[t,:]^T dy[t,:]
+hipError_t launch_db_partial(const uint16_t* us_t, int t_pad, const uint16_t* dy, int T, int d_out,
+                             int rank, int tsplit, float* part, hipStream_t st);
+// dA partials over token slices: part[z][L][rank] = sum_{t in slice z} P[t,:]^T dU[t,:]
+hipError_t launch_da_partial(const float* P, const float* dU, int T, int L, int rank, int tsplit,
+                             float* part, hipStream_t st);
+// out[i] = (accumulate ? out[i] : 0) + sum_z part[z][i], fixed order
+hipError_t launch_reduce_partials(const float* part, int nparts, size_t n, float* out,
+                                  int accumulate, hipStream_t st);
+// beta_out = beta + (s/g) A B
+hipError_t launch_merge(const float* beta, const float* A, const float* B, int L, int d_out,
+                        int rank, int g, float s, float* beta_out, hipStream_t st);
+
+}  // namespace qalora

@@ -1,0 +1,166 @@
+// Group-wise min-max quantization (Eq. 1 of the paper applied to each group of g
+// consecutive rows of each column, Sec. 3.3), and pack / unpack between the canonical
+// one-code-per-byte matrix and the private bit-packed format.
+//
+// HBM-bound, one pass over W plus a second pass that hits L2: a thread owns one
+// (group, column) pair, adjacent threads own adjacent columns, so every load and store
+// is coalesced along D_out.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace qalora {
+
+// The arithmetic below is the fp32 recipe of the C ABI, operation by operation, with
+// explicit round-to-nearest intrinsics so that no contraction or reciprocal sneaks in.
+template <int NBITS>
+__global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__ W,
+                                                       uint32_t* __restrict__ plane0,
+                                                       uint32_t* __restrict__ plane1,
+                                                       float* __restrict__ alpha,
+                                                       float* __restrict__ beta, int d_in,
+                                                       int d_out, int g) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const int l = blockIdx.y;
+  if (j >= d_out) return;
+  const int i0 = l * g;
+  const float* col = W + (size_t)i0 * d_out + j;
+  float mn = col[0];
+  float mx = mn;
+  for (int q = 1; q < g; ++q) {
+    const float w = col[(size_t)q * d_out];
+    if (w < mn) mn = w;
+    if (w > mx) mx = w;
+  }
+  constexpr int QMAX = (1 << NBITS) - 1;
+  const float range = __fsub_rn(mx, mn);
+  float a = __fdiv_rn(range, (float)QMAX);
+  const bool degenerate = !(a > 0.0f);
+  if (degenerate) a = 1.0f;
+  alpha[(size_t)l * d_out + j] = a;
+  beta[(size_t)l * d_out + j] = mn;
+
+  constexpr int RB0 = PackFmt<NBITS>::kRowsPerWord0;
+  constexpr int LOW_BITS = (NBITS == 3) ? 2 : NBITS;
+  constexpr int ROWS = (NBITS == 3) ? 32 : RB0;  // rows handled per outer step
+  for (int q0 = 0; q0 < g; q0 += ROWS) {
+    uint32_t hiword = 0;
+#pragma unroll
+    for (int h = 0; h < ROWS / RB0; ++h) {
+      uint32_t word = 0;
+#pragma unroll
+      for (int p = 0; p < RB0; ++p) {
+        int c = 0;
+        if (!degenerate) {
+          const float d = __fsub_rn(col[(size_t)(q0 + h * RB0 + p) * d_out], mn);
+          const float r = rintf(__fdiv_rn(d, a));
+          c = (int)r;
+          c = c < 0 ? 0 : (c > QMAX ? QMAX : c);
+        }
+        word |= (uint32_t)(c & ((1 << LOW_BITS) - 1)) << (LOW_BITS * (p >> 1) + 16 * (p & 1));
+        if constexpr (NBITS == 3) {
+          const int pp = h * RB0 + p;
+          hiword |= (uint32_t)(c >> 2) << ((pp >> 1) + 16 * (pp & 1));
+        }
+      }
+      plane0[(size_t)((i0 + q0) / RB0 + h) * d_out + j] = word;
+    }
+    if constexpr (NBITS == 3) plane1[(size_t)((i0 + q0) / 32) * d_out + j] = hiword;
+  }
+}
+
+// One thread rebuilds the codes of 8 rows of one column.
+template <int NBITS>
+__global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict__ plane0,
+                                                     const uint32_t* __restrict__ plane1,
+                                                     uint8_t* __restrict__ codes, int d_in,
+                                                     int d_out) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const int i0 = blockIdx.y * 8;
+  if (j >= d_out || i0 >= d_in) return;
+  constexpr int RB0 = PackFmt<NBITS>::kRowsPerWord0;
+  uint32_t w0 = plane0[(size_t)(i0 / RB0) * d_out + j] >> patch_preshift0<NBITS>(i0);
+  uint32_t w1 = 0;
+  if constexpr (NBITS == 3) w1 = plane1[(size_t)(i0 / 32) * d_out + j] >> patch_preshift1(i0);
+#pragma unroll
+  for (int p = 0; p < 8; ++p)
+    codes[(size_t)(i0 + p) * d_out + j] = (uint8_t)patch_code<NBITS>(w0, w1, p);
+}
+
+// One thread builds the word(s) of ROWS consecutive rows of one column.
+template <int NBITS>
+__global__ __launch_bounds__(256) void pack_kernel(const uint8_t* __restrict__ codes,
+                                                   uint32_t* __restrict__ plane0,
+                                                   uint32_t* __restrict__ plane1, int d_in,
+                                                   int d_out) {
+  constexpr int RB0 = PackFmt<NBITS>::kRowsPerWord0;
+  constexpr int LOW_BITS = (NBITS == 3) ? 2 : NBITS;
+  constexpr int ROWS = (NBITS == 3) ? 32 : RB0;
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const int i0 = blockIdx.y * ROWS;
+  if (j >= d_out || i0 >= d_in) return;
+  uint32_t hiword = 0;
+#pragma unroll
+  for (int h = 0; h < ROWS / RB0; ++h) {
+    uint32_t word = 0;
+#pragma unroll
+    for (int p = 0; p < RB0; ++p) {
+      const uint32_t c = codes[(size_t)(i0 + h * RB0 + p) * d_out + j] & ((1u << NBITS) - 1);
+      word |= (c & ((1u << LOW_BITS) - 1)) << (LOW_BITS * (p >> 1) + 16 * (p & 1));
+      if constexpr (NBITS == 3) {
+        const int pp = h * RB0 + p;
+        hiword |= (c >> 2) << ((pp >> 1) + 16 * (pp & 1));
+      }
+    }
+    plane0[(size_t)(i0 / RB0 + h) * d_out + j] = word;
+  }
+  if constexpr (NBITS == 3) plane1[(size_t)(i0 / 32) * d_out + j] = hiword;
+}
+
+template <int NBITS>
+static void quantize_n(const float* W, uint32_t* p0, uint32_t* p1, float* alpha, float* beta,
+                       int d_in, int d_out, int g, hipStream_t st) {
+  dim3 grid(ceil_div(d_out, 256), d_in / g);
+  quantize_kernel<NBITS><<<grid, 256, 0, st>>>(W, p0, p1, alpha, beta, d_in, d_out, g);
+}
+template <int NBITS>
+static void unpack_n(const uint32_t* p0, const uint32_t* p1, uint8_t* codes, int d_in, int d_out,
+                     hipStream_t st) {
+  dim3 grid(ceil_div(d_out, 256), d_in / 8);
+  unpack_kernel<NBITS><<<grid, 256, 0, st>>>(p0, p1, codes, d_in, d_out);
+}
+template <int NBITS>
+static void pack_n(const uint8_t* codes, uint32_t* p0, uint32_t* p1, int d_in, int d_out,
+                   hipStream_t st) {
+  constexpr int ROWS = (NBITS == 3) ? 32 : PackFmt<NBITS>::kRowsPerWord0;
+  dim3 grid(ceil_div(d_out, 256), d_in / ROWS);
+  pack_kernel<NBITS><<<grid, 256, 0, st>>>(codes, p0, p1, d_in, d_out);
+}
+
+void launch_quantize(int bits, const float* W, void* packed, float* alpha, float* beta, int d_in,
+                     int d_out, int g, hipStream_t st) {
+  uint32_t* p0 = static_cast<uint32_t*>(packed);
+  uint32_t* p1 = p0 + plane0_words(bits, d_in, d_out);
+  if (bits == 4) quantize_n<4>(W, p0, p1, alpha, beta, d_in, d_out, g, st);
+  else if (bits == 3) quantize_n<3>(W, p0, p1, alpha, beta, d_in, d_out, g, st);
+  else quantize_n<2>(W, p0, p1, alpha, beta, d_in, d_out, g, st);
+}
+
+void launch_unpack(int bits, const void* packed, uint8_t* codes, int d_in, int d_out,
+                   hipStream_t st) {
+  const uint32_t* p0 = static_cast<const uint32_t*>(packed);
+  const uint32_t* p1 = p0 + plane0_words(bits, d_in, d_out);
+  if (bits == 4) unpack_n<4>(p0, p1, codes, d_in, d_out, st);
+  else if (bits == 3) unpack_n<3>(p0, p1, codes, d_in, d_out, st);
+  else unpack_n<2>(p0, p1, codes, d_in, d_out, st);
+}
+
+void launch_pack(int bits, const uint8_t* codes, void* packed, int d_in, int d_out,
+                 hipStream_t st) {
+  uint32_t* p0 = static_cast<uint32_t*>(packed);
+  uint32_t* p1 = p0 + plane0_words(bits, d_in, d_out);
+  if (bits == 4) pack_n<4>(codes, p0, p1, d_in, d_out, st);
+  else if (bits == 3) pack_n<3>(codes, p0, p1, d_in, d_out, st);
+  else pack_n<2>(codes, p0, p1, d_in, d_out, st);
+}
+
+}  // namespace qalora

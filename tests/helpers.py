@@ -1,0 +1,43 @@
+"""Shared helpers of the GPU parity tests: upload seeded inputs, run the oracle, compare."""
+import numpy as np
+import torch
+
+import oracle
+from paper_2309_14717_amd import synth
+
+TOL = 2e-3  # max|delta| / max|ref|, bf16 operands with fp32 accumulation
+
+
+def rel_err(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    denom = np.abs(ref).max()
+    return float(np.abs(got - ref).max() / denom) if denom > 0 else float(np.abs(got).max())
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t.to(dtype) if dtype is not None else t
+
+
+def layer_on_gpu(api, cfg, inputs=None, quantized=None):
+    """Quantize on both sides (or take a given triple) and upload everything.
+
+    Returns a dict with the oracle-side numpy arrays (o_*) and device tensors."""
+    d = inputs if inputs is not None else synth.make_inputs(cfg)
+    desc = api.make_desc(cfg.d_in, cfg.d_out, cfg.bits, cfg.group, cfg.rank, cfg.s)
+    out = dict(cfg=cfg, desc=desc, np=d)
+    if quantized is None:
+        codes, alpha, beta = oracle.quantize(d["W"], cfg.bits, cfg.group)
+        packed, g_alpha, g_beta = api.quantize(desc, dev(d["W"]))
+    else:
+        codes, alpha, beta = quantized
+        packed = api.pack(desc, dev(codes))
+        g_alpha, g_beta = dev(alpha), dev(beta)
+    out.update(codes=codes, alpha=alpha, beta=beta, packed=packed, g_alpha=g_alpha, g_beta=g_beta)
+    out["x"] = dev(d["x"], torch.bfloat16)
+    out["dy"] = dev(d["dy"], torch.bfloat16)
+    if cfg.rank > 0:
+        out["A"] = dev(d["A"])
+        out["B"] = dev(d["B"])
+    return out
