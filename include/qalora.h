@@ -22,7 +22,8 @@
  *     `stream` (a hipStream_t passed as void*; NULL = the default stream) and the
  *     results are ready when that stream reaches the end of the enqueued work.
  *   - Scratch memory comes from the caller through (ws, ws_bytes); ask
- *     qalora_workspace_bytes for the size.  ws contents are undefined afterwards.
+ *     qalora_workspace_bytes for the size (forward and backward always need some, at least
+ *     8 bytes per token).  ws contents are undefined afterwards.
  *   - Inputs are read-only.  Outputs must not alias inputs unless stated.
  *   - Device pointers must be 16-byte aligned (QALORA_EALIGN otherwise).
  *   - Every entry returns a status (0 = QALORA_OK, negative = error).  Argument errors
@@ -115,7 +116,9 @@ int qalora_pack(const qalora_desc* desc, const uint8_t* codes, void* packed, voi
  *      adapter-free layer, e.g. after qalora_merge (then s is ignored).
  * out: y [tokens, d_out], fp32 or bf16 per y_dtype (bf16 = round-to-nearest-even of the
  *      fp32 result).
- * W~ is rounded to bf16 before the matrix units for tokens > 16; accumulation is fp32. */
+ * Precision: x is used exactly (each token row is scaled by a power of two and converted to
+ * fp16), W~ is rounded to fp16 (11 significant bits) before the matrix cores, accumulation
+ * is fp32; the adapter branch is evaluated to about 2^-16 relative. */
 int qalora_forward(const qalora_desc* desc, int tokens, const void* x, const void* packed,
                    const float* alpha, const float* beta, const float* A, const float* B,
                    void* y, int y_dtype, void* ws, size_t ws_bytes, void* stream);

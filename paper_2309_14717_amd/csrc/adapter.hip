@@ -12,9 +12,55 @@
 namespace qalora {
 
 // ---------------------------------------------------------------------------------------
+// Per-row power-of-two scale for the fp16 matrix-core path: scale = 2^(14 - e) where e is the
+// unbiased exponent of the row's largest magnitude, so the scaled row peaks in [2^14, 2^15).
+// (.x = scale, .y = 1/scale).  Rows that are all zero (or hold inf/nan) get 1.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ float2 scale_from_maxbits(uint32_t maxbits) {
+  const int e = (int)(maxbits >> 7);  // biased exponent of the largest |bf16|
+  if (e < 15 || e >= 255) return float2{1.0f, 1.0f};
+  return float2{__uint_as_float((uint32_t)(268 - e) << 23), __uint_as_float((uint32_t)(e - 14) << 23)};
+}
+
+__device__ __forceinline__ uint32_t max_abs_bits(uint4 q, uint32_t m) {
+  const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    m = max(m, w[e] & 0x7fffu);
+    m = max(m, (w[e] >> 16) & 0x7fffu);
+  }
+  return m;
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) v = max(v, (uint32_t)__shfl_xor((int)v, off, 64));
+  return v;
+}
+
+// One wavefront per row.
+__global__ __launch_bounds__(256) void row_scale_kernel(const uint16_t* __restrict__ a, int rows,
+                                                        int cols, float2* __restrict__ rs) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  uint32_t m = 0;
+  for (int ch = lane; ch < cols / 8; ch += 64)
+    m = max_abs_bits(*reinterpret_cast<const uint4*>(a + (size_t)row * cols + 8 * ch), m);
+  m = wave_max_u32(m);
+  if (lane == 0) rs[row] = scale_from_maxbits(m);
+}
+
+hipError_t launch_row_scale(const uint16_t* a, int rows, int cols, float2* rs, hipStream_t st) {
+  row_scale_kernel<<<ceil_div(rows, 4), 256, 0, st>>>(a, rows, cols, rs);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
 // pool_g(x) and U = pool_g(x) A.   One block = 8 tokens, one wavefront = 2 of them.
 // The group average uses a wavefront butterfly: each lane sums 8 consecutive bf16 inputs
 // (one 128-bit load), then lanes of the same group (g/8 of them) combine with xor-shuffles.
+// The same sweep over the row yields its largest magnitude, hence its power-of-two scale.
 // ---------------------------------------------------------------------------------------
 constexpr int POOL_TB = 8;
 
@@ -22,37 +68,48 @@ __global__ __launch_bounds__(256) void pool_down_kernel(const uint16_t* __restri
                                                         const float* __restrict__ A, float s,
                                                         int T, int d_in, int g, int rank,
                                                         float* __restrict__ P_out,
+                                                        float2* __restrict__ rs_out,
                                                         uint16_t* __restrict__ u_ext, int ktail,
                                                         uint16_t* __restrict__ us_t, int t_pad) {
   extern __shared__ float P_s[];  // [POOL_TB][L]
+  __shared__ float sc_s[POOL_TB];
   const int L = d_in / g;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int t0 = blockIdx.x * POOL_TB;
   const int lpg = g / 8;  // lanes per group
   const bool butterfly = (lpg <= 64) && ((lpg & (lpg - 1)) == 0);
   const float inv_g = 1.0f / (float)g;
+  const int nchunks = d_in / 8;
 
-  if (butterfly) {
-    const int nchunks = d_in / 8;
-    for (int tt = wave * 2; tt < wave * 2 + 2; ++tt) {
-      const int t = t0 + tt;
-      for (int c0 = 0; c0 < nchunks; c0 += 64) {
-        const int ch = c0 + lane;
-        float v = 0.0f;
-        if (t < T && ch < nchunks) {
-          const uint4 q = *reinterpret_cast<const uint4*>(x + (size_t)t * d_in + 8 * ch);
-          const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+  for (int tt = wave * 2; tt < wave * 2 + 2; ++tt) {
+    const int t = t0 + tt;
+    uint32_t amax = 0;
+    for (int c0 = 0; c0 < nchunks; c0 += 64) {
+      const int ch = c0 + lane;
+      float v = 0.0f;
+      if (t < T && ch < nchunks) {
+        const uint4 q = *reinterpret_cast<const uint4*>(x + (size_t)t * d_in + 8 * ch);
+        amax = max_abs_bits(q, amax);
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            v += bf16_bits_to_f32(w[e] & 0xffffu);
-            v += __uint_as_float(w[e] & 0xffff0000u);
-          }
+        for (int e = 0; e < 4; ++e) {
+          v += bf16_bits_to_f32(w[e] & 0xffffu);
+          v += __uint_as_float(w[e] & 0xffff0000u);
         }
+      }
+      if (butterfly) {
         for (int off = 1; off < lpg; off <<= 1) v += __shfl_xor(v, off, 64);
         if (ch < nchunks && (lane & (lpg - 1)) == 0) P_s[tt * L + ch / lpg] = v * inv_g;
       }
     }
-  } else {
+    amax = wave_max_u32(amax);
+    if (lane == 0) {
+      const float2 sc = scale_from_maxbits(amax);
+      sc_s[tt] = sc.x;
+      if (rs_out && t < T) rs_out[t] = sc;
+    }
+  }
+  if (!butterfly) {
     for (int o = tid; o < POOL_TB * L; o += 256) {
       const int tt = o / L, l = o % L;
       const int t = t0 + tt;
@@ -77,15 +134,18 @@ __global__ __launch_bounds__(256) void pool_down_kernel(const uint16_t* __restri
     if (t >= T) continue;
     float u = 0.0f;
     for (int l = 0; l < L; ++l) u = __builtin_fmaf(P_s[tt * L + l], A[(size_t)l * rank + k], u);
+    u *= s;
     uint16_t hi, lo;
-    split_bf16(s * u, hi, lo);
     if (u_ext) {
+      // the forward tail shares the accumulator of the scaled main product
+      split_bf16(u * sc_s[tt], hi, lo);
       uint16_t* row = u_ext + (size_t)t * ktail;
       row[k] = hi;
       row[rank + k] = lo;
       row[2 * rank + k] = hi;
     }
     if (us_t) {
+      split_bf16(u, hi, lo);
       us_t[(size_t)k * t_pad + t] = hi;
       us_t[(size_t)(rp + k) * t_pad + t] = lo;
     }
@@ -106,8 +166,8 @@ __global__ void fill_zero_kernel(uint4* __restrict__ p, size_t n16) {
 }
 
 hipError_t launch_pool_down(const uint16_t* x, const float* A, float s, int T, int d_in, int g,
-                            int rank, float* P_out, uint16_t* u_ext, int ktail, uint16_t* us_t,
-                            int t_pad, hipStream_t st) {
+                            int rank, float* P_out, float2* rs_out, uint16_t* u_ext, int ktail,
+                            uint16_t* us_t, int t_pad, hipStream_t st) {
   const int L = d_in / g;
   const size_t smem = (size_t)POOL_TB * L * sizeof(float);
   static size_t smem_limit = 48 * 1024;
@@ -125,7 +185,7 @@ hipError_t launch_pool_down(const uint16_t* x, const float* A, float s, int T, i
         reinterpret_cast<uint4*>(us_t), n16);
   }
   pool_down_kernel<<<ceil_div(T, POOL_TB), 256, smem, st>>>(x, A, s, T, d_in, g, rank, P_out,
-                                                            u_ext, ktail, us_t, t_pad);
+                                                            rs_out, u_ext, ktail, us_t, t_pad);
   return hipGetLastError();
 }
 
@@ -198,6 +258,7 @@ hipError_t launch_prep_bwd(const float* A, const float* B, int L, int rank, int 
 
 __global__ __launch_bounds__(256) void du_finalize_kernel(const float* __restrict__ raw,
                                                           int ksplit, int T, int rank, float s,
+                                                          const float2* __restrict__ rs,
                                                           float* __restrict__ dU,
                                                           uint16_t* __restrict__ du_ext,
                                                           int ktail) {
@@ -216,16 +277,17 @@ __global__ __launch_bounds__(256) void du_finalize_kernel(const float* __restric
     v *= s;
     if (c < rank) dU[(size_t)t * rank + k] = v;
     uint16_t hi, lo;
-    split_bf16(v, hi, lo);
+    split_bf16(v * rs[t].x, hi, lo);  // the backward tail rides on the scaled main product
     out = (c >= rank && c < 2 * rank) ? lo : hi;
   }
   du_ext[idx] = out;
 }
 
-hipError_t launch_du_finalize(const float* raw, int ksplit, int T, int rank, float s, float* dU,
-                              uint16_t* du_ext, int ktail, hipStream_t st) {
+hipError_t launch_du_finalize(const float* raw, int ksplit, int T, int rank, float s,
+                              const float2* rs, float* dU, uint16_t* du_ext, int ktail,
+                              hipStream_t st) {
   const size_t n = (size_t)T * ktail;
-  du_finalize_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(raw, ksplit, T, rank, s, dU,
+  du_finalize_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(raw, ksplit, T, rank, s, rs, dU,
                                                                   du_ext, ktail);
   return hipGetLastError();
 }

@@ -19,22 +19,26 @@ int row_align_for_bits(int bits) { return bits == 4 ? 8 : (bits == 2 ? 16 : 32);
 // the compute call always agree.
 struct FwdPlan {
   int ktail;
-  size_t u_ext, b_ext_t, total;
+  size_t rs, u_ext, b_ext_t, total;
 };
 struct BwdPlan {
   int ktail, rp, t_pad, ksplit, tsplit_b, tsplit_a;
-  size_t P, us_t, b_hl, a_ext_t, du_raw, dU, du_ext, db_part, da_part, total;
+  size_t rs, P, us_t, b_hl, a_ext_t, du_raw, dU, du_ext, db_part, da_part, total;
 };
 
 FwdPlan plan_forward(const qalora_desc& d, int T) {
   FwdPlan p{};
   p.ktail = adapter_ktail(d.rank);
   size_t off = 0;
-  p.u_ext = off;
-  off += align_up((size_t)T * p.ktail * 2);
-  p.b_ext_t = off;
-  off += align_up((size_t)d.d_out * p.ktail * 2);
-  p.total = d.rank > 0 ? off : 0;
+  p.rs = off;
+  off += align_up((size_t)T * sizeof(float2));
+  if (d.rank > 0) {
+    p.u_ext = off;
+    off += align_up((size_t)T * p.ktail * 2);
+    p.b_ext_t = off;
+    off += align_up((size_t)d.d_out * p.ktail * 2);
+  }
+  p.total = off;
   return p;
 }
 
@@ -44,6 +48,11 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
   p.ktail = adapter_ktail(d.rank);
   p.rp = rank_pad32(d.rank);
   p.t_pad = round_up(T, 64);
+  if (d.rank <= 0) {  // adapter-free: only the row scales of dy
+    p.rs = 0;
+    p.total = align_up((size_t)T * sizeof(float2));
+    return p;
+  }
   // dU product: [T, 2rp] output tiles of 64 x 128; split K = d_out to fill the chip.
   {
     const int tiles = ceil_div(T, 64) * ceil_div(2 * p.rp, 128);
@@ -72,6 +81,7 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
     off += align_up(bytes);
     return o;
   };
+  p.rs = take((size_t)T * sizeof(float2));
   p.P = take((size_t)T * L * 4);
   p.us_t = take((size_t)2 * p.rp * p.t_pad * 2);
   p.b_hl = take((size_t)2 * p.rp * d.d_out * 2);
@@ -81,7 +91,7 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
   p.du_ext = take((size_t)T * p.ktail * 2);
   p.db_part = take((size_t)p.tsplit_b * d.rank * d.d_out * 4);
   p.da_part = take((size_t)p.tsplit_a * L * d.rank * 4);
-  p.total = d.rank > 0 ? off : 0;
+  p.total = off;
   return p;
 }
 
@@ -175,9 +185,11 @@ int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* 
     return QALORA_EALIGN;
   const bool adapter = A && B && d->rank > 0;
   FwdPlan plan = plan_forward(*d, tokens);
-  if (adapter && (!ws || ws_bytes < plan.total)) return QALORA_EWORKSPACE;
+  if (!adapter) plan.total = align_up((size_t)tokens * sizeof(float2));
+  if (!ws || ws_bytes < plan.total) return QALORA_EWORKSPACE;
   hipStream_t st = as_stream(stream);
   char* w = static_cast<char*>(ws);
+  float2* rs = reinterpret_cast<float2*>(w + plan.rs);
 
   GemmArgs g{};
   g.a_main = static_cast<const uint16_t*>(x);
@@ -194,11 +206,15 @@ int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* 
   g.d_in = d->d_in;
   g.d_out = d->d_out;
   g.group = d->group;
-  if (adapter) {
+  g.row_scale = rs;
+  if (!adapter) {
+    if (launch_row_scale(static_cast<const uint16_t*>(x), tokens, d->d_in, rs, st) != hipSuccess)
+      return QALORA_EHIP;
+  } else {
     uint16_t* u_ext = reinterpret_cast<uint16_t*>(w + plan.u_ext);
     uint16_t* b_ext_t = reinterpret_cast<uint16_t*>(w + plan.b_ext_t);
     if (launch_pool_down(static_cast<const uint16_t*>(x), A, d->s, tokens, d->d_in, d->group,
-                         d->rank, nullptr, u_ext, plan.ktail, nullptr, 0, st) != hipSuccess)
+                         d->rank, nullptr, rs, u_ext, plan.ktail, nullptr, 0, st) != hipSuccess)
       return QALORA_EHIP;
     if (launch_prep_b_fwd(B, d->rank, d->d_out, b_ext_t, plan.ktail, st) != hipSuccess)
       return QALORA_EHIP;
@@ -227,11 +243,14 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
       misaligned(dB) || misaligned(ws))
     return QALORA_EALIGN;
   BwdPlan plan = plan_backward(*d, tokens);
-  if (adapter && (!ws || ws_bytes < plan.total)) return QALORA_EWORKSPACE;
+  if (!adapter) plan.total = align_up((size_t)tokens * sizeof(float2));
+  if (!ws || ws_bytes < plan.total) return QALORA_EWORKSPACE;
   hipStream_t st = as_stream(stream);
   char* w = static_cast<char*>(ws);
   const int L = d->d_in / d->group;
   const uint16_t* dy16 = static_cast<const uint16_t*>(dy);
+  float2* rs = reinterpret_cast<float2*>(w + plan.rs);
+  if (launch_row_scale(dy16, tokens, d->d_out, rs, st) != hipSuccess) return QALORA_EHIP;
 
   uint16_t* du_ext = nullptr;
   uint16_t* a_ext_t = nullptr;
@@ -248,7 +267,7 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
 
     // P = pool(x), sU = s P A (transposed hi/lo for the dB product)
     if (launch_pool_down(static_cast<const uint16_t*>(x), A, d->s, tokens, d->d_in, d->group,
-                         d->rank, P, nullptr, 0, us_t, plan.t_pad, st) != hipSuccess)
+                         d->rank, P, nullptr, nullptr, 0, us_t, plan.t_pad, st) != hipSuccess)
       return QALORA_EHIP;
     if (launch_prep_bwd(A, B, L, d->rank, d->d_out, d->group, b_hl, a_ext_t, plan.ktail, st) !=
         hipSuccess)
@@ -264,7 +283,7 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
     g.N = 2 * plan.rp;
     g.group = 1;
     if (launch_gemm_plain(g, plan.ksplit, st) != hipSuccess) return QALORA_EHIP;
-    if (launch_du_finalize(du_raw, plan.ksplit, tokens, d->rank, d->s, dU, du_ext, plan.ktail,
+    if (launch_du_finalize(du_raw, plan.ksplit, tokens, d->rank, d->s, rs, dU, du_ext, plan.ktail,
                            st) != hipSuccess)
       return QALORA_EHIP;
     // dB = (sU)^T dy
@@ -297,6 +316,7 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
     g.d_in = d->d_in;
     g.d_out = d->d_out;
     g.group = d->group;
+    g.row_scale = rs;
     if (adapter) {
       g.a_tail = du_ext;
       g.lda_tail = plan.ktail;

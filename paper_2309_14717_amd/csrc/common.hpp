@@ -8,6 +8,8 @@ namespace qalora {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -117,6 +119,20 @@ __device__ __forceinline__ uint32_t patch_code(uint32_t w0s, uint32_t w1s, int p
     const uint32_t hi = (w1s >> ((p >> 1) + 16 * (p & 1))) & 1u;
     return lo | (hi << 2);
   }
+}
+
+// The codes of rows 2m and 2m+1 (m = 0..3) of the patch, for one column, as an exact pair
+// of fp16 integers (low half = even row).  0x6400 is fp16 1024.0, whose mantissa unit is 1,
+// so (0x6400 | c) - 1024 == c for c < 1024 without any int->float conversion.
+template <int NBITS>
+__device__ __forceinline__ f16x2 patch_code_pair_f16(uint32_t w0s, uint32_t w1s, int m) {
+  constexpr int LB = (NBITS == 3) ? 2 : NBITS;  // code bits held in plane 0
+  constexpr uint32_t kMask0 = ((1u << LB) - 1u) * 0x00010001u;
+  uint32_t u = (w0s >> (LB * m)) & kMask0;
+  if constexpr (NBITS == 3) u |= ((w1s >> m) & 0x00010001u) << 2;
+  u |= 0x64006400u;
+  const f16x2 k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
+  return __builtin_bit_cast(f16x2, u) - k1024;
 }
 
 }  // namespace qalora

@@ -18,13 +18,15 @@ void launch_pack(int bits, const uint8_t* codes, void* packed, int d_in, int d_o
 struct GemmArgs {
   const uint16_t* a_main;  // bf16 [M, K_main]: x (forward) or dy (backward)
   int lda_main;
-  const uint16_t* a_tail;  // bf16 [M, K_tail]: hi/lo split of s*U (forward) or dU (backward)
+  const uint16_t* a_tail;  // bf16 [M, K_tail]: hi/lo split of s*U (forward) or dU (backward),
+                           // each row pre-multiplied by its row scale
   int lda_tail;
   const uint32_t* plane0;  // packed codes
   const uint32_t* plane1;
   const float* alpha;      // [L, d_out]
   const float* beta;       // [L, d_out]
   const uint16_t* b_tail;  // bf16: forward [d_out, K_tail] (B~^T); backward [L, K_tail] (A~/g)
+  const float2* row_scale; // [M] (scale, 1/scale): power-of-two row scales of a_main
   void* out;               // [ksplit][M, N] fp32, or [M, N] bf16
   int out_bf16;
   int M, N;                // tokens; d_out (forward) or d_in (backward)
@@ -43,20 +45,25 @@ __host__ __device__ inline int adapter_ktail(int rank) { return rank > 0 ? ((3 *
 __host__ __device__ inline int rank_pad32(int rank) { return ((rank + 31) / 32) * 32; }
 
 // x -> P = pool_g(x) (optional, fp32 [T, L]) and U = P A, written as
-//   u_ext   bf16 [T, ktail]      = [hi(sU) | lo(sU) | hi(sU) | 0]   (forward tail operand), and/or
+//   rs_out  [T] row scales of x (optional),
+//   u_ext   bf16 [T, ktail]      = [hi | lo | hi | 0] of sU * row scale (forward tail operand), and/or
 //   us_t    bf16 [2*rp, t_pad]   = rows hi(sU)^T then lo(sU)^T      (dB operand, t contiguous)
 hipError_t launch_pool_down(const uint16_t* x, const float* A, float s, int T, int d_in, int g,
-                            int rank, float* P_out, uint16_t* u_ext, int ktail, uint16_t* us_t,
-                            int t_pad, hipStream_t st);
+                            int rank, float* P_out, float2* rs_out, uint16_t* u_ext, int ktail,
+                            uint16_t* us_t, int t_pad, hipStream_t st);
+// rs[row] = (2^(14-e), 2^(e-14)), e = exponent of the largest |a[row, :]| (bf16 [rows, cols])
+hipError_t launch_row_scale(const uint16_t* a, int rows, int cols, float2* rs, hipStream_t st);
 // B fp32 [rank, d_out] -> b_ext_t bf16 [d_out, ktail] = [hi | hi | lo | 0] per output column
 hipError_t launch_prep_b_fwd(const float* B, int rank, int d_out, uint16_t* b_ext_t, int ktail,
                              hipStream_t st);
 // B -> b_hl bf16 [2*rp, d_out] (hi rows then lo rows);  A -> a_ext_t bf16 [L, ktail] = [hi|hi|lo]/g
 hipError_t launch_prep_bwd(const float* A, const float* B, int L, int rank, int d_out, int g,
                            uint16_t* b_hl, uint16_t* a_ext_t, int ktail, hipStream_t st);
-// dU = s * sum_z (raw[z][:, :rp] + raw[z][:, rp:]) -> dU fp32 [T, rank], du_ext bf16 [T, ktail]
-hipError_t launch_du_finalize(const float* raw, int ksplit, int T, int rank, float s, float* dU,
-                              uint16_t* du_ext, int ktail, hipStream_t st);
+// dU = s * sum_z (raw[z][:, :rp] + raw[z][:, rp:]) -> dU fp32 [T, rank], and du_ext bf16
+// [T, ktail] = [hi | lo | hi | 0] of dU * rs[t].x (rs = row scales of dy)
+hipError_t launch_du_finalize(const float* raw, int ksplit, int T, int rank, float s,
+                              const float2* rs, float* dU, uint16_t* du_ext, int ktail,
+                              hipStream_t st);
 // dB partials over token slices: part[z][rank][d_out] = sum_{t in slice z} sU[t,:]^T dy[t,:]
 hipError_t launch_db_partial(const uint16_t* us_t, int t_pad, const uint16_t* dy, int T, int d_out,
                              int rank, int tsplit, float* part, hipStream_t st);

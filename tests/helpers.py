@@ -1,4 +1,6 @@
 """Shared helpers of the GPU parity tests: upload seeded inputs, run the oracle, compare."""
+import os
+
 import numpy as np
 import torch
 
@@ -6,6 +8,20 @@ import oracle
 from paper_2309_14717_amd import synth
 
 TOL = 2e-3  # max|delta| / max|ref|, bf16 operands with fp32 accumulation
+
+
+_REPORT = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out",
+                       "parity_report.txt")
+
+
+def record(case, **errs):
+    """Append measured parity numbers to gpurun_out/parity_report.txt (best effort)."""
+    try:
+        os.makedirs(os.path.dirname(_REPORT), exist_ok=True)
+        with open(_REPORT, "a") as f:
+            f.write(case + " " + " ".join(f"{k}={v:.3e}" for k, v in errs.items()) + "\n")
+    except OSError:
+        pass
 
 
 def rel_err(got, ref):

@@ -65,7 +65,8 @@ def test_packed_and_workspace_sizes(lib):
     assert f >= 4096 * 192 * 2 + 4096 * 192 * 2 and b > f
     assert api.workspace_bytes(d, 4096, 99) == 0
     d0 = api.make_desc(4096, 4096, 4, 32, 0, 0.0)
-    assert api.workspace_bytes(d0, 4096, api.OP_FORWARD) == 0
+    assert 4096 * 8 <= api.workspace_bytes(d0, 4096, api.OP_FORWARD) < f
+    assert 4096 * 8 <= api.workspace_bytes(d0, 4096, api.OP_BACKWARD) < b
     assert api.packed_bytes(api.make_desc(4096, 4096, 7, 32)) == 0
 
 
@@ -80,6 +81,7 @@ def test_argument_errors_are_caught_before_launch(lib):
     assert lib.qalora_forward(ref, 64, P(good), P(good), P(good), P(good), P(good), None, P(good), 0, None, 0, None) == api.EINVAL
     assert lib.qalora_forward(ref, 64, P(good), P(good), P(good), P(good), None, None, P(good), 7, None, 0, None) == api.EINVAL
     assert lib.qalora_forward(ref, 64, P(odd), P(good), P(good), P(good), None, None, P(good), 0, None, 0, None) == api.EALIGN
+    assert lib.qalora_forward(ref, 64, P(good), P(good), P(good), P(good), None, None, P(good), 0, None, 0, None) == api.EWORKSPACE
     assert lib.qalora_forward(ref, 64, P(good), P(good), P(good), P(good), P(good), P(good), P(good), 0, None, 0, None) == api.EWORKSPACE
     assert lib.qalora_forward(ref, 64, P(good), P(good), P(good), P(good), P(good), P(good), P(good), 0, P(good), 64, None) == api.EWORKSPACE
     assert lib.qalora_backward(ref, 64, None, P(good), P(good), P(good), P(good), None, None, P(good), 0, None, None, 0, None, 0, None) == api.EINVAL
