@@ -144,6 +144,21 @@ int qalora_backward(const qalora_desc* desc, int tokens, const void* dy, const v
 int qalora_merge(const qalora_desc* desc, const float* beta, const float* A, const float* B,
                  float* beta_out, void* stream);
 
+/* Measurement aid (used by the benchmark, not part of the layer): arm a pair of HIP events
+ * (hipEvent_t passed as void*, created by the caller with timing enabled).  The next dense
+ * contraction kernel of the given direction (0 = the y = x W~ kernel of qalora_forward,
+ * 1 = the dx = dy W~^T kernel of qalora_backward) launched by this process records `start`
+ * right before and `stop` right after itself on its stream, then disarms.  Passing NULLs
+ * disarms.  Process-wide and not thread safe; returns QALORA_EINVAL for a bad direction. */
+int qalora_profile_arm(int direction, void* start_event, void* stop_event);
+
+/* Create / time / destroy timing events for qalora_profile_arm (thin wrappers over
+ * hipEventCreate, hipEventElapsedTime, hipEventDestroy so that a caller without HIP
+ * headers can use the aid).  elapsed_ms requires both events to have completed. */
+int qalora_profile_event_create(void** event);
+int qalora_profile_event_elapsed_ms(void* start_event, void* stop_event, float* ms);
+int qalora_profile_event_destroy(void* event);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,8 @@ OP_QUANTIZE, OP_FORWARD, OP_BACKWARD, OP_MERGE = 0, 1, 2, 3
 EXPORTS = (
     "qalora_status_string", "qalora_check_desc", "qalora_packed_bytes", "qalora_workspace_bytes",
     "qalora_quantize", "qalora_unpack", "qalora_pack", "qalora_forward", "qalora_backward",
-    "qalora_merge",
+    "qalora_merge", "qalora_profile_arm", "qalora_profile_event_create",
+    "qalora_profile_event_elapsed_ms", "qalora_profile_event_destroy",
 )
 
 
@@ -65,6 +66,10 @@ def load() -> ctypes.CDLL:
     lib.qalora_forward.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
     lib.qalora_backward.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, vp, i, vp, vp, i, vp, sz, vp]
     lib.qalora_merge.argtypes = [cp, vp, vp, vp, vp, vp]
+    lib.qalora_profile_arm.argtypes = [i, vp, vp]
+    lib.qalora_profile_event_create.argtypes = [ctypes.POINTER(vp)]
+    lib.qalora_profile_event_elapsed_ms.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float)]
+    lib.qalora_profile_event_destroy.argtypes = [vp]
     _lib = lib
     return lib
 
@@ -178,3 +183,37 @@ def merge(desc: Desc, beta, A, B, out=None):
     _check(load().qalora_merge(ctypes.byref(desc), _p(beta), _p(A), _p(B), _p(out), _stream()),
            "qalora_merge")
     return out
+
+
+class KernelTimer:
+    """HIP-event pairs recorded by the library around its dense-contraction kernel
+    (measurement aid of the C ABI); ``direction`` 0 = forward kernel, 1 = backward kernel."""
+
+    def __init__(self, direction: int, n: int):
+        self.direction = direction
+        self.pairs = []
+        for _ in range(n):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            _check(load().qalora_profile_event_create(ctypes.byref(a)), "event_create")
+            _check(load().qalora_profile_event_create(ctypes.byref(b)), "event_create")
+            self.pairs.append((a, b))
+        self.used = 0
+
+    def arm(self):
+        a, b = self.pairs[self.used]
+        self.used += 1
+        _check(load().qalora_profile_arm(self.direction, a, b), "profile_arm")
+
+    def elapsed_ms(self):
+        out = []
+        for a, b in self.pairs[: self.used]:
+            ms = ctypes.c_float()
+            _check(load().qalora_profile_event_elapsed_ms(a, b, ctypes.byref(ms)), "event_elapsed")
+            out.append(ms.value)
+        return out
+
+    def close(self):
+        for a, b in self.pairs:
+            load().qalora_profile_event_destroy(a)
+            load().qalora_profile_event_destroy(b)
+        self.pairs = []

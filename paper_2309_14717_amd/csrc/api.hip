@@ -341,4 +341,32 @@ int qalora_merge(const qalora_desc* d, const float* beta, const float* A, const 
              : QALORA_EHIP;
 }
 
+int qalora_profile_arm(int direction, void* start_event, void* stop_event) {
+  if (direction != 0 && direction != 1) return QALORA_EINVAL;
+  g_profile_hook[direction] =
+      ProfileHook{static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event)};
+  return QALORA_OK;
+}
+
+int qalora_profile_event_create(void** event) {
+  if (!event) return QALORA_EINVAL;
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return QALORA_EHIP;
+  *event = e;
+  return QALORA_OK;
+}
+
+int qalora_profile_event_elapsed_ms(void* start_event, void* stop_event, float* ms) {
+  if (!start_event || !stop_event || !ms) return QALORA_EINVAL;
+  return hipEventElapsedTime(ms, static_cast<hipEvent_t>(start_event),
+                             static_cast<hipEvent_t>(stop_event)) == hipSuccess
+             ? QALORA_OK
+             : QALORA_EHIP;
+}
+
+int qalora_profile_event_destroy(void* event) {
+  if (!event) return QALORA_EINVAL;
+  return hipEventDestroy(static_cast<hipEvent_t>(event)) == hipSuccess ? QALORA_OK : QALORA_EHIP;
+}
+
 }  // extern "C"

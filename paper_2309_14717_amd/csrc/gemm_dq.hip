@@ -345,10 +345,21 @@ static hipError_t launch_dir(const GemmArgs& a, hipStream_t st) {
   return launch_cfg<NBITS, BWD, 64, 256, 1, 4, true>(a, 1, st);
 }
 
-hipError_t launch_gemm_dq(int bits, bool bwd, const GemmArgs& a, hipStream_t st) {
+ProfileHook g_profile_hook[2] = {{nullptr, nullptr}, {nullptr, nullptr}};
+
+static hipError_t launch_bits(int bits, bool bwd, const GemmArgs& a, hipStream_t st) {
   if (bits == 4) return bwd ? launch_dir<4, true>(a, st) : launch_dir<4, false>(a, st);
   if (bits == 3) return bwd ? launch_dir<3, true>(a, st) : launch_dir<3, false>(a, st);
   return bwd ? launch_dir<2, true>(a, st) : launch_dir<2, false>(a, st);
+}
+
+hipError_t launch_gemm_dq(int bits, bool bwd, const GemmArgs& a, hipStream_t st) {
+  ProfileHook hook = g_profile_hook[bwd ? 1 : 0];
+  g_profile_hook[bwd ? 1 : 0] = ProfileHook{nullptr, nullptr};
+  if (hook.start) (void)hipEventRecord(hook.start, st);
+  const hipError_t e = launch_bits(bits, bwd, a, st);
+  if (hook.stop) (void)hipEventRecord(hook.stop, st);
+  return e;
 }
 
 // Plain bf16 x bf16^T product  out[z][M][N] = a_tail[M, Kz] . b_tail[N, Kz]^T  with the K

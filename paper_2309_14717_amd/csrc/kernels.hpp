@@ -35,6 +35,11 @@ struct GemmArgs {
   int d_in, d_out, group;
 };
 hipError_t launch_gemm_dq(int bits, bool bwd, const GemmArgs& a, hipStream_t st);
+// Measurement aid: events recorded around the next launch_gemm_dq of each direction.
+struct ProfileHook {
+  hipEvent_t start, stop;
+};
+extern ProfileHook g_profile_hook[2];
 hipError_t launch_gemm_plain(const GemmArgs& a, int ksplit, hipStream_t st);
 
 // --- adapter.hip --------------------------------------------------------------------
