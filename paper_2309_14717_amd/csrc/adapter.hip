@@ -38,21 +38,43 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
   return v;
 }
 
-// One wavefront per row.
-__global__ __launch_bounds__(256) void row_scale_kernel(const uint16_t* __restrict__ a, int rows,
-                                                        int cols, float2* __restrict__ rs) {
+// 8 bf16 -> 8 fp16 after scaling by `sc` (a power of two chosen so nothing overflows; exact
+// unless an element is more than 2^31 below the row maximum).
+__device__ __forceinline__ uint4 bf16x8_to_f16x8_scaled(uint4 v, float sc) {
+  uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const f32x2 f = {__uint_as_float(w[e] << 16) * sc, __uint_as_float(w[e] & 0xffff0000u) * sc};
+    w[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, f16x2));
+  }
+  return uint4{w[0], w[1], w[2], w[3]};
+}
+
+// a bf16 [rows, cols] -> a16 fp16 [rows, cols] = a * rs[row].x, and rs.  One wavefront per
+// row: a first sweep finds the row maximum, a second (served by L2) converts.
+__global__ __launch_bounds__(256) void convert_rows_kernel(const uint16_t* __restrict__ a,
+                                                           int rows, int cols,
+                                                           float2* __restrict__ rs,
+                                                           uint16_t* __restrict__ a16) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
+  const uint16_t* src = a + (size_t)row * cols;
   uint32_t m = 0;
   for (int ch = lane; ch < cols / 8; ch += 64)
-    m = max_abs_bits(*reinterpret_cast<const uint4*>(a + (size_t)row * cols + 8 * ch), m);
+    m = max_abs_bits(*reinterpret_cast<const uint4*>(src + 8 * ch), m);
   m = wave_max_u32(m);
-  if (lane == 0) rs[row] = scale_from_maxbits(m);
+  const float2 sc = scale_from_maxbits(m);
+  if (lane == 0) rs[row] = sc;
+  uint16_t* dst = a16 + (size_t)row * cols;
+  for (int ch = lane; ch < cols / 8; ch += 64)
+    *reinterpret_cast<uint4*>(dst + 8 * ch) =
+        bf16x8_to_f16x8_scaled(*reinterpret_cast<const uint4*>(src + 8 * ch), sc.x);
 }
 
-hipError_t launch_row_scale(const uint16_t* a, int rows, int cols, float2* rs, hipStream_t st) {
-  row_scale_kernel<<<ceil_div(rows, 4), 256, 0, st>>>(a, rows, cols, rs);
+hipError_t launch_convert_rows(const uint16_t* a, int rows, int cols, float2* rs, uint16_t* a16,
+                               hipStream_t st) {
+  convert_rows_kernel<<<ceil_div(rows, 4), 256, 0, st>>>(a, rows, cols, rs, a16);
   return hipGetLastError();
 }
 
@@ -69,6 +91,7 @@ __global__ __launch_bounds__(256) void pool_down_kernel(const uint16_t* __restri
                                                         int T, int d_in, int g, int rank,
                                                         float* __restrict__ P_out,
                                                         float2* __restrict__ rs_out,
+                                                        uint16_t* __restrict__ x16,
                                                         uint16_t* __restrict__ u_ext, int ktail,
                                                         uint16_t* __restrict__ us_t, int t_pad) {
   extern __shared__ float P_s[];  // [POOL_TB][L]
@@ -103,10 +126,15 @@ __global__ __launch_bounds__(256) void pool_down_kernel(const uint16_t* __restri
       }
     }
     amax = wave_max_u32(amax);
+    const float2 sc = scale_from_maxbits(amax);
     if (lane == 0) {
-      const float2 sc = scale_from_maxbits(amax);
       sc_s[tt] = sc.x;
       if (rs_out && t < T) rs_out[t] = sc;
+    }
+    if (x16 && t < T) {  // second sweep over the row (L2): scaled fp16 copy for the matrix cores
+      for (int ch = lane; ch < nchunks; ch += 64)
+        *reinterpret_cast<uint4*>(x16 + (size_t)t * d_in + 8 * ch) = bf16x8_to_f16x8_scaled(
+            *reinterpret_cast<const uint4*>(x + (size_t)t * d_in + 8 * ch), sc.x);
     }
   }
   if (!butterfly) {
@@ -166,8 +194,9 @@ __global__ void fill_zero_kernel(uint4* __restrict__ p, size_t n16) {
 }
 
 hipError_t launch_pool_down(const uint16_t* x, const float* A, float s, int T, int d_in, int g,
-                            int rank, float* P_out, float2* rs_out, uint16_t* u_ext, int ktail,
-                            uint16_t* us_t, int t_pad, hipStream_t st) {
+                            int rank, float* P_out, float2* rs_out, uint16_t* x16,
+                            uint16_t* u_ext, int ktail, uint16_t* us_t, int t_pad,
+                            hipStream_t st) {
   const int L = d_in / g;
   const size_t smem = (size_t)POOL_TB * L * sizeof(float);
   static size_t smem_limit = 48 * 1024;
@@ -184,8 +213,8 @@ hipError_t launch_pool_down(const uint16_t* x, const float* A, float s, int T, i
     fill_zero_kernel<<<(int)(nblk < 1024 ? nblk : 1024), 256, 0, st>>>(
         reinterpret_cast<uint4*>(us_t), n16);
   }
-  pool_down_kernel<<<ceil_div(T, POOL_TB), 256, smem, st>>>(x, A, s, T, d_in, g, rank, P_out,
-                                                            rs_out, u_ext, ktail, us_t, t_pad);
+  pool_down_kernel<<<ceil_div(T, POOL_TB), 256, smem, st>>>(
+      x, A, s, T, d_in, g, rank, P_out, rs_out, x16, u_ext, ktail, us_t, t_pad);
   return hipGetLastError();
 }
 

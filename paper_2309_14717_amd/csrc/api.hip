@@ -19,11 +19,11 @@ int row_align_for_bits(int bits) { return bits == 4 ? 8 : (bits == 2 ? 16 : 32);
 // the compute call always agree.
 struct FwdPlan {
   int ktail;
-  size_t rs, u_ext, b_ext_t, total;
+  size_t rs, a16, u_ext, b_ext_t, total;
 };
 struct BwdPlan {
   int ktail, rp, t_pad, ksplit, tsplit_b, tsplit_a;
-  size_t rs, P, us_t, b_hl, a_ext_t, du_raw, dU, du_ext, db_part, da_part, total;
+  size_t rs, a16, P, us_t, b_hl, a_ext_t, du_raw, dU, du_ext, db_part, da_part, total;
 };
 
 FwdPlan plan_forward(const qalora_desc& d, int T) {
@@ -32,6 +32,8 @@ FwdPlan plan_forward(const qalora_desc& d, int T) {
   size_t off = 0;
   p.rs = off;
   off += align_up((size_t)T * sizeof(float2));
+  p.a16 = off;
+  off += align_up((size_t)T * d.d_in * 2);
   if (d.rank > 0) {
     p.u_ext = off;
     off += align_up((size_t)T * p.ktail * 2);
@@ -48,9 +50,10 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
   p.ktail = adapter_ktail(d.rank);
   p.rp = rank_pad32(d.rank);
   p.t_pad = round_up(T, 64);
-  if (d.rank <= 0) {  // adapter-free: only the row scales of dy
+  if (d.rank <= 0) {  // adapter-free: only the row scales and the fp16 copy of dy
     p.rs = 0;
-    p.total = align_up((size_t)T * sizeof(float2));
+    p.a16 = align_up((size_t)T * sizeof(float2));
+    p.total = p.a16 + align_up((size_t)T * d.d_out * 2);
     return p;
   }
   // dU product: [T, 2rp] output tiles of 64 x 128; split K = d_out to fill the chip.
@@ -82,6 +85,7 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
     return o;
   };
   p.rs = take((size_t)T * sizeof(float2));
+  p.a16 = take((size_t)T * d.d_out * 2);
   p.P = take((size_t)T * L * 4);
   p.us_t = take((size_t)2 * p.rp * p.t_pad * 2);
   p.b_hl = take((size_t)2 * p.rp * d.d_out * 2);
@@ -185,14 +189,15 @@ int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* 
     return QALORA_EALIGN;
   const bool adapter = A && B && d->rank > 0;
   FwdPlan plan = plan_forward(*d, tokens);
-  if (!adapter) plan.total = align_up((size_t)tokens * sizeof(float2));
+  if (!adapter) plan.total = plan.a16 + align_up((size_t)tokens * d->d_in * 2);
   if (!ws || ws_bytes < plan.total) return QALORA_EWORKSPACE;
   hipStream_t st = as_stream(stream);
   char* w = static_cast<char*>(ws);
   float2* rs = reinterpret_cast<float2*>(w + plan.rs);
+  uint16_t* x16 = reinterpret_cast<uint16_t*>(w + plan.a16);
 
   GemmArgs g{};
-  g.a_main = static_cast<const uint16_t*>(x);
+  g.a_main = x16;
   g.lda_main = d->d_in;
   g.plane0 = static_cast<const uint32_t*>(packed);
   g.plane1 = g.plane0 + plane0_words(d->bits, d->d_in, d->d_out);
@@ -208,13 +213,14 @@ int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* 
   g.group = d->group;
   g.row_scale = rs;
   if (!adapter) {
-    if (launch_row_scale(static_cast<const uint16_t*>(x), tokens, d->d_in, rs, st) != hipSuccess)
+    if (launch_convert_rows(static_cast<const uint16_t*>(x), tokens, d->d_in, rs, x16, st) !=
+        hipSuccess)
       return QALORA_EHIP;
   } else {
     uint16_t* u_ext = reinterpret_cast<uint16_t*>(w + plan.u_ext);
     uint16_t* b_ext_t = reinterpret_cast<uint16_t*>(w + plan.b_ext_t);
     if (launch_pool_down(static_cast<const uint16_t*>(x), A, d->s, tokens, d->d_in, d->group,
-                         d->rank, nullptr, rs, u_ext, plan.ktail, nullptr, 0, st) != hipSuccess)
+                         d->rank, nullptr, rs, x16, u_ext, plan.ktail, nullptr, 0, st) != hipSuccess)
       return QALORA_EHIP;
     if (launch_prep_b_fwd(B, d->rank, d->d_out, b_ext_t, plan.ktail, st) != hipSuccess)
       return QALORA_EHIP;
@@ -243,14 +249,19 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
       misaligned(dB) || misaligned(ws))
     return QALORA_EALIGN;
   BwdPlan plan = plan_backward(*d, tokens);
-  if (!adapter) plan.total = align_up((size_t)tokens * sizeof(float2));
+  if (!adapter) {
+    plan.rs = 0;
+    plan.a16 = align_up((size_t)tokens * sizeof(float2));
+    plan.total = plan.a16 + align_up((size_t)tokens * d->d_out * 2);
+  }
   if (!ws || ws_bytes < plan.total) return QALORA_EWORKSPACE;
   hipStream_t st = as_stream(stream);
   char* w = static_cast<char*>(ws);
   const int L = d->d_in / d->group;
-  const uint16_t* dy16 = static_cast<const uint16_t*>(dy);
+  const uint16_t* dy16 = static_cast<const uint16_t*>(dy);  // bf16 bits
   float2* rs = reinterpret_cast<float2*>(w + plan.rs);
-  if (launch_row_scale(dy16, tokens, d->d_out, rs, st) != hipSuccess) return QALORA_EHIP;
+  uint16_t* dyh = reinterpret_cast<uint16_t*>(w + plan.a16);  // fp16 scaled copy of dy
+  if (launch_convert_rows(dy16, tokens, d->d_out, rs, dyh, st) != hipSuccess) return QALORA_EHIP;
 
   uint16_t* du_ext = nullptr;
   uint16_t* a_ext_t = nullptr;
@@ -267,7 +278,8 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
 
     // P = pool(x), sU = s P A (transposed hi/lo for the dB product)
     if (launch_pool_down(static_cast<const uint16_t*>(x), A, d->s, tokens, d->d_in, d->group,
-                         d->rank, P, nullptr, nullptr, 0, us_t, plan.t_pad, st) != hipSuccess)
+                         d->rank, P, nullptr, nullptr, nullptr, 0, us_t, plan.t_pad, st) !=
+        hipSuccess)
       return QALORA_EHIP;
     if (launch_prep_bwd(A, B, L, d->rank, d->d_out, d->group, b_hl, a_ext_t, plan.ktail, st) !=
         hipSuccess)
@@ -302,7 +314,7 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
   }
   if (dx) {
     GemmArgs g{};
-    g.a_main = dy16;
+    g.a_main = dyh;
     g.lda_main = d->d_out;
     g.plane0 = static_cast<const uint32_t*>(packed);
     g.plane1 = g.plane0 + plane0_words(d->bits, d->d_in, d->d_out);

@@ -16,7 +16,8 @@ void launch_pack(int bits, const uint8_t* codes, void* packed, int d_in, int d_o
 
 // --- gemm_dq.hip --------------------------------------------------------------------
 struct GemmArgs {
-  const uint16_t* a_main;  // bf16 [M, K_main]: x (forward) or dy (backward)
+  const uint16_t* a_main;  // fp16 [M, K_main]: x (forward) or dy (backward), each row already
+                           // multiplied by its power-of-two row scale
   int lda_main;
   const uint16_t* a_tail;  // bf16 [M, K_tail]: hi/lo split of s*U (forward) or dU (backward),
                            // each row pre-multiplied by its row scale
@@ -50,14 +51,17 @@ __host__ __device__ inline int adapter_ktail(int rank) { return rank > 0 ? ((3 *
 __host__ __device__ inline int rank_pad32(int rank) { return ((rank + 31) / 32) * 32; }
 
 // x -> P = pool_g(x) (optional, fp32 [T, L]) and U = P A, written as
-//   rs_out  [T] row scales of x (optional),
+//   rs_out  [T] row scales of x and x16 fp16 [T, d_in] = x * row scale (both optional),
 //   u_ext   bf16 [T, ktail]      = [hi | lo | hi | 0] of sU * row scale (forward tail operand), and/or
 //   us_t    bf16 [2*rp, t_pad]   = rows hi(sU)^T then lo(sU)^T      (dB operand, t contiguous)
 hipError_t launch_pool_down(const uint16_t* x, const float* A, float s, int T, int d_in, int g,
-                            int rank, float* P_out, float2* rs_out, uint16_t* u_ext, int ktail,
-                            uint16_t* us_t, int t_pad, hipStream_t st);
-// rs[row] = (2^(14-e), 2^(e-14)), e = exponent of the largest |a[row, :]| (bf16 [rows, cols])
-hipError_t launch_row_scale(const uint16_t* a, int rows, int cols, float2* rs, hipStream_t st);
+                            int rank, float* P_out, float2* rs_out, uint16_t* x16,
+                            uint16_t* u_ext, int ktail, uint16_t* us_t, int t_pad,
+                            hipStream_t st);
+// rs[row] = (2^(14-e), 2^(e-14)), e = exponent of the largest |a[row, :]| (bf16 [rows, cols]);
+// a16 = fp16(a * rs[row].x), exact
+hipError_t launch_convert_rows(const uint16_t* a, int rows, int cols, float2* rs, uint16_t* a16,
+                               hipStream_t st);
 // B fp32 [rank, d_out] -> b_ext_t bf16 [d_out, ktail] = [hi | hi | lo | 0] per output column
 hipError_t launch_prep_b_fwd(const float* B, int rank, int d_out, uint16_t* b_ext_t, int ktail,
                              hipStream_t st);
