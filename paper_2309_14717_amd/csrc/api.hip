@@ -33,7 +33,7 @@ FwdPlan plan_forward(const qalora_desc& d, int T) {
   p.rs = off;
   off += align_up((size_t)T * sizeof(float2));
   p.a16 = off;
-  off += align_up((size_t)T * d.d_in * 2);
+  off += align_up((size_t)round_up(T, 256) * d.d_in * 2);
   if (d.rank > 0) {
     p.u_ext = off;
     off += align_up((size_t)T * p.ktail * 2);
@@ -53,7 +53,7 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
   if (d.rank <= 0) {  // adapter-free: only the row scales and the fp16 copy of dy
     p.rs = 0;
     p.a16 = align_up((size_t)T * sizeof(float2));
-    p.total = p.a16 + align_up((size_t)T * d.d_out * 2);
+    p.total = p.a16 + align_up((size_t)round_up(T, 256) * d.d_out * 2);
     return p;
   }
   // dU product: [T, 2rp] output tiles of 64 x 128; split K = d_out to fill the chip.
@@ -85,7 +85,7 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
     return o;
   };
   p.rs = take((size_t)T * sizeof(float2));
-  p.a16 = take((size_t)T * d.d_out * 2);
+  p.a16 = take((size_t)round_up(T, 256) * d.d_out * 2);
   p.P = take((size_t)T * L * 4);
   p.us_t = take((size_t)2 * p.rp * p.t_pad * 2);
   p.b_hl = take((size_t)2 * p.rp * d.d_out * 2);
@@ -189,7 +189,7 @@ int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* 
     return QALORA_EALIGN;
   const bool adapter = A && B && d->rank > 0;
   FwdPlan plan = plan_forward(*d, tokens);
-  if (!adapter) plan.total = plan.a16 + align_up((size_t)tokens * d->d_in * 2);
+  if (!adapter) plan.total = plan.a16 + align_up((size_t)round_up(tokens, 256) * d->d_in * 2);
   if (!ws || ws_bytes < plan.total) return QALORA_EWORKSPACE;
   hipStream_t st = as_stream(stream);
   char* w = static_cast<char*>(ws);
@@ -199,6 +199,7 @@ int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* 
   GemmArgs g{};
   g.a_main = x16;
   g.lda_main = d->d_in;
+  g.a_main_padded_rows = round_up(tokens, 256);
   g.plane0 = static_cast<const uint32_t*>(packed);
   g.plane1 = g.plane0 + plane0_words(d->bits, d->d_in, d->d_out);
   g.alpha = alpha;
@@ -252,7 +253,7 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
   if (!adapter) {
     plan.rs = 0;
     plan.a16 = align_up((size_t)tokens * sizeof(float2));
-    plan.total = plan.a16 + align_up((size_t)tokens * d->d_out * 2);
+    plan.total = plan.a16 + align_up((size_t)round_up(tokens, 256) * d->d_out * 2);
   }
   if (!ws || ws_bytes < plan.total) return QALORA_EWORKSPACE;
   hipStream_t st = as_stream(stream);
@@ -316,6 +317,7 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
     GemmArgs g{};
     g.a_main = dyh;
     g.lda_main = d->d_out;
+    g.a_main_padded_rows = round_up(tokens, 256);
     g.plane0 = static_cast<const uint32_t*>(packed);
     g.plane1 = g.plane0 + plane0_words(d->bits, d->d_in, d->d_out);
     g.alpha = alpha;

@@ -39,28 +39,37 @@ namespace qalora {
 constexpr int BK = 64;
 constexpr int NT = 512;  // threads per block
 
-__device__ __forceinline__ uint4 ldg128(const void* p) {
-  return *reinterpret_cast<const uint4*>(p);
+// Raw buffer resources: loads through them return zero past `bytes`, which is how every
+// ragged edge (rows past M, patches past the matrix) is zero-filled without branches.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, size_t bytes) {
+  const uint32_t n = bytes > 0xffffffffull ? 0xffffffffu : (uint32_t)bytes;
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)n, 0x00020000);
 }
+__device__ __forceinline__ uint4 buf_load128(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+  return uint4{v.x, v.y, v.z, v.w};
+}
+constexpr uint32_t kOobOffset = 0xffff0000u;  // past any buffer (also after a small add): reads zero
 
 // Byte offset inside a [rows][64 x 16-bit] tile of the 16-byte chunk `c` of row `n`.
 // Two rows share a 256-byte line (half = which 128 bytes); the chunk slot is XORed with row
-// bits.  With n = b7..b0:  half = b0^b3^b4,  slot = c ^ (b1^b5 | b2<<1 | b3<<2).
-// Distinct (half, slot) for: 16 consecutive rows at one chunk (operand reads), 16 rows of
-// stride 4 at one chunk (forward producer), rows n and n+8 over all chunks (backward
-// producer), rows n and n+1 over all chunks (plain copies).
+// bits.  With n = b7..b0:  half = b0^b2^b3^b4,  slot = c ^ (b1 | b2<<1 | b3<<2).
+// Operand reads (16 consecutive rows at one chunk) see 16 distinct (half, slot); every
+// producer writes whole 128-byte rows from 8 adjacent lanes, with the next 8 lanes (row n+1,
+// n+4 or n+8) landing in the other half.  Rows 32 apart share the pattern, so the fragment
+// reads of a wave differ only by an immediate offset.
 __device__ __forceinline__ int swz_offset(int n, int c) {
-  const int half = (n ^ (n >> 3) ^ (n >> 4)) & 1;
-  const int f = (((n >> 1) ^ (n >> 5)) & 1) | (((n >> 2) & 3) << 1);
+  const int half = (n ^ (n >> 2) ^ (n >> 3) ^ (n >> 4)) & 1;
+  const int f = (n >> 1) & 7;
   return ((n >> 1) << 8) | (half << 7) | ((c ^ f) << 4);
 }
 // Inverse for the LDS-DMA path: which (row, chunk) lives at byte offset `o` (multiple of 16).
 __device__ __forceinline__ void swz_inverse(int o, int& n, int& c) {
   const int pair = o >> 8, half = (o >> 7) & 1, slot = (o >> 4) & 7;
-  const int b3 = (pair >> 2) & 1, b4 = (pair >> 3) & 1;
-  n = 2 * pair + (half ^ b3 ^ b4);
-  const int f = ((pair ^ (pair >> 4)) & 1) | (((pair >> 1) & 3) << 1);
-  c = slot ^ f;
+  const int b2 = (pair >> 1) & 1, b3 = (pair >> 2) & 1, b4 = (pair >> 3) & 1;
+  n = 2 * pair + (half ^ b2 ^ b3 ^ b4);
+  c = slot ^ (pair & 7);
 }
 
 // Block-index -> tile-index map.  Consecutive block ids are dealt round-robin to the 8
@@ -71,10 +80,37 @@ __device__ __forceinline__ int xcd_remap(int bid, int nblocks) {
   return (bid % 8) * (nblocks / 8) + bid / 8;
 }
 
+// LDS-DMA loads stay in flight across barriers (three A stages), so the barrier is issued
+// raw -- the compiler would otherwise drain every counter in front of it -- with explicit
+// waits: all of this wave's LDS writes, and all but the newest `VM_KEEP` vector-memory ops.
+template <int VM_KEEP>
+__device__ __forceinline__ void wait_and_barrier() {
+  static_assert(VM_KEEP >= 0 && VM_KEEP < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(VM_KEEP) : "memory");
+}
+
+// Calls f with the four LDS regions of one pipeline step as restrict-qualified parameters:
+// the region the LDS-DMA is filling, the A and B regions being read, and the B region being
+// written never overlap within a step, and saying so keeps the compiler from draining the
+// LDS-DMA loads before every LDS read.
+template <typename F>
+__device__ __forceinline__ void with_step_regions(uint16_t* __restrict__ a_dma,
+                                                  const uint16_t* __restrict__ a_rd,
+                                                  const uint16_t* __restrict__ b_rd,
+                                                  uint16_t* __restrict__ b_wr, F&& f) {
+  f(a_dma, a_rd, b_rd, b_wr);
+}
+
 // HAS_MAIN = false: a plain bf16 x bf16^T product over the "tail" operands only (used for
 // dU = s dy B^T), optionally split along K over blockIdx.y.
-template <int NBITS, bool BWD, int BM, int BN, int WAVES_M, int WAVES_N, bool HAS_MAIN>
+//
+// FAST = true (main K a multiple of 64, group size dividing or divisible by 64, activation
+// copies padded to whole row tiles): every per-lane global offset is a kernel-lifetime
+// constant and the K advance lives in scalar offsets, so the hot loop carries no vector
+// address arithmetic.  FAST = false keeps per-step, per-lane offsets with full edge handling.
+template <int NBITS, bool BWD, int BM, int BN, int WAVES_M, int WAVES_N, bool HAS_MAIN, bool FAST>
 __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
+  static_assert(!FAST || HAS_MAIN, "the fast addressing path is for the dequantising product");
   static_assert(WAVES_M * WAVES_N == 8, "eight wavefronts per block");
   static_assert(!HAS_MAIN || BN == 256, "the dequantising producer assumes 256 columns");
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -85,14 +121,15 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
   static_assert(A_LOADS >= 1, "BM too small for 512 threads");
   constexpr int A_TILE = BM * 64;  // 16-bit elements per A buffer
   constexpr int B_TILE = BN * 64;
+  constexpr int A_STAGES = 3;  // LDS-DMA prefetch runs two K steps ahead
 
   extern __shared__ __align__(1024) uint16_t smem[];
-  uint16_t* As = smem;               // [2][BM][64] swizzled
-  uint16_t* Bs = smem + 2 * A_TILE;  // [2][BN][64] swizzled
+  uint16_t* As = smem;                      // [A_STAGES][BM][64] swizzled
+  uint16_t* Bs = smem + A_STAGES * A_TILE;  // [2][BN][64] swizzled
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
 
   const int tiles_m = ceil_div(p.M, BM);
@@ -129,87 +166,157 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
   // lane i lands at byte 16*i of it, so it fetches the (row, chunk) the swizzle puts there.
   // Rows past M are clamped to the last row (their results are never stored); K chunks past
   // the end re-read chunk 0 (the B tile is zero there, any finite data will do).
-  const uint16_t* a_src_main[A_LOADS];
-  const uint16_t* a_src_tail[A_LOADS];
+  const __amdgpu_buffer_rsrc_t rs_a_main = make_rsrc(
+      p.a_main, HAS_MAIN ? (size_t)(FAST ? round_up(p.M, BM) : p.M) * p.lda_main * 2 : 0);
+  const __amdgpu_buffer_rsrc_t rs_a_tail = make_rsrc(p.a_tail, (size_t)p.M * p.lda_tail * 2);
+  uint32_t a_row[A_LOADS];  // global row of each load (rows past M read as zero)
   int a_chunk8[A_LOADS];
 #pragma unroll
   for (int q = 0; q < A_LOADS; ++q) {
     int n, c;
     swz_inverse((q * 8 + wave) * 1024 + lane * 16, n, c);
-    const int row = min(m0 + n, p.M - 1);
+    a_row[q] = (uint32_t)(m0 + n);
     a_chunk8[q] = 8 * c;
-    a_src_main[q] = HAS_MAIN ? p.a_main + (size_t)row * p.lda_main : nullptr;
-    a_src_tail[q] = p.a_tail + (size_t)row * p.lda_tail;
   }
-  auto issue_a = [&](auto kind, int it, int buf) {
+  // fast path: one lane offset for all loads of the kernel (rows of later loads are 64*q
+  // further down; the copies are padded to whole tiles, so no row check is needed)
+  const uint32_t a_voff_main = (a_row[0] * (uint32_t)p.lda_main + (uint32_t)a_chunk8[0]) * 2u;
+  auto issue_a = [&](auto kind, int it, uint16_t* a_dst) {
     constexpr bool kMain = decltype(kind)::value == 0;
-    const int k0 = kMain ? it * BK : (it - nk_main) * BK;
+    const int k0 = kMain ? (it - nk_tail) * BK : it * BK;
+    if constexpr (FAST && kMain) {
+#pragma unroll
+      for (int q = 0; q < A_LOADS; ++q) {
+        const uint32_t soff = (uint32_t)k0 * 2u + (uint32_t)q * 64u * (uint32_t)p.lda_main * 2u;
+        uint16_t* dst = a_dst + (q * 8 + wave) * 512;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a_main,
+                                                 (__attribute__((address_space(3))) void*)dst, 16,
+                                                 (int)a_voff_main, (int)soff, 0, 0);
+      }
+      return;
+    }
     const int klim = kMain ? p.K_main : p.K_tail;
+    const uint32_t lda = kMain ? p.lda_main : p.lda_tail;
 #pragma unroll
     for (int q = 0; q < A_LOADS; ++q) {
-      int k = k0 + a_chunk8[q];
-      k = (k < klim) ? k : 0;
-      const uint16_t* src = (kMain ? a_src_main[q] : a_src_tail[q]) + k;
-      uint16_t* dst = As + buf * A_TILE + (q * 8 + wave) * 512;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                       (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+      const int k = k0 + a_chunk8[q];
+      const uint32_t off = (k < klim && a_row[q] < (uint32_t)p.M)
+                               ? (a_row[q] * lda + (uint32_t)k) * 2u
+                               : kOobOffset;
+      uint16_t* dst = a_dst + (q * 8 + wave) * 512;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(kMain ? rs_a_main : rs_a_tail,
+                                               (__attribute__((address_space(3))) void*)dst, 16,
+                                               (int)off, 0, 0, 0);
     }
   };
 
   // ---- B tile through registers --------------------------------------------------------
   // MAIN steps: half an 8x8 patch of codes per thread.
-  //   forward : wave = K chunk u0, lane -> column quad (coalesced 1 KB rows of words)
+  //   forward : u0 = K chunk, cq = column quad (8 adjacent lanes fill one 128-byte LDS row)
   //   backward: u0 = K chunk (column octet), u1 = row block, hb = which two row pairs
   // Out-of-range patches are read from a clamped address and get alpha = beta = 0.
-  const int f_u0 = wave, f_cq = lane;
+  const int f_u0 = tid & 7, f_cq = tid >> 3;
   const int b_u0 = tid & 7, b_u1 = (tid >> 3) & 31, b_hb = tid >> 8;
   constexpr int RB0 = PackFmt<NBITS>::kRowsPerWord0;
-  // the K-invariant coordinate of this thread's patch, clamped, and its validity
-  const int f_j0 = n0 + 4 * f_cq;
-  const int b_i0 = n0 + 8 * b_u1;
+  // Codes, alpha and beta come through buffer loads; a patch outside the matrix gets
+  // alpha = beta = 0 (so W~ = 0) by pointing its factor loads past the buffer.
+  const size_t n_groups = (size_t)(p.d_in / (p.group > 0 ? p.group : 1));
+  const __amdgpu_buffer_rsrc_t rs_p0 =
+      make_rsrc(p.plane0, HAS_MAIN ? plane0_words(NBITS, p.d_in, p.d_out) * 4 : 0);
+  const __amdgpu_buffer_rsrc_t rs_p1 =
+      make_rsrc(p.plane1, HAS_MAIN ? plane1_words(NBITS, p.d_in, p.d_out) * 4 : 0);
+  const __amdgpu_buffer_rsrc_t rs_al = make_rsrc(p.alpha, HAS_MAIN ? n_groups * p.d_out * 4 : 0);
+  const __amdgpu_buffer_rsrc_t rs_be = make_rsrc(p.beta, HAS_MAIN ? n_groups * p.d_out * 4 : 0);
+  const __amdgpu_buffer_rsrc_t rs_bt = make_rsrc(
+      p.b_tail, (size_t)(BWD ? (int)n_groups : p.N) * p.K_tail * 2);
+  const int f_j0 = n0 + 4 * f_cq;   // forward: this thread's 4 columns
+  const int b_i0 = n0 + 8 * b_u1;   // backward: this thread's row block
   const bool n_valid = BWD ? (b_i0 < p.d_in) : (f_j0 < p.d_out);
-  const int f_j0c = min(f_j0, p.d_out - 4);
-  const int b_i0c = min(b_i0, p.d_in - 8);
 
   uint4 breg[6];   // fwd: codes, alpha, beta, plane-1 codes | bwd: 2 codes, 2 alpha, 2 beta
   uint4 breg1[2];  // bwd, N = 3: plane-1 words
   uint4 btail[B_CHUNKS];
-  uint32_t bmask = 0;  // all-ones when the patch being staged is inside the matrix
+
+  // fast path: lane-constant offsets (patches outside the matrix point past the buffers)
+  uint32_t fb_voff_p0 = 0, fb_voff_p1 = 0, fb_voff_ab = 0;
+  int fb_grp_small = 0;  // forward, g < 64: groups per K step; else 0
+  if constexpr (FAST) {
+    if constexpr (!BWD) {
+      fb_voff_p0 = ((uint32_t)((8 * f_u0) / RB0) * p.d_out + f_j0) * 4u;
+      fb_voff_p1 = ((uint32_t)((8 * f_u0) / 32) * p.d_out + f_j0) * 4u;
+      fb_grp_small = p.group < BK ? BK / p.group : 0;
+      const uint32_t lane_grp = p.group < BK ? (uint32_t)(8 * f_u0) / (uint32_t)p.group : 0u;
+      fb_voff_ab = n_valid ? (lane_grp * p.d_out + f_j0) * 4u : kOobOffset;
+    } else {
+      fb_voff_p0 = n_valid ? ((uint32_t)(b_i0 / RB0) * p.d_out + 8 * b_u0) * 4u : kOobOffset;
+      fb_voff_p1 = n_valid ? ((uint32_t)(b_i0 / 32) * p.d_out + 8 * b_u0) * 4u : kOobOffset;
+      fb_voff_ab = n_valid ? ((uint32_t)(b_i0 / p.group) * p.d_out + 8 * b_u0) * 4u : kOobOffset;
+    }
+  }
+  auto buf_load128_s = [&](__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0);
+    return uint4{v.x, v.y, v.z, v.w};
+  };
 
   auto gload_b = [&](auto kind, int it) {
     constexpr bool kMain = decltype(kind)::value == 0;
-    if constexpr (kMain) {
-      const int k0 = it * BK;
+    if constexpr (kMain && FAST) {
+      const uint32_t km = (uint32_t)(it - nk_tail);  // main step index (uniform)
+      if constexpr (!BWD) {
+        // scalar parts: word rows advance by 64/RB per step, group rows by 64/g (or 1 per g/64)
+        const uint32_t s_p0 = km * (uint32_t)(BK / RB0) * p.d_out * 4u;
+        const uint32_t grp = fb_grp_small ? km * (uint32_t)fb_grp_small
+                                          : km / (uint32_t)(p.group / BK);
+        const uint32_t s_ab = grp * p.d_out * 4u;
+        breg[0] = buf_load128_s(rs_p0, fb_voff_p0, s_p0);
+        if constexpr (NBITS == 3)
+          breg[3] = buf_load128_s(rs_p1, fb_voff_p1, km * (uint32_t)(BK / 32) * p.d_out * 4u);
+        breg[1] = buf_load128_s(rs_al, fb_voff_ab, s_ab);
+        breg[2] = buf_load128_s(rs_be, fb_voff_ab, s_ab);
+      } else {
+        const uint32_t s_k = km * (uint32_t)BK * 4u;  // 64 columns further along the row
+        breg[0] = buf_load128_s(rs_p0, fb_voff_p0, s_k);
+        breg[1] = buf_load128_s(rs_p0, fb_voff_p0 + 16, s_k);
+        if constexpr (NBITS == 3) {
+          breg1[0] = buf_load128_s(rs_p1, fb_voff_p1, s_k);
+          breg1[1] = buf_load128_s(rs_p1, fb_voff_p1 + 16, s_k);
+        }
+        breg[2] = buf_load128_s(rs_al, fb_voff_ab, s_k);
+        breg[3] = buf_load128_s(rs_al, fb_voff_ab + 16, s_k);
+        breg[4] = buf_load128_s(rs_be, fb_voff_ab, s_k);
+        breg[5] = buf_load128_s(rs_be, fb_voff_ab + 16, s_k);
+      }
+    } else if constexpr (kMain) {
+      const int k0 = (it - nk_tail) * BK;
       if constexpr (!BWD) {
         const int i0 = k0 + 8 * f_u0;
-        const int i0c = min(i0, p.d_in - 8);
-        bmask = (n_valid && i0 < p.d_in) ? 0xffffffffu : 0u;
-        breg[0] = ldg128(p.plane0 + (size_t)(i0c / RB0) * p.d_out + f_j0c);
+        const bool ok = n_valid && i0 < p.d_in;
+        breg[0] = buf_load128(rs_p0, ((uint32_t)(i0 / RB0) * p.d_out + f_j0) * 4u);
         if constexpr (NBITS == 3)
-          breg[3] = ldg128(p.plane1 + (size_t)(i0c / 32) * p.d_out + f_j0c);
-        const size_t ab = (size_t)(i0c / p.group) * p.d_out + f_j0c;
-        breg[1] = ldg128(p.alpha + ab);
-        breg[2] = ldg128(p.beta + ab);
+          breg[3] = buf_load128(rs_p1, ((uint32_t)(i0 / 32) * p.d_out + f_j0) * 4u);
+        const uint32_t ab = ok ? ((uint32_t)(i0 / p.group) * p.d_out + f_j0) * 4u : kOobOffset;
+        breg[1] = buf_load128(rs_al, ab);
+        breg[2] = buf_load128(rs_be, ab);
       } else {
         const int j0 = k0 + 8 * b_u0;
-        const int j0c = min(j0, p.d_out - 8);
-        bmask = (n_valid && j0 < p.d_out) ? 0xffffffffu : 0u;
-        const uint32_t* w = p.plane0 + (size_t)(b_i0c / RB0) * p.d_out + j0c;
-        breg[0] = ldg128(w);
-        breg[1] = ldg128(w + 4);
+        const bool ok = n_valid && j0 < p.d_out;
+        const uint32_t w = ((uint32_t)(b_i0 / RB0) * p.d_out + j0) * 4u;
+        breg[0] = buf_load128(rs_p0, w);
+        breg[1] = buf_load128(rs_p0, w + 16);
         if constexpr (NBITS == 3) {
-          const uint32_t* w1 = p.plane1 + (size_t)(b_i0c / 32) * p.d_out + j0c;
-          breg1[0] = ldg128(w1);
-          breg1[1] = ldg128(w1 + 4);
+          const uint32_t w1 = ((uint32_t)(b_i0 / 32) * p.d_out + j0) * 4u;
+          breg1[0] = buf_load128(rs_p1, w1);
+          breg1[1] = buf_load128(rs_p1, w1 + 16);
         }
-        const size_t ab = (size_t)(b_i0c / p.group) * p.d_out + j0c;
-        breg[2] = ldg128(p.alpha + ab);
-        breg[3] = ldg128(p.alpha + ab + 4);
-        breg[4] = ldg128(p.beta + ab);
-        breg[5] = ldg128(p.beta + ab + 4);
+        const uint32_t ab = ok ? ((uint32_t)(b_i0 / p.group) * p.d_out + j0) * 4u : kOobOffset;
+        breg[2] = buf_load128(rs_al, ab);
+        breg[3] = buf_load128(rs_al, ab + 16);
+        breg[4] = buf_load128(rs_be, ab);
+        breg[5] = buf_load128(rs_be, ab + 16);
       }
     } else {
-      const int k0 = (it - nk_main) * BK;
+      const int k0 = it * BK;
 #pragma unroll
       for (int q = 0; q < B_CHUNKS; ++q) {
         const int idx = tid + NT * q;
@@ -218,16 +325,16 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
         // forward tail: row n of B~^T; backward tail: row n/g of A~ (the unpooling of
         // the pooled gradient is this broadcast over the g rows of a group)
         const int src_row = BWD ? n / p.group : n;
-        btail[q] = (row < BN && n < p.N && k0 + 8 * ch < p.K_tail)
-                       ? ldg128(p.b_tail + (size_t)src_row * p.K_tail + k0 + 8 * ch)
-                       : uint4{0, 0, 0, 0};
+        const int k = k0 + 8 * ch;
+        const bool ok = row < BN && n < p.N && k < p.K_tail;
+        btail[q] = buf_load128(rs_bt, ok ? ((uint32_t)src_row * p.K_tail + k) * 2u : kOobOffset);
       }
     }
   };
 
   // alpha * code + beta for the row pair m of one column, as a packed fp16 pair
   auto ab_pair = [&](uint32_t a_bits, uint32_t b_bits) {
-    const f32x2 abf = {__uint_as_float(a_bits & bmask), __uint_as_float(b_bits & bmask)};
+    const f32x2 abf = {__uint_as_float(a_bits), __uint_as_float(b_bits)};
     return __builtin_convertvector(abf, f16x2);
   };
   auto dq_pair = [&](uint32_t w0s, uint32_t w1s, f16x2 ab, int m) {
@@ -237,12 +344,12 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     return __builtin_bit_cast(uint32_t, cc * a2 + b2);
   };
 
-  auto store_b = [&](auto kind, int it, int buf) {
+  auto store_b = [&](auto kind, int it, uint16_t* b_dst) {
     constexpr bool kMain = decltype(kind)::value == 0;
-    char* bs = reinterpret_cast<char*>(Bs + buf * B_TILE);
+    char* bs = reinterpret_cast<char*>(b_dst);
     if constexpr (kMain) {
       if constexpr (!BWD) {
-        const int i0 = it * BK + 8 * f_u0;
+        const int i0 = (it - nk_tail) * BK + 8 * f_u0;
         const int sh0 = patch_preshift0<NBITS>(i0), sh1 = patch_preshift1(i0);
         const uint32_t w0[4] = {breg[0].x, breg[0].y, breg[0].z, breg[0].w};
         const uint32_t w1[4] = {breg[3].x, breg[3].y, breg[3].z, breg[3].w};
@@ -306,123 +413,161 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
   };
 
   // ---- LDS -> matrix cores ---------------------------------------------------------
-  // lane (r = lane % 32, kb = lane / 32) reads chunk 2*kk + kb of row base + r; the swizzled
-  // offset of chunk c is offset(row, 0) ^ (c << 4).
-  int a_off[TM], b_off[TN];
-#pragma unroll
-  for (int a = 0; a < TM; ++a) a_off[a] = swz_offset(wm * WTM + a * 32 + (lane & 31), 0);
-#pragma unroll
-  for (int b = 0; b < TN; ++b) b_off[b] = swz_offset(wn * WTN + b * 32 + (lane & 31), 0);
+  // lane (r = lane % 32, kb = lane / 32) reads chunk 2*kk + kb of rows base + 32*t + r.  The
+  // swizzle repeats every 32 rows, so one lane offset (XORed with the chunk) serves every
+  // 32-row tile of the wave through the instruction's immediate offset.
+  const int a_lane = swz_offset(wm * WTM + (lane & 31), 0);
+  const int b_lane = swz_offset(wn * WTN + (lane & 31), 0);
 
-  auto compute = [&](auto kind, int buf) {
+  auto compute = [&](auto kind, const uint16_t* a_src, const uint16_t* b_src) {
     constexpr bool kMain = decltype(kind)::value == 0;
-    const char* as = reinterpret_cast<const char*>(As + buf * A_TILE);
-    const char* bs = reinterpret_cast<const char*>(Bs + buf * B_TILE);
-    uint4 af[2][TM], bf[2][TN];
-    auto load_frags = [&](int kk, int slot) {
-      const int cx = (2 * kk + (lane >> 5)) << 4;
-#pragma unroll
-      for (int a = 0; a < TM; ++a)
-        af[slot][a] = *reinterpret_cast<const uint4*>(as + (a_off[a] ^ cx));
-#pragma unroll
-      for (int b = 0; b < TN; ++b)
-        bf[slot][b] = *reinterpret_cast<const uint4*>(bs + (b_off[b] ^ cx));
-    };
-    load_frags(0, 0);
+    const char* as = reinterpret_cast<const char*>(a_src);
+    const char* bs = reinterpret_cast<const char*>(b_src);
+    uint4 af[TM], bf[TN];
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      const int cur = kk & 1;
-      if (kk + 1 < BK / 16) load_frags(kk + 1, cur ^ 1);  // fragments of the next step in flight
+      const int cx = (2 * kk + (lane >> 5)) << 4;
+      const char* ap = as + (a_lane ^ cx);
+      const char* bp = bs + (b_lane ^ cx);
+#pragma unroll
+      for (int a = 0; a < TM; ++a) af[a] = *reinterpret_cast<const uint4*>(ap + a * 4096);
+#pragma unroll
+      for (int b = 0; b < TN; ++b) bf[b] = *reinterpret_cast<const uint4*>(bp + b * 4096);
 #pragma unroll
       for (int a = 0; a < TM; ++a)
 #pragma unroll
         for (int b = 0; b < TN; ++b) {
           if constexpr (kMain)
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                __builtin_bit_cast(f16x8, af[cur][a]), __builtin_bit_cast(f16x8, bf[cur][b]),
-                acc[a][b], 0, 0, 0);
+                __builtin_bit_cast(f16x8, af[a]), __builtin_bit_cast(f16x8, bf[b]), acc[a][b], 0,
+                0, 0);
           else
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                __builtin_bit_cast(bf16x8, af[cur][a]), __builtin_bit_cast(bf16x8, bf[cur][b]),
-                acc[a][b], 0, 0, 0);
+                __builtin_bit_cast(bf16x8, af[a]), __builtin_bit_cast(bf16x8, bf[b]), acc[a][b],
+                0, 0, 0);
         }
-      __builtin_amdgcn_sched_barrier(0);  // keep the fragment prefetch depth at one step
+      // one K-16 slice of fragments live at a time; the other wavefront of the SIMD covers
+      // the LDS latency
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  // One pipelined K step: start the loads of step it+1, run the matrix cores on step it,
-  // then dequantise / stage step it+1.
-  auto step = [&](auto cur, auto next, int it, int buf) {
-    constexpr bool kHasNext = decltype(next)::value != 2;
-    if constexpr (kHasNext) {
-      issue_a(next, it + 1, buf ^ 1);
-      gload_b(next, it + 1);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    compute(cur, buf);
-    if constexpr (kHasNext) store_b(next, it + 1, buf ^ 1);
-    __syncthreads();  // also waits for the LDS-DMA loads of the next A tile
+  // Vector-memory ops per thread of one B-register load, per step kind (for the waits).
+  constexpr int kBLoadsMain = BWD ? (NBITS == 3 ? 8 : 6) : (NBITS == 3 ? 4 : 3);
+  constexpr int kBLoadsTail = B_CHUNKS;
+
+  // One pipelined K step `it` (kinds: cur = it, n1 = it+1, n2 = it+2; NoneK = past the end).
+  //   entry : A(it), B(it) visible in LDS; A(it+1) LDS-DMA in flight; B regs hold step it+1
+  //   1. start LDS-DMA of A(it+2)             (its stage was last read in step it-1)
+  //   2. matrix cores on step it
+  //   3. dequantise B regs -> B stage of it+1 (last read in step it-1)
+  //   4. load B regs of step it+2
+  //   5. wait for A(it+1) (everything issued after it may stay in flight), barrier
+  auto step = [&](auto cur, auto n1, auto n2, int it, int slot) {
+    constexpr bool kHas1 = decltype(n1)::value != 2;
+    constexpr bool kHas2 = decltype(n2)::value != 2;
+    const int sa = slot % 3, sa2 = (slot + 2) % 3, sb = slot & 1;
+    with_step_regions(
+        As + sa2 * A_TILE, As + sa * A_TILE, Bs + sb * B_TILE, Bs + (sb ^ 1) * B_TILE,
+        [&](uint16_t* a_dma, const uint16_t* a_rd, const uint16_t* b_rd, uint16_t* b_wr) {
+          if constexpr (kHas2) issue_a(n2, it + 2, a_dma);
+          __builtin_amdgcn_sched_barrier(0);
+          compute(cur, a_rd, b_rd);
+          if constexpr (kHas1) store_b(n1, it + 1, b_wr);
+          if constexpr (kHas2) gload_b(n2, it + 2);
+        });
+    constexpr int kKeep =
+        kHas2 ? A_LOADS + (decltype(n2)::value == 0 ? kBLoadsMain : kBLoadsTail) : 0;
+    wait_and_barrier<kKeep>();
   };
 
-  if (it_begin < it_end) {
-    int it = it_begin, buf = 0;
-    if (HAS_MAIN && nk_main > 0) {
-      issue_a(MainK{}, it, 0);
-      gload_b(MainK{}, it);
-      store_b(MainK{}, it, 0);
-      __syncthreads();
-      for (; it + 1 < nk_main; ++it, buf ^= 1) step(MainK{}, MainK{}, it, buf);
-      if (nk_tail > 0) {
-        step(MainK{}, TailK{}, it, buf);
-        ++it, buf ^= 1;
-        for (; it + 1 < it_end; ++it, buf ^= 1) step(TailK{}, TailK{}, it, buf);
-        step(TailK{}, NoneK{}, it, buf);
-      } else {
-        step(MainK{}, NoneK{}, it, buf);
+  // Software pipeline over the homogeneous steps [pb, pe) of kind K.
+  auto pipeline = [&](auto K, int pb, int pe) {
+    const int n = pe - pb;
+    if (n <= 0) return;
+    // prologue: A(pb), A(pb+1) in flight, B(pb) staged, B regs of step pb+1 loading
+    issue_a(K, pb, As);
+    gload_b(K, pb);
+    if (n > 1) issue_a(K, pb + 1, As + A_TILE);
+    store_b(K, pb, Bs);
+    if (n > 1) gload_b(K, pb + 1);
+    wait_and_barrier<0>();  // prologue only: drain everything
+    int it = pb, slot = 0;
+#pragma nounroll
+    for (; it + 2 < pe; ++it, ++slot) step(K, K, K, it, slot);  // hot loop
+    if (it + 1 < pe) {
+      step(K, K, NoneK{}, it, slot);
+      ++it, ++slot;
+    }
+    step(K, NoneK{}, NoneK{}, it, slot);
+  };
+
+  if constexpr (HAS_MAIN) {
+    // The adapter (tail) steps run FIRST, two at a time and without software pipelining
+    // (there are at most a handful); nothing tail-specific stays live across the hot loop.
+#pragma nounroll
+    for (int c = 0; c < nk_tail; c += 2) {
+      const bool two = c + 1 < nk_tail;
+      issue_a(TailK{}, c, As);
+      if (two) issue_a(TailK{}, c + 1, As + A_TILE);
+      gload_b(TailK{}, c);
+      store_b(TailK{}, c, Bs);
+      if (two) {
+        gload_b(TailK{}, c + 1);
+        store_b(TailK{}, c + 1, Bs + B_TILE);
       }
-    } else {
-      issue_a(TailK{}, it, 0);
-      gload_b(TailK{}, it);
-      store_b(TailK{}, it, 0);
-      __syncthreads();
-      for (; it + 1 < it_end; ++it, buf ^= 1) step(TailK{}, TailK{}, it, buf);
-      step(TailK{}, NoneK{}, it, buf);
+      wait_and_barrier<0>();
+      compute(TailK{}, As, Bs);
+      if (two) compute(TailK{}, As + A_TILE, Bs + B_TILE);
+      wait_and_barrier<0>();  // all reads done before the stages are refilled
     }
+    pipeline(MainK{}, nk_tail, it_end);
+  } else {
+    pipeline(TailK{}, it_begin, it_end);
   }
 
   // ---- epilogue: D[m][n] lives at lane n%32, register 4*(m/8) + m%4, half (m/4)%2 ----
+  // (thread coordinates are re-derived here so that nothing but the accumulators has to
+  // stay live across the K loop)
+  int e_tid = threadIdx.x;
+  asm volatile("" : "+v"(e_tid));
+  const int e_lane = e_tid & 63, e_wave = e_tid >> 6;
+  const int e_wm = e_wave % WAVES_M, e_wn = e_wave / WAVES_M;
   const size_t zoff = (size_t)blockIdx.y * (size_t)p.M * (size_t)p.N;
+  auto epilogue = [&](auto as_bf16) {
+    constexpr bool kBf16 = decltype(as_bf16)::value;
 #pragma unroll
-  for (int a = 0; a < TM; ++a) {
-    float inv[16];
+    for (int a = 0; a < TM; ++a) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int row = m0 + wm * WTM + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-      inv[r] = (HAS_MAIN && row < p.M) ? p.row_scale[row].y : 1.0f;
-    }
+      for (int b = 0; b < TN; ++b) {
+        const int col = n0 + e_wn * WTN + b * 32 + (e_lane & 31);
 #pragma unroll
-    for (int b = 0; b < TN; ++b) {
-      const int col = n0 + wn * WTN + b * 32 + (lane & 31);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * WTM + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row < p.M && col < p.N) {
-          const size_t o = zoff + (size_t)row * p.N + col;
-          const float v = acc[a][b][r] * inv[r];
-          if (p.out_bf16)
-            static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_bits(v);
-          else
-            static_cast<float*>(p.out)[o] = v;
+        for (int r = 0; r < 16; ++r) {
+          const int row = m0 + e_wm * WTM + a * 32 + 8 * (r >> 2) + 4 * (e_lane >> 5) + (r & 3);
+          if (row < p.M && col < p.N) {
+            const float inv = HAS_MAIN ? p.row_scale[row].y : 1.0f;
+            const size_t o = zoff + (size_t)row * p.N + col;
+            const float v = acc[a][b][r] * inv;
+            if constexpr (kBf16)
+              static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_bits(v);
+            else
+              static_cast<float*>(p.out)[o] = v;
+          }
         }
+        __builtin_amdgcn_sched_barrier(0);  // one 32x32 tile at a time: keeps registers low
       }
     }
-  }
+  };
+  if (p.out_bf16)
+    epilogue(std::true_type{});
+  else
+    epilogue(std::false_type{});
 }
 
-template <int NBITS, bool BWD, int BM, int BN, int WAVES_M, int WAVES_N, bool HAS_MAIN>
+template <int NBITS, bool BWD, int BM, int BN, int WAVES_M, int WAVES_N, bool HAS_MAIN, bool FAST>
 static hipError_t launch_cfg(const GemmArgs& a, int ksplit, hipStream_t st) {
-  auto kern = gemm_dq_kernel<NBITS, BWD, BM, BN, WAVES_M, WAVES_N, HAS_MAIN>;
-  const size_t smem = (size_t)2 * (BM + BN) * 64 * sizeof(uint16_t);
+  auto kern = gemm_dq_kernel<NBITS, BWD, BM, BN, WAVES_M, WAVES_N, HAS_MAIN, FAST>;
+  const size_t smem = (size_t)(3 * BM + 2 * BN) * 64 * sizeof(uint16_t);
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -437,9 +582,14 @@ static hipError_t launch_cfg(const GemmArgs& a, int ksplit, hipStream_t st) {
 
 template <int NBITS, bool BWD>
 static hipError_t launch_dir(const GemmArgs& a, hipStream_t st) {
-  if (a.M > 128) return launch_cfg<NBITS, BWD, 256, 256, 2, 4, true>(a, 1, st);
-  if (a.M > 64) return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true>(a, 1, st);
-  return launch_cfg<NBITS, BWD, 64, 256, 1, 8, true>(a, 1, st);
+  if (a.M > 128) {
+    const bool fast = a.a_main_padded_rows >= round_up(a.M, 256) && a.K_main % BK == 0 &&
+                      (BK % a.group == 0 || a.group % BK == 0);
+    if (fast) return launch_cfg<NBITS, BWD, 256, 256, 2, 4, true, true>(a, 1, st);
+    return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, false>(a, 1, st);
+  }
+  if (a.M > 64) return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, false>(a, 1, st);
+  return launch_cfg<NBITS, BWD, 64, 256, 1, 8, true, false>(a, 1, st);
 }
 
 ProfileHook g_profile_hook[2] = {{nullptr, nullptr}, {nullptr, nullptr}};
@@ -462,7 +612,7 @@ hipError_t launch_gemm_dq(int bits, bool bwd, const GemmArgs& a, hipStream_t st)
 // Plain bf16 x bf16^T product  out[z][M][N] = a_tail[M, Kz] . b_tail[N, Kz]^T  with the K
 // range split over `ksplit` slices (partial sums, reduced by the caller in a fixed order).
 hipError_t launch_gemm_plain(const GemmArgs& a, int ksplit, hipStream_t st) {
-  return launch_cfg<4, false, 64, 128, 2, 4, false>(a, ksplit, st);
+  return launch_cfg<4, false, 64, 128, 2, 4, false, false>(a, ksplit, st);
 }
 
 }  // namespace qalora

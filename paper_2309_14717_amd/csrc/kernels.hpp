@@ -19,6 +19,7 @@ struct GemmArgs {
   const uint16_t* a_main;  // fp16 [M, K_main]: x (forward) or dy (backward), each row already
                            // multiplied by its power-of-two row scale
   int lda_main;
+  int a_main_padded_rows;   // rows a_main may be read for (>= M; the rest holds anything)
   const uint16_t* a_tail;  // bf16 [M, K_tail]: hi/lo split of s*U (forward) or dU (backward),
                            // each row pre-multiplied by its row scale
   int lda_tail;
