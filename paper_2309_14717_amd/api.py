@@ -13,7 +13,8 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libqalora_hip.so")
+# QALORA_LIB points at an alternative build of the same library (kernel experiments)
+LIB_PATH = os.environ.get("QALORA_LIB") or os.path.join(_HERE, "libqalora_hip.so")
 
 OK, EINVAL, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1

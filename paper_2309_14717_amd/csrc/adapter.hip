@@ -50,275 +50,284 @@ __device__ __forceinline__ uint4 bf16x8_to_f16x8_scaled(uint4 v, float sc) {
   return uint4{w[0], w[1], w[2], w[3]};
 }
 
-// a bf16 [rows, cols] -> a16 fp16 [rows, cols] = a * rs[row].x, and rs.  One wavefront per
-// row: a first sweep finds the row maximum, a second (served by L2) converts.
-__global__ __launch_bounds__(256) void convert_rows_kernel(const uint16_t* __restrict__ a,
-                                                           int rows, int cols,
-                                                           float2* __restrict__ rs,
-                                                           uint16_t* __restrict__ a16) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
-  const uint16_t* src = a + (size_t)row * cols;
-  uint32_t m = 0;
-  for (int ch = lane; ch < cols / 8; ch += 64)
-    m = max_abs_bits(*reinterpret_cast<const uint4*>(src + 8 * ch), m);
-  m = wave_max_u32(m);
-  const float2 sc = scale_from_maxbits(m);
-  if (lane == 0) rs[row] = sc;
-  uint16_t* dst = a16 + (size_t)row * cols;
-  for (int ch = lane; ch < cols / 8; ch += 64)
-    *reinterpret_cast<uint4*>(dst + 8 * ch) =
-        bf16x8_to_f16x8_scaled(*reinterpret_cast<const uint4*>(src + 8 * ch), sc.x);
-}
-
-hipError_t launch_convert_rows(const uint16_t* a, int rows, int cols, float2* rs, uint16_t* a16,
-                               hipStream_t st) {
-  convert_rows_kernel<<<ceil_div(rows, 4), 256, 0, st>>>(a, rows, cols, rs, a16);
-  return hipGetLastError();
-}
-
 // ---------------------------------------------------------------------------------------
-// pool_g(x) and U = pool_g(x) A.   One block = 8 tokens, one wavefront = 2 of them.
-// The group average uses a wavefront butterfly: each lane sums 8 consecutive bf16 inputs
-// (one 128-bit load), then lanes of the same group (g/8 of them) combine with xor-shuffles.
-// The same sweep over the row yields its largest magnitude, hence its power-of-two scale.
+// The "front" launch: every row-wise and elementwise preparation step of a forward or a
+// backward call, as independent jobs of ONE kernel (the steps are tiny; launches are not).
+//   rows job 1 : x -> row scale, fp16 scaled copy (forward), P = pool_g(x), U = P A as
+//                u_ext / us_t.  One wavefront per token, the row held in registers: a single
+//                sweep of 128-bit loads gives the maximum (scale), the group sums (wavefront
+//                butterfly over the g/8 lanes of a group) and the converted copy.
+//   rows job 2 : dy -> row scale + fp16 scaled copy (backward)
+//   prep job   : hi/lo splits of B (and A) into the operand layouts of the matrix kernels
 // ---------------------------------------------------------------------------------------
-constexpr int POOL_TB = 8;
+constexpr int ROWS_PER_BLOCK = 4;  // one wavefront each
+constexpr int ROW_BATCH = 8;       // 128-bit chunks per lane held in registers (4096 elements)
 
-__global__ __launch_bounds__(256) void pool_down_kernel(const uint16_t* __restrict__ x,
-                                                        const float* __restrict__ A, float s,
-                                                        int T, int d_in, int g, int rank,
-                                                        float* __restrict__ P_out,
-                                                        float2* __restrict__ rs_out,
-                                                        uint16_t* __restrict__ x16,
-                                                        uint16_t* __restrict__ u_ext, int ktail,
-                                                        uint16_t* __restrict__ us_t, int t_pad) {
-  extern __shared__ float P_s[];  // [POOL_TB][L]
-  __shared__ float sc_s[POOL_TB];
-  const int L = d_in / g;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int t0 = blockIdx.x * POOL_TB;
-  const int lpg = g / 8;  // lanes per group
-  const bool butterfly = (lpg <= 64) && ((lpg & (lpg - 1)) == 0);
-  const float inv_g = 1.0f / (float)g;
-  const int nchunks = d_in / 8;
+struct FrontArgs {
+  // rows job 1 (x)
+  const uint16_t* x;
+  int T, d_in;
+  float2* rs_x;         // optional
+  uint16_t* x16;        // optional, [T, d_in]
+  const float* A;       // optional: enables pooling and U
+  float s;
+  int g, rank;
+  float* P_out;         // optional [T, L]
+  uint16_t* u_ext;      // optional [T, ktail]
+  int ktail;
+  uint16_t* us_t;       // optional [2*rp, t_pad]
+  int t_pad;
+  // rows job 2 (dy): scale + convert only
+  const uint16_t* y;
+  int Ty, d_y;
+  float2* rs_y;
+  uint16_t* y16;
+  // prep job
+  const float* B;
+  int d_out, L;
+  uint16_t* b_ext_t;    // forward: [d_out, ktail]
+  uint16_t* b_hl;       // backward: [2*rp, d_out]
+  uint16_t* a_ext_t;    // backward: [L, ktail]
+  int nb_rows1, nb_rows2, nb_prep;
+};
 
-  for (int tt = wave * 2; tt < wave * 2 + 2; ++tt) {
-    const int t = t0 + tt;
-    uint32_t amax = 0;
-    for (int c0 = 0; c0 < nchunks; c0 += 64) {
-      const int ch = c0 + lane;
-      float v = 0.0f;
-      if (t < T && ch < nchunks) {
-        const uint4 q = *reinterpret_cast<const uint4*>(x + (size_t)t * d_in + 8 * ch);
-        amax = max_abs_bits(q, amax);
-        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+// One wavefront processes one bf16 row: returns the row scale; optionally writes the fp16
+// scaled copy and the group averages (to P_s, LDS, [L]).
+__device__ __forceinline__ float2 process_row(const uint16_t* __restrict__ src, int cols,
+                                              uint16_t* __restrict__ dst16, float* P_s, int g,
+                                              int lane) {
+  const int nch = cols / 8;
+  const int lpg = g > 0 ? g / 8 : 0;
+  const bool butterfly = P_s && lpg <= 64 && (lpg & (lpg - 1)) == 0;
+  const float inv_g = g > 0 ? 1.0f / (float)g : 0.0f;
+  uint32_t amax = 0;
+  uint4 v[ROW_BATCH];
+  const bool resident = nch <= 64 * ROW_BATCH;  // whole row fits the register batch
+  for (int base = 0; base < nch; base += 64 * ROW_BATCH) {
+#pragma unroll
+    for (int c = 0; c < ROW_BATCH; ++c) {
+      const int ch = base + c * 64 + lane;
+      v[c] = ch < nch ? *reinterpret_cast<const uint4*>(src + 8 * ch) : uint4{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int c = 0; c < ROW_BATCH; ++c) {
+      amax = max_abs_bits(v[c], amax);
+      if (butterfly) {
+        const int ch = base + c * 64 + lane;
+        const uint32_t w[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+        float sum = 0.0f;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          v += bf16_bits_to_f32(w[e] & 0xffffu);
-          v += __uint_as_float(w[e] & 0xffff0000u);
+          sum += bf16_bits_to_f32(w[e] & 0xffffu);
+          sum += __uint_as_float(w[e] & 0xffff0000u);
+        }
+        for (int off = 1; off < lpg; off <<= 1) sum += __shfl_xor(sum, off, 64);
+        if (ch < nch && (lane & (lpg - 1)) == 0) P_s[ch / lpg] = sum * inv_g;
+      }
+    }
+  }
+  amax = wave_max_u32(amax);
+  const float2 sc = scale_from_maxbits(amax);
+  if (dst16) {
+    if (resident) {
+#pragma unroll
+      for (int c = 0; c < ROW_BATCH; ++c) {
+        const int ch = c * 64 + lane;
+        if (ch < nch)
+          *reinterpret_cast<uint4*>(dst16 + 8 * ch) = bf16x8_to_f16x8_scaled(v[c], sc.x);
+      }
+    } else {  // second sweep, served by L2
+      for (int ch = lane; ch < nch; ch += 64)
+        *reinterpret_cast<uint4*>(dst16 + 8 * ch) =
+            bf16x8_to_f16x8_scaled(*reinterpret_cast<const uint4*>(src + 8 * ch), sc.x);
+    }
+  }
+  if (P_s && !butterfly) {  // group sizes the butterfly does not cover: plain loop
+    const int L = cols / g;
+    for (int l = lane; l < L; l += 64) {
+      float sum = 0.0f;
+      for (int q = 0; q < g; ++q) sum += bf16_bits_to_f32(src[l * g + q]);
+      P_s[l] = sum * inv_g;
+    }
+  }
+  return sc;
+}
+
+__global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
+  extern __shared__ float P_all[];  // [ROWS_PER_BLOCK][L] when pooling
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int bid = blockIdx.x;
+  if (bid < a.nb_rows1) {
+    // ---- rows job 1: x ---------------------------------------------------------------
+    const int t = bid * ROWS_PER_BLOCK + wave;
+    const int L = a.A ? a.d_in / a.g : 0;
+    const int rp = rank_pad32(a.rank);
+    float* P_s = a.A ? P_all + wave * L : nullptr;
+    float2 sc = float2{1.0f, 1.0f};
+    if (t < a.T) {
+      sc = process_row(a.x + (size_t)t * a.d_in, a.d_in,
+                       a.x16 ? a.x16 + (size_t)t * a.d_in : nullptr, P_s, a.g, lane);
+      if (lane == 0 && a.rs_x) a.rs_x[t] = sc;
+    } else if (a.A) {
+      for (int l = lane; l < L; l += 64) P_s[l] = 0.0f;
+    }
+    if (!a.A) return;
+    __syncthreads();
+    if (t < a.T && a.P_out)
+      for (int l = lane; l < L; l += 64) a.P_out[(size_t)t * L + l] = P_s[l];
+    // U = P A for the block's 4 tokens, cooperatively: thread (k, q) covers a quarter of the
+    // groups for all 4 tokens (each A element is loaded once per block), then the quarters
+    // are added in fixed order.
+    float* part = P_all + ROWS_PER_BLOCK * L;  // [4 quarters][4 tokens][128]
+    const int lq0 = (L * wave) / 4, lq1 = (L * (wave + 1)) / 4;
+    for (int k = lane; k < a.rank; k += 64) {
+      float u[ROWS_PER_BLOCK] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 4
+      for (int l = lq0; l < lq1; ++l) {
+        const float av = a.A[(size_t)l * a.rank + k];
+#pragma unroll
+        for (int r = 0; r < ROWS_PER_BLOCK; ++r) u[r] = __builtin_fmaf(P_all[r * L + l], av, u[r]);
+      }
+#pragma unroll
+      for (int r = 0; r < ROWS_PER_BLOCK; ++r) part[(wave * ROWS_PER_BLOCK + r) * 128 + k] = u[r];
+    }
+    __syncthreads();
+    if (t < a.T) {
+      for (int k = lane; k < rp; k += 64) {
+        float u = 0.0f;
+        if (k < a.rank) {
+          u = ((part[(0 * ROWS_PER_BLOCK + wave) * 128 + k] + part[(1 * ROWS_PER_BLOCK + wave) * 128 + k]) +
+               part[(2 * ROWS_PER_BLOCK + wave) * 128 + k]) +
+              part[(3 * ROWS_PER_BLOCK + wave) * 128 + k];
+          u *= a.s;
+        }
+        uint16_t hi, lo;
+        if (a.u_ext && k < a.rank) {
+          // the forward tail shares the accumulator of the scaled main product
+          split_bf16(u * sc.x, hi, lo);
+          uint16_t* row = a.u_ext + (size_t)t * a.ktail;
+          row[k] = hi;
+          row[a.rank + k] = lo;
+          row[2 * a.rank + k] = hi;
+        }
+        if (a.us_t) {
+          split_bf16(u, hi, lo);  // zero for the padding rows k >= rank
+          a.us_t[(size_t)k * a.t_pad + t] = hi;
+          a.us_t[(size_t)(rp + k) * a.t_pad + t] = lo;
         }
       }
-      if (butterfly) {
-        for (int off = 1; off < lpg; off <<= 1) v += __shfl_xor(v, off, 64);
-        if (ch < nchunks && (lane & (lpg - 1)) == 0) P_s[tt * L + ch / lpg] = v * inv_g;
+      if (a.u_ext)
+        for (int c = 3 * a.rank + lane; c < a.ktail; c += 64) a.u_ext[(size_t)t * a.ktail + c] = 0;
+    } else if (a.us_t && t < a.t_pad) {
+      // token padding of the transposed operand must read as zero
+      for (int k = lane; k < 2 * rp; k += 64) a.us_t[(size_t)k * a.t_pad + t] = 0;
+    }
+    return;
+  }
+  bid -= a.nb_rows1;
+  if (bid < a.nb_rows2) {
+    // ---- rows job 2: dy -> scale + fp16 copy ----------------------------------------------
+    const int t = bid * ROWS_PER_BLOCK + wave;
+    if (t < a.Ty) {
+      const float2 sc = process_row(a.y + (size_t)t * a.d_y, a.d_y, a.y16 + (size_t)t * a.d_y,
+                                    nullptr, 0, lane);
+      if (lane == 0) a.rs_y[t] = sc;
+    }
+    return;
+  }
+  bid -= a.nb_rows2;
+  // ---- prep job: elementwise hi/lo splits ------------------------------------------------
+  const size_t idx = (size_t)bid * 256 + tid;
+  const int rp = rank_pad32(a.rank);
+  if (a.b_ext_t) {
+    // forward: b_ext_t[j][c] = [hi | hi | lo | 0] of B[:, j]
+    if (idx < (size_t)a.d_out * a.ktail) {
+      const int j = (int)(idx / a.ktail), c = (int)(idx % a.ktail);
+      uint16_t v = 0;
+      if (c < 3 * a.rank) {
+        uint16_t hi, lo;
+        split_bf16(a.B[(size_t)(c % a.rank) * a.d_out + j], hi, lo);
+        v = (c < 2 * a.rank) ? hi : lo;
       }
+      a.b_ext_t[idx] = v;
     }
-    amax = wave_max_u32(amax);
-    const float2 sc = scale_from_maxbits(amax);
-    if (lane == 0) {
-      sc_s[tt] = sc.x;
-      if (rs_out && t < T) rs_out[t] = sc;
-    }
-    if (x16 && t < T) {  // second sweep over the row (L2): scaled fp16 copy for the matrix cores
-      for (int ch = lane; ch < nchunks; ch += 64)
-        *reinterpret_cast<uint4*>(x16 + (size_t)t * d_in + 8 * ch) = bf16x8_to_f16x8_scaled(
-            *reinterpret_cast<const uint4*>(x + (size_t)t * d_in + 8 * ch), sc.x);
-    }
+    return;
   }
-  if (!butterfly) {
-    for (int o = tid; o < POOL_TB * L; o += 256) {
-      const int tt = o / L, l = o % L;
-      const int t = t0 + tt;
-      float v = 0.0f;
-      if (t < T)
-        for (int q = 0; q < g; ++q) v += bf16_bits_to_f32(x[(size_t)t * d_in + l * g + q]);
-      P_s[o] = v * inv_g;
+  const size_t nb = (size_t)2 * rp * a.d_out;
+  const size_t na = (size_t)a.L * a.ktail;
+  if (idx < nb) {
+    // backward: b_hl rows = hi(B) then lo(B) (rows padded to rp with zeros)
+    const int row = (int)(idx / a.d_out), j = (int)(idx % a.d_out);
+    const int k = row % rp;
+    uint16_t v = 0;
+    if (k < a.rank) {
+      uint16_t hi, lo;
+      split_bf16(a.B[(size_t)k * a.d_out + j], hi, lo);
+      v = (row < rp) ? hi : lo;
     }
-  }
-  __syncthreads();
-
-  if (P_out) {
-    for (int o = tid; o < POOL_TB * L; o += 256) {
-      const int t = t0 + o / L;
-      if (t < T) P_out[(size_t)t * L + o % L] = P_s[o];
+    a.b_hl[idx] = v;
+  } else if (idx < nb + na) {
+    // backward: a_ext_t[l][c] = [hi | hi | lo | 0] of A[l, :] / g
+    const size_t o = idx - nb;
+    const int l = (int)(o / a.ktail), c = (int)(o % a.ktail);
+    uint16_t v = 0;
+    if (c < 3 * a.rank) {
+      uint16_t hi, lo;
+      split_bf16(a.A[(size_t)l * a.rank + c % a.rank] / (float)a.g, hi, lo);
+      v = (c < 2 * a.rank) ? hi : lo;
     }
-  }
-  const int rp = rank_pad32(rank);
-  for (int o = tid; o < POOL_TB * rank; o += 256) {
-    const int tt = o / rank, k = o % rank;
-    const int t = t0 + tt;
-    if (t >= T) continue;
-    float u = 0.0f;
-    for (int l = 0; l < L; ++l) u = __builtin_fmaf(P_s[tt * L + l], A[(size_t)l * rank + k], u);
-    u *= s;
-    uint16_t hi, lo;
-    if (u_ext) {
-      // the forward tail shares the accumulator of the scaled main product
-      split_bf16(u * sc_s[tt], hi, lo);
-      uint16_t* row = u_ext + (size_t)t * ktail;
-      row[k] = hi;
-      row[rank + k] = lo;
-      row[2 * rank + k] = hi;
-    }
-    if (us_t) {
-      split_bf16(u, hi, lo);
-      us_t[(size_t)k * t_pad + t] = hi;
-      us_t[(size_t)(rp + k) * t_pad + t] = lo;
-    }
-  }
-  if (u_ext) {
-    const int npad = ktail - 3 * rank;
-    for (int o = tid; o < POOL_TB * npad; o += 256) {
-      const int t = t0 + o / npad;
-      if (t < T) u_ext[(size_t)t * ktail + 3 * rank + o % npad] = 0;
-    }
+    a.a_ext_t[o] = v;
   }
 }
 
-__global__ void fill_zero_kernel(uint4* __restrict__ p, size_t n16) {
-  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16;
-       i += (size_t)gridDim.x * blockDim.x)
-    p[i] = uint4{0, 0, 0, 0};
-}
-
-hipError_t launch_pool_down(const uint16_t* x, const float* A, float s, int T, int d_in, int g,
-                            int rank, float* P_out, float2* rs_out, uint16_t* x16,
-                            uint16_t* u_ext, int ktail, uint16_t* us_t, int t_pad,
-                            hipStream_t st) {
-  const int L = d_in / g;
-  const size_t smem = (size_t)POOL_TB * L * sizeof(float);
+static hipError_t launch_front(FrontArgs a, hipStream_t st) {
+  a.nb_rows1 = a.x ? ceil_div(a.us_t ? a.t_pad : a.T, ROWS_PER_BLOCK) : 0;
+  a.nb_rows2 = a.y ? ceil_div(a.Ty, ROWS_PER_BLOCK) : 0;
+  size_t nprep = 0;
+  if (a.b_ext_t) nprep = (size_t)a.d_out * a.ktail;
+  else if (a.b_hl) nprep = (size_t)2 * rank_pad32(a.rank) * a.d_out + (size_t)a.L * a.ktail;
+  a.nb_prep = (int)((nprep + 255) / 256);
+  const size_t smem =
+      a.A ? ((size_t)ROWS_PER_BLOCK * (a.d_in / a.g) + 4 * ROWS_PER_BLOCK * 128) * sizeof(float) : 0;
   static size_t smem_limit = 48 * 1024;
   if (smem > smem_limit) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pool_down_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(front_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     smem_limit = smem;
   }
-  if (us_t) {
-    // padding rows / columns of the transposed operand must read as zero
-    const size_t n16 = (size_t)2 * rank_pad32(rank) * t_pad * sizeof(uint16_t) / 16;
-    const size_t nblk = (n16 + 255) / 256;
-    fill_zero_kernel<<<(int)(nblk < 1024 ? nblk : 1024), 256, 0, st>>>(
-        reinterpret_cast<uint4*>(us_t), n16);
-  }
-  pool_down_kernel<<<ceil_div(T, POOL_TB), 256, smem, st>>>(
-      x, A, s, T, d_in, g, rank, P_out, rs_out, x16, u_ext, ktail, us_t, t_pad);
+  const int nblocks = a.nb_rows1 + a.nb_rows2 + a.nb_prep;
+  if (nblocks == 0) return hipSuccess;
+  front_kernel<<<nblocks, 256, smem, st>>>(a);
   return hipGetLastError();
 }
 
-// ---------------------------------------------------------------------------------------
-// Operand preparation (elementwise hi/lo splits).
-// ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void prep_b_fwd_kernel(const float* __restrict__ B, int rank,
-                                                         int d_out, uint16_t* __restrict__ bt,
-                                                         int ktail) {
-  const size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-  if (idx >= (size_t)d_out * ktail) return;
-  const int j = (int)(idx / ktail), c = (int)(idx % ktail);
-  uint16_t v = 0;
-  if (c < 3 * rank) {
-    const int k = c % rank;
-    uint16_t hi, lo;
-    split_bf16(B[(size_t)k * d_out + j], hi, lo);
-    v = (c < 2 * rank) ? hi : lo;
+hipError_t launch_front_forward(const uint16_t* x, int T, int d_in, float2* rs, uint16_t* x16,
+                                const float* A, const float* B, float s, int g, int rank,
+                                int d_out, uint16_t* u_ext, uint16_t* b_ext_t, int ktail,
+                                hipStream_t st) {
+  FrontArgs a{};
+  a.x = x; a.T = T; a.d_in = d_in; a.rs_x = rs; a.x16 = x16;
+  if (A && rank > 0) {
+    a.A = A; a.s = s; a.g = g; a.rank = rank; a.u_ext = u_ext; a.ktail = ktail;
+    a.B = B; a.d_out = d_out; a.b_ext_t = b_ext_t;
   }
-  bt[idx] = v;
+  return launch_front(a, st);
 }
 
-hipError_t launch_prep_b_fwd(const float* B, int rank, int d_out, uint16_t* b_ext_t, int ktail,
-                             hipStream_t st) {
-  const size_t n = (size_t)d_out * ktail;
-  prep_b_fwd_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(B, rank, d_out, b_ext_t, ktail);
-  return hipGetLastError();
-}
-
-__global__ __launch_bounds__(256) void prep_bwd_kernel(const float* __restrict__ A,
-                                                       const float* __restrict__ B, int L,
-                                                       int rank, int d_out, int g,
-                                                       uint16_t* __restrict__ b_hl,
-                                                       uint16_t* __restrict__ a_ext_t,
-                                                       int ktail) {
-  const int rp = rank_pad32(rank);
-  const size_t nb = (size_t)2 * rp * d_out;
-  const size_t na = (size_t)L * ktail;
-  const size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-  if (idx < nb) {
-    const int row = (int)(idx / d_out), j = (int)(idx % d_out);
-    const int k = row % rp;
-    uint16_t v = 0;
-    if (k < rank) {
-      uint16_t hi, lo;
-      split_bf16(B[(size_t)k * d_out + j], hi, lo);
-      v = (row < rp) ? hi : lo;
-    }
-    b_hl[idx] = v;
-  } else if (idx < nb + na) {
-    const size_t o = idx - nb;
-    const int l = (int)(o / ktail), c = (int)(o % ktail);
-    uint16_t v = 0;
-    if (c < 3 * rank) {
-      uint16_t hi, lo;
-      split_bf16(A[(size_t)l * rank + c % rank] / (float)g, hi, lo);
-      v = (c < 2 * rank) ? hi : lo;
-    }
-    a_ext_t[o] = v;
+hipError_t launch_front_backward(const uint16_t* dy, int T, int d_out, float2* rs_dy,
+                                 uint16_t* dy16, const uint16_t* x, int d_in, const float* A,
+                                 const float* B, float s, int g, int rank, float* P,
+                                 uint16_t* us_t, int t_pad, uint16_t* b_hl, uint16_t* a_ext_t,
+                                 int ktail, hipStream_t st) {
+  FrontArgs a{};
+  a.y = dy; a.Ty = T; a.d_y = d_out; a.rs_y = rs_dy; a.y16 = dy16;
+  if (A && rank > 0) {
+    a.x = x; a.T = T; a.d_in = d_in; a.A = A; a.s = s; a.g = g; a.rank = rank;
+    a.P_out = P; a.us_t = us_t; a.t_pad = t_pad; a.ktail = ktail;
+    a.B = B; a.d_out = d_out; a.L = d_in / g; a.b_hl = b_hl; a.a_ext_t = a_ext_t;
   }
-}
-
-hipError_t launch_prep_bwd(const float* A, const float* B, int L, int rank, int d_out, int g,
-                           uint16_t* b_hl, uint16_t* a_ext_t, int ktail, hipStream_t st) {
-  const size_t n = (size_t)2 * rank_pad32(rank) * d_out + (size_t)L * ktail;
-  prep_bwd_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(A, B, L, rank, d_out, g, b_hl,
-                                                               a_ext_t, ktail);
-  return hipGetLastError();
-}
-
-__global__ __launch_bounds__(256) void du_finalize_kernel(const float* __restrict__ raw,
-                                                          int ksplit, int T, int rank, float s,
-                                                          const float2* __restrict__ rs,
-                                                          float* __restrict__ dU,
-                                                          uint16_t* __restrict__ du_ext,
-                                                          int ktail) {
-  const int rp = rank_pad32(rank);
-  const size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-  if (idx >= (size_t)T * ktail) return;
-  const int t = (int)(idx / ktail), c = (int)(idx % ktail);
-  uint16_t out = 0;
-  if (c < 3 * rank) {
-    const int k = c % rank;
-    float v = 0.0f;
-    for (int z = 0; z < ksplit; ++z) {
-      const float* r = raw + ((size_t)z * T + t) * (2 * rp);
-      v += r[k] + r[rp + k];
-    }
-    v *= s;
-    if (c < rank) dU[(size_t)t * rank + k] = v;
-    uint16_t hi, lo;
-    split_bf16(v * rs[t].x, hi, lo);  // the backward tail rides on the scaled main product
-    out = (c >= rank && c < 2 * rank) ? lo : hi;
-  }
-  du_ext[idx] = out;
-}
-
-hipError_t launch_du_finalize(const float* raw, int ksplit, int T, int rank, float s,
-                              const float2* rs, float* dU, uint16_t* du_ext, int ktail,
-                              hipStream_t st) {
-  const size_t n = (size_t)T * ktail;
-  du_finalize_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(raw, ksplit, T, rank, s, rs, dU,
-                                                                  du_ext, ktail);
-  return hipGetLastError();
+  return launch_front(a, st);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -412,21 +421,29 @@ hipError_t launch_db_partial(const uint16_t* us_t, int t_pad, const uint16_t* dy
 }
 
 // ---------------------------------------------------------------------------------------
-// dA = P^T dU over a token slice, fp32 on the vector units (67 MFLOP at LLaMA-7B shapes).
-// Block = 64 groups x all ranks; thread = 4 groups x up to 8 ranks (rank <= 128).
+// dA = P^T dU over a token slice, fp32 on the vector units (67 MFLOP at LLaMA-7B shapes),
+// fused with the finalisation of dU: dU[t,k] = s * sum_z (raw[z][t][k] + raw[z][t][rp+k]) is
+// rebuilt from the split-K partials of the dU product while staging, and the blocks of the
+// first group tile also emit the backward tail operand du_ext = [hi | lo | hi | 0] of
+// dU * (row scale of dy).  Block = 64 groups x all ranks; thread = 4 groups x up to 8 ranks.
 // ---------------------------------------------------------------------------------------
 constexpr int DA_TT = 16;
 
 __global__ __launch_bounds__(256) void da_partial_kernel(const float* __restrict__ P,
-                                                         const float* __restrict__ dU, int T,
+                                                         const float* __restrict__ raw,
+                                                         int ksplit, float s,
+                                                         const float2* __restrict__ rs, int T,
                                                          int L, int rank, int tsplit,
-                                                         float* __restrict__ part) {
+                                                         float* __restrict__ part,
+                                                         uint16_t* __restrict__ du_ext,
+                                                         int ktail) {
   __shared__ float p_s[DA_TT][64];
   __shared__ float du_s[DA_TT][128];
   const int tid = threadIdx.x;
   const int lq = tid >> 4, kq = tid & 15;
   const int l0 = blockIdx.x * 64;
   const int z = blockIdx.y;
+  const int rp = rank_pad32(rank);
   const int per = ceil_div(ceil_div(T, DA_TT), tsplit) * DA_TT;
   const int t_begin = z * per, t_end = min(T, t_begin + per);
 
@@ -443,7 +460,31 @@ __global__ __launch_bounds__(256) void da_partial_kernel(const float* __restrict
     }
     for (int idx = tid; idx < DA_TT * 128; idx += 256) {
       const int tt = idx >> 7, k = idx & 127;
-      du_s[tt][k] = (t0 + tt < t_end && k < rank) ? dU[(size_t)(t0 + tt) * rank + k] : 0.0f;
+      const int t = t0 + tt;
+      float v = 0.0f;
+      if (t < t_end && k < rank) {
+        for (int q = 0; q < ksplit; ++q) {
+          const float* r = raw + ((size_t)q * T + t) * (2 * rp);
+          v += r[k] + r[rp + k];
+        }
+        v *= s;
+        if (blockIdx.x == 0) {
+          uint16_t hi, lo;
+          split_bf16(v * rs[t].x, hi, lo);  // the backward tail rides on the scaled main product
+          uint16_t* row = du_ext + (size_t)t * ktail;
+          row[k] = hi;
+          row[rank + k] = lo;
+          row[2 * rank + k] = hi;
+        }
+      }
+      du_s[tt][k] = v;
+    }
+    if (blockIdx.x == 0) {
+      const int npad = ktail - 3 * rank;
+      for (int idx = tid; idx < DA_TT * npad; idx += 256) {
+        const int t = t0 + idx / npad;
+        if (t < t_end) du_ext[(size_t)t * ktail + 3 * rank + idx % npad] = 0;
+      }
     }
     __syncthreads();
 #pragma unroll
@@ -472,28 +513,54 @@ __global__ __launch_bounds__(256) void da_partial_kernel(const float* __restrict
   }
 }
 
-hipError_t launch_da_partial(const float* P, const float* dU, int T, int L, int rank, int tsplit,
-                             float* part, hipStream_t st) {
+hipError_t launch_da_partial(const float* P, const float* raw, int ksplit, float s,
+                             const float2* rs, int T, int L, int rank, int tsplit, float* part,
+                             uint16_t* du_ext, int ktail, hipStream_t st) {
   dim3 grid(ceil_div(L, 64), tsplit);
-  da_partial_kernel<<<grid, 256, 0, st>>>(P, dU, T, L, rank, tsplit, part);
+  da_partial_kernel<<<grid, 256, 0, st>>>(P, raw, ksplit, s, rs, T, L, rank, tsplit, part, du_ext,
+                                          ktail);
   return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ part,
-                                                              int nparts, size_t n,
-                                                              float* __restrict__ out,
-                                                              int accumulate) {
-  const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  float v = accumulate ? out[i] : 0.0f;
-  for (int z = 0; z < nparts; ++z) v += part[(size_t)z * n + i];
-  out[i] = v;
+// out[i] = (accumulate ? out[i] : 0) + sum_z part[z][i] in a fixed order, for two outputs in
+// one launch.  Block = 64 outputs x 4 part groups: thread (o, q) adds parts q, q+4, q+8, ...
+// (coalesced across o, loads independent so they pipeline), then the four group sums are
+// added in order 0..3.
+__global__ __launch_bounds__(256) void reduce2_kernel(const float* __restrict__ part_a,
+                                                      int nparts_a, size_t n_a,
+                                                      float* __restrict__ out_a,
+                                                      const float* __restrict__ part_b,
+                                                      int nparts_b, size_t n_b,
+                                                      float* __restrict__ out_b, int accumulate,
+                                                      int blocks_a) {
+  __shared__ float sums[4][64];
+  const int o = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const bool second = (int)blockIdx.x >= blocks_a;
+  const float* part = second ? part_b : part_a;
+  const int nparts = second ? nparts_b : nparts_a;
+  const size_t n = second ? n_b : n_a;
+  float* out = second ? out_b : out_a;
+  const size_t i = (size_t)(second ? blockIdx.x - blocks_a : blockIdx.x) * 64 + o;
+  float v = 0.0f;
+  if (i < n) {
+#pragma unroll 8
+    for (int z = q; z < nparts; z += 4) v += part[(size_t)z * n + i];
+  }
+  sums[q][o] = v;
+  __syncthreads();
+  if (q == 0 && i < n) {
+    float r = accumulate ? out[i] : 0.0f;
+    r += ((sums[0][o] + sums[1][o]) + sums[2][o]) + sums[3][o];
+    out[i] = r;
+  }
 }
 
-hipError_t launch_reduce_partials(const float* part, int nparts, size_t n, float* out,
-                                  int accumulate, hipStream_t st) {
-  reduce_partials_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(part, nparts, n, out,
-                                                                      accumulate);
+hipError_t launch_reduce2(const float* part_a, int nparts_a, size_t n_a, float* out_a,
+                          const float* part_b, int nparts_b, size_t n_b, float* out_b,
+                          int accumulate, hipStream_t st) {
+  const int blocks_a = (int)((n_a + 63) / 64), blocks_b = (int)((n_b + 63) / 64);
+  reduce2_kernel<<<blocks_a + blocks_b, 256, 0, st>>>(part_a, nparts_a, n_a, out_a, part_b,
+                                                       nparts_b, n_b, out_b, accumulate, blocks_a);
   return hipGetLastError();
 }
 

@@ -72,11 +72,10 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
     p.tsplit_b = ts > steps ? steps : ts;
   }
   {
-    const int blocks = ceil_div(L, 64);
-    int ts = ceil_div(256, blocks);
-    ts = ts > 64 ? 64 : ts;
+    // one 16-token chunk per block where possible: the work is tiny and latency-bound, so
+    // maximise the number of independent blocks
     const int steps = ceil_div(T, 16);
-    p.tsplit_a = ts > steps ? steps : ts;
+    p.tsplit_a = steps > 256 ? 256 : steps;
   }
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -213,18 +212,13 @@ int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* 
   g.d_out = d->d_out;
   g.group = d->group;
   g.row_scale = rs;
-  if (!adapter) {
-    if (launch_convert_rows(static_cast<const uint16_t*>(x), tokens, d->d_in, rs, x16, st) !=
-        hipSuccess)
-      return QALORA_EHIP;
-  } else {
-    uint16_t* u_ext = reinterpret_cast<uint16_t*>(w + plan.u_ext);
-    uint16_t* b_ext_t = reinterpret_cast<uint16_t*>(w + plan.b_ext_t);
-    if (launch_pool_down(static_cast<const uint16_t*>(x), A, d->s, tokens, d->d_in, d->group,
-                         d->rank, nullptr, rs, x16, u_ext, plan.ktail, nullptr, 0, st) != hipSuccess)
-      return QALORA_EHIP;
-    if (launch_prep_b_fwd(B, d->rank, d->d_out, b_ext_t, plan.ktail, st) != hipSuccess)
-      return QALORA_EHIP;
+  uint16_t* u_ext = adapter ? reinterpret_cast<uint16_t*>(w + plan.u_ext) : nullptr;
+  uint16_t* b_ext_t = adapter ? reinterpret_cast<uint16_t*>(w + plan.b_ext_t) : nullptr;
+  if (launch_front_forward(static_cast<const uint16_t*>(x), tokens, d->d_in, rs, x16,
+                           adapter ? A : nullptr, B, d->s, d->group, d->rank, d->d_out, u_ext,
+                           b_ext_t, plan.ktail, st) != hipSuccess)
+    return QALORA_EHIP;
+  if (adapter) {
     g.a_tail = u_ext;
     g.lda_tail = plan.ktail;
     g.b_tail = b_ext_t;
@@ -262,28 +256,28 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
   const uint16_t* dy16 = static_cast<const uint16_t*>(dy);  // bf16 bits
   float2* rs = reinterpret_cast<float2*>(w + plan.rs);
   uint16_t* dyh = reinterpret_cast<uint16_t*>(w + plan.a16);  // fp16 scaled copy of dy
-  if (launch_convert_rows(dy16, tokens, d->d_out, rs, dyh, st) != hipSuccess) return QALORA_EHIP;
 
   uint16_t* du_ext = nullptr;
   uint16_t* a_ext_t = nullptr;
-  if (adapter) {
+  if (!adapter) {
+    if (launch_front_backward(dy16, tokens, d->d_out, rs, dyh, nullptr, d->d_in, nullptr, nullptr,
+                              0.0f, d->group, 0, nullptr, nullptr, 0, nullptr, nullptr, 0,
+                              st) != hipSuccess)
+      return QALORA_EHIP;
+  } else {
     float* P = reinterpret_cast<float*>(w + plan.P);
     uint16_t* us_t = reinterpret_cast<uint16_t*>(w + plan.us_t);
     uint16_t* b_hl = reinterpret_cast<uint16_t*>(w + plan.b_hl);
     a_ext_t = reinterpret_cast<uint16_t*>(w + plan.a_ext_t);
     float* du_raw = reinterpret_cast<float*>(w + plan.du_raw);
-    float* dU = reinterpret_cast<float*>(w + plan.dU);
     du_ext = reinterpret_cast<uint16_t*>(w + plan.du_ext);
     float* db_part = reinterpret_cast<float*>(w + plan.db_part);
     float* da_part = reinterpret_cast<float*>(w + plan.da_part);
 
-    // P = pool(x), sU = s P A (transposed hi/lo for the dB product)
-    if (launch_pool_down(static_cast<const uint16_t*>(x), A, d->s, tokens, d->d_in, d->group,
-                         d->rank, P, nullptr, nullptr, nullptr, 0, us_t, plan.t_pad, st) !=
-        hipSuccess)
-      return QALORA_EHIP;
-    if (launch_prep_bwd(A, B, L, d->rank, d->d_out, d->group, b_hl, a_ext_t, plan.ktail, st) !=
-        hipSuccess)
+    // row scales + fp16 copy of dy; P = pool(x), sU^T hi/lo; hi/lo operands of A and B
+    if (launch_front_backward(dy16, tokens, d->d_out, rs, dyh, static_cast<const uint16_t*>(x),
+                              d->d_in, A, B, d->s, d->group, d->rank, P, us_t, plan.t_pad, b_hl,
+                              a_ext_t, plan.ktail, st) != hipSuccess)
       return QALORA_EHIP;
     // dU = s dy B^T : plain bf16 product against the hi/lo rows of B, split over K = d_out
     GemmArgs g{};
@@ -296,21 +290,16 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
     g.N = 2 * plan.rp;
     g.group = 1;
     if (launch_gemm_plain(g, plan.ksplit, st) != hipSuccess) return QALORA_EHIP;
-    if (launch_du_finalize(du_raw, plan.ksplit, tokens, d->rank, d->s, rs, dU, du_ext, plan.ktail,
-                           st) != hipSuccess)
-      return QALORA_EHIP;
-    // dB = (sU)^T dy
+    // dB = (sU)^T dy (partials over token slices)
     if (launch_db_partial(us_t, plan.t_pad, dy16, tokens, d->d_out, d->rank, plan.tsplit_b,
                           db_part, st) != hipSuccess)
       return QALORA_EHIP;
-    if (launch_reduce_partials(db_part, plan.tsplit_b, (size_t)d->rank * d->d_out, dB, accumulate,
-                               st) != hipSuccess)
+    // dA = P^T dU (partials), dU finalised on the fly, du_ext for the dx tail
+    if (launch_da_partial(P, du_raw, plan.ksplit, d->s, rs, tokens, L, d->rank, plan.tsplit_a,
+                          da_part, du_ext, plan.ktail, st) != hipSuccess)
       return QALORA_EHIP;
-    // dA = P^T dU
-    if (launch_da_partial(P, dU, tokens, L, d->rank, plan.tsplit_a, da_part, st) != hipSuccess)
-      return QALORA_EHIP;
-    if (launch_reduce_partials(da_part, plan.tsplit_a, (size_t)L * d->rank, dA, accumulate, st) !=
-        hipSuccess)
+    if (launch_reduce2(da_part, plan.tsplit_a, (size_t)L * d->rank, dA, db_part, plan.tsplit_b,
+                       (size_t)d->rank * d->d_out, dB, accumulate, st) != hipSuccess)
       return QALORA_EHIP;
   }
   if (dx) {

@@ -429,10 +429,16 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
       const int cx = (2 * kk + (lane >> 5)) << 4;
       const char* ap = as + (a_lane ^ cx);
       const char* bp = bs + (b_lane ^ cx);
+#ifdef QALORA_EXP_FEWER_LDS
+      if (kk == 0) {
+#endif
 #pragma unroll
       for (int a = 0; a < TM; ++a) af[a] = *reinterpret_cast<const uint4*>(ap + a * 4096);
 #pragma unroll
       for (int b = 0; b < TN; ++b) bf[b] = *reinterpret_cast<const uint4*>(bp + b * 4096);
+#ifdef QALORA_EXP_FEWER_LDS
+      }
+#endif
 #pragma unroll
       for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -470,14 +476,33 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     with_step_regions(
         As + sa2 * A_TILE, As + sa * A_TILE, Bs + sb * B_TILE, Bs + (sb ^ 1) * B_TILE,
         [&](uint16_t* a_dma, const uint16_t* a_rd, const uint16_t* b_rd, uint16_t* b_wr) {
+#ifndef QALORA_EXP_NO_A
           if constexpr (kHas2) issue_a(n2, it + 2, a_dma);
+#endif
+          __builtin_amdgcn_sched_barrier(0);
+          // The two wavefronts of a SIMD run the two halves of the step in opposite order,
+          // so one feeds the matrix core while the other dequantises on the vector ALU.
+#ifndef QALORA_EXP_NO_B
+          if (wave >= 4) {
+            if constexpr (kHas1) store_b(n1, it + 1, b_wr);
+            if constexpr (kHas2) gload_b(n2, it + 2);
+          }
+#endif
           __builtin_amdgcn_sched_barrier(0);
           compute(cur, a_rd, b_rd);
-          if constexpr (kHas1) store_b(n1, it + 1, b_wr);
-          if constexpr (kHas2) gload_b(n2, it + 2);
+#ifndef QALORA_EXP_NO_B
+          if (wave < 4) {
+            if constexpr (kHas1) store_b(n1, it + 1, b_wr);
+            if constexpr (kHas2) gload_b(n2, it + 2);
+          }
+#endif
         });
+#ifdef QALORA_EXP_NO_B
+    constexpr int kKeep = kHas2 ? A_LOADS : 0;
+#else
     constexpr int kKeep =
         kHas2 ? A_LOADS + (decltype(n2)::value == 0 ? kBLoadsMain : kBLoadsTail) : 0;
+#endif
     wait_and_barrier<kKeep>();
   };
 

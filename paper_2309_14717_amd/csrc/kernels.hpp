@@ -51,38 +51,36 @@ __host__ __device__ inline int adapter_ktail(int rank) { return rank > 0 ? ((3 *
 // Rows of the hi (and of the lo) section of a bf16 hi/lo split of a [rank, *] matrix.
 __host__ __device__ inline int rank_pad32(int rank) { return ((rank + 31) / 32) * 32; }
 
-// x -> P = pool_g(x) (optional, fp32 [T, L]) and U = P A, written as
-//   rs_out  [T] row scales of x and x16 fp16 [T, d_in] = x * row scale (both optional),
-//   u_ext   bf16 [T, ktail]      = [hi | lo | hi | 0] of sU * row scale (forward tail operand), and/or
-//   us_t    bf16 [2*rp, t_pad]   = rows hi(sU)^T then lo(sU)^T      (dB operand, t contiguous)
-hipError_t launch_pool_down(const uint16_t* x, const float* A, float s, int T, int d_in, int g,
-                            int rank, float* P_out, float2* rs_out, uint16_t* x16,
-                            uint16_t* u_ext, int ktail, uint16_t* us_t, int t_pad,
-                            hipStream_t st);
-// rs[row] = (2^(14-e), 2^(e-14)), e = exponent of the largest |a[row, :]| (bf16 [rows, cols]);
-// a16 = fp16(a * rs[row].x), exact
-hipError_t launch_convert_rows(const uint16_t* a, int rows, int cols, float2* rs, uint16_t* a16,
-                               hipStream_t st);
-// B fp32 [rank, d_out] -> b_ext_t bf16 [d_out, ktail] = [hi | hi | lo | 0] per output column
-hipError_t launch_prep_b_fwd(const float* B, int rank, int d_out, uint16_t* b_ext_t, int ktail,
-                             hipStream_t st);
-// B -> b_hl bf16 [2*rp, d_out] (hi rows then lo rows);  A -> a_ext_t bf16 [L, ktail] = [hi|hi|lo]/g
-hipError_t launch_prep_bwd(const float* A, const float* B, int L, int rank, int d_out, int g,
-                           uint16_t* b_hl, uint16_t* a_ext_t, int ktail, hipStream_t st);
-// dU = s * sum_z (raw[z][:, :rp] + raw[z][:, rp:]) -> dU fp32 [T, rank], and du_ext bf16
-// [T, ktail] = [hi | lo | hi | 0] of dU * rs[t].x (rs = row scales of dy)
-hipError_t launch_du_finalize(const float* raw, int ksplit, int T, int rank, float s,
-                              const float2* rs, float* dU, uint16_t* du_ext, int ktail,
-                              hipStream_t st);
+// Forward front launch: x -> rs (row scales), x16 = fp16(x * scale), and with an adapter
+//   u_ext   bf16 [T, ktail]      = [hi | lo | hi | 0] of s (pool_g(x) A) * row scale
+//   b_ext_t bf16 [d_out, ktail]  = [hi | hi | lo | 0] of B per output column
+hipError_t launch_front_forward(const uint16_t* x, int T, int d_in, float2* rs, uint16_t* x16,
+                                const float* A, const float* B, float s, int g, int rank,
+                                int d_out, uint16_t* u_ext, uint16_t* b_ext_t, int ktail,
+                                hipStream_t st);
+// Backward front launch: dy -> rs_dy, dy16; and with an adapter
+//   P       fp32 [T, L]          = pool_g(x)
+//   us_t    bf16 [2*rp, t_pad]   = rows hi(sU)^T then lo(sU)^T (token-contiguous, zero padded)
+//   b_hl    bf16 [2*rp, d_out]   = hi(B) rows then lo(B) rows
+//   a_ext_t bf16 [L, ktail]      = [hi | hi | lo | 0] of A / g
+hipError_t launch_front_backward(const uint16_t* dy, int T, int d_out, float2* rs_dy,
+                                 uint16_t* dy16, const uint16_t* x, int d_in, const float* A,
+                                 const float* B, float s, int g, int rank, float* P,
+                                 uint16_t* us_t, int t_pad, uint16_t* b_hl, uint16_t* a_ext_t,
+                                 int ktail, hipStream_t st);
 // dB partials over token slices: part[z][rank][d_out] = sum_{t in slice z} sU[t,:]^T dy[t,:]
 hipError_t launch_db_partial(const uint16_t* us_t, int t_pad, const uint16_t* dy, int T, int d_out,
                              int rank, int tsplit, float* part, hipStream_t st);
-// dA partials over token slices: part[z][L][rank] = sum_{t in slice z} P[t,:]^T dU[t,:]
-hipError_t launch_da_partial(const float* P, const float* dU, int T, int L, int rank, int tsplit,
-                             float* part, hipStream_t st);
-// out[i] = (accumulate ? out[i] : 0) + sum_z part[z][i], fixed order
-hipError_t launch_reduce_partials(const float* part, int nparts, size_t n, float* out,
-                                  int accumulate, hipStream_t st);
+// dA partials over token slices, part[z][L][rank] = sum_{t in slice z} P[t,:]^T dU[t,:], with
+// dU = s * sum_q (raw[q][:, :rp] + raw[q][:, rp:]) rebuilt from the split-K partials of the dU
+// product; also writes du_ext bf16 [T, ktail] = [hi | lo | hi | 0] of dU * rs[t].x
+hipError_t launch_da_partial(const float* P, const float* raw, int ksplit, float s,
+                             const float2* rs, int T, int L, int rank, int tsplit, float* part,
+                             uint16_t* du_ext, int ktail, hipStream_t st);
+// out = (accumulate ? out : 0) + sum_z part[z], fixed order, for two outputs in one launch
+hipError_t launch_reduce2(const float* part_a, int nparts_a, size_t n_a, float* out_a,
+                          const float* part_b, int nparts_b, size_t n_b, float* out_b,
+                          int accumulate, hipStream_t st);
 // beta_out = beta + (s/g) A B
 hipError_t launch_merge(const float* beta, const float* A, const float* B, int L, int d_out,
                         int rank, int g, float s, float* beta_out, hipStream_t st);
