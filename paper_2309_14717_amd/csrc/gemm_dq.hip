@@ -24,11 +24,12 @@
 // either axis -- down the rows (forward, K = input rows) or across the columns (backward,
 // K = output columns).
 //
-// Tiling: 512 threads = 8 wavefronts (two per SIMD, so one can dequantise while the other
-// feeds the matrix core), block tile BM x BN x 64, double-buffered in LDS.  The A tile goes
-// global -> LDS directly (128-bit LDS-DMA loads, no registers); the B tile goes through
-// registers for dequantisation.  LDS rows are 128 bytes, XOR-swizzled so that operand reads
-// (16 consecutive rows, one 16-byte chunk) and both producers' writes are bank-conflict free.
+// Tiling: 512 threads = 8 wavefronts (two per SIMD), block tile BM x BN x 64.  The A tile
+// goes global -> LDS directly (128-bit buffer LDS-DMA loads, no registers), three stages deep,
+// issued two K steps ahead; the B tile goes through registers for dequantisation into two LDS
+// stages.  Loads stay in flight across the per-step barrier (counted s_waitcnt).  LDS rows are
+// 128 bytes, XOR-swizzled so that operand reads (16 consecutive rows, one 16-byte chunk) and
+// all producers' writes are bank-conflict free.
 #include <type_traits>
 
 #include "common.hpp"
@@ -134,9 +135,16 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
 
   const int tiles_m = ceil_div(p.M, BM);
   const int tiles_n = ceil_div(p.N, BN);
+  // Each XCD gets a contiguous run of tile ids, and ids walk bands of kGroupM row tiles across
+  // all column tiles: the 32 blocks resident on one XCD then share kGroupM activation row
+  // panels and 32 / kGroupM weight column panels in that XCD's L2.
   const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
-  const int m0 = (tile % tiles_m) * BM;
-  const int n0 = (tile / tiles_m) * BN;
+  constexpr int kGroupM = 4;
+  const int band = tile / (kGroupM * tiles_n);
+  const int band_rows = min(kGroupM, tiles_m - band * kGroupM);
+  const int in_band = tile - band * kGroupM * tiles_n;
+  const int m0 = (band * kGroupM + in_band % band_rows) * BM;
+  const int n0 = (in_band / band_rows) * BN;
 
   const int nk_main = HAS_MAIN ? ceil_div(p.K_main, BK) : 0;
   const int nk_tail = ceil_div(p.K_tail, BK);
@@ -423,38 +431,35 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     constexpr bool kMain = decltype(kind)::value == 0;
     const char* as = reinterpret_cast<const char*>(a_src);
     const char* bs = reinterpret_cast<const char*>(b_src);
-    uint4 af[TM], bf[TN];
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
+    uint4 af[2][TM], bf[2][TN];
+    auto load_frags = [&](int kk, int slot) {
       const int cx = (2 * kk + (lane >> 5)) << 4;
       const char* ap = as + (a_lane ^ cx);
       const char* bp = bs + (b_lane ^ cx);
-#ifdef QALORA_EXP_FEWER_LDS
-      if (kk == 0) {
-#endif
 #pragma unroll
-      for (int a = 0; a < TM; ++a) af[a] = *reinterpret_cast<const uint4*>(ap + a * 4096);
+      for (int a = 0; a < TM; ++a) af[slot][a] = *reinterpret_cast<const uint4*>(ap + a * 4096);
 #pragma unroll
-      for (int b = 0; b < TN; ++b) bf[b] = *reinterpret_cast<const uint4*>(bp + b * 4096);
-#ifdef QALORA_EXP_FEWER_LDS
-      }
-#endif
+      for (int b = 0; b < TN; ++b) bf[slot][b] = *reinterpret_cast<const uint4*>(bp + b * 4096);
+    };
+    load_frags(0, 0);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      const int cur = kk & 1;
+      if (kk + 1 < BK / 16) load_frags(kk + 1, cur ^ 1);  // next slice in flight under the MFMAs
 #pragma unroll
       for (int a = 0; a < TM; ++a)
 #pragma unroll
         for (int b = 0; b < TN; ++b) {
           if constexpr (kMain)
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                __builtin_bit_cast(f16x8, af[a]), __builtin_bit_cast(f16x8, bf[b]), acc[a][b], 0,
-                0, 0);
+                __builtin_bit_cast(f16x8, af[cur][a]), __builtin_bit_cast(f16x8, bf[cur][b]),
+                acc[a][b], 0, 0, 0);
           else
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                __builtin_bit_cast(bf16x8, af[a]), __builtin_bit_cast(bf16x8, bf[b]), acc[a][b],
-                0, 0, 0);
+                __builtin_bit_cast(bf16x8, af[cur][a]), __builtin_bit_cast(bf16x8, bf[cur][b]),
+                acc[a][b], 0, 0, 0);
         }
-      // one K-16 slice of fragments live at a time; the other wavefront of the SIMD covers
-      // the LDS latency
-      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_sched_barrier(0);  // keep the fragment prefetch depth at one slice
     }
   };
 
@@ -476,33 +481,14 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     with_step_regions(
         As + sa2 * A_TILE, As + sa * A_TILE, Bs + sb * B_TILE, Bs + (sb ^ 1) * B_TILE,
         [&](uint16_t* a_dma, const uint16_t* a_rd, const uint16_t* b_rd, uint16_t* b_wr) {
-#ifndef QALORA_EXP_NO_A
           if constexpr (kHas2) issue_a(n2, it + 2, a_dma);
-#endif
-          __builtin_amdgcn_sched_barrier(0);
-          // The two wavefronts of a SIMD run the two halves of the step in opposite order,
-          // so one feeds the matrix core while the other dequantises on the vector ALU.
-#ifndef QALORA_EXP_NO_B
-          if (wave >= 4) {
-            if constexpr (kHas1) store_b(n1, it + 1, b_wr);
-            if constexpr (kHas2) gload_b(n2, it + 2);
-          }
-#endif
           __builtin_amdgcn_sched_barrier(0);
           compute(cur, a_rd, b_rd);
-#ifndef QALORA_EXP_NO_B
-          if (wave < 4) {
-            if constexpr (kHas1) store_b(n1, it + 1, b_wr);
-            if constexpr (kHas2) gload_b(n2, it + 2);
-          }
-#endif
+          if constexpr (kHas1) store_b(n1, it + 1, b_wr);
+          if constexpr (kHas2) gload_b(n2, it + 2);
         });
-#ifdef QALORA_EXP_NO_B
-    constexpr int kKeep = kHas2 ? A_LOADS : 0;
-#else
     constexpr int kKeep =
         kHas2 ? A_LOADS + (decltype(n2)::value == 0 ? kBLoadsMain : kBLoadsTail) : 0;
-#endif
     wait_and_barrier<kKeep>();
   };
 
