@@ -100,6 +100,11 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
+// The small-token streaming path covers INT4 with groups that are whole 32-row MFMA blocks.
+inline bool use_smallt(const qalora_desc& d, int tokens) {
+  return tokens <= 16 && d.bits == 4 && d.group % 32 == 0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -138,7 +143,16 @@ size_t qalora_workspace_bytes(const qalora_desc* d, int tokens, int op) {
   switch (op) {
     case QALORA_OP_QUANTIZE:
     case QALORA_OP_MERGE: return 0;
-    case QALORA_OP_FORWARD: return tokens > 0 ? plan_forward(*d, tokens).total : 0;
+    case QALORA_OP_FORWARD: {
+      if (tokens <= 0) return 0;
+      size_t need = plan_forward(*d, tokens).total;
+      if (use_smallt(*d, tokens)) {
+        const int ks = smallt_ksplit(d->d_in, d->d_out, d->group);
+        const size_t st = ks > 1 ? align_up((size_t)ks * tokens * d->d_out * 4) : 0;
+        if (st > need) need = st;
+      }
+      return need;
+    }
     case QALORA_OP_BACKWARD: return tokens > 0 ? plan_backward(*d, tokens).total : 0;
     default: return 0;
   }
@@ -187,6 +201,25 @@ int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* 
       misaligned(A) || misaligned(B) || misaligned(y) || misaligned(ws))
     return QALORA_EALIGN;
   const bool adapter = A && B && d->rank > 0;
+  if (!adapter && use_smallt(*d, tokens)) {
+    // memory-bound regime: stream the weight once on the exact-operand path
+    const int ks = smallt_ksplit(d->d_in, d->d_out, d->group);
+    const size_t need = ks > 1 ? align_up((size_t)ks * tokens * d->d_out * 4) : 0;
+    if (need > 0 && (!ws || ws_bytes < need)) return QALORA_EWORKSPACE;
+    SmallTArgs a{};
+    a.x = static_cast<const uint16_t*>(x);
+    a.plane0 = static_cast<const uint32_t*>(packed);
+    a.alpha = alpha;
+    a.beta = beta;
+    a.out = y;
+    a.partial = static_cast<float*>(ws);
+    a.out_bf16 = (y_dtype == QALORA_BF16);
+    a.T = tokens;
+    a.d_in = d->d_in;
+    a.d_out = d->d_out;
+    a.group = d->group;
+    return launch_smallt(a, ks, as_stream(stream)) == hipSuccess ? QALORA_OK : QALORA_EHIP;
+  }
   FwdPlan plan = plan_forward(*d, tokens);
   if (!adapter) plan.total = plan.a16 + align_up((size_t)round_up(tokens, 256) * d->d_in * 2);
   if (!ws || ws_bytes < plan.total) return QALORA_EWORKSPACE;

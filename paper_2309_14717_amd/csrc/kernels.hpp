@@ -44,6 +44,21 @@ struct ProfileHook {
 extern ProfileHook g_profile_hook[2];
 hipError_t launch_gemm_plain(const GemmArgs& a, int ksplit, hipStream_t st);
 
+// --- smallt.hip ---------------------------------------------------------------------
+// Adapter-free forward for T <= 16 tokens, INT4, group a multiple of 32 (memory-bound path).
+struct SmallTArgs {
+  const uint16_t* x;       // bf16 [T, d_in]
+  const uint32_t* plane0;  // packed INT4 codes
+  const float* alpha;      // [L, d_out]
+  const float* beta;       // [L, d_out]
+  void* out;               // [T, d_out] fp32 or bf16
+  float* partial;          // [ksplit, T, d_out] fp32 when ksplit > 1
+  int out_bf16;
+  int T, d_in, d_out, group;
+};
+int smallt_ksplit(int d_in, int d_out, int group);
+hipError_t launch_smallt(const SmallTArgs& a, int ksplit, hipStream_t st);
+
 // --- adapter.hip --------------------------------------------------------------------
 // Tail width of the adapter operands: three bf16 sections of `rank` columns, zero padded
 // to a multiple of 64.

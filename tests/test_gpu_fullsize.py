@@ -1,0 +1,101 @@
+"""GPU parity at the full benchmark sizes, in the launch configurations bench.py times.
+
+The dense outputs (y, dx) are compared on sampled token rows -- every output row depends on its
+own input row only, so the oracle evaluates exactly those rows, over ALL columns (tile-edge rows
+0/255/256/... are always in the sample).  The adapter gradients (dA, dB) reduce over all tokens
+and are compared in full.  Codes, alpha, beta are compared bit for bit in full."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2309_14717_amd import synth
+from helpers import TOL, dev, layer_on_gpu, record, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_rows(T, extra=6, seed=0):
+    edge = [0, 1, 31, 32, 63, 64, 127, 128, 255, 256, 257, T // 2, T - 257, T - 256, T - 1]
+    rng = np.random.default_rng(seed)
+    rows = sorted(set([r for r in edge if 0 <= r < T] + rng.integers(0, T, extra).tolist()))
+    return np.array(rows)
+
+
+def check_layer(gpu_api, cfg, rows=None, check_grads=True):
+    L = layer_on_gpu(gpu_api, cfg)
+    d = L["np"]
+    assert np.array_equal(gpu_api.unpack(L["desc"], L["packed"]).cpu().numpy(), L["codes"])
+    assert np.array_equal(L["g_alpha"].cpu().numpy().view(np.uint32), L["alpha"].view(np.uint32))
+    assert np.array_equal(L["g_beta"].cpu().numpy().view(np.uint32), L["beta"].view(np.uint32))
+    rows = sample_rows(cfg.tokens) if rows is None else rows
+    y = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"], L["A"], L["B"])
+    ref = oracle.forward(d["x"][rows], L["codes"], L["alpha"], L["beta"], cfg.group, d["A"], d["B"], cfg.s)
+    errs = dict(y=rel_err(y[torch.from_numpy(rows).cuda()].cpu().numpy(), ref))
+    dx, dA, dB = gpu_api.backward(L["desc"], L["dy"], L["x"], L["packed"], L["g_alpha"], L["g_beta"],
+                                  L["A"], L["B"])
+    rdx, _, _ = oracle.backward(d["dy"][rows], d["x"][rows], L["codes"], L["alpha"], L["beta"], cfg.group,
+                                d["A"], d["B"], cfg.s, want_dAdB=False)
+    errs["dx"] = rel_err(dx[torch.from_numpy(rows).cuda()].cpu().numpy(), rdx)
+    if check_grads:
+        _, rdA, rdB = oracle.backward(d["dy"], d["x"], L["codes"], L["alpha"], L["beta"], cfg.group,
+                                      d["A"], d["B"], cfg.s, want_dx=False)
+        errs["dA"] = rel_err(dA.cpu().numpy(), rdA)
+        errs["dB"] = rel_err(dB.cpu().numpy(), rdB)
+    record(f"fullsize {cfg.name} N={cfg.bits} g={cfg.group} T={cfg.tokens}", **errs)
+    assert max(errs.values()) <= TOL, errs
+    return L
+
+
+def test_config2_attention_projection(gpu_api):
+    check_layer(gpu_api, synth.CONFIGS["c2"])
+
+
+@pytest.mark.parametrize("name", ["c3_gate", "c3_down"])
+def test_config3_mlp_shapes(gpu_api, name):
+    check_layer(gpu_api, synth.CONFIGS[name], rows=sample_rows(4096, extra=2))
+
+
+@pytest.mark.parametrize("bits,group", [(2, 32), (3, 32), (4, 32), (2, 64), (4, 64), (2, 128), (3, 128), (4, 128), (3, 64)])
+def test_config4_low_bit_sweep(gpu_api, bits, group):
+    cfg = synth.CONFIGS["c4"].scaled(bits=bits, group=group)
+    L = check_layer(gpu_api, cfg, rows=sample_rows(cfg.tokens, extra=0)[::2], check_grads=(group == 32))
+    # merge, then the post-merge quantized forward against the adapted one (App. B.3)
+    d = L["np"]
+    rows = np.array([0, 255, 256, cfg.tokens - 1])
+    beta_m = gpu_api.merge(L["desc"], L["g_beta"], L["A"], L["B"])
+    ref_m = oracle.merge(L["beta"], d["A"], d["B"], cfg.group, cfg.s)
+    assert rel_err(beta_m.cpu().numpy(), ref_m) <= 1e-5
+    y_m = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], beta_m)
+    ref = oracle.forward(d["x"][rows], L["codes"], L["alpha"], L["beta"], cfg.group, d["A"], d["B"], cfg.s)
+    err = rel_err(y_m[torch.from_numpy(rows).cuda()].cpu().numpy(), ref)
+    record(f"fullsize c4 post-merge N={bits} g={group}", y=err)
+    assert err <= TOL
+
+
+@pytest.mark.parametrize("name", ["c5_up", "c5_down"])
+def test_config5_post_merge_inference(gpu_api, name):
+    """Merged model, adapter-free forward at T in {1, 4, 16} (streaming path, full oracle) and
+    T = 256 (matrix path, sampled rows)."""
+    cfg = synth.CONFIGS[name].scaled(tokens=256)
+    L = layer_on_gpu(gpu_api, cfg)
+    d = L["np"]
+    beta_m = gpu_api.merge(L["desc"], L["g_beta"], L["A"], L["B"])
+    ref_beta = oracle.merge(L["beta"], d["A"], d["B"], cfg.group, cfg.s)
+    assert rel_err(beta_m.cpu().numpy(), ref_beta) <= 1e-5
+    beta_np = beta_m.cpu().numpy()  # what the device will use from here on
+    ref16 = oracle.forward(d["x"][:16], L["codes"], L["alpha"], beta_np, cfg.group)
+    for T in (1, 4, 16):
+        y = gpu_api.forward(L["desc"], L["x"][:T].contiguous(), L["packed"], L["g_alpha"], beta_m)
+        err = rel_err(y.cpu().numpy(), ref16[:T])
+        record(f"fullsize {name} post-merge T={T}", y=err)
+        assert err <= 1e-5  # exact-operand path: only fp32 accumulation order differs
+        yb = gpu_api.forward(L["desc"], L["x"][:T].contiguous(), L["packed"], L["g_alpha"], beta_m,
+                             out_dtype=torch.bfloat16)
+        assert torch.equal(yb, y.to(torch.bfloat16))
+    rows = np.array([0, 17, 63, 64, 128, 255])
+    y256 = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], beta_m)
+    ref = oracle.forward(d["x"][rows], L["codes"], L["alpha"], beta_np, cfg.group)
+    err = rel_err(y256[torch.from_numpy(rows).cuda()].cpu().numpy(), ref)
+    record(f"fullsize {name} post-merge T=256", y=err)
+    assert err <= TOL

@@ -201,3 +201,20 @@ def test_rerun_is_bit_identical(gpu_api):
 def test_unsupported_shape_raises(gpu_api):
     with pytest.raises(gpu_api.QaloraError):
         gpu_api.quantize(gpu_api.make_desc(36, 64, 4, 4), torch.zeros(36, 64, device="cuda"))
+
+
+# ------------------------------------------------------------------ small-token streaming path
+@pytest.mark.parametrize("tokens", [1, 3, 16])
+@pytest.mark.parametrize("group,d_in,d_out", [(32, 1024, 520), (64, 2048, 136), (128, 768, 64)])
+def test_small_token_forward(gpu_api, tokens, group, d_in, d_out):
+    """T <= 16, adapter-free, INT4: exact-operand streaming kernel (ragged column slab, uneven
+    split of the groups over wavefronts and blocks)."""
+    cfg = synth.LayerConfig("st", tokens, d_in, d_out, 4, group, 8, 0.5, seed=11)
+    L = layer_on_gpu(gpu_api, cfg)
+    y = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"])
+    ref = oracle.forward(L["np"]["x"], L["codes"], L["alpha"], L["beta"], cfg.group)
+    err = rel_err(y.cpu().numpy(), ref)
+    record(f"small_token T={tokens} g={group} {d_in}x{d_out}", y=err)
+    assert err <= 1e-5
+    y2 = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"])
+    assert torch.equal(y, y2)
