@@ -100,9 +100,20 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
-// The small-token streaming path covers INT4 with groups that are whole 32-row MFMA blocks.
+// The small-token streaming path covers INT4 with groups of 32, 64 or 128 rows, input widths
+// that are whole 128-row chunks, and operands its 32-bit buffer offsets can address.
 inline bool use_smallt(const qalora_desc& d, int tokens) {
-  return tokens <= 16 && d.bits == 4 && d.group % 32 == 0;
+  if (tokens > 16 || d.bits != 4) return false;
+  if (d.group != 32 && d.group != 64 && d.group != 128) return false;
+  if (d.d_in % 128 != 0) return false;
+  return (size_t)d.d_in / 8 * (size_t)d.d_out * 4 < 0xf0000000ull;
+}
+
+// Workspace of the small-token path: one flag and one [16 x slab] fp32 partial per block.
+inline size_t smallt_workspace(const qalora_desc& d, int tokens) {
+  (void)tokens;
+  return align_up((size_t)ST_MAX_BLOCKS * 8) +
+         align_up((size_t)smallt_plan(d.d_in, d.d_out).blocks * ST_PARTIAL_FLOATS * 4);
 }
 
 }  // namespace
@@ -147,8 +158,7 @@ size_t qalora_workspace_bytes(const qalora_desc* d, int tokens, int op) {
       if (tokens <= 0) return 0;
       size_t need = plan_forward(*d, tokens).total;
       if (use_smallt(*d, tokens)) {
-        const int ks = smallt_ksplit(d->d_in, d->d_out, d->group);
-        const size_t st = ks > 1 ? align_up((size_t)ks * tokens * d->d_out * 4) : 0;
+        const size_t st = smallt_workspace(*d, tokens);
         if (st > need) need = st;
       }
       return need;
@@ -203,22 +213,22 @@ int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* 
   const bool adapter = A && B && d->rank > 0;
   if (!adapter && use_smallt(*d, tokens)) {
     // memory-bound regime: stream the weight once on the exact-operand path
-    const int ks = smallt_ksplit(d->d_in, d->d_out, d->group);
-    const size_t need = ks > 1 ? align_up((size_t)ks * tokens * d->d_out * 4) : 0;
-    if (need > 0 && (!ws || ws_bytes < need)) return QALORA_EWORKSPACE;
+    const size_t need = smallt_workspace(*d, tokens);
+    if (!ws || ws_bytes < need) return QALORA_EWORKSPACE;
     SmallTArgs a{};
     a.x = static_cast<const uint16_t*>(x);
     a.plane0 = static_cast<const uint32_t*>(packed);
     a.alpha = alpha;
     a.beta = beta;
     a.out = y;
-    a.partial = static_cast<float*>(ws);
+    a.flags = static_cast<unsigned long long*>(ws);
+    a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + align_up((size_t)ST_MAX_BLOCKS * 8));
     a.out_bf16 = (y_dtype == QALORA_BF16);
     a.T = tokens;
     a.d_in = d->d_in;
     a.d_out = d->d_out;
     a.group = d->group;
-    return launch_smallt(a, ks, as_stream(stream)) == hipSuccess ? QALORA_OK : QALORA_EHIP;
+    return launch_smallt(a, as_stream(stream)) == hipSuccess ? QALORA_OK : QALORA_EHIP;
   }
   FwdPlan plan = plan_forward(*d, tokens);
   if (!adapter) plan.total = plan.a16 + align_up((size_t)round_up(tokens, 256) * d->d_in * 2);

@@ -45,19 +45,28 @@ extern ProfileHook g_profile_hook[2];
 hipError_t launch_gemm_plain(const GemmArgs& a, int ksplit, hipStream_t st);
 
 // --- smallt.hip ---------------------------------------------------------------------
-// Adapter-free forward for T <= 16 tokens, INT4, group a multiple of 32 (memory-bound path).
+// Adapter-free forward for T <= 16 tokens, INT4, group 32 / 64 / 128 (memory-bound path).
+constexpr int ST_MAX_BLOCKS = 256; // one block per compute unit
+constexpr int ST_PARTIAL_FLOATS = 16 * 512;  // one [16 tokens x widest slab] tile per block
 struct SmallTArgs {
   const uint16_t* x;       // bf16 [T, d_in]
   const uint32_t* plane0;  // packed INT4 codes
   const float* alpha;      // [L, d_out]
   const float* beta;       // [L, d_out]
   void* out;               // [T, d_out] fp32 or bf16
-  float* partial;          // [ksplit, T, d_out] fp32 when ksplit > 1
+  float* partial;          // [blocks][ST_PARTIAL_FLOATS] fp32, accumulator-register layout: runs that end inside a slab
+  unsigned long long* flags;  // [blocks]: set to `nonce` once the block's partial is complete
+  unsigned long long nonce;   // filled in by the launcher, unique per call
   int out_bf16;
   int T, d_in, d_out, group;
 };
-int smallt_ksplit(int d_in, int d_out, int group);
-hipError_t launch_smallt(const SmallTArgs& a, int ksplit, hipStream_t st);
+// Launch shape: blocks = slabs * parts; `halves` (1 or 2) is how many ways a block splits its
+// own chunks, which sets the slab width (512 or 256 columns).
+struct SmallTPlan {
+  int halves, slab_cols, slabs, parts, blocks;
+};
+SmallTPlan smallt_plan(int d_in, int d_out);
+hipError_t launch_smallt(const SmallTArgs& a, hipStream_t st);
 
 // --- adapter.hip --------------------------------------------------------------------
 // Tail width of the adapter operands: three bf16 sections of `rank` columns, zero padded

@@ -10,141 +10,376 @@
 // sums of x in exactly the accumulator layout the update needs.  alpha and beta are applied in
 // fp32 once per group, so this path is more accurate than the large-T one.
 //
-// Streaming: a wavefront owns 64 output columns and a range of groups; per group it issues
-// three 16-byte loads per lane (codes, alpha, beta: 1 KB + 256 B + 256 B contiguous pieces) and
-// one for x.  The eight wavefronts of a block split the groups of one 64-column slab and
-// combine through LDS in fixed order; blocks may further split K (partials reduced by a
-// second small kernel, fixed order).
+// Decomposition.  The weight is cut into slabs of 256 or 512 output columns, and the 128-row
+// chunks of each slab into m equal parts, m chosen so that slabs x m fills the 256 compute units
+// with one block each; every block streams the same number of bytes.  Parts 0 .. m-2 leave
+// their partial result in the workspace and raise a flag; the block of the last part (the
+// highest-numbered one, so the others are already running or finished) waits for the flags,
+// adds the partials in part order, then its own, and writes y.  The order of every sum is
+// fixed by the shape alone: reruns are bit-identical.  The waits are bounded; if one ever ran
+// out the block would write NaN instead of a wrong number.
+//
+// Inside a block the sixteen wavefronts are column groups of 32 columns each: sixteen of them
+// (512-column slab), or eight times two halves of the block's chunks (256-column slab; the
+// halves meet in LDS at the end).  x for the block's rows is staged once in LDS (one token
+// row per wavefront) and read from there as MFMA operands, so the only traffic through the
+// texture path is the weight itself.  Per chunk a lane issues four 8-byte code loads (2 columns
+// x 8 rows each) and ONE alpha and ONE beta load: lane group kb = lane / 16 fetches the factors
+// of the chunk's kb-th quantization group and the wavefront hands them round with ds_bpermute.
+// All of them are buffer loads whose per-lane offset is fixed (the running position lives in
+// the scalar offset); lanes outside the matrix read zeros from the range check.  Three chunk
+// buffers rotate, so two chunks of loads are always in flight behind the one being multiplied.
+#include <atomic>
+
 #include "common.hpp"
 #include "kernels.hpp"
 
 namespace qalora {
 
-constexpr int ST_WAVES = 8;
+namespace {
 
-__global__ __launch_bounds__(64 * ST_WAVES) void smallt_kernel(const SmallTArgs p) {
-  __shared__ float red[ST_WAVES][16][64];
+constexpr int ST_WAVES = 16;
+constexpr int ST_THREADS = 64 * ST_WAVES;
+constexpr int ST_CW = 2;                         // columns per lane
+constexpr int ST_WCOLS = 16 * ST_CW;             // columns per wavefront
+constexpr int ST_XCHUNKS = 32;                   // chunks of x staged in LDS at a time
+constexpr int ST_XROW = ST_XCHUNKS * 256 + 16;   // bytes per token row in LDS (+16: bank spread)
+constexpr int ST_XPIECES = ST_XCHUNKS * 16 / 64; // 1 KB wavefront copies per staged token row
+constexpr uint32_t ST_SPIN_LIMIT = 1u << 18;     // bounded wait: the kernel always terminates
+constexpr uint32_t kStOob = 0xffff0000u;         // beyond every buffer: the range check returns zero
+constexpr int ST_NT = 2;                         // cache policy "nontemporal": streamed once
+
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t st_rsrc(const void* base, size_t bytes) {
+  const uint32_t n = bytes > 0xffffffffull ? 0xffffffffu : (uint32_t)bytes;
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)n, 0x00020000);
+}
+
+// One 128-row chunk of a wavefront's weight operands, as loaded.
+struct Chunk {
+  u32x2 w[4];    // codes: step st = rows 32*st + 8*kb .. +7 of the lane's 2 columns
+  u32x2 al, be;  // factors of group (first group of the chunk) + kb
+};
+
+// LDS-only barrier: does not wait for the global loads that are in flight.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+}  // namespace
+
+// SUB : 32-row steps per quantization group (group = 32 * SUB; 1, 2 or 4)
+// KH  : ways a block splits its own chunks (1: sixteen column groups, slab of 512 columns;
+//       2: eight column groups x two halves, slab of 256 columns)
+template <int SUB, int KH>
+__global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) {
+  extern __shared__ __align__(16) unsigned char xs[];  // [16][ST_XROW]
+  __shared__ int poison;
+  constexpr int CW = ST_CW;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, kb = lane >> 4;
-  const int j0 = blockIdx.x * 64 + 4 * n;  // this lane's 4 columns
-  const bool col_ok = j0 < p.d_out;
+  constexpr int NCG = ST_WAVES / KH;   // column groups (32 columns each)
+  constexpr int ST_SLAB_COLS = NCG * ST_WCOLS;
+  const int cg = wave % NCG;
+  const int kh = wave / NCG;           // which share of every staged piece's chunks
   const int L = p.d_in / p.group;
-  const int sub = p.group / 32;  // 32-row MFMA blocks per group
+  const int C = p.d_in / 128;                      // chunks per slab
+  const int S = ceil_div(p.d_out, ST_SLAB_COLS);   // slabs
+  const int m = gridDim.x / S;                     // parts per slab
+  const int b = blockIdx.x, s = b / m, part = b - s * m;
+  const int ca = (int)((long)C * part / m), ce = (int)((long)C * (part + 1) / m);
 
-  // groups of this block, then of this wavefront
-  const int per_block = ceil_div(L, (int)gridDim.y);
-  const int gb = blockIdx.y * per_block, ge = min(L, gb + per_block);
-  const int per_wave = ceil_div(max(ge - gb, 0), ST_WAVES);
-  const int l_begin = gb + wave * per_wave, l_end = min(ge, l_begin + per_wave);
-
-  f32x4 acc[4];
-#pragma unroll
-  for (int q = 0; q < 4; ++q) acc[q] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-
-  const uint32_t kMask = 0x000f000fu;
-  const bf16x8 ones = __builtin_bit_cast(bf16x8, uint4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
-  const bool row_ok = n < p.T;  // A operand row = token n
-  const uint16_t* xrow = p.x + (size_t)(row_ok ? n : 0) * p.d_in + 8 * kb;
-  const uint32_t* wcol = p.plane0 + (size_t)kb * p.d_out + (col_ok ? j0 : 0);
-
-#pragma unroll 2
-  for (int l = l_begin; l < l_end; ++l) {
-    f32x4 d[4], dsx = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-    for (int q = 0; q < 4; ++q) d[q] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    for (int sb = 0; sb < sub; ++sb) {
-      const int i0 = l * p.group + 32 * sb;
-      uint4 w = *reinterpret_cast<const uint4*>(wcol + (size_t)(i0 / 8) * p.d_out);
-      uint4 xa = *reinterpret_cast<const uint4*>(xrow + i0);
-      if (!row_ok) xa = uint4{0, 0, 0, 0};
-      if (!col_ok) w = uint4{0, 0, 0, 0};
-      const bf16x8 a = __builtin_bit_cast(bf16x8, xa);
-      const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        uint4 b;
-        b.x = (ww[q] & kMask) | 0x43004300u;
-        b.y = ((ww[q] >> 4) & kMask) | 0x43004300u;
-        b.z = ((ww[q] >> 8) & kMask) | 0x43004300u;
-        b.w = ((ww[q] >> 12) & kMask) | 0x43004300u;
-        d[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b), d[q], 0, 0, 0);
-      }
-      dsx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ones, dsx, 0, 0, 0);
-    }
-    f32x4 al = f32x4{0.0f, 0.0f, 0.0f, 0.0f}, be = al;
-    if (col_ok) {
-      al = *reinterpret_cast<const f32x4*>(p.alpha + (size_t)l * p.d_out + j0);
-      be = *reinterpret_cast<const f32x4*>(p.beta + (size_t)l * p.d_out + j0);
-    }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float bp = __builtin_fmaf(-128.0f, al[q], be[q]);  // codes carry a +128 offset
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-        acc[q][r] = __builtin_fmaf(al[q], d[q][r], __builtin_fmaf(bp, dsx[r], acc[q][r]));
-    }
+  if (tid == 0) poison = 0;
+  // token rows that do not exist stay zero for the whole kernel
+  if (wave >= p.T) {
+    for (int o = lane; o < ST_XROW / 16; o += 64)
+      *reinterpret_cast<u32x4*>(xs + wave * ST_XROW + o * 16) = u32x4{0, 0, 0, 0};
   }
 
-  // combine the wavefronts of the block in fixed order
+  const __amdgpu_buffer_rsrc_t rs_w = st_rsrc(p.plane0, (size_t)(p.d_in / 8) * p.d_out * 4);
+  const __amdgpu_buffer_rsrc_t rs_x = st_rsrc(p.x, (size_t)p.T * p.d_in * 2);
+  const __amdgpu_buffer_rsrc_t rs_al = st_rsrc(p.alpha, (size_t)L * p.d_out * 4);
+  const __amdgpu_buffer_rsrc_t rs_be = st_rsrc(p.beta, (size_t)L * p.d_out * 4);
+  const uint32_t step_w = 4u * p.d_out * 4u;  // four packed rows per 32-row step
+  const uint32_t row_ab = (uint32_t)p.d_out * 4u;
+  // Mask and bias live in registers (not literals) so that "(w >> k) & mask | bias" is one
+  // shift and one v_and_or_b32: a VOP3 instruction cannot carry a 32-bit literal on this target.
+  uint32_t kMask, kBias;
+  asm volatile("s_mov_b32 %0, 0x000f000f" : "=s"(kMask));
+  asm volatile("v_mov_b32 %0, 0x43004300" : "=v"(kBias));
+  const bf16x8 ones = __builtin_bit_cast(bf16x8, u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
+  const f32x4 zero4 = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  const unsigned char* xs_lane = xs + n * ST_XROW + 16 * kb;
+
+  {
+    const int jw = cg * ST_WCOLS + CW * n;  // column inside the slab
+    const int j0 = s * ST_SLAB_COLS + jw;
+    const bool col_ok = j0 < p.d_out;
+    const uint32_t voff_w = col_ok ? ((uint32_t)kb * p.d_out + j0) * 4u : kStOob;
+    const uint32_t voff_ab = (col_ok && kb < 4 / SUB) ? ((uint32_t)kb * p.d_out + j0) * 4u : kStOob;
+
+    auto load_chunk = [&](Chunk& ch, int c) {
+      c = min(c, C - 1);  // prefetches past the range re-read the last chunk (unused)
 #pragma unroll
-  for (int q = 0; q < 4; ++q)
+      for (int st = 0; st < 4; ++st)
+        ch.w[st] = __builtin_amdgcn_raw_buffer_load_b64(rs_w, (int)voff_w,
+                                                        (int)((uint32_t)(4 * c + st) * step_w), ST_NT);
+      const uint32_t so = (uint32_t)(4 * c / SUB) * row_ab;
+      ch.al = __builtin_amdgcn_raw_buffer_load_b64(rs_al, (int)voff_ab, (int)so, ST_NT);
+      ch.be = __builtin_amdgcn_raw_buffer_load_b64(rs_be, (int)voff_ab, (int)so, ST_NT);
+    };
+
+    f32x4 acc[CW];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) red[wave][4 * q + r][lane] = acc[q][r];
-  __syncthreads();
-  // wavefront w finishes accumulator registers 2w and 2w+1
+    for (int q = 0; q < CW; ++q) acc[q] = zero4;
+
+    // xrel: chunk index relative to the staged piece
+    auto compute_chunk = [&](const Chunk& ch, int xrel) {
+      u32x4 xa[4];
 #pragma unroll
-  for (int e = 0; e < 2; ++e) {
-    const int reg = 2 * wave + e;
-    float v = 0.0f;
+      for (int st = 0; st < 4; ++st)
+        xa[st] = *reinterpret_cast<const u32x4*>(xs_lane + xrel * 256 + st * 64);
+      f32x4 d[CW], dsx;
 #pragma unroll
-    for (int w = 0; w < ST_WAVES; ++w) v += red[w][reg][lane];
-    const int q = reg >> 2, r = reg & 3;
-    const int row = 4 * kb + r, col = j0 + q;  // D layout: lane (n, kb) holds rows 4*kb + r
-    if (row < p.T && col_ok) {
-      if (gridDim.y > 1) {
-        p.partial[((size_t)blockIdx.y * p.T + row) * p.d_out + col] = v;
-      } else if (p.out_bf16) {
-        static_cast<uint16_t*>(p.out)[(size_t)row * p.d_out + col] = f32_to_bf16_bits(v);
-      } else {
-        static_cast<float*>(p.out)[(size_t)row * p.d_out + col] = v;
+      for (int st = 0; st < 4; ++st) {
+        const bool first = (st % SUB) == 0, last = (st % SUB) == SUB - 1;
+        const bf16x8 a = __builtin_bit_cast(bf16x8, xa[st]);
+#pragma unroll
+        for (int q = 0; q < CW; ++q) {
+          const uint32_t w = ch.w[st][q];
+          u32x4 bv;
+          bv.x = (w & kMask) | kBias;
+          bv.y = ((w >> 4) & kMask) | kBias;
+          bv.z = ((w >> 8) & kMask) | kBias;
+          bv.w = ((w >> 12) & kMask) | kBias;
+          d[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bv),
+                                                         first ? zero4 : d[q], 0, 0, 0);
+        }
+        dsx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ones, first ? zero4 : dsx, 0, 0, 0);
+        if (last) {
+          const int src = (n + 16 * (st / SUB)) * 4;  // the lane group holding this group's factors
+#pragma unroll
+          for (int q = 0; q < CW; ++q) {
+            const float al = __int_as_float(__builtin_amdgcn_ds_bpermute(src, (int)ch.al[q]));
+            const float be = __int_as_float(__builtin_amdgcn_ds_bpermute(src, (int)ch.be[q]));
+            const float bp = __builtin_fmaf(-128.0f, al, be);  // codes carry a +128 offset
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              acc[q][r] = __builtin_fmaf(al, d[q][r], __builtin_fmaf(bp, dsx[r], acc[q][r]));
+          }
+        }
+      }
+    };
+
+    for (int pa = ca; pa < ce; pa += ST_XCHUNKS) {  // pieces of at most ST_XCHUNKS chunks
+      const int pe = min(ce, pa + ST_XCHUNKS);
+      const int np = (pe - pa) * 16;  // 16-byte pieces per token row
+      lds_barrier();  // every wavefront is done reading the previous piece
+      // x of this piece: wavefront w copies token row w straight into LDS (no registers).  The
+      // copies are issued BEFORE the weight prefetch, so waiting for them leaves it in flight.
+      if (wave < p.T) {
+        const uint32_t xoff = ((uint32_t)wave * p.d_in + (uint32_t)pa * 128) * 2u + lane * 16u;
+#pragma unroll
+        for (int k = 0; k < ST_XPIECES; ++k)
+          if (lane + 64 * k < np)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rs_x, (__attribute__((address_space(3))) void*)(xs + wave * ST_XROW + k * 1024), 16,
+                (int)xoff, k * 1024, 0, 0);
+      }
+      // this wavefront's share of the piece: the first or the second half of its chunks
+      const int pm = KH == 2 ? pa + (pe - pa + 1) / 2 : pe;
+      const int wa = kh ? pm : pa, we = kh ? pe : pm;
+      Chunk b0, b1, b2;
+      load_chunk(b0, wa);
+      load_chunk(b1, wa + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      // twelve weight loads were issued after the copies: once at most twelve are outstanding,
+      // the copies have landed
+      asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+      lds_barrier();
+
+      int c = wa;
+#pragma nounroll
+      for (; c + 2 < we; c += 3) {
+        load_chunk(b2, c + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_chunk(b0, c - pa);
+        __builtin_amdgcn_sched_barrier(0);
+        load_chunk(b0, c + 3);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_chunk(b1, c + 1 - pa);
+        __builtin_amdgcn_sched_barrier(0);
+        load_chunk(b1, c + 4);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_chunk(b2, c + 2 - pa);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (c < we) compute_chunk(b0, c - pa);
+      if (c + 1 < we) compute_chunk(b1, c + 1 - pa);
+    }
+
+    // ---- the two halves of the block meet in LDS (fixed order: first half + second half) ----
+    if constexpr (KH == 2) {
+      float* red = reinterpret_cast<float*>(xs);  // [8 column groups][8 registers][64 lanes]
+      lds_barrier();                              // x is no longer needed
+      if (kh == 1) {
+#pragma unroll
+        for (int q = 0; q < CW; ++q)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) red[(cg * 8 + 4 * q + r) * 64 + lane] = acc[q][r];
+      }
+      lds_barrier();
+      if (kh == 0) {
+#pragma unroll
+        for (int q = 0; q < CW; ++q)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc[q][r] += red[(cg * 8 + 4 * q + r) * 64 + lane];
+      }
+    }
+
+    // ---- hand over, or finish the slab (wavefronts of the first half hold the sums) --------
+    // D layout: lane (n, kb) holds rows 4*kb + r of columns 2n, 2n+1.  A partial keeps that
+    // layout, [column group][r][lane] x 8 bytes: every store and load is 512 contiguous bytes.
+    if (part < m - 1) {
+      // The partial and the flag are written with device-scope atomic stores (write-through to
+      // the level all compute units share), so no cache write-back or invalidate is needed --
+      // those walk a whole L2 and cost far more than the few KB moved here.
+      unsigned long long* dst =
+          reinterpret_cast<unsigned long long*>(p.partial + (size_t)b * ST_PARTIAL_FLOATS) + cg * 256 + lane;
+      if (kh == 0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (4 * kb + r < p.T)
+            __hip_atomic_store(dst + r * 64,
+                               __builtin_bit_cast(unsigned long long, f32x2{acc[0][r], acc[1][r]}),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // every store of this wavefront has landed
+      __syncthreads();
+      if (tid == 0)
+        __hip_atomic_store(p.flags + b, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      f32x2 tot[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) tot[r] = f32x2{0.0f, 0.0f};
+      if (m > 1) {
+        const int bf = b - (m - 1);  // block of part 0 of this slab
+        // one thread per flag, all polling at once
+        for (int i = tid; i < m - 1; i += ST_THREADS) {
+          uint32_t spins = 0;
+          while (__hip_atomic_load(p.flags + bf + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != p.nonce) {
+            if (++spins > ST_SPIN_LIMIT) {
+              poison = 1;
+              break;
+            }
+            __builtin_amdgcn_s_sleep(8);
+          }
+        }
+        __syncthreads();
+        // partials in part order, eight blocks' loads in flight at a time
+        if (kh == 0) {
+          for (int i0 = 0; i0 < m - 1; i0 += 8) {
+            f32x2 v[8][4];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+              const unsigned long long* src =
+                  reinterpret_cast<const unsigned long long*>(p.partial + (size_t)(bf + i0 + i) * ST_PARTIAL_FLOATS) +
+                  cg * 256 + lane;
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                v[i][r] = f32x2{0.0f, 0.0f};
+                if (i0 + i < m - 1 && 4 * kb + r < p.T)
+                  v[i][r] = __builtin_bit_cast(
+                      f32x2, __hip_atomic_load(src + r * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+              }
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) tot[r] += v[i][r];
+          }
+        }
+      }
+      const bool bad = (m > 1) && poison != 0;
+      if (kh == 0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = 4 * kb + r;
+          f32x2 v = tot[r] + f32x2{acc[0][r], acc[1][r]};
+          if (bad) v = f32x2{__builtin_nanf(""), __builtin_nanf("")};  // a wait ran out: make it loud
+          if (row < p.T && col_ok) {
+            if (p.out_bf16)
+              *reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(p.out) + (size_t)row * p.d_out + j0) =
+                  pack_bf16x2(v[0], v[1]);
+            else
+              *reinterpret_cast<f32x2*>(static_cast<float*>(p.out) + (size_t)row * p.d_out + j0) = v;
+          }
+        }
       }
     }
   }
 }
 
-__global__ __launch_bounds__(256) void smallt_reduce_kernel(const float* __restrict__ partial,
-                                                            int nparts, size_t n, void* out,
-                                                            int out_bf16) {
-  const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  float v = 0.0f;
-  for (int z = 0; z < nparts; ++z) v += partial[(size_t)z * n + i];
-  if (out_bf16)
-    static_cast<uint16_t*>(out)[i] = f32_to_bf16_bits(v);
-  else
-    static_cast<float*>(out)[i] = v;
+// Launch shape: slabs x parts with parts chosen to fill the compute units (at least one chunk
+// per part); of the two slab widths, the one that occupies more compute units (ties: the
+// narrower slab, which has fewer partials to add).
+SmallTPlan smallt_plan(int d_in, int d_out) {
+  const int chunks = d_in / 128;
+  SmallTPlan best{};
+  for (int halves = 2; halves >= 1; --halves) {
+    SmallTPlan pl;
+    pl.halves = halves;
+    pl.slab_cols = (ST_WAVES / halves) * ST_WCOLS;
+    pl.slabs = ceil_div(d_out, pl.slab_cols);
+    int m = ST_MAX_BLOCKS / pl.slabs;
+    if (m > chunks) m = chunks;
+    if (m < 1) m = 1;
+    pl.parts = m;
+    pl.blocks = pl.slabs * m;
+    const int busy = pl.blocks < ST_MAX_BLOCKS ? pl.blocks : ST_MAX_BLOCKS;
+    const int best_busy = best.blocks < ST_MAX_BLOCKS ? best.blocks : ST_MAX_BLOCKS;
+    if (halves == 2 || busy > best_busy) best = pl;
+  }
+  return best;
 }
 
-int smallt_ksplit(int d_in, int d_out, int group) {
-  const int slabs = ceil_div(d_out, 64);
-  const int L = d_in / group;
-  int ks = ceil_div(640, slabs);            // aim for a few blocks per compute unit
-  const int max_ks = L / (ST_WAVES * 4);    // but keep >= 4 groups per wavefront
-  if (ks > max_ks) ks = max_ks;
-  if (ks > 16) ks = 16;
-  return ks < 1 ? 1 : ks;
-}
-
-hipError_t launch_smallt(const SmallTArgs& a, int ksplit, hipStream_t st) {
-  dim3 grid(ceil_div(a.d_out, 64), ksplit);
-  smallt_kernel<<<grid, 64 * ST_WAVES, 0, st>>>(a);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess || ksplit == 1) return e;
-  const size_t n = (size_t)a.T * a.d_out;
-  smallt_reduce_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(a.partial, ksplit, n, a.out,
-                                                                    a.out_bf16);
+template <int SUB, int KH>
+static hipError_t launch_sub(const SmallTArgs& a, int grid, hipStream_t st) {
+  const size_t smem = 16 * ST_XROW;
+  static bool attr_set = false;  // per instantiation
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(smallt_kernel<SUB, KH>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  smallt_kernel<SUB, KH><<<grid, ST_THREADS, smem, st>>>(a);
   return hipGetLastError();
+}
+
+hipError_t launch_smallt(const SmallTArgs& args, hipStream_t st) {
+  static std::atomic<unsigned long long> calls{0};
+  SmallTArgs a = args;
+  // a value no earlier call of this process has written to the flags (and never zero)
+  unsigned long long z = (calls.fetch_add(1) + 1) * 0x9e3779b97f4a7c15ull;
+  z ^= z >> 31;  // both steps are bijections that fix zero, and the count is never zero
+  a.nonce = z;
+  const SmallTPlan pl = smallt_plan(a.d_in, a.d_out);
+  const int sub = a.group / 32;
+  if (pl.halves == 2) {
+    if (sub == 1) return launch_sub<1, 2>(a, pl.blocks, st);
+    if (sub == 2) return launch_sub<2, 2>(a, pl.blocks, st);
+    if (sub == 4) return launch_sub<4, 2>(a, pl.blocks, st);
+  } else {
+    if (sub == 1) return launch_sub<1, 1>(a, pl.blocks, st);
+    if (sub == 2) return launch_sub<2, 1>(a, pl.blocks, st);
+    if (sub == 4) return launch_sub<4, 1>(a, pl.blocks, st);
+  }
+  return hipErrorInvalidValue;
 }
 
 }  // namespace qalora

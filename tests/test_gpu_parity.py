@@ -218,3 +218,19 @@ def test_small_token_forward(gpu_api, tokens, group, d_in, d_out):
     assert err <= 1e-5
     y2 = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"])
     assert torch.equal(y, y2)
+
+
+def test_small_token_wide_slab_path(gpu_api):
+    """A shape for which the 512-column slabs fill more compute units than the 256-column ones
+    (13312 columns: 26 slabs x 9 parts against 52 x 4), so the other kernel variant and a
+    nine-way cross-block sum are exercised; bf16 output equals the rounded fp32 output."""
+    cfg = synth.LayerConfig("stw", 5, 1152, 13312, 4, 64, 8, 0.5, seed=12)
+    L = layer_on_gpu(gpu_api, cfg)
+    y = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"])
+    ref = oracle.forward(L["np"]["x"], L["codes"], L["alpha"], L["beta"], cfg.group)
+    err = rel_err(y.cpu().numpy(), ref)
+    record("small_token wide slab T=5 g=64 1152x13312", y=err)
+    assert err <= 1e-5
+    yb = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"], out_dtype=torch.bfloat16)
+    assert torch.equal(yb, y.to(torch.bfloat16))
+    assert torch.equal(y, gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"]))
