@@ -1,12 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the QA-LoRA adapted linear layer on one MI355X.
 
-One "step" = one adapted forward (y = x W~ + s (pool(x) A) B) plus one backward
-(dx, dA, dB) of a single linear layer through the C-ABI library, on seeded synthetic
-tensors already resident in HBM.  Quantization of W is setup and is not timed; merge and
-the post-merge forward are reported separately in "extras".
+Workloads (``--workload``), all on seeded synthetic tensors already resident in HBM:
 
-Prints ONE JSON line (see README for the fields).
+  c2 (default)  one adapted forward (y = x W~ + s (pool(x) A) B) plus one backward (dx, dA, dB) of
+                the LLaMA-7B attention-projection layer.  "extras" also reports quantize, merge,
+                the post-merge forward and the small-token (memory-bound) table of the c5 shapes.
+  c3            the SwiGLU MLP block of one LLaMA-7B decoder layer: gate/up/down adapted linears,
+                forward and backward (dx, dA, dB of all three); the elementwise glue is torch.
+  c4            one layer of the LLaMA-13B low-bit sweep at --bits / --group.
+  c5            post-merge inference at --tokens (1, 4, 16 or 256): one forward of the
+                8192x22016 layer plus one of the 22016x8192 layer, rotating over eight weight
+                sets (> 1 GB) so that nothing is served from the last-level cache.
+
+A "step" is one pass of the workload.  Quantization of W is setup and is not timed.
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -23,13 +31,16 @@ sys.path.insert(0, ROOT)
 
 PEAK_MFMA_TFLOPS = 2500.0   # MI355X dense bf16 / fp16 matrix peak
 PEAK_HBM_GBS = 8000.0
+METRIC = "QA-LoRA linear fwd+bwd TFLOP/s & % of MFMA/HBM roofline, LLaMA-7B shapes"
 
 
-def layer_flops(cfg):
-    """Algorithmic flops of one forward + backward (two dense contractions, no dW product,
+def layer_flops(cfg, adapter=True):
+    """Algorithmic flops of one forward and one backward (two dense contractions, no dW product,
     plus the adapter products); unpack / dequant / pooling count zero."""
     T, di, do, r, L = cfg.tokens, cfg.d_in, cfg.d_out, cfg.rank, cfg.groups
     main = 2.0 * T * di * do
+    if not adapter:
+        return dict(fwd=main, bwd=main, fwd_kernel=main, bwd_kernel=main)
     fwd_adapter = 2.0 * T * L * r + 2.0 * T * r * do
     bwd_adapter = 2 * (2.0 * T * r * do) + 2 * (2.0 * T * L * r)
     return dict(fwd=main + fwd_adapter, bwd=main + bwd_adapter,
@@ -37,9 +48,16 @@ def layer_flops(cfg):
                 bwd_kernel=main + 2.0 * T * L * r)           # dy W~^T + dU A^T (unpooled)
 
 
-def read_traffic(workload):
+def forward_bytes(cfg, tokens, out_bytes=2):
+    """Algorithmic HBM bytes of one adapter-free forward: every operand once."""
+    codes = cfg.d_in * cfg.d_out * cfg.bits // 8
+    factors = 2 * cfg.groups * cfg.d_out * 4
+    return codes + factors + tokens * cfg.d_in * 2 + tokens * cfg.d_out * out_bytes
+
+
+def read_traffic(name):
     """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary."""
-    path = os.path.join(ROOT, "profiles", f"gemm_dq_{workload}_pmc.txt")
+    path = os.path.join(ROOT, "profiles", name)
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -49,15 +67,154 @@ def read_traffic(workload):
     return None
 
 
+class Layer:
+    """One quantized layer on the device, with adapters and preallocated outputs / workspace."""
+
+    def __init__(self, api, torch, cfg, odt, gen=None, want_bwd=True, merged=False):
+        self.api, self.cfg = api, cfg
+        from paper_2309_14717_amd import synth
+        dev = "cuda"
+        self.desc = api.make_desc(cfg.d_in, cfg.d_out, cfg.bits, cfg.group, cfg.rank, cfg.s)
+        if gen is None:   # host generator: the arrays the parity tests and the oracle use
+            d = synth.make_inputs(cfg)
+            self.host = d
+            W = torch.from_numpy(d["W"]).to(dev)
+            self.x = torch.from_numpy(d["x"]).to(dev).to(torch.bfloat16)
+            self.dy = torch.from_numpy(d["dy"]).to(dev).to(torch.bfloat16) if want_bwd else None
+            self.A = torch.from_numpy(d["A"]).to(dev)
+            self.B = torch.from_numpy(d["B"]).to(dev)
+        else:             # device generator: extra weight sets of the same distribution
+            self.host = None
+            W = torch.randn((cfg.d_in, cfg.d_out), generator=gen, device=dev) * cfg.w_std
+            self.x = torch.randn((cfg.tokens, cfg.d_in), generator=gen, device=dev).to(torch.bfloat16)
+            self.dy = None
+            self.A = torch.randn((cfg.groups, cfg.rank), generator=gen, device=dev) * cfg.ab_std
+            self.B = torch.randn((cfg.rank, cfg.d_out), generator=gen, device=dev) * cfg.ab_std
+        self.W = W
+        self.packed, self.alpha, self.beta = api.quantize(self.desc, W)
+        self.beta_m = api.merge(self.desc, self.beta, self.A, self.B) if merged else None
+        T = cfg.tokens
+        self.y = torch.empty((T, cfg.d_out), dtype=odt, device=dev)
+        self.ws_f = torch.empty(max(16, api.workspace_bytes(self.desc, T, api.OP_FORWARD)), dtype=torch.uint8, device=dev)
+        if want_bwd:
+            self.dx = torch.empty((T, cfg.d_in), dtype=odt, device=dev)
+            self.dA, self.dB = torch.zeros_like(self.A), torch.zeros_like(self.B)
+            self.ws_b = torch.empty(api.workspace_bytes(self.desc, T, api.OP_BACKWARD), dtype=torch.uint8, device=dev)
+
+    def drop_w(self):
+        self.W = None
+
+    def forward(self, x=None):
+        a = self.api
+        return a.forward(self.desc, self.x if x is None else x, self.packed, self.alpha, self.beta,
+                         self.A, self.B, ws=self.ws_f, y=self.y)
+
+    def forward_merged(self, x=None, y=None, ws=None):
+        a = self.api
+        return a.forward(self.desc, self.x if x is None else x, self.packed, self.alpha, self.beta_m,
+                         ws=self.ws_f if ws is None else ws, y=self.y if y is None else y)
+
+    def backward(self, dy=None, x=None):
+        a = self.api
+        return a.backward(self.desc, self.dy if dy is None else dy, self.x if x is None else x,
+                          self.packed, self.alpha, self.beta, self.A, self.B, dA=self.dA, dB=self.dB,
+                          ws=self.ws_b, dx=self.dx)
+
+
+def timed(torch, fn, n=20, warm=2):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s.record()
+    for _ in range(n):
+        fn()
+    e.record()
+    torch.cuda.synchronize()
+    return s.elapsed_time(e) / n
+
+
+def run_steps(torch, api, step, steps, warmup, directions=(0, 1)):
+    """Warm up, then time exactly `steps` steps; per-direction kernel times from armed events."""
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    timers = {d: api.KernelTimer(d, steps) for d in directions}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for t in timers.values():
+            t.arm()
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kms = {d: float(np.mean(t.elapsed_ms())) for d, t in timers.items()}
+    for t in timers.values():
+        t.close()
+    return (t1 - t0) * 1e3 / steps, kms
+
+
+def small_token_sets(torch, api, synth, name, n_sets, odt):
+    """`n_sets` merged layers of one c5 shape (distinct weights, same distribution)."""
+    cfg = synth.CONFIGS[name].scaled(tokens=256)
+    gen = torch.Generator(device="cuda").manual_seed(1000 + cfg.seed)
+    sets = []
+    for i in range(n_sets):
+        L = Layer(api, torch, cfg, odt, gen=gen if i else None, want_bwd=False, merged=True)
+        L.drop_w()
+        sets.append(L)
+    return cfg, sets
+
+
+def small_token_table(torch, api, synth, odt, n_sets=8, tokens=(1, 4, 16, 256), iters=48):
+    rows = []
+    for name in ("c5_up", "c5_down"):
+        cfg, sets = small_token_sets(torch, api, synth, name, n_sets, odt)
+        for T in tokens:
+            x = sets[0].x[:T].contiguous()
+            y = torch.empty((T, cfg.d_out), dtype=odt, device="cuda")
+            ws = torch.empty(api.workspace_bytes(sets[0].desc, T, api.OP_FORWARD), dtype=torch.uint8, device="cuda")
+            it = iter(range(10 ** 9))
+            ms = timed(torch, lambda: sets[next(it) % n_sets].forward_merged(x=x, y=y, ws=ws), n=iters, warm=n_sets)
+            by = forward_bytes(cfg, T, y.element_size())
+            fl = 2.0 * T * cfg.d_in * cfg.d_out
+            rows.append({"shape": f"{cfg.d_in}x{cfg.d_out}", "tokens": T, "us": round(ms * 1e3, 2),
+                         "GB/s": round(by / ms / 1e6, 1), "frac_hbm": round(by / ms / 1e6 / PEAK_HBM_GBS, 4),
+                         "TFLOP/s": round(fl / ms / 1e9, 2)})
+        del sets
+        torch.cuda.empty_cache()
+    return rows
+
+
+def cpu_oracle_baseline(fn_flops_pairs, label):
+    """Time the oracle (as it stands) on the host: list of (callable, flops)."""
+    import oracle
+    tc = time.perf_counter()
+    flops = 0.0
+    for fn, fl in fn_flops_pairs:
+        fn()
+        flops += fl
+    dt = time.perf_counter() - tc
+    return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "sample": f"{label}, fp64, {dt:.1f} s"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--bits", type=int, default=4, help="c4: code width")
+    ap.add_argument("--group", type=int, default=32, help="c4: group size")
+    ap.add_argument("--tokens", type=int, default=16, help="c5: tokens per call")
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch the library's plain copy kernel (256 MiB, 4 times): the "
+                         "yardstick for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the layer shards by tokens with one "
@@ -72,111 +229,178 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     api.load()
-    cfg = synth.CONFIGS[args.workload]
-    d = synth.make_inputs(cfg)
-    dev = "cuda"
-    W = torch.from_numpy(d["W"]).to(dev)
-    x = torch.from_numpy(d["x"]).to(dev).to(torch.bfloat16)
-    dy = torch.from_numpy(d["dy"]).to(dev).to(torch.bfloat16)
-    A = torch.from_numpy(d["A"]).to(dev)
-    B = torch.from_numpy(d["B"]).to(dev)
-    desc = api.make_desc(cfg.d_in, cfg.d_out, cfg.bits, cfg.group, cfg.rank, cfg.s)
-
-    tq = time.perf_counter()
-    packed, alpha, beta = api.quantize(desc, W)
-    torch.cuda.synchronize()
-    quantize_ms_cold = (time.perf_counter() - tq) * 1e3
-
     odt = torch.bfloat16 if args.out_dtype == "bf16" else torch.float32
-    y = torch.empty((cfg.tokens, cfg.d_out), dtype=odt, device=dev)
-    dx = torch.empty((cfg.tokens, cfg.d_in), dtype=odt, device=dev)
-    dA, dB = torch.zeros_like(A), torch.zeros_like(B)
-    ws_f = torch.empty(api.workspace_bytes(desc, cfg.tokens, api.OP_FORWARD), dtype=torch.uint8, device=dev)
-    ws_b = torch.empty(api.workspace_bytes(desc, cfg.tokens, api.OP_BACKWARD), dtype=torch.uint8, device=dev)
+    extras, cpu_baseline = {}, None
+    if args.calibrate_copy:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            api.profile_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
 
-    def step():
-        api.forward(desc, x, packed, alpha, beta, A, B, ws=ws_f, y=y)
-        api.backward(desc, dy, x, packed, alpha, beta, A, B, dA=dA, dB=dB, ws=ws_b, dx=dx)
+    if args.workload in ("c1", "c2", "c4"):
+        cfg = synth.CONFIGS[args.workload]
+        if args.workload == "c4":
+            cfg = cfg.scaled(bits=args.bits, group=args.group)
+        L = Layer(api, torch, cfg, odt)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
+        def step():
+            L.forward()
+            L.backward()
 
-    # ---- timed region: exactly `steps` steps, kernel events armed inside the library ----
-    kt_f = api.KernelTimer(0, args.steps)
-    kt_b = api.KernelTimer(1, args.steps)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        kt_f.arm()
-        kt_b.arm()
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kf = float(np.mean(kt_f.elapsed_ms()))
-    kb = float(np.mean(kt_b.elapsed_ms()))
-    kt_f.close()
-    kt_b.close()
+        ms_per_step, kms = run_steps(torch, api, step, args.steps, args.warmup)
+        fl = layer_flops(cfg)
+        total_flops = fl["fwd"] + fl["bwd"]
+        kf, kb = kms[0], kms[1]
+        dom = ("fwd", kf, fl["fwd_kernel"]) if kf >= kb else ("bwd", kb, fl["bwd_kernel"])
+        achieved = dom[2] / (dom[1] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": f"gemm_dq_kernel<{cfg.bits},{dom[0]}>",
+                    "achieved": round(achieved, 2), "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / PEAK_MFMA_TFLOPS, 4), "avg_kernel_ms": round(dom[1], 4),
+                    "fwd_kernel_ms": round(kf, 4), "bwd_kernel_ms": round(kb, 4),
+                    "traffic": read_traffic(f"gemm_dq_{args.workload}_pmc.txt")}
+        workload = (f"{cfg.name}: QA-LoRA linear fwd+bwd, T={cfg.tokens}, {cfg.d_in}x{cfg.d_out}, "
+                    f"INT{cfg.bits} g={cfg.group}, rank {cfg.rank}, s={cfg.s}, x/dy bf16, outputs {args.out_dtype}")
+        if not args.no_extras:
+            beta_m = torch.empty_like(L.beta)
+            L.beta_m = beta_m
+            merge_ms = timed(torch, lambda: api.merge(L.desc, L.beta, L.A, L.B, out=beta_m))
+            extras = {
+                "fwd_ms": round(timed(torch, L.forward), 4),
+                "bwd_ms": round(timed(torch, L.backward), 4),
+                "quantize_ms": round(timed(torch, lambda: api.quantize(L.desc, L.W), 5), 4),
+                "merge_ms": round(merge_ms, 4),
+                "merge_GB/s": round(2 * L.beta.numel() * 4 / merge_ms / 1e6, 1),
+                "post_merge_fwd_ms": round(timed(torch, L.forward_merged), 4),
+            }
+            if args.workload == "c2":
+                L.drop_w()
+                extras["small_token_post_merge_forward"] = small_token_table(torch, api, synth, odt)
+        if not args.no_cpu_baseline:
+            import oracle
+            d = L.host
+            n = min(args.cpu_sample_tokens, cfg.tokens)
+            codes = api.unpack(L.desc, L.packed).cpu().numpy()
+            al, be = L.alpha.cpu().numpy(), L.beta.cpu().numpy()
+            cpu_baseline = cpu_oracle_baseline(
+                [(lambda: oracle.forward(d["x"][:n], codes, al, be, cfg.group, d["A"], d["B"], cfg.s), fl["fwd"] * n / cfg.tokens),
+                 (lambda: oracle.backward(d["dy"][:n], d["x"][:n], codes, al, be, cfg.group, d["A"], d["B"], cfg.s),
+                  fl["bwd"] * n / cfg.tokens)],
+                f"forward+backward of the first {n} of {cfg.tokens} tokens of the same layer")
 
-    fl = layer_flops(cfg)
-    total_flops = fl["fwd"] + fl["bwd"]
+    elif args.workload == "c3":
+        import torch.nn.functional as F
+        gate = Layer(api, torch, synth.CONFIGS["c3_gate"], odt)
+        gate.drop_w()
+        up = Layer(api, torch, synth.CONFIGS["c3_up"], odt)
+        up.drop_w()
+        down = Layer(api, torch, synth.CONFIGS["c3_down"], odt)
+        down.drop_w()
+        x, dy = gate.x, down.dy
+
+        def step():
+            # forward: y = down( silu(gate(x)) * up(x) )
+            g = gate.forward(x)
+            u = up.forward(x)
+            sg = torch.sigmoid(g.float())
+            h = (g.float() * sg * u.float()).to(torch.bfloat16)
+            down.forward(h)
+            # backward
+            dh, _, _ = down.backward(dy, h)
+            dhf, gf, uf = dh.float(), g.float(), u.float()
+            du = (dhf * gf * sg).to(torch.bfloat16)
+            dg = (dhf * uf * (sg * (1.0 + gf * (1.0 - sg)))).to(torch.bfloat16)
+            dx1, _, _ = gate.backward(dg, x)
+            dx2, _, _ = up.backward(du, x)
+            return dx1.add_(dx2)
+
+        ms_per_step, kms = run_steps(torch, api, step, args.steps, args.warmup)
+        fls = [layer_flops(l.cfg) for l in (gate, up, down)]
+        total_flops = sum(f["fwd"] + f["bwd"] for f in fls)
+        # armed events catch the first contraction of each direction: gate forward, down backward
+        kf, kb = kms[0], kms[1]
+        cands = [("fwd 4096x11008", kf, fls[0]["fwd_kernel"]), ("bwd 11008x4096", kb, fls[2]["bwd_kernel"])]
+        dom = max(cands, key=lambda c: c[1])
+        achieved = dom[2] / (dom[1] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": f"gemm_dq_kernel<4,{dom[0]}>", "achieved": round(achieved, 2),
+                    "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_TFLOPS, 4),
+                    "avg_kernel_ms": round(dom[1], 4), "gate_fwd_kernel_ms": round(kf, 4),
+                    "down_bwd_kernel_ms": round(kb, 4), "traffic": read_traffic("gemm_dq_c3_pmc.txt")}
+        workload = ("c3: LLaMA-7B SwiGLU MLP block fwd+bwd, T=4096, gate/up 4096x11008 + down 11008x4096, "
+                    f"INT4 g=32, rank 64, s=0.25, bf16 activations, outputs {args.out_dtype}; elementwise glue in torch")
+        cfg = gate.cfg
+        if not args.no_cpu_baseline:
+            import oracle
+            d = gate.host
+            n = min(256, cfg.tokens)
+            codes = api.unpack(gate.desc, gate.packed).cpu().numpy()
+            al, be = gate.alpha.cpu().numpy(), gate.beta.cpu().numpy()
+            cpu_baseline = cpu_oracle_baseline(
+                [(lambda: oracle.forward(d["x"][:n], codes, al, be, cfg.group, d["A"], d["B"], cfg.s),
+                  fls[0]["fwd"] * n / cfg.tokens),
+                 (lambda: oracle.backward(d["dy"][:n], d["x"][:n], codes, al, be, cfg.group, d["A"], d["B"], cfg.s),
+                  fls[0]["bwd"] * n / cfg.tokens)],
+                f"forward+backward of the gate projection on the first {n} of {cfg.tokens} tokens")
+
+    else:  # c5
+        T = args.tokens
+        n_sets = 8
+        cfg_u, ups = small_token_sets(torch, api, synth, "c5_up", n_sets, odt)
+        cfg_d, downs = small_token_sets(torch, api, synth, "c5_down", n_sets, odt)
+        xu, xd = ups[0].x[:T].contiguous(), downs[0].x[:T].contiguous()
+        yu = torch.empty((T, cfg_u.d_out), dtype=odt, device="cuda")
+        yd = torch.empty((T, cfg_d.d_out), dtype=odt, device="cuda")
+        ws_u = torch.empty(api.workspace_bytes(ups[0].desc, T, api.OP_FORWARD), dtype=torch.uint8, device="cuda")
+        ws_d = torch.empty(api.workspace_bytes(downs[0].desc, T, api.OP_FORWARD), dtype=torch.uint8, device="cuda")
+        counter = [0]
+
+        def step():
+            i = counter[0] % n_sets
+            counter[0] += 1
+            ups[i].forward_merged(x=xu, y=yu, ws=ws_u)      # arms catch this kernel (first forward of the step)
+            downs[i].forward_merged(x=xd, y=yd, ws=ws_d)
+
+        ms_per_step, kms = run_steps(torch, api, step, args.steps, max(args.warmup, n_sets), directions=(0,))
+        total_flops = 2.0 * T * (cfg_u.d_in * cfg_u.d_out + cfg_d.d_in * cfg_d.d_out)
+        by_u = forward_bytes(cfg_u, T, yu.element_size())
+        by_step = by_u + forward_bytes(cfg_d, T, yd.element_size())
+        k = kms[0]
+        if T <= 16:
+            ach = by_u / k / 1e6
+            roofline = {"bound": "hbm", "kernel": "smallt_kernel (8192x22016)", "achieved": round(ach, 1),
+                        "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4),
+                        "avg_kernel_ms": round(k, 5), "traffic": read_traffic("smallt_c5_pmc.txt")}
+        else:
+            ach = 2.0 * T * cfg_u.d_in * cfg_u.d_out / (k * 1e-3) / 1e12
+            roofline = {"bound": "mfma", "kernel": "gemm_dq_kernel<4,fwd> (8192x22016)", "achieved": round(ach, 2),
+                        "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_MFMA_TFLOPS, 4),
+                        "avg_kernel_ms": round(k, 5), "hbm_GB/s": round(by_u / k / 1e6, 1), "traffic": None}
+        extras = {"GB/s_whole_step": round(by_step / ms_per_step / 1e6, 1),
+                  "frac_hbm_whole_step": round(by_step / ms_per_step / 1e6 / PEAK_HBM_GBS, 4),
+                  "bytes_per_step": by_step, "weight_sets": n_sets}
+        workload = (f"c5: post-merge forward, T={T}, 8192x22016 then 22016x8192, INT4 g=32, merged beta, "
+                    f"x bf16, outputs {args.out_dtype}, {n_sets} weight sets rotated")
+        cfg = cfg_u
+        if not args.no_cpu_baseline:
+            import oracle
+            L0 = ups[0]
+            n = min(T, 16)
+            codes = api.unpack(L0.desc, L0.packed).cpu().numpy()
+            al, be = L0.alpha.cpu().numpy(), L0.beta_m.cpu().numpy()
+            xh = L0.x[:n].float().cpu().numpy()
+            cpu_baseline = cpu_oracle_baseline(
+                [(lambda: oracle.forward(xh, codes, al, be, cfg.group), 2.0 * n * cfg.d_in * cfg.d_out)],
+                f"post-merge forward of the 8192x22016 layer on {n} tokens")
+
     value = total_flops / (ms_per_step * 1e-3) / 1e12
-
-    dom = ("fwd", kf, fl["fwd_kernel"]) if kf >= kb else ("bwd", kb, fl["bwd_kernel"])
-    achieved = dom[2] / (dom[1] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": f"gemm_dq_kernel<{cfg.bits},{dom[0]}>",
-                "achieved": round(achieved, 2), "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_MFMA_TFLOPS, 4),
-                "avg_kernel_ms": round(dom[1], 4),
-                "fwd_kernel_ms": round(kf, 4), "bwd_kernel_ms": round(kb, 4),
-                "traffic": read_traffic(args.workload)}
-
-    # ---- extras: the rows of the path that are not per-step (untimed toward `value`) ----
-    def timed(fn, n=20):
-        fn()
-        torch.cuda.synchronize()
-        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        s.record()
-        for _ in range(n):
-            fn()
-        e.record()
-        torch.cuda.synchronize()
-        return s.elapsed_time(e) / n
-
-    beta_m = torch.empty_like(beta)
-    extras = {
-        "fwd_ms": round(timed(lambda: api.forward(desc, x, packed, alpha, beta, A, B, ws=ws_f, y=y)), 4),
-        "bwd_ms": round(timed(lambda: api.backward(desc, dy, x, packed, alpha, beta, A, B, dA=dA, dB=dB, ws=ws_b, dx=dx)), 4),
-        "quantize_ms": round(timed(lambda: api.quantize(desc, W), 5), 4),
-        "merge_ms": round(timed(lambda: api.merge(desc, beta, A, B, out=beta_m)), 4),
-        "post_merge_fwd_ms": round(timed(lambda: api.forward(desc, x, packed, alpha, beta_m, ws=ws_f, y=y)), 4),
-    }
-
-    cpu_baseline = None
-    if not args.no_cpu_baseline:
-        import oracle
-        n = min(args.cpu_sample_tokens, cfg.tokens)
-        codes = api.unpack(desc, packed).cpu().numpy()
-        al, be = alpha.cpu().numpy(), beta.cpu().numpy()
-        tc = time.perf_counter()
-        oracle.forward(d["x"][:n], codes, al, be, cfg.group, d["A"], d["B"], cfg.s)
-        oracle.backward(d["dy"][:n], d["x"][:n], codes, al, be, cfg.group, d["A"], d["B"], cfg.s)
-        dt = time.perf_counter() - tc
-        cpu_baseline = {"value": round(total_flops * (n / cfg.tokens) / dt / 1e12, 6), "unit": "TFLOP/s",
-                        "cores": oracle.num_threads(), "kind": "oracle",
-                        "sample": f"forward+backward of the first {n} of {cfg.tokens} tokens of the "
-                                  f"same layer, fp64, {dt:.1f} s"}
-
     out = {
-        "metric": "QA-LoRA linear fwd+bwd TFLOP/s & % of MFMA/HBM roofline, LLaMA-7B shapes",
-        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: QA-LoRA linear fwd+bwd, T={cfg.tokens}, "
-                               f"{cfg.d_in}x{cfg.d_out}, INT{cfg.bits} g={cfg.group}, rank {cfg.rank}, "
-                               f"s={cfg.s}, x/dy bf16, outputs {args.out_dtype}",
-                   "flops_per_step": total_flops, "frac_of_mfma_peak": round(value / PEAK_MFMA_TFLOPS, 4)},
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16" if args.workload != "c5" or args.tokens > 16 else "bf16",
+        "data": "synthetic",
+        "config": {"workload": workload, "flops_per_step": total_flops,
+                   "frac_of_mfma_peak": round(value / PEAK_MFMA_TFLOPS, 4)},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "extras": extras,
     }
     print(json.dumps(out))

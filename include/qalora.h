@@ -29,8 +29,8 @@
  *   - Every entry returns a status (0 = QALORA_OK, negative = error).  Argument errors
  *     are detected on the host before anything is launched; no partial work is
  *     enqueued in that case.  Nothing throws.
- *   - Supported shapes: bits in {2,3,4}; group a multiple of 8 that divides d_in;
- *     d_out a multiple of 8; rank a multiple of 8 (or 0), at most 512.  Anything else
+ *   - Supported shapes: bits in {2,3,4}; group dividing d_in and a multiple of 8 (4-bit),
+ *     16 (2-bit) or 32 (3-bit); d_out a multiple of 8; rank at most 128.  Anything else
  *     that is well-formed returns QALORA_EUNSUPPORTED -- there is no fallback path.
  *   - Results are deterministic: a rerun on the same inputs is bit-identical.
  */
@@ -158,6 +158,11 @@ int qalora_profile_arm(int direction, void* start_event, void* stop_event);
 int qalora_profile_event_create(void** event);
 int qalora_profile_event_elapsed_ms(void* start_event, void* stop_event, float* ms);
 int qalora_profile_event_destroy(void* event);
+
+/* Measurement aid: a plain device-to-device copy kernel of `bytes` bytes (a multiple of 16; both
+ * pointers 16-byte aligned, buffers must not overlap).  It reads and writes exactly `bytes` of
+ * HBM once, which makes it the yardstick the hardware traffic counters are scaled by. */
+int qalora_profile_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

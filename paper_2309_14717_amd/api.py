@@ -24,7 +24,7 @@ EXPORTS = (
     "qalora_status_string", "qalora_check_desc", "qalora_packed_bytes", "qalora_workspace_bytes",
     "qalora_quantize", "qalora_unpack", "qalora_pack", "qalora_forward", "qalora_backward",
     "qalora_merge", "qalora_profile_arm", "qalora_profile_event_create",
-    "qalora_profile_event_elapsed_ms", "qalora_profile_event_destroy",
+    "qalora_profile_event_elapsed_ms", "qalora_profile_event_destroy", "qalora_profile_copy",
 )
 
 
@@ -71,6 +71,7 @@ def load() -> ctypes.CDLL:
     lib.qalora_profile_event_create.argtypes = [ctypes.POINTER(vp)]
     lib.qalora_profile_event_elapsed_ms.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float)]
     lib.qalora_profile_event_destroy.argtypes = [vp]
+    lib.qalora_profile_copy.argtypes = [vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -184,6 +185,13 @@ def merge(desc: Desc, beta, A, B, out=None):
     _check(load().qalora_merge(ctypes.byref(desc), _p(beta), _p(A), _p(B), _p(out), _stream()),
            "qalora_merge")
     return out
+
+
+def profile_copy(dst: torch.Tensor, src: torch.Tensor):
+    """Plain copy kernel of known size (yardstick for the HBM traffic counters)."""
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == n
+    _check(load().qalora_profile_copy(_p(dst), _p(src), n, _stream()), "qalora_profile_copy")
 
 
 class KernelTimer:
