@@ -189,17 +189,21 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
   // fast path: one lane offset for all loads of the kernel (rows of later loads are 64*q
   // further down; the copies are padded to whole tiles, so no row check is needed)
   const uint32_t a_voff_main = (a_row[0] * (uint32_t)p.lda_main + (uint32_t)a_chunk8[0]) * 2u;
-  auto issue_a = [&](auto kind, int it, uint16_t* a_dst) {
+  // `live` = false (a step past the end of the K range): same number of loads, aimed outside
+  // the buffer, so the in-flight count the waits rely on does not depend on the position.
+  auto issue_a = [&](auto kind, int it, uint16_t* a_dst, bool live) {
     constexpr bool kMain = decltype(kind)::value == 0;
     const int k0 = kMain ? (it - nk_tail) * BK : it * BK;
     if constexpr (FAST && kMain) {
+      const uint32_t voff = live ? a_voff_main : kOobOffset;
 #pragma unroll
       for (int q = 0; q < A_LOADS; ++q) {
-        const uint32_t soff = (uint32_t)k0 * 2u + (uint32_t)q * 64u * (uint32_t)p.lda_main * 2u;
+        const uint32_t soff =
+            live ? (uint32_t)k0 * 2u + (uint32_t)q * 64u * (uint32_t)p.lda_main * 2u : 0u;
         uint16_t* dst = a_dst + (q * 8 + wave) * 512;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a_main,
                                                  (__attribute__((address_space(3))) void*)dst, 16,
-                                                 (int)a_voff_main, (int)soff, 0, 0);
+                                                 (int)voff, (int)soff, 0, 0);
       }
       return;
     }
@@ -208,7 +212,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
 #pragma unroll
     for (int q = 0; q < A_LOADS; ++q) {
       const int k = k0 + a_chunk8[q];
-      const uint32_t off = (k < klim && a_row[q] < (uint32_t)p.M)
+      const uint32_t off = (live && k < klim && a_row[q] < (uint32_t)p.M)
                                ? (a_row[q] * lda + (uint32_t)k) * 2u
                                : kOobOffset;
       uint16_t* dst = a_dst + (q * 8 + wave) * 512;
@@ -241,24 +245,28 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
   const int b_i0 = n0 + 8 * b_u1;   // backward: this thread's row block
   const bool n_valid = BWD ? (b_i0 < p.d_in) : (f_j0 < p.d_out);
 
-  uint4 breg[6];   // fwd: codes, alpha, beta, plane-1 codes | bwd: 2 codes, 2 alpha, 2 beta
-  uint4 breg1[2];  // bwd, N = 3: plane-1 words
+  // Two register sets: the set of step it+1 is being dequantised while the set of step it+2
+  // is loading (its loads then have a whole K step to land).
+  uint4 bregs[2][6];   // fwd: codes, alpha, beta, plane-1 codes | bwd: 2 codes, 2 alpha, 2 beta
+  uint4 bregs1[2][2];  // bwd, N = 3: plane-1 words
   uint4 btail[B_CHUNKS];
+  using Set0 = std::integral_constant<int, 0>;
+  using Set1 = std::integral_constant<int, 1>;
 
   // fast path: lane-constant offsets (patches outside the matrix point past the buffers)
-  uint32_t fb_voff_p0 = 0, fb_voff_p1 = 0, fb_voff_ab = 0;
+  uint32_t fb_voff_p0_c = 0, fb_voff_p1_c = 0, fb_voff_ab_c = 0;
   int fb_grp_small = 0;  // forward, g < 64: groups per K step; else 0
   if constexpr (FAST) {
     if constexpr (!BWD) {
-      fb_voff_p0 = ((uint32_t)((8 * f_u0) / RB0) * p.d_out + f_j0) * 4u;
-      fb_voff_p1 = ((uint32_t)((8 * f_u0) / 32) * p.d_out + f_j0) * 4u;
+      fb_voff_p0_c = n_valid ? ((uint32_t)((8 * f_u0) / RB0) * p.d_out + f_j0) * 4u : kOobOffset;
+      fb_voff_p1_c = n_valid ? ((uint32_t)((8 * f_u0) / 32) * p.d_out + f_j0) * 4u : kOobOffset;
       fb_grp_small = p.group < BK ? BK / p.group : 0;
       const uint32_t lane_grp = p.group < BK ? (uint32_t)(8 * f_u0) / (uint32_t)p.group : 0u;
-      fb_voff_ab = n_valid ? (lane_grp * p.d_out + f_j0) * 4u : kOobOffset;
+      fb_voff_ab_c = n_valid ? (lane_grp * p.d_out + f_j0) * 4u : kOobOffset;
     } else {
-      fb_voff_p0 = n_valid ? ((uint32_t)(b_i0 / RB0) * p.d_out + 8 * b_u0) * 4u : kOobOffset;
-      fb_voff_p1 = n_valid ? ((uint32_t)(b_i0 / 32) * p.d_out + 8 * b_u0) * 4u : kOobOffset;
-      fb_voff_ab = n_valid ? ((uint32_t)(b_i0 / p.group) * p.d_out + 8 * b_u0) * 4u : kOobOffset;
+      fb_voff_p0_c = n_valid ? ((uint32_t)(b_i0 / RB0) * p.d_out + 8 * b_u0) * 4u : kOobOffset;
+      fb_voff_p1_c = n_valid ? ((uint32_t)(b_i0 / 32) * p.d_out + 8 * b_u0) * 4u : kOobOffset;
+      fb_voff_ab_c = n_valid ? ((uint32_t)(b_i0 / p.group) * p.d_out + 8 * b_u0) * 4u : kOobOffset;
     }
   }
   auto buf_load128_s = [&](__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
@@ -267,10 +275,15 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     return uint4{v.x, v.y, v.z, v.w};
   };
 
-  auto gload_b = [&](auto kind, int it) {
+  auto gload_b = [&](auto kind, int it, auto set, bool live) {
     constexpr bool kMain = decltype(kind)::value == 0;
+    uint4(&breg)[6] = bregs[decltype(set)::value];
+    uint4(&breg1)[2] = bregs1[decltype(set)::value];
     if constexpr (kMain && FAST) {
-      const uint32_t km = (uint32_t)(it - nk_tail);  // main step index (uniform)
+      const uint32_t km = live ? (uint32_t)(it - nk_tail) : 0u;  // main step index (uniform)
+      const uint32_t fb_voff_p0 = live ? fb_voff_p0_c : kOobOffset;
+      const uint32_t fb_voff_p1 = live ? fb_voff_p1_c : kOobOffset;
+      const uint32_t fb_voff_ab = live ? fb_voff_ab_c : kOobOffset;
       if constexpr (!BWD) {
         // scalar parts: word rows advance by 64/RB per step, group rows by 64/g (or 1 per g/64)
         const uint32_t s_p0 = km * (uint32_t)(BK / RB0) * p.d_out * 4u;
@@ -299,21 +312,21 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
       const int k0 = (it - nk_tail) * BK;
       if constexpr (!BWD) {
         const int i0 = k0 + 8 * f_u0;
-        const bool ok = n_valid && i0 < p.d_in;
-        breg[0] = buf_load128(rs_p0, ((uint32_t)(i0 / RB0) * p.d_out + f_j0) * 4u);
+        const bool ok = live && n_valid && i0 < p.d_in;
+        breg[0] = buf_load128(rs_p0, ok ? ((uint32_t)(i0 / RB0) * p.d_out + f_j0) * 4u : kOobOffset);
         if constexpr (NBITS == 3)
-          breg[3] = buf_load128(rs_p1, ((uint32_t)(i0 / 32) * p.d_out + f_j0) * 4u);
+          breg[3] = buf_load128(rs_p1, ok ? ((uint32_t)(i0 / 32) * p.d_out + f_j0) * 4u : kOobOffset);
         const uint32_t ab = ok ? ((uint32_t)(i0 / p.group) * p.d_out + f_j0) * 4u : kOobOffset;
         breg[1] = buf_load128(rs_al, ab);
         breg[2] = buf_load128(rs_be, ab);
       } else {
         const int j0 = k0 + 8 * b_u0;
-        const bool ok = n_valid && j0 < p.d_out;
-        const uint32_t w = ((uint32_t)(b_i0 / RB0) * p.d_out + j0) * 4u;
+        const bool ok = live && n_valid && j0 < p.d_out;
+        const uint32_t w = ok ? ((uint32_t)(b_i0 / RB0) * p.d_out + j0) * 4u : kOobOffset;
         breg[0] = buf_load128(rs_p0, w);
         breg[1] = buf_load128(rs_p0, w + 16);
         if constexpr (NBITS == 3) {
-          const uint32_t w1 = ((uint32_t)(b_i0 / 32) * p.d_out + j0) * 4u;
+          const uint32_t w1 = ok ? ((uint32_t)(b_i0 / 32) * p.d_out + j0) * 4u : kOobOffset;
           breg1[0] = buf_load128(rs_p1, w1);
           breg1[1] = buf_load128(rs_p1, w1 + 16);
         }
@@ -334,7 +347,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
         // the pooled gradient is this broadcast over the g rows of a group)
         const int src_row = BWD ? n / p.group : n;
         const int k = k0 + 8 * ch;
-        const bool ok = row < BN && n < p.N && k < p.K_tail;
+        const bool ok = live && row < BN && n < p.N && k < p.K_tail;
         btail[q] = buf_load128(rs_bt, ok ? ((uint32_t)src_row * p.K_tail + k) * 2u : kOobOffset);
       }
     }
@@ -352,8 +365,15 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     return __builtin_bit_cast(uint32_t, cc * a2 + b2);
   };
 
-  auto store_b = [&](auto kind, int it, uint16_t* b_dst) {
+  // Dequantise the register set `set` of step `it` into the B stage b_dst.  The work is cut in
+  // four pieces (piece = 0..3, or -1 for all of it) so that it can be spread over the four
+  // K-16 slices of the matrix-core work of the step before.
+  uint32_t wt[8][2];  // backward: [column][row pair] (W~[2m][c], W~[2m+1][c]), kept across pieces
+  auto store_b = [&](auto kind, int it, uint16_t* b_dst, auto set, auto piece_c) {
     constexpr bool kMain = decltype(kind)::value == 0;
+    constexpr int piece = decltype(piece_c)::value;
+    uint4(&breg)[6] = bregs[decltype(set)::value];
+    uint4(&breg1)[2] = bregs1[decltype(set)::value];
     char* bs = reinterpret_cast<char*>(b_dst);
     if constexpr (kMain) {
       if constexpr (!BWD) {
@@ -365,6 +385,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
         const uint32_t be[4] = {breg[2].x, breg[2].y, breg[2].z, breg[2].w};
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
+          if (piece >= 0 && c != piece) continue;
           const uint32_t w0s = w0[c] >> sh0;
           const uint32_t w1s = (NBITS == 3) ? (w1[c] >> sh1) : 0u;
           const f16x2 ab = ab_pair(al[c], be[c]);
@@ -388,15 +409,17 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
                                 breg[3].x, breg[3].y, breg[3].z, breg[3].w};
         const uint32_t be[8] = {breg[4].x, breg[4].y, breg[4].z, breg[4].w,
                                 breg[5].x, breg[5].y, breg[5].z, breg[5].w};
-        uint32_t wt[8][2];  // [column][row pair]: (W~[2m][c], W~[2m+1][c])
+        // pieces 0, 1, 2 dequantise columns 0-2, 3-5, 6-7; piece 3 gathers and writes
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
+          if (piece >= 0 && c / 3 != piece) continue;
           const uint32_t w0s = w0[c] >> sh0;
           const uint32_t w1s = (NBITS == 3) ? (w1[c] >> sh1) : 0u;
           const f16x2 ab = ab_pair(al[c], be[c]);
           wt[c][0] = dq_pair(w0s, w1s, ab, 0);
           wt[c][1] = dq_pair(w0s, w1s, ab, 1);
         }
+        if (piece >= 0 && piece != 3) return;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {  // row 4*hb + r of the patch: gather the 8 columns
           uint32_t o[4];
@@ -411,6 +434,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
         }
       }
     } else {
+      static_assert(piece < 0, "tail tiles are copied in one go");
 #pragma unroll
       for (int q = 0; q < B_CHUNKS; ++q) {
         const int idx = tid + NT * q;
@@ -419,15 +443,19 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
       }
     }
   };
+  using AllPieces = std::integral_constant<int, -1>;
 
   // ---- LDS -> matrix cores ---------------------------------------------------------
   // lane (r = lane % 32, kb = lane / 32) reads chunk 2*kk + kb of rows base + 32*t + r.  The
   // swizzle repeats every 32 rows, so one lane offset (XORed with the chunk) serves every
   // 32-row tile of the wave through the instruction's immediate offset.
+  static_assert(BK == 64, "four K-16 slices per step");
+  constexpr int kSideValuPerMfma = 5;  // side-work VALU instructions slotted behind each MFMA
   const int a_lane = swz_offset(wm * WTM + (lane & 31), 0);
   const int b_lane = swz_offset(wn * WTN + (lane & 31), 0);
 
-  auto compute = [&](auto kind, const uint16_t* a_src, const uint16_t* b_src) {
+  // `side(kk)` is extra work issued in the shadow of the matrix-core instructions of slice kk.
+  auto compute = [&](auto kind, const uint16_t* a_src, const uint16_t* b_src, auto&& side) {
     constexpr bool kMain = decltype(kind)::value == 0;
     const char* as = reinterpret_cast<const char*>(a_src);
     const char* bs = reinterpret_cast<const char*>(b_src);
@@ -442,10 +470,15 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
       for (int b = 0; b < TN; ++b) bf[slot][b] = *reinterpret_cast<const uint4*>(bp + b * 4096);
     };
     load_frags(0, 0);
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      const int cur = kk & 1;
+    auto slice = [&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value;
+      constexpr int cur = kk & 1;
+#ifdef GX_NOFRAG
+      if (kk == 0) load_frags(kk + 1, cur ^ 1);
+#else
       if (kk + 1 < BK / 16) load_frags(kk + 1, cur ^ 1);  // next slice in flight under the MFMAs
+#endif
+      side(kk_c);
 #pragma unroll
       for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -459,59 +492,26 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
                 __builtin_bit_cast(bf16x8, af[cur][a]), __builtin_bit_cast(bf16x8, bf[cur][b]),
                 acc[a][b], 0, 0, 0);
         }
-      __builtin_amdgcn_sched_barrier(0);  // keep the fragment prefetch depth at one slice
-    }
+      // one matrix-core instruction, then whatever else is ready (LDS reads of the next
+      // slice, the side work), eight times over; nothing crosses into the next slice
+#pragma unroll
+      for (int i = 0; i < TM * TN; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+        __builtin_amdgcn_sched_group_barrier(0x002, kSideValuPerMfma, 0);  // VALU
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    slice(std::integral_constant<int, 0>{});
+    slice(std::integral_constant<int, 1>{});
+    slice(std::integral_constant<int, 2>{});
+    slice(std::integral_constant<int, 3>{});
   };
+  auto no_side = [](auto) {};
 
   // Vector-memory ops per thread of one B-register load, per step kind (for the waits).
   constexpr int kBLoadsMain = BWD ? (NBITS == 3 ? 8 : 6) : (NBITS == 3 ? 4 : 3);
   constexpr int kBLoadsTail = B_CHUNKS;
-
-  // One pipelined K step `it` (kinds: cur = it, n1 = it+1, n2 = it+2; NoneK = past the end).
-  //   entry : A(it), B(it) visible in LDS; A(it+1) LDS-DMA in flight; B regs hold step it+1
-  //   1. start LDS-DMA of A(it+2)             (its stage was last read in step it-1)
-  //   2. matrix cores on step it
-  //   3. dequantise B regs -> B stage of it+1 (last read in step it-1)
-  //   4. load B regs of step it+2
-  //   5. wait for A(it+1) (everything issued after it may stay in flight), barrier
-  auto step = [&](auto cur, auto n1, auto n2, int it, int slot) {
-    constexpr bool kHas1 = decltype(n1)::value != 2;
-    constexpr bool kHas2 = decltype(n2)::value != 2;
-    const int sa = slot % 3, sa2 = (slot + 2) % 3, sb = slot & 1;
-    with_step_regions(
-        As + sa2 * A_TILE, As + sa * A_TILE, Bs + sb * B_TILE, Bs + (sb ^ 1) * B_TILE,
-        [&](uint16_t* a_dma, const uint16_t* a_rd, const uint16_t* b_rd, uint16_t* b_wr) {
-          if constexpr (kHas2) issue_a(n2, it + 2, a_dma);
-          __builtin_amdgcn_sched_barrier(0);
-          compute(cur, a_rd, b_rd);
-          if constexpr (kHas1) store_b(n1, it + 1, b_wr);
-          if constexpr (kHas2) gload_b(n2, it + 2);
-        });
-    constexpr int kKeep =
-        kHas2 ? A_LOADS + (decltype(n2)::value == 0 ? kBLoadsMain : kBLoadsTail) : 0;
-    wait_and_barrier<kKeep>();
-  };
-
-  // Software pipeline over the homogeneous steps [pb, pe) of kind K.
-  auto pipeline = [&](auto K, int pb, int pe) {
-    const int n = pe - pb;
-    if (n <= 0) return;
-    // prologue: A(pb), A(pb+1) in flight, B(pb) staged, B regs of step pb+1 loading
-    issue_a(K, pb, As);
-    gload_b(K, pb);
-    if (n > 1) issue_a(K, pb + 1, As + A_TILE);
-    store_b(K, pb, Bs);
-    if (n > 1) gload_b(K, pb + 1);
-    wait_and_barrier<0>();  // prologue only: drain everything
-    int it = pb, slot = 0;
-#pragma nounroll
-    for (; it + 2 < pe; ++it, ++slot) step(K, K, K, it, slot);  // hot loop
-    if (it + 1 < pe) {
-      step(K, K, NoneK{}, it, slot);
-      ++it, ++slot;
-    }
-    step(K, NoneK{}, NoneK{}, it, slot);
-  };
 
   if constexpr (HAS_MAIN) {
     // The adapter (tail) steps run FIRST, two at a time and without software pipelining
@@ -519,53 +519,185 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
 #pragma nounroll
     for (int c = 0; c < nk_tail; c += 2) {
       const bool two = c + 1 < nk_tail;
-      issue_a(TailK{}, c, As);
-      if (two) issue_a(TailK{}, c + 1, As + A_TILE);
-      gload_b(TailK{}, c);
-      store_b(TailK{}, c, Bs);
+      issue_a(TailK{}, c, As, true);
+      if (two) issue_a(TailK{}, c + 1, As + A_TILE, true);
+      gload_b(TailK{}, c, Set0{}, true);
+      store_b(TailK{}, c, Bs, Set0{}, AllPieces{});
       if (two) {
-        gload_b(TailK{}, c + 1);
-        store_b(TailK{}, c + 1, Bs + B_TILE);
+        gload_b(TailK{}, c + 1, Set0{}, true);
+        store_b(TailK{}, c + 1, Bs + B_TILE, Set0{}, AllPieces{});
       }
       wait_and_barrier<0>();
-      compute(TailK{}, As, Bs);
-      if (two) compute(TailK{}, As + A_TILE, Bs + B_TILE);
+      compute(TailK{}, As, Bs, no_side);
+      if (two) compute(TailK{}, As + A_TILE, Bs + B_TILE, no_side);
       wait_and_barrier<0>();  // all reads done before the stages are refilled
     }
-    pipeline(MainK{}, nk_tail, it_end);
+
+    // Main steps.  K step `it` in pipeline slot `slot` (A stage slot % 3, B stage and register
+    // set slot % 2, the parity `par` being a compile-time constant):
+    //   entry : A(it), B(it) visible in LDS; the LDS-DMA of A(it+1) and the register loads of
+    //           step it+1 (set par^1) were issued one step ago
+    //   1. start the LDS-DMA of A(it+2) and the register loads of step it+2 (set par)
+    //   2. wait until only those are outstanding: A(it+1) and the registers of it+1 have landed
+    //   3. matrix cores on step it; in their shadow, slice by slice, the registers of it+1 are
+    //      dequantised into the other B stage
+    //   4. this wave's LDS writes done, barrier
+    // Steps past the end issue the same number of loads, aimed outside the buffers.
+    const int pb = nk_tail, pe = it_end;
+    constexpr int kKeep = A_LOADS + kBLoadsMain;
+    auto step = [&](int it, int slot, auto par) {
+      constexpr int kPar = decltype(par)::value;
+      using SetCur = std::integral_constant<int, kPar>;
+      using SetNext = std::integral_constant<int, kPar ^ 1>;
+      const int sa = slot % 3, sa2 = (slot + 2) % 3;
+      with_step_regions(
+          As + sa2 * A_TILE, As + sa * A_TILE, Bs + kPar * B_TILE, Bs + (kPar ^ 1) * B_TILE,
+          [&](uint16_t* a_dma, const uint16_t* a_rd, const uint16_t* b_rd, uint16_t* b_wr) {
+            const bool live2 = it + 2 < pe;
+#ifndef GX_NOADMA
+            issue_a(MainK{}, it + 2, a_dma, live2);
+#endif
+#ifndef GX_NOBLOAD
+            gload_b(MainK{}, it + 2, SetCur{}, live2);
+#endif
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kKeep) : "memory");
+#ifdef GX_NOSIDE
+            compute(MainK{}, a_rd, b_rd, no_side);
+#else
+            compute(MainK{}, a_rd, b_rd,
+                    [&](auto kk) { store_b(MainK{}, it + 1, b_wr, SetNext{}, kk); });
+#endif
+          });
+#ifdef GX_NOBAR
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#else
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#endif
+    };
+    if (pe > pb) {
+      // prologue: A(pb), A(pb+1) in flight, registers of pb (set 0) and pb+1 (set 1) loading;
+      // B(pb) dequantised into stage 0
+      issue_a(MainK{}, pb, As, true);
+      gload_b(MainK{}, pb, Set0{}, true);
+      issue_a(MainK{}, pb + 1, As + A_TILE, pb + 1 < pe);
+      gload_b(MainK{}, pb + 1, Set1{}, pb + 1 < pe);
+      __builtin_amdgcn_sched_barrier(0);
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kKeep) : "memory");
+      store_b(MainK{}, pb, Bs, Set0{}, AllPieces{});
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      int it = pb, slot = 0;
+#pragma nounroll
+      for (; it + 1 < pe; it += 2, slot += 2) {  // hot loop: two steps, one per parity
+        step(it, slot, Set0{});
+        step(it + 1, slot + 1, Set1{});
+      }
+      if (it < pe) step(it, slot, Set0{});
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the out-of-range loads of the last steps
+    }
   } else {
-    pipeline(TailK{}, it_begin, it_end);
+    // Plain product over the tail operands: one register set, so the copy of step it+1 into
+    // LDS and the loads of step it+2 follow the matrix-core work of step it.
+    //   entry : A(it), B(it) visible in LDS; A(it+1) LDS-DMA in flight; registers hold it+1
+    auto step = [&](auto n1, auto n2, int it, int slot) {
+      constexpr bool kHas1 = decltype(n1)::value != 2;
+      constexpr bool kHas2 = decltype(n2)::value != 2;
+      const int sa = slot % 3, sa2 = (slot + 2) % 3, sb = slot & 1;
+      with_step_regions(
+          As + sa2 * A_TILE, As + sa * A_TILE, Bs + sb * B_TILE, Bs + (sb ^ 1) * B_TILE,
+          [&](uint16_t* a_dma, const uint16_t* a_rd, const uint16_t* b_rd, uint16_t* b_wr) {
+            if constexpr (kHas2) issue_a(TailK{}, it + 2, a_dma, true);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(TailK{}, a_rd, b_rd, no_side);
+            if constexpr (kHas1) store_b(TailK{}, it + 1, b_wr, Set0{}, AllPieces{});
+            if constexpr (kHas2) gload_b(TailK{}, it + 2, Set0{}, true);
+          });
+      constexpr int kKeepT = kHas2 ? A_LOADS + kBLoadsTail : 0;
+      wait_and_barrier<kKeepT>();
+    };
+    const int pb = it_begin, pe = it_end;
+    const int n = pe - pb;
+    if (n > 0) {
+      issue_a(TailK{}, pb, As, true);
+      gload_b(TailK{}, pb, Set0{}, true);
+      if (n > 1) issue_a(TailK{}, pb + 1, As + A_TILE, true);
+      store_b(TailK{}, pb, Bs, Set0{}, AllPieces{});
+      if (n > 1) gload_b(TailK{}, pb + 1, Set0{}, true);
+      wait_and_barrier<0>();  // prologue only: drain everything
+      int it = pb, slot = 0;
+#pragma nounroll
+      for (; it + 2 < pe; ++it, ++slot) step(TailK{}, TailK{}, it, slot);  // hot loop
+      if (it + 1 < pe) {
+        step(TailK{}, NoneK{}, it, slot);
+        ++it, ++slot;
+      }
+      step(NoneK{}, NoneK{}, it, slot);
+    }
   }
 
   // ---- epilogue: D[m][n] lives at lane n%32, register 4*(m/8) + m%4, half (m/4)%2 ----
-  // (thread coordinates are re-derived here so that nothing but the accumulators has to
-  // stay live across the K loop)
+  // The tile is rescaled, converted and transposed through LDS (free by now), so that global
+  // memory sees 16-byte stores covering whole 512- or 1024-byte rows of the tile.  The row
+  // scales are fetched once into LDS first.  (Thread coordinates are re-derived here so that
+  // nothing but the accumulators has to stay live across the K loop.)
   int e_tid = threadIdx.x;
   asm volatile("" : "+v"(e_tid));
   const int e_lane = e_tid & 63, e_wave = e_tid >> 6;
   const int e_wm = e_wave % WAVES_M, e_wn = e_wave / WAVES_M;
   const size_t zoff = (size_t)blockIdx.y * (size_t)p.M * (size_t)p.N;
+  float* inv_s = reinterpret_cast<float*>(smem);  // [BM]
+  char* stage = reinterpret_cast<char*>(smem) + BM * 4;
+  __syncthreads();  // every wave is past its last LDS read of the K loop
+  if (e_tid < BM)
+    inv_s[e_tid] = (HAS_MAIN && m0 + e_tid < p.M) ? p.row_scale[m0 + e_tid].y : 1.0f;
   auto epilogue = [&](auto as_bf16) {
     constexpr bool kBf16 = decltype(as_bf16)::value;
+    constexpr int ES = kBf16 ? 2 : 4;
+    constexpr int ROW = BN * ES + 16;  // staged row stride (+16: spreads rows over banks)
+    constexpr int kLds = (3 * BM + 2 * BN) * 64 * 2;
+    constexpr int kPasses = (BM * ROW + BM * 4 > kLds) ? 2 : 1;
+    constexpr int RP = BM / kPasses;  // rows staged per pass
+    static_assert(RP % WTM == 0 && RP * ROW + BM * 4 <= kLds, "a pass is whole wave row-bands");
+    constexpr int CPR = BN * ES / 16;  // 16-byte chunks per row
+    static_assert(NT % CPR == 0, "threads tile the rows of a pass");
+    __syncthreads();  // row scales visible
 #pragma unroll
-    for (int a = 0; a < TM; ++a) {
+    for (int pass = 0; pass < kPasses; ++pass) {
+      if (pass > 0) __syncthreads();  // the previous pass has been read out
+      if ((e_wm * WTM) / RP == pass) {
+        const int rbase = e_wm * WTM - pass * RP;
 #pragma unroll
-      for (int b = 0; b < TN; ++b) {
-        const int col = n0 + e_wn * WTN + b * 32 + (e_lane & 31);
+        for (int a = 0; a < TM; ++a) {
+          f32x4 inv[4];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = m0 + e_wm * WTM + a * 32 + 8 * (r >> 2) + 4 * (e_lane >> 5) + (r & 3);
-          if (row < p.M && col < p.N) {
-            const float inv = HAS_MAIN ? p.row_scale[row].y : 1.0f;
-            const size_t o = zoff + (size_t)row * p.N + col;
-            const float v = acc[a][b][r] * inv;
-            if constexpr (kBf16)
-              static_cast<uint16_t*>(p.out)[o] = f32_to_bf16_bits(v);
-            else
-              static_cast<float*>(p.out)[o] = v;
+          for (int g4 = 0; g4 < 4; ++g4)
+            inv[g4] = *reinterpret_cast<const f32x4*>(inv_s + e_wm * WTM + a * 32 + 8 * g4 + 4 * (e_lane >> 5));
+#pragma unroll
+          for (int b = 0; b < TN; ++b) {
+            const int cl = e_wn * WTN + b * 32 + (e_lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int rl = rbase + a * 32 + 8 * (r >> 2) + 4 * (e_lane >> 5) + (r & 3);
+              const float v = acc[a][b][r] * inv[r >> 2][r & 3];
+              if constexpr (kBf16)
+                *reinterpret_cast<uint16_t*>(stage + rl * ROW + cl * 2) = f32_to_bf16_bits(v);
+              else
+                *reinterpret_cast<float*>(stage + rl * ROW + cl * 4) = v;
+            }
           }
         }
-        __builtin_amdgcn_sched_barrier(0);  // one 32x32 tile at a time: keeps registers low
+      }
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < RP * CPR / NT; ++k) {
+        const int idx = e_tid + NT * k;
+        const int rl = idx / CPR, ch = idx % CPR;
+        const int row = m0 + pass * RP + rl, col = n0 + ch * (16 / ES);
+        if (row < p.M && col < p.N) {
+          const uint4 v = *reinterpret_cast<const uint4*>(stage + rl * ROW + ch * 16);
+          char* o = static_cast<char*>(p.out) + (zoff + (size_t)row * p.N + col) * ES;
+          *reinterpret_cast<uint4*>(o) = v;
+        }
       }
     }
   };
