@@ -23,10 +23,36 @@ FLAGS = [
 ]
 
 
+# Kernels whose waits on outstanding memory operations are counted by hand: a register spill
+# would add scratch traffic to the same counter, so they must compile with zero scratch.
+NO_SCRATCH = {"gemm_dq.hip": "gemm_dq_kernel", "smallt.hip": "smallt_kernel"}
+
+
+def _check_no_scratch(src: str, remarks: str) -> None:
+    """Parse -Rpass-analysis=kernel-resource-usage remarks; fail on any scratch use."""
+    name, bad = None, []
+    for line in remarks.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split()[0]
+        elif "ScratchSize [bytes/lane]:" in line and name and NO_SCRATCH[src] in name:
+            if int(line.split("ScratchSize [bytes/lane]:")[1].split()[0]) != 0:
+                bad.append(name)
+    if bad:
+        raise RuntimeError(f"{src}: kernels with hand-counted waits use scratch memory: {bad}")
+
+
 def _compile(src: str, extra) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
     cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
-    subprocess.check_call(cmd)
+    if src in NO_SCRATCH:
+        cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if res.returncode != 0:
+            sys.stderr.write(res.stdout)
+            raise subprocess.CalledProcessError(res.returncode, cmd)
+        _check_no_scratch(src, res.stdout)
+    else:
+        subprocess.check_call(cmd)
     return obj
 
 

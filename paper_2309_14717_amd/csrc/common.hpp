@@ -124,15 +124,26 @@ __device__ __forceinline__ uint32_t patch_code(uint32_t w0s, uint32_t w1s, int p
 // The codes of rows 2m and 2m+1 (m = 0..3) of the patch, for one column, as an exact pair
 // of fp16 integers (low half = even row).  0x6400 is fp16 1024.0, whose mantissa unit is 1,
 // so (0x6400 | c) - 1024 == c for c < 1024 without any int->float conversion.
+// `mask` and `magic` are the constants (2^LB - 1) * 0x00010001 and 0x64006400 handed in by the
+// caller: a kernel that keeps them in registers gets "(w >> k) & mask | magic" as one shift and
+// one v_and_or_b32 (a VOP3 instruction cannot carry a 32-bit literal on gfx9-class targets).
 template <int NBITS>
-__device__ __forceinline__ f16x2 patch_code_pair_f16(uint32_t w0s, uint32_t w1s, int m) {
+__device__ __forceinline__ f16x2 patch_code_pair_f16(uint32_t w0s, uint32_t w1s, int m,
+                                                     uint32_t mask, uint32_t magic) {
   constexpr int LB = (NBITS == 3) ? 2 : NBITS;  // code bits held in plane 0
-  constexpr uint32_t kMask0 = ((1u << LB) - 1u) * 0x00010001u;
-  uint32_t u = (w0s >> (LB * m)) & kMask0;
-  if constexpr (NBITS == 3) u |= ((w1s >> m) & 0x00010001u) << 2;
-  u |= 0x64006400u;
+  uint32_t u;
+  if constexpr (NBITS == 3) {
+    u = ((w0s >> (LB * m)) & mask) | (((w1s >> m) & 0x00010001u) << 2);
+    u |= magic;
+  } else {
+    u = ((w0s >> (LB * m)) & mask) | magic;
+  }
   const f16x2 k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
   return __builtin_bit_cast(f16x2, u) - k1024;
+}
+template <int NBITS>
+__host__ __device__ constexpr uint32_t patch_code_mask() {
+  return ((1u << ((NBITS == 3) ? 2 : NBITS)) - 1u) * 0x00010001u;
 }
 
 }  // namespace qalora

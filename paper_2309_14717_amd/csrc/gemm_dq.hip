@@ -358,10 +358,16 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     const f32x2 abf = {__uint_as_float(a_bits), __uint_as_float(b_bits)};
     return __builtin_convertvector(abf, f16x2);
   };
+  // extraction constants held in registers (see patch_code_pair_f16)
+  uint32_t dq_mask = patch_code_mask<NBITS>(), dq_magic = 0x64006400u;
+  if constexpr (NBITS != 3) {  // (the 3-bit extraction has a second plane and no such fusion)
+    asm volatile("s_mov_b32 %0, %1" : "=s"(dq_mask) : "n"(patch_code_mask<NBITS>()));
+    asm volatile("v_mov_b32 %0, 0x64006400" : "=v"(dq_magic));
+  }
   auto dq_pair = [&](uint32_t w0s, uint32_t w1s, f16x2 ab, int m) {
     const f16x2 a2 = {ab.x, ab.x};
     const f16x2 b2 = {ab.y, ab.y};
-    const f16x2 cc = patch_code_pair_f16<NBITS>(w0s, w1s, m);
+    const f16x2 cc = patch_code_pair_f16<NBITS>(w0s, w1s, m, dq_mask, dq_magic);
     return __builtin_bit_cast(uint32_t, cc * a2 + b2);
   };
 
