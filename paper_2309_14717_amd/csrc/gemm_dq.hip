@@ -101,6 +101,15 @@ __device__ __forceinline__ void with_step_regions(uint16_t* __restrict__ a_dma,
                                                   uint16_t* __restrict__ b_wr, F&& f) {
   f(a_dma, a_rd, b_rd, b_wr);
 }
+// Main pipeline: additionally the A stage of the next step (read at the end of the step).
+template <typename F>
+__device__ __forceinline__ void with_step_regions(uint16_t* __restrict__ a_dma,
+                                                  const uint16_t* __restrict__ a_rd,
+                                                  const uint16_t* __restrict__ a_nx,
+                                                  const uint16_t* __restrict__ b_rd,
+                                                  uint16_t* __restrict__ b_wr, F&& f) {
+  f(a_dma, a_rd, a_nx, b_rd, b_wr);
+}
 
 // HAS_MAIN = false: a plain bf16 x bf16^T product over the "tail" operands only (used for
 // dU = s dy B^T), optionally split along K over blockIdx.y.
@@ -372,8 +381,8 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
   };
 
   // Dequantise the register set `set` of step `it` into the B stage b_dst.  The work is cut in
-  // four pieces (piece = 0..3, or -1 for all of it) so that it can be spread over the four
-  // K-16 slices of the matrix-core work of the step before.
+  // three pieces (piece = 0..2, or -1 for all of it) so that it can be spread over the first
+  // three K-16 slices of the matrix-core work of the step before.
   uint32_t wt[8][2];  // backward: [column][row pair] (W~[2m][c], W~[2m+1][c]), kept across pieces
   auto store_b = [&](auto kind, int it, uint16_t* b_dst, auto set, auto piece_c) {
     constexpr bool kMain = decltype(kind)::value == 0;
@@ -391,7 +400,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
         const uint32_t be[4] = {breg[2].x, breg[2].y, breg[2].z, breg[2].w};
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-          if (piece >= 0 && c != piece) continue;
+          if (piece >= 0 && (piece == 2 ? c < 2 : c != piece)) continue;  // columns {0}, {1}, {2, 3}
           const uint32_t w0s = w0[c] >> sh0;
           const uint32_t w1s = (NBITS == 3) ? (w1[c] >> sh1) : 0u;
           const f16x2 ab = ab_pair(al[c], be[c]);
@@ -415,17 +424,17 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
                                 breg[3].x, breg[3].y, breg[3].z, breg[3].w};
         const uint32_t be[8] = {breg[4].x, breg[4].y, breg[4].z, breg[4].w,
                                 breg[5].x, breg[5].y, breg[5].z, breg[5].w};
-        // pieces 0, 1, 2 dequantise columns 0-2, 3-5, 6-7; piece 3 gathers and writes
+        // pieces 0 and 1 dequantise columns 0-3 and 4-7; piece 2 gathers and writes
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
-          if (piece >= 0 && c / 3 != piece) continue;
+          if (piece >= 0 && c / 4 != piece) continue;
           const uint32_t w0s = w0[c] >> sh0;
           const uint32_t w1s = (NBITS == 3) ? (w1[c] >> sh1) : 0u;
           const f16x2 ab = ab_pair(al[c], be[c]);
           wt[c][0] = dq_pair(w0s, w1s, ab, 0);
           wt[c][1] = dq_pair(w0s, w1s, ab, 1);
         }
-        if (piece >= 0 && piece != 3) return;
+        if (piece >= 0 && piece != 2) return;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {  // row 4*hb + r of the patch: gather the 8 columns
           uint32_t o[4];
@@ -479,11 +488,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     auto slice = [&](auto kk_c) {
       constexpr int kk = decltype(kk_c)::value;
       constexpr int cur = kk & 1;
-#ifdef GX_NOFRAG
-      if (kk == 0) load_frags(kk + 1, cur ^ 1);
-#else
       if (kk + 1 < BK / 16) load_frags(kk + 1, cur ^ 1);  // next slice in flight under the MFMAs
-#endif
       side(kk_c);
 #pragma unroll
       for (int a = 0; a < TM; ++a)
@@ -514,6 +519,57 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     slice(std::integral_constant<int, 3>{});
   };
   auto no_side = [](auto) {};
+
+  // Main-pipeline variant.  The fragment registers live across steps: slices 0-2 carry the
+  // side work (the dequantisation of the next step, one piece each), then the block
+  // synchronises, and slice 3 runs while the first fragments of the NEXT step are fetched
+  // from the stages that barrier has just published -- so a step starts on the matrix cores
+  // at once instead of waiting for an LDS round trip.
+  uint4 maf[2][TM], mbf[2][TN];
+  auto load_frags_main = [&](const uint16_t* a_src, const uint16_t* b_src, int kk, auto slot_c) {
+    constexpr int slot = decltype(slot_c)::value;
+    const int cx = (2 * kk + (lane >> 5)) << 4;
+    const char* ap = reinterpret_cast<const char*>(a_src) + (a_lane ^ cx);
+    const char* bp = reinterpret_cast<const char*>(b_src) + (b_lane ^ cx);
+#pragma unroll
+    for (int a = 0; a < TM; ++a) maf[slot][a] = *reinterpret_cast<const uint4*>(ap + a * 4096);
+#pragma unroll
+    for (int b = 0; b < TN; ++b) mbf[slot][b] = *reinterpret_cast<const uint4*>(bp + b * 4096);
+  };
+  auto compute_main = [&](const uint16_t* a_rd, const uint16_t* b_rd, const uint16_t* a_nx,
+                          const uint16_t* b_nx, auto&& side) {
+    auto slice = [&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value;
+      constexpr int cur = kk & 1;
+      using Nxt = std::integral_constant<int, cur ^ 1>;
+      if constexpr (kk < 3) {
+        load_frags_main(a_rd, b_rd, kk + 1, Nxt{});
+        side(kk_c);
+      } else {
+        load_frags_main(a_nx, b_nx, 0, Nxt{});
+      }
+#pragma unroll
+      for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+              __builtin_bit_cast(f16x8, maf[cur][a]), __builtin_bit_cast(f16x8, mbf[cur][b]),
+              acc[a][b], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < TM * TN; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+        __builtin_amdgcn_sched_group_barrier(0x002, kSideValuPerMfma, 0);  // VALU
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    slice(std::integral_constant<int, 0>{});
+    slice(std::integral_constant<int, 1>{});
+    slice(std::integral_constant<int, 2>{});
+    // this wave's LDS writes (next B stage) and reads (fragments of slice 3) are done
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    slice(std::integral_constant<int, 3>{});
+  };
 
   // Vector-memory ops per thread of one B-register load, per step kind (for the waits).
   constexpr int kBLoadsMain = BWD ? (NBITS == 3 ? 8 : 6) : (NBITS == 3 ? 4 : 3);
@@ -555,31 +611,20 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
       constexpr int kPar = decltype(par)::value;
       using SetCur = std::integral_constant<int, kPar>;
       using SetNext = std::integral_constant<int, kPar ^ 1>;
-      const int sa = slot % 3, sa2 = (slot + 2) % 3;
+      const int sa = slot % 3, sa1 = (slot + 1) % 3, sa2 = (slot + 2) % 3;
       with_step_regions(
-          As + sa2 * A_TILE, As + sa * A_TILE, Bs + kPar * B_TILE, Bs + (kPar ^ 1) * B_TILE,
-          [&](uint16_t* a_dma, const uint16_t* a_rd, const uint16_t* b_rd, uint16_t* b_wr) {
+          As + sa2 * A_TILE, As + sa * A_TILE, As + sa1 * A_TILE, Bs + kPar * B_TILE,
+          Bs + (kPar ^ 1) * B_TILE,
+          [&](uint16_t* a_dma, const uint16_t* a_rd, const uint16_t* a_nx, const uint16_t* b_rd,
+              uint16_t* b_wr) {
             const bool live2 = it + 2 < pe;
-#ifndef GX_NOADMA
             issue_a(MainK{}, it + 2, a_dma, live2);
-#endif
-#ifndef GX_NOBLOAD
             gload_b(MainK{}, it + 2, SetCur{}, live2);
-#endif
             __builtin_amdgcn_sched_barrier(0);
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kKeep) : "memory");
-#ifdef GX_NOSIDE
-            compute(MainK{}, a_rd, b_rd, no_side);
-#else
-            compute(MainK{}, a_rd, b_rd,
-                    [&](auto kk) { store_b(MainK{}, it + 1, b_wr, SetNext{}, kk); });
-#endif
+            compute_main(a_rd, b_rd, a_nx, b_wr,
+                         [&](auto kk) { store_b(MainK{}, it + 1, b_wr, SetNext{}, kk); });
           });
-#ifdef GX_NOBAR
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#else
-      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-#endif
     };
     if (pe > pb) {
       // prologue: A(pb), A(pb+1) in flight, registers of pb (set 0) and pb+1 (set 1) loading;
@@ -592,6 +637,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kKeep) : "memory");
       store_b(MainK{}, pb, Bs, Set0{}, AllPieces{});
       asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      load_frags_main(As, Bs, 0, Set0{});
       int it = pb, slot = 0;
 #pragma nounroll
       for (; it + 1 < pe; it += 2, slot += 2) {  // hot loop: two steps, one per parity
@@ -732,9 +778,13 @@ static hipError_t launch_cfg(const GemmArgs& a, int ksplit, hipStream_t st) {
 template <int NBITS, bool BWD>
 static hipError_t launch_dir(const GemmArgs& a, hipStream_t st) {
   if (a.M > 128) {
-    const bool fast = a.a_main_padded_rows >= round_up(a.M, 256) && a.K_main % BK == 0 &&
-                      (BK % a.group == 0 || a.group % BK == 0);
-    if (fast) return launch_cfg<NBITS, BWD, 256, 256, 2, 4, true, true>(a, 1, st);
+    // (the 3-bit backward producer holds two code planes in both register sets: it does not
+    // fit the 256-row tile without spilling and takes the 128-row tile instead)
+    if constexpr (!(NBITS == 3 && BWD)) {
+      const bool fast = a.a_main_padded_rows >= round_up(a.M, 256) && a.K_main % BK == 0 &&
+                        (BK % a.group == 0 || a.group % BK == 0);
+      if (fast) return launch_cfg<NBITS, BWD, 256, 256, 2, 4, true, true>(a, 1, st);
+    }
     return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, false>(a, 1, st);
   }
   if (a.M > 64) return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, false>(a, 1, st);
