@@ -18,12 +18,12 @@ int row_align_for_bits(int bits) { return bits == 4 ? 8 : (bits == 2 ? 16 : 32);
 // Workspace plans.  Offsets are a pure function of (desc, tokens), so the size query and
 // the compute call always agree.
 struct FwdPlan {
-  int ktail;
-  size_t rs, a16, u_ext, b_ext_t, total;
+  int ktail, gsplit;
+  size_t rs, a16, u_ext, b_ext_t, gpart, total;
 };
 struct BwdPlan {
-  int ktail, rp, t_pad, ksplit, tsplit_b, tsplit_a;
-  size_t rs, a16, P, us_t, b_hl, a_ext_t, du_raw, du_ext, db_part, da_part, total;
+  int ktail, rp, t_pad, ksplit, tsplit_b, tsplit_a, gsplit;
+  size_t rs, a16, P, us_t, b_hl, a_ext_t, du_raw, du_ext, db_part, da_part, gpart, total;
 };
 
 FwdPlan plan_forward(const qalora_desc& d, int T) {
@@ -40,6 +40,11 @@ FwdPlan plan_forward(const qalora_desc& d, int T) {
     p.b_ext_t = off;
     off += align_up((size_t)d.d_out * p.ktail * 2);
   }
+  p.gsplit = gemm_dq_ksplit(T, d.d_out, d.d_in);
+  if (p.gsplit > 1) {
+    p.gpart = off;
+    off += align_up((size_t)p.gsplit * T * d.d_out * 4);
+  }
   p.total = off;
   return p;
 }
@@ -54,6 +59,11 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
     p.rs = 0;
     p.a16 = align_up((size_t)T * sizeof(float2));
     p.total = p.a16 + align_up((size_t)round_up(T, 256) * d.d_out * 2);
+    p.gsplit = gemm_dq_ksplit(T, d.d_in, d.d_out);
+    if (p.gsplit > 1) {
+      p.gpart = p.total;
+      p.total += align_up((size_t)p.gsplit * T * d.d_in * 4);
+    }
     return p;
   }
   // dU product: [T, 2rp] output tiles of 64 x 128; split K = d_out to fill the chip.
@@ -93,6 +103,8 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
   p.du_ext = take((size_t)T * p.ktail * 2);
   p.db_part = take((size_t)p.tsplit_b * d.rank * d.d_out * 4);
   p.da_part = take((size_t)p.tsplit_a * L * d.rank * 4);
+  p.gsplit = gemm_dq_ksplit(T, d.d_in, d.d_out);
+  if (p.gsplit > 1) p.gpart = take((size_t)p.gsplit * T * d.d_in * 4);
   p.total = off;
   return p;
 }
@@ -237,7 +249,13 @@ int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* 
     return launch_smallt(a, as_stream(stream)) == hipSuccess ? QALORA_OK : QALORA_EHIP;
   }
   FwdPlan plan = plan_forward(*d, tokens);
-  if (!adapter) plan.total = plan.a16 + align_up((size_t)round_up(tokens, 256) * d->d_in * 2);
+  if (!adapter) {  // no adapter operands: the partial sums (if any) follow the fp16 copy
+    plan.total = plan.a16 + align_up((size_t)round_up(tokens, 256) * d->d_in * 2);
+    if (plan.gsplit > 1) {
+      plan.gpart = plan.total;
+      plan.total += align_up((size_t)plan.gsplit * tokens * d->d_out * 4);
+    }
+  }
   if (!ws || ws_bytes < plan.total) return QALORA_EWORKSPACE;
   hipStream_t st = as_stream(stream);
   char* w = static_cast<char*>(ws);
@@ -261,6 +279,8 @@ int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* 
   g.d_out = d->d_out;
   g.group = d->group;
   g.row_scale = rs;
+  g.ksplit = plan.gsplit;
+  g.partial = plan.gsplit > 1 ? reinterpret_cast<float*>(w + plan.gpart) : nullptr;
   uint16_t* u_ext = adapter ? reinterpret_cast<uint16_t*>(w + plan.u_ext) : nullptr;
   uint16_t* b_ext_t = adapter ? reinterpret_cast<uint16_t*>(w + plan.b_ext_t) : nullptr;
   if (launch_front_forward(static_cast<const uint16_t*>(x), tokens, d->d_in, rs, x16,
@@ -297,6 +317,10 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
     plan.rs = 0;
     plan.a16 = align_up((size_t)tokens * sizeof(float2));
     plan.total = plan.a16 + align_up((size_t)round_up(tokens, 256) * d->d_out * 2);
+    if (plan.gsplit > 1) {
+      plan.gpart = plan.total;
+      plan.total += align_up((size_t)plan.gsplit * tokens * d->d_in * 4);
+    }
   }
   if (!ws || ws_bytes < plan.total) return QALORA_EWORKSPACE;
   hipStream_t st = as_stream(stream);
@@ -369,6 +393,8 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
     g.d_out = d->d_out;
     g.group = d->group;
     g.row_scale = rs;
+    g.ksplit = plan.gsplit;
+    g.partial = plan.gsplit > 1 ? reinterpret_cast<float*>(w + plan.gpart) : nullptr;
     if (adapter) {
       g.a_tail = du_ext;
       g.lda_tail = plan.ktail;

@@ -157,11 +157,24 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
 
   const int nk_main = HAS_MAIN ? ceil_div(p.K_main, BK) : 0;
   const int nk_tail = ceil_div(p.K_tail, BK);
+  // blockIdx.y splits the K range (partial sums, added by a later launch in a fixed order):
+  // the tail steps of a plain product, or the main steps of the dequantising one (whose
+  // adapter tail then belongs to slice 0 alone).
   int it_begin = 0, it_end = nk_main + nk_tail;
-  if (!HAS_MAIN && gridDim.y > 1) {
-    const int per = ceil_div(nk_tail, (int)gridDim.y);
-    it_begin = blockIdx.y * per;
-    it_end = min(nk_tail, it_begin + per);
+  int nk_tail_run = nk_tail;  // tail steps this block runs in front of its main steps
+  if (gridDim.y > 1) {
+    if constexpr (HAS_MAIN) {
+      const int per = ceil_div(nk_main, (int)gridDim.y);
+      it_begin = nk_tail + blockIdx.y * per;
+      it_end = min(nk_main + nk_tail, it_begin + per);
+      if (blockIdx.y != 0) nk_tail_run = 0;
+    } else {
+      const int per = ceil_div(nk_tail, (int)gridDim.y);
+      it_begin = blockIdx.y * per;
+      it_end = min(nk_tail, it_begin + per);
+    }
+  } else if constexpr (HAS_MAIN) {
+    it_begin = nk_tail;
   }
 
   f32x16 acc[TM][TN];
@@ -579,8 +592,8 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     // The adapter (tail) steps run FIRST, two at a time and without software pipelining
     // (there are at most a handful); nothing tail-specific stays live across the hot loop.
 #pragma nounroll
-    for (int c = 0; c < nk_tail; c += 2) {
-      const bool two = c + 1 < nk_tail;
+    for (int c = 0; c < nk_tail_run; c += 2) {
+      const bool two = c + 1 < nk_tail_run;
       issue_a(TailK{}, c, As, true);
       if (two) issue_a(TailK{}, c + 1, As + A_TILE, true);
       gload_b(TailK{}, c, Set0{}, true);
@@ -605,7 +618,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     //      dequantised into the other B stage
     //   4. this wave's LDS writes done, barrier
     // Steps past the end issue the same number of loads, aimed outside the buffers.
-    const int pb = nk_tail, pe = it_end;
+    const int pb = it_begin, pe = it_end;
     constexpr int kKeep = A_LOADS + kBLoadsMain;
     auto step = [&](int it, int slot, auto par) {
       constexpr int kPar = decltype(par)::value;
@@ -777,18 +790,46 @@ static hipError_t launch_cfg(const GemmArgs& a, int ksplit, hipStream_t st) {
 
 template <int NBITS, bool BWD>
 static hipError_t launch_dir(const GemmArgs& a, hipStream_t st) {
+  const int ks = a.ksplit > 1 ? a.ksplit : 1;
   if (a.M > 128) {
     // (the 3-bit backward producer holds two code planes in both register sets: it does not
     // fit the 256-row tile without spilling and takes the 128-row tile instead)
     if constexpr (!(NBITS == 3 && BWD)) {
       const bool fast = a.a_main_padded_rows >= round_up(a.M, 256) && a.K_main % BK == 0 &&
                         (BK % a.group == 0 || a.group % BK == 0);
-      if (fast) return launch_cfg<NBITS, BWD, 256, 256, 2, 4, true, true>(a, 1, st);
+      if (fast) return launch_cfg<NBITS, BWD, 256, 256, 2, 4, true, true>(a, ks, st);
     }
-    return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, false>(a, 1, st);
+    return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, false>(a, ks, st);
   }
-  if (a.M > 64) return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, false>(a, 1, st);
-  return launch_cfg<NBITS, BWD, 64, 256, 1, 8, true, false>(a, 1, st);
+  if (a.M > 64) return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, false>(a, ks, st);
+  return launch_cfg<NBITS, BWD, 64, 256, 1, 8, true, false>(a, ks, st);
+}
+
+// K splits of the dequantising product for token counts that leave most compute units
+// without a tile: enough slices to occupy them, at least eight K steps each.
+int gemm_dq_ksplit(int M, int N, int K_main) {
+  const int bm = M > 128 ? 256 : (M > 64 ? 128 : 64);
+  const int tiles = ceil_div(M, bm) * ceil_div(N, 256);
+  if (tiles >= 128) return 1;
+  int ks = 256 / tiles;
+  const int max_ks = ceil_div(K_main, BK) / 8;
+  if (ks > max_ks) ks = max_ks;
+  if (ks > 16) ks = 16;
+  return ks < 1 ? 1 : ks;
+}
+
+// out = sum over the K slices of the partial products, slice order, converted on the way out
+__global__ __launch_bounds__(256) void split_reduce_kernel(const float* __restrict__ part,
+                                                           int nparts, size_t n4, void* out,
+                                                           int out_bf16) {
+  const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;  // group of 4 elements
+  if (i >= n4) return;
+  f32x4 v = reinterpret_cast<const f32x4*>(part)[i];
+  for (int z = 1; z < nparts; ++z) v += reinterpret_cast<const f32x4*>(part)[(size_t)z * n4 + i];
+  if (out_bf16)
+    reinterpret_cast<uint2*>(out)[i] = uint2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+  else
+    reinterpret_cast<f32x4*>(out)[i] = v;
 }
 
 ProfileHook g_profile_hook[2] = {{nullptr, nullptr}, {nullptr, nullptr}};
@@ -799,11 +840,23 @@ static hipError_t launch_bits(int bits, bool bwd, const GemmArgs& a, hipStream_t
   return bwd ? launch_dir<2, true>(a, st) : launch_dir<2, false>(a, st);
 }
 
-hipError_t launch_gemm_dq(int bits, bool bwd, const GemmArgs& a, hipStream_t st) {
+hipError_t launch_gemm_dq(int bits, bool bwd, const GemmArgs& args, hipStream_t st) {
+  GemmArgs a = args;
+  const bool split = a.ksplit > 1;
+  if (split) {  // slices write fp32 partials; the sum is converted afterwards
+    a.out = a.partial;
+    a.out_bf16 = 0;
+  }
   ProfileHook hook = g_profile_hook[bwd ? 1 : 0];
   g_profile_hook[bwd ? 1 : 0] = ProfileHook{nullptr, nullptr};
   if (hook.start) (void)hipEventRecord(hook.start, st);
-  const hipError_t e = launch_bits(bits, bwd, a, st);
+  hipError_t e = launch_bits(bits, bwd, a, st);
+  if (e == hipSuccess && split) {
+    const size_t n4 = (size_t)a.M * a.N / 4;  // N is a multiple of 8
+    split_reduce_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, st>>>(a.partial, a.ksplit, n4,
+                                                                      args.out, args.out_bf16);
+    e = hipGetLastError();
+  }
   if (hook.stop) (void)hipEventRecord(hook.stop, st);
   return e;
 }

@@ -31,12 +31,16 @@ struct GemmArgs {
   const float2* row_scale; // [M] (scale, 1/scale): power-of-two row scales of a_main
   void* out;               // [ksplit][M, N] fp32, or [M, N] bf16
   int out_bf16;
+  float* partial;          // [ksplit][M, N] fp32 when ksplit > 1 (dequantising product)
+  int ksplit;              // K slices of the dequantising product (0 or 1: none)
   int M, N;                // tokens; d_out (forward) or d_in (backward)
   int K_main;              // d_in (forward) or d_out (backward); 0 for a plain product
   int K_tail;              // multiple of 64 (zero padded), may be 0
   int d_in, d_out, group;
 };
 hipError_t launch_gemm_dq(int bits, bool bwd, const GemmArgs& a, hipStream_t st);
+// K slices the dequantising product should use for an [M x K_main] x [K_main x N] problem.
+int gemm_dq_ksplit(int M, int N, int K_main);
 // Measurement aid: events recorded around the next launch_gemm_dq of each direction.
 struct ProfileHook {
   hipEvent_t start, stop;
