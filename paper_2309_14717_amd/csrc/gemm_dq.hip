@@ -792,11 +792,13 @@ template <int NBITS, bool BWD>
 static hipError_t launch_dir(const GemmArgs& a, hipStream_t st) {
   const int ks = a.ksplit > 1 ? a.ksplit : 1;
   if (a.M > 128) {
+    const bool fast = a.a_main_padded_rows >= round_up(a.M, 256) && a.K_main % BK == 0 &&
+                      (BK % a.group == 0 || a.group % BK == 0);
     // (the 3-bit backward producer holds two code planes in both register sets: it does not
     // fit the 256-row tile without spilling and takes the 128-row tile instead)
-    if constexpr (!(NBITS == 3 && BWD)) {
-      const bool fast = a.a_main_padded_rows >= round_up(a.M, 256) && a.K_main % BK == 0 &&
-                        (BK % a.group == 0 || a.group % BK == 0);
+    if constexpr (NBITS == 3 && BWD) {
+      if (fast) return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, true>(a, ks, st);
+    } else {
       if (fast) return launch_cfg<NBITS, BWD, 256, 256, 2, 4, true, true>(a, ks, st);
     }
     return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, false>(a, ks, st);
