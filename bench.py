@@ -202,8 +202,8 @@ def cpu_oracle_baseline(fn_flops_pairs, label):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--bits", type=int, default=4, help="c4: code width")
     ap.add_argument("--group", type=int, default=32, help="c4: group size")

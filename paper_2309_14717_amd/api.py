@@ -110,9 +110,9 @@ def _check(rc, where):
 
 
 def _workspace(desc, tokens, op, ws):
-    need = workspace_bytes(desc, tokens, op)
+    # a caller-provided workspace is passed through as it is (the library checks its size)
     if ws is None:
-        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(max(workspace_bytes(desc, tokens, op), 16), dtype=torch.uint8, device="cuda")
     return ws, ws.numel()
 
 
