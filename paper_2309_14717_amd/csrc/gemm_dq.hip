@@ -217,11 +217,14 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     constexpr bool kMain = decltype(kind)::value == 0;
     const int k0 = kMain ? (it - nk_tail) * BK : it * BK;
     if constexpr (FAST && kMain) {
-      const uint32_t voff = live ? a_voff_main : kOobOffset;
+      // branch-free on purpose: OR-ing the mask into a valid offset puts it past any buffer
+      // (the range check looks at the vector offset alone, whatever the scalar offset is).
+      // A branch around a load would make the compiler's count of loads in flight -- and with
+      // it every wait it inserts for the code registers -- one too strict.
+      const uint32_t voff = a_voff_main | (live ? 0u : kOobOffset);
 #pragma unroll
       for (int q = 0; q < A_LOADS; ++q) {
-        const uint32_t soff =
-            live ? (uint32_t)k0 * 2u + (uint32_t)q * 64u * (uint32_t)p.lda_main * 2u : 0u;
+        const uint32_t soff = (uint32_t)k0 * 2u + (uint32_t)q * 64u * (uint32_t)p.lda_main * 2u;
         uint16_t* dst = a_dst + (q * 8 + wave) * 512;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a_main,
                                                  (__attribute__((address_space(3))) void*)dst, 16,
@@ -302,10 +305,11 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     uint4(&breg)[6] = bregs[decltype(set)::value];
     uint4(&breg1)[2] = bregs1[decltype(set)::value];
     if constexpr (kMain && FAST) {
-      const uint32_t km = live ? (uint32_t)(it - nk_tail) : 0u;  // main step index (uniform)
-      const uint32_t fb_voff_p0 = live ? fb_voff_p0_c : kOobOffset;
-      const uint32_t fb_voff_p1 = live ? fb_voff_p1_c : kOobOffset;
-      const uint32_t fb_voff_ab = live ? fb_voff_ab_c : kOobOffset;
+      const uint32_t km = (uint32_t)(it - nk_tail);  // main step index (uniform)
+      const uint32_t dead = live ? 0u : kOobOffset;   // branch-free, as for the A tile
+      const uint32_t fb_voff_p0 = fb_voff_p0_c | dead;
+      const uint32_t fb_voff_p1 = fb_voff_p1_c | dead;
+      const uint32_t fb_voff_ab = fb_voff_ab_c | dead;
       if constexpr (!BWD) {
         // scalar parts: word rows advance by 64/RB per step, group rows by 64/g (or 1 per g/64)
         const uint32_t s_p0 = km * (uint32_t)(BK / RB0) * p.d_out * 4u;
