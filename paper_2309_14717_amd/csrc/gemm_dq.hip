@@ -542,6 +542,8 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
   // synchronises, and slice 3 runs while the first fragments of the NEXT step are fetched
   // from the stages that barrier has just published -- so a step starts on the matrix cores
   // at once instead of waiting for an LDS round trip.
+  constexpr int kMainB = BWD ? (NBITS == 3 ? 8 : 6) : (NBITS == 3 ? 4 : 3);
+  constexpr int kMidKeep = kMainB + A_LOADS + kMainB;  // see the main step below
   uint4 maf[2][TM], mbf[2][TN];
   auto load_frags_main = [&](const uint16_t* a_src, const uint16_t* b_src, int kk, auto slot_c) {
     constexpr int slot = decltype(slot_c)::value;
@@ -554,7 +556,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     for (int b = 0; b < TN; ++b) mbf[slot][b] = *reinterpret_cast<const uint4*>(bp + b * 4096);
   };
   auto compute_main = [&](const uint16_t* a_rd, const uint16_t* b_rd, const uint16_t* a_nx,
-                          const uint16_t* b_nx, auto&& side) {
+                          const uint16_t* b_nx, auto&& side, auto&& after_barrier) {
     auto slice = [&](auto kk_c) {
       constexpr int kk = decltype(kk_c)::value;
       constexpr int cur = kk & 1;
@@ -584,7 +586,11 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     slice(std::integral_constant<int, 1>{});
     slice(std::integral_constant<int, 2>{});
     // this wave's LDS writes (next B stage) and reads (fragments of slice 3) are done
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // ... and its share of A(it+1) has landed: the loads issued since (registers of it+2, A(it+2),
+    // registers... see the step) may stay in flight
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(kMidKeep) : "memory");
+    after_barrier();
+    __builtin_amdgcn_sched_barrier(0);
     slice(std::integral_constant<int, 3>{});
   };
 
@@ -614,44 +620,47 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
 
     // Main steps.  K step `it` in pipeline slot `slot` (A stage slot % 3, B stage and register
     // set slot % 2, the parity `par` being a compile-time constant):
-    //   entry : A(it), B(it) visible in LDS; the LDS-DMA of A(it+1) and the register loads of
-    //           step it+1 (set par^1) were issued one step ago
-    //   1. start the LDS-DMA of A(it+2) and the register loads of step it+2 (set par)
-    //   2. wait until only those are outstanding: A(it+1) and the registers of it+1 have landed
-    //   3. matrix cores on step it; in their shadow, slice by slice, the registers of it+1 are
-    //      dequantised into the other B stage
-    //   4. this wave's LDS writes done, barrier
+    //   entry : A(it), B(it) visible in LDS; the LDS-DMA of A(it+1), A(it+2) and the register
+    //           loads of step it+1 (set par^1) are in flight or done
+    //   1. start the register loads of step it+2 (set par)
+    //   2. slices 0-2 on the matrix cores; between them, piece by piece, the registers of it+1
+    //      (the compiler waits for exactly those) are dequantised into the other B stage
+    //   3. wait until A(it+1) has landed -- issued since: registers it+1... the three newest
+    //      groups (registers of it+1's successor, A(it+2), registers of it+2) may stay in
+    //      flight -- then barrier
+    //   4. start the LDS-DMA of A(it+3) into the stage of A(it), which nobody reads any more
+    //   5. slice 3, fetching the first fragments of step it+1
     // Steps past the end issue the same number of loads, aimed outside the buffers.
     const int pb = it_begin, pe = it_end;
-    constexpr int kKeep = A_LOADS + kBLoadsMain;
     auto step = [&](int it, int slot, auto par) {
       constexpr int kPar = decltype(par)::value;
       using SetCur = std::integral_constant<int, kPar>;
       using SetNext = std::integral_constant<int, kPar ^ 1>;
-      const int sa = slot % 3, sa1 = (slot + 1) % 3, sa2 = (slot + 2) % 3;
+      const int sa = slot % 3, sa1 = (slot + 1) % 3;
+      uint16_t* a_cur = As + sa * A_TILE;
       with_step_regions(
-          As + sa2 * A_TILE, As + sa * A_TILE, As + sa1 * A_TILE, Bs + kPar * B_TILE,
+          As + ((slot + 2) % 3) * A_TILE, a_cur, As + sa1 * A_TILE, Bs + kPar * B_TILE,
           Bs + (kPar ^ 1) * B_TILE,
-          [&](uint16_t* a_dma, const uint16_t* a_rd, const uint16_t* a_nx, const uint16_t* b_rd,
+          [&](uint16_t*, const uint16_t* a_rd, const uint16_t* a_nx, const uint16_t* b_rd,
               uint16_t* b_wr) {
-            const bool live2 = it + 2 < pe;
-            issue_a(MainK{}, it + 2, a_dma, live2);
-            gload_b(MainK{}, it + 2, SetCur{}, live2);
+            gload_b(MainK{}, it + 2, SetCur{}, it + 2 < pe);
             __builtin_amdgcn_sched_barrier(0);
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kKeep) : "memory");
-            compute_main(a_rd, b_rd, a_nx, b_wr,
-                         [&](auto kk) { store_b(MainK{}, it + 1, b_wr, SetNext{}, kk); });
+            compute_main(
+                a_rd, b_rd, a_nx, b_wr,
+                [&](auto kk) { store_b(MainK{}, it + 1, b_wr, SetNext{}, kk); },
+                [&]() { issue_a(MainK{}, it + 3, a_cur, it + 3 < pe); });
           });
     };
     if (pe > pb) {
-      // prologue: A(pb), A(pb+1) in flight, registers of pb (set 0) and pb+1 (set 1) loading;
-      // B(pb) dequantised into stage 0
+      // prologue: A(pb), A(pb+1), A(pb+2) in flight, registers of pb (set 0) and pb+1 (set 1)
+      // loading; B(pb) dequantised into stage 0
       issue_a(MainK{}, pb, As, true);
       gload_b(MainK{}, pb, Set0{}, true);
       issue_a(MainK{}, pb + 1, As + A_TILE, pb + 1 < pe);
       gload_b(MainK{}, pb + 1, Set1{}, pb + 1 < pe);
+      issue_a(MainK{}, pb + 2, As + 2 * A_TILE, pb + 2 < pe);
       __builtin_amdgcn_sched_barrier(0);
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kKeep) : "memory");
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * A_LOADS + kBLoadsMain) : "memory");
       store_b(MainK{}, pb, Bs, Set0{}, AllPieces{});
       asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
       load_frags_main(As, Bs, 0, Set0{});
