@@ -17,13 +17,16 @@
  * Conventions for every entry point
  *   - All pointers are DEVICE pointers unless marked "host".  All matrices are dense
  *     row-major with no padding.  The descriptor is a host struct, read during the call.
- *   - The caller owns every buffer.  The library allocates nothing, frees nothing,
- *     keeps no state between calls and never synchronises: work is enqueued on
- *     `stream` (a hipStream_t passed as void*; NULL = the default stream) and the
- *     results are ready when that stream reaches the end of the enqueued work.
+ *   - The caller owns every buffer.  The library allocates nothing, frees nothing and
+ *     never synchronises: work is enqueued on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream) and the results are ready when that stream reaches the
+ *     end of the enqueued work.  No state that affects a result is kept between calls
+ *     (the only process state is a call counter that tags flags in the workspace, and the
+ *     events armed through qalora_profile_arm).
  *   - Scratch memory comes from the caller through (ws, ws_bytes); ask
  *     qalora_workspace_bytes for the size (forward and backward always need some, at least
- *     8 bytes per token).  ws contents are undefined afterwards.
+ *     8 bytes per token).  ws contents are undefined afterwards.  Two calls that may run
+ *     at the same time (different streams) must not share a workspace.
  *   - Inputs are read-only.  Outputs must not alias inputs unless stated.
  *   - Device pointers must be 16-byte aligned (QALORA_EALIGN otherwise).
  *   - Every entry returns a status (0 = QALORA_OK, negative = error).  Argument errors
@@ -118,7 +121,11 @@ int qalora_pack(const qalora_desc* desc, const uint8_t* codes, void* packed, voi
  *      fp32 result).
  * Precision: x is used exactly (each token row is scaled by a power of two and converted to
  * fp16), W~ is rounded to fp16 (11 significant bits) before the matrix cores, accumulation
- * is fp32; the adapter branch is evaluated to about 2^-16 relative. */
+ * is fp32; the adapter branch is evaluated to about 2^-16 relative.  Without an adapter, for
+ * tokens <= 16, 4-bit codes, group 32/64/128 and d_in a multiple of 128, a streaming kernel
+ * takes over whose operands are exact (only the fp32 accumulation order differs from the
+ * definition); its cross-block sum waits on flags with a bound -- should a wait ever run out
+ * (another kernel holding the compute units for ~0.3 s) the affected outputs are NaN. */
 int qalora_forward(const qalora_desc* desc, int tokens, const void* x, const void* packed,
                    const float* alpha, const float* beta, const float* A, const float* B,
                    void* y, int y_dtype, void* ws, size_t ws_bytes, void* stream);

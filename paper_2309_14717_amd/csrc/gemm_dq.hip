@@ -25,11 +25,15 @@
 // K = output columns).
 //
 // Tiling: 512 threads = 8 wavefronts (two per SIMD), block tile BM x BN x 64.  The A tile
-// goes global -> LDS directly (128-bit buffer LDS-DMA loads, no registers), three stages deep,
-// issued two K steps ahead; the B tile goes through registers for dequantisation into two LDS
-// stages.  Loads stay in flight across the per-step barrier (counted s_waitcnt).  LDS rows are
-// 128 bytes, XOR-swizzled so that operand reads (16 consecutive rows, one 16-byte chunk) and
-// all producers' writes are bank-conflict free.
+// goes global -> LDS directly (128-bit buffer LDS-DMA loads, no registers), three stages deep;
+// the B tile goes through two alternating register sets for dequantisation into two LDS
+// stages.  Vector instructions do not hide under matrix instructions on this target (they
+// share the issue cycles of the SIMD), so the producer is kept as short as it can be and is
+// spread between the matrix instructions of the step before; one barrier per step, placed
+// so that the next step's first operand fragments are already in registers when it starts.
+// Loads stay in flight across the barrier (counted s_waitcnt).  LDS rows are 128 bytes,
+// XOR-swizzled so that operand reads (16 consecutive rows, one 16-byte chunk) and all
+// producers' writes are bank-conflict free.  The epilogue transposes through LDS.
 #include <type_traits>
 
 #include "common.hpp"
