@@ -636,10 +636,14 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     //   5. slice 3, fetching the first fragments of step it+1
     // Steps past the end issue the same number of loads, aimed outside the buffers.
     const int pb = it_begin, pe = it_end;
+    // (The 3-bit backward producer of the 256-row tile holds two code planes and has no
+    // registers left for a second set: it keeps ONE set and reloads it in slice 2, as soon as
+    // the dequantisation has read it -- half a step of lead instead of a whole one.)
+    constexpr bool kSingleSet = (NBITS == 3 && BWD && BM == 256);
     auto step = [&](int it, int slot, auto par) {
       constexpr int kPar = decltype(par)::value;
-      using SetCur = std::integral_constant<int, kPar>;
-      using SetNext = std::integral_constant<int, kPar ^ 1>;
+      using SetCur = std::integral_constant<int, kSingleSet ? 0 : kPar>;
+      using SetNext = std::integral_constant<int, kSingleSet ? 0 : (kPar ^ 1)>;
       const int sa = slot % 3, sa1 = (slot + 1) % 3;
       uint16_t* a_cur = As + sa * A_TILE;
       with_step_regions(
@@ -647,11 +651,15 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
           Bs + (kPar ^ 1) * B_TILE,
           [&](uint16_t*, const uint16_t* a_rd, const uint16_t* a_nx, const uint16_t* b_rd,
               uint16_t* b_wr) {
-            gload_b(MainK{}, it + 2, SetCur{}, it + 2 < pe);
+            if constexpr (!kSingleSet) gload_b(MainK{}, it + 2, SetCur{}, it + 2 < pe);
             __builtin_amdgcn_sched_barrier(0);
             compute_main(
                 a_rd, b_rd, a_nx, b_wr,
-                [&](auto kk) { store_b(MainK{}, it + 1, b_wr, SetNext{}, kk); },
+                [&](auto kk) {
+                  store_b(MainK{}, it + 1, b_wr, SetNext{}, kk);
+                  if constexpr (kSingleSet && decltype(kk)::value == 2)
+                    gload_b(MainK{}, it + 2, SetCur{}, it + 2 < pe);
+                },
                 [&]() { issue_a(MainK{}, it + 3, a_cur, it + 3 < pe); });
           });
     };
@@ -661,11 +669,13 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
       issue_a(MainK{}, pb, As, true);
       gload_b(MainK{}, pb, Set0{}, true);
       issue_a(MainK{}, pb + 1, As + A_TILE, pb + 1 < pe);
-      gload_b(MainK{}, pb + 1, Set1{}, pb + 1 < pe);
+      if constexpr (!kSingleSet) gload_b(MainK{}, pb + 1, Set1{}, pb + 1 < pe);
       issue_a(MainK{}, pb + 2, As + 2 * A_TILE, pb + 2 < pe);
       __builtin_amdgcn_sched_barrier(0);
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * A_LOADS + kBLoadsMain) : "memory");
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * A_LOADS + (kSingleSet ? 0 : kBLoadsMain))
+                   : "memory");
       store_b(MainK{}, pb, Bs, Set0{}, AllPieces{});
+      if constexpr (kSingleSet) gload_b(MainK{}, pb + 1, Set0{}, pb + 1 < pe);
       asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
       load_frags_main(As, Bs, 0, Set0{});
       int it = pb, slot = 0;
@@ -811,13 +821,7 @@ static hipError_t launch_dir(const GemmArgs& a, hipStream_t st) {
   if (a.M > 128) {
     const bool fast = a.a_main_padded_rows >= round_up(a.M, 256) && a.K_main % BK == 0 &&
                       (BK % a.group == 0 || a.group % BK == 0);
-    // (the 3-bit backward producer holds two code planes in both register sets: it does not
-    // fit the 256-row tile without spilling and takes the 128-row tile instead)
-    if constexpr (NBITS == 3 && BWD) {
-      if (fast) return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, true>(a, ks, st);
-    } else {
-      if (fast) return launch_cfg<NBITS, BWD, 256, 256, 2, 4, true, true>(a, ks, st);
-    }
+    if (fast) return launch_cfg<NBITS, BWD, 256, 256, 2, 4, true, true>(a, ks, st);
     return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, false>(a, ks, st);
   }
   if (a.M > 64) return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, false>(a, ks, st);
