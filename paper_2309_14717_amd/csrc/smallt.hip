@@ -93,13 +93,6 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
   const int b = blockIdx.x, s = b / m, part = b - s * m;
   const int ca = (int)((long)C * part / m), ce = (int)((long)C * (part + 1) / m);
 
-  if (tid == 0) poison = 0;
-  // token rows that do not exist stay zero for the whole kernel
-  if (wave >= p.T) {
-    for (int o = lane; o < ST_XROW / 16; o += 64)
-      *reinterpret_cast<u32x4*>(xs + wave * ST_XROW + o * 16) = u32x4{0, 0, 0, 0};
-  }
-
   const __amdgpu_buffer_rsrc_t rs_w = st_rsrc(p.plane0, (size_t)(p.d_in / 8) * p.d_out * 4);
   const __amdgpu_buffer_rsrc_t rs_x = st_rsrc(p.x, (size_t)p.T * p.d_in * 2);
   const __amdgpu_buffer_rsrc_t rs_al = st_rsrc(p.alpha, (size_t)L * p.d_out * 4);
@@ -183,7 +176,7 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
     for (int pa = ca; pa < ce; pa += ST_XCHUNKS) {  // pieces of at most ST_XCHUNKS chunks
       const int pe = min(ce, pa + ST_XCHUNKS);
       const int np = (pe - pa) * 16;  // 16-byte pieces per token row
-      lds_barrier();  // every wavefront is done reading the previous piece
+      if (pa != ca) lds_barrier();  // every wavefront is done reading the previous piece
       // x of this piece: wavefront w copies token row w straight into LDS (no registers).  The
       // copies are issued BEFORE the weight prefetch, so waiting for them leaves it in flight.
       if (wave < p.T) {
@@ -202,6 +195,15 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
       load_chunk(b0, wa, we);
       load_chunk(b1, wa + 1, we);
       __builtin_amdgcn_sched_barrier(0);
+      if (pa == ca) {
+        // first piece: with the loads above already in flight, clear what must start at zero --
+        // the token rows that do not exist (they stay zero for the whole kernel)
+        if (tid == 0) poison = 0;
+        if (wave >= p.T) {
+          for (int o = lane; o < ST_XROW / 16; o += 64)
+            *reinterpret_cast<u32x4*>(xs + wave * ST_XROW + o * 16) = u32x4{0, 0, 0, 0};
+        }
+      }
       // twelve weight loads were issued after the copies: once at most twelve are outstanding,
       // the copies have landed
       asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
