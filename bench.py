@@ -290,7 +290,8 @@ def main():
                 f"forward+backward of the first {n} of {cfg.tokens} tokens of the same layer")
 
     elif args.workload == "c3":
-        import torch.nn.functional as F
+        if odt != torch.bfloat16:
+            sys.exit("bench.py: workload c3 chains layers through bf16 activations; use --out-dtype bf16")
         gate = Layer(api, torch, synth.CONFIGS["c3_gate"], odt)
         gate.drop_w()
         up = Layer(api, torch, synth.CONFIGS["c3_up"], odt)
@@ -298,19 +299,18 @@ def main():
         down = Layer(api, torch, synth.CONFIGS["c3_down"], odt)
         down.drop_w()
         x, dy = gate.x, down.dy
+        h = torch.empty_like(gate.y)
+        dg, du = torch.empty_like(gate.y), torch.empty_like(gate.y)
 
         def step():
             # forward: y = down( silu(gate(x)) * up(x) )
             g = gate.forward(x)
             u = up.forward(x)
-            sg = torch.sigmoid(g.float())
-            h = (g.float() * sg * u.float()).to(torch.bfloat16)
+            api.swiglu_forward(g, u, out=h)
             down.forward(h)
             # backward
             dh, _, _ = down.backward(dy, h)
-            dhf, gf, uf = dh.float(), g.float(), u.float()
-            du = (dhf * gf * sg).to(torch.bfloat16)
-            dg = (dhf * uf * (sg * (1.0 + gf * (1.0 - sg)))).to(torch.bfloat16)
+            api.swiglu_backward(dh, g, u, dgate=dg, dup=du)
             dx1, _, _ = gate.backward(dg, x)
             dx2, _, _ = up.backward(du, x)
             return dx1.add_(dx2)
@@ -328,7 +328,7 @@ def main():
                     "avg_kernel_ms": round(dom[1], 4), "gate_fwd_kernel_ms": round(kf, 4),
                     "down_bwd_kernel_ms": round(kb, 4), "traffic": read_traffic("gemm_dq_c3_pmc.txt")}
         workload = ("c3: LLaMA-7B SwiGLU MLP block fwd+bwd, T=4096, gate/up 4096x11008 + down 11008x4096, "
-                    f"INT4 g=32, rank 64, s=0.25, bf16 activations, outputs {args.out_dtype}; elementwise glue in torch")
+                    f"INT4 g=32, rank 64, s=0.25, bf16 activations, outputs {args.out_dtype}; SwiGLU glue fused (one kernel each way)")
         cfg = gate.cfg
         if not args.no_cpu_baseline:
             import oracle

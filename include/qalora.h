@@ -171,6 +171,16 @@ int qalora_profile_event_destroy(void* event);
  * HBM once, which makes it the yardstick the hardware traffic counters are scaled by. */
 int qalora_profile_copy(void* dst, const void* src, size_t bytes, void* stream);
 
+/* Benchmark-harness glue, not part of the QA-LoRA layer: the elementwise part of a LLaMA
+ * SwiGLU MLP block around three adapted linears (the MLP-block workload of the benchmark).
+ *   forward : h[i] = silu(gate[i]) * up[i],  silu(v) = v / (1 + exp(-v))
+ *   backward: dgate[i] = dh[i] * up[i] * d silu(gate[i]),  dup[i] = dh[i] * silu(gate[i])
+ * All arrays bf16, n elements (n a multiple of 8, pointers 16-byte aligned); arithmetic in
+ * fp32, results rounded to bf16.  Outputs must not alias inputs. */
+int qalora_swiglu_forward(const void* gate, const void* up, void* h, size_t n, void* stream);
+int qalora_swiglu_backward(const void* dh, const void* gate, const void* up, void* dgate,
+                           void* dup, size_t n, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

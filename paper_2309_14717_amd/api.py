@@ -25,6 +25,7 @@ EXPORTS = (
     "qalora_quantize", "qalora_unpack", "qalora_pack", "qalora_forward", "qalora_backward",
     "qalora_merge", "qalora_profile_arm", "qalora_profile_event_create",
     "qalora_profile_event_elapsed_ms", "qalora_profile_event_destroy", "qalora_profile_copy",
+    "qalora_swiglu_forward", "qalora_swiglu_backward",
 )
 
 
@@ -72,6 +73,8 @@ def load() -> ctypes.CDLL:
     lib.qalora_profile_event_elapsed_ms.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float)]
     lib.qalora_profile_event_destroy.argtypes = [vp]
     lib.qalora_profile_copy.argtypes = [vp, vp, sz, vp]
+    lib.qalora_swiglu_forward.argtypes = [vp, vp, vp, sz, vp]
+    lib.qalora_swiglu_backward.argtypes = [vp, vp, vp, vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -192,6 +195,26 @@ def profile_copy(dst: torch.Tensor, src: torch.Tensor):
     n = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == n
     _check(load().qalora_profile_copy(_p(dst), _p(src), n, _stream()), "qalora_profile_copy")
+
+
+def swiglu_forward(gate, up, out=None):
+    """Harness glue: h = silu(gate) * up, bf16 tensors of equal shape."""
+    if out is None:
+        out = torch.empty_like(gate)
+    _check(load().qalora_swiglu_forward(_p(gate), _p(up), _p(out), gate.numel(), _stream()),
+           "qalora_swiglu_forward")
+    return out
+
+
+def swiglu_backward(dh, gate, up, dgate=None, dup=None):
+    """Harness glue: gradients of h = silu(gate) * up with respect to gate and up (bf16)."""
+    if dgate is None:
+        dgate = torch.empty_like(gate)
+    if dup is None:
+        dup = torch.empty_like(up)
+    _check(load().qalora_swiglu_backward(_p(dh), _p(gate), _p(up), _p(dgate), _p(dup), gate.numel(),
+                                         _stream()), "qalora_swiglu_backward")
+    return dgate, dup
 
 
 class KernelTimer:

@@ -457,4 +457,21 @@ int qalora_profile_copy(void* dst, const void* src, size_t bytes, void* stream) 
   return hipGetLastError() == hipSuccess ? QALORA_OK : QALORA_EHIP;
 }
 
+int qalora_swiglu_forward(const void* gate, const void* up, void* h, size_t n, void* stream) {
+  if (!gate || !up || !h || n == 0 || n % 8 != 0) return QALORA_EINVAL;
+  if (misaligned(gate) || misaligned(up) || misaligned(h)) return QALORA_EALIGN;
+  return launch_swiglu_forward(gate, up, h, n, as_stream(stream)) == hipSuccess ? QALORA_OK
+                                                                                 : QALORA_EHIP;
+}
+
+int qalora_swiglu_backward(const void* dh, const void* gate, const void* up, void* dgate,
+                           void* dup, size_t n, void* stream) {
+  if (!dh || !gate || !up || !dgate || !dup || n == 0 || n % 8 != 0) return QALORA_EINVAL;
+  if (misaligned(dh) || misaligned(gate) || misaligned(up) || misaligned(dgate) || misaligned(dup))
+    return QALORA_EALIGN;
+  return launch_swiglu_backward(dh, gate, up, dgate, dup, n, as_stream(stream)) == hipSuccess
+             ? QALORA_OK
+             : QALORA_EHIP;
+}
+
 }  // extern "C"
