@@ -27,6 +27,11 @@
  *     qalora_workspace_bytes for the size (forward and backward always need some, at least
  *     8 bytes per token).  ws contents are undefined afterwards.  Two calls that may run
  *     at the same time (different streams) must not share a workspace.
+ *   - Stream capture: forward, backward and merge may be captured into a HIP graph and
+ *     replayed (they enqueue kernels only: no memset, copy, allocation or event unless
+ *     qalora_profile_arm armed one).  Make one eager call of the same shape first: the
+ *     first use of a kernel sets its dynamic-LDS attribute, which is not stream work.  The
+ *     workspace passed at capture is used by every replay.
  *   - Inputs are read-only.  Outputs must not alias inputs unless stated.
  *   - Device pointers must be 16-byte aligned (QALORA_EALIGN otherwise).
  *   - Every entry returns a status (0 = QALORA_OK, negative = error).  Argument errors

@@ -285,6 +285,9 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
             }
             __builtin_amdgcn_s_sleep(8);
           }
+          // Consumed: clear it, so that a replay of this very launch (a captured graph repeats
+          // the nonce) waits for its own producers instead of seeing this launch's flags.
+          __hip_atomic_store(p.flags + bf + i, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __syncthreads();
         // partials in part order, eight blocks' loads in flight at a time
