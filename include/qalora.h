@@ -164,6 +164,17 @@ int qalora_merge(const qalora_desc* desc, const float* beta, const float* A, con
  * disarms.  Process-wide and not thread safe; returns QALORA_EINVAL for a bad direction. */
 int qalora_profile_arm(int direction, void* start_event, void* stop_event);
 
+/* Measurement aid: which clock did the chip run the kernel at?  Call after qalora_profile_arm
+ * for the same direction (arming events clears it): the armed dense contraction kernel then
+ * also stores four 64-bit counts to `counts` (device, 32 bytes, 16-byte aligned) from its first
+ * block: shader-clock cycles and constant-rate wall-clock ticks when the block starts, and both
+ * again when it ends.  (cycles_end - cycles_start) / (ticks_end - ticks_start) x the wall-clock
+ * rate (qalora_profile_wall_clock_khz; 100 MHz on this hardware) is the average shader clock
+ * over that block's life -- under load well below the nominal 2.4 GHz that the published
+ * matrix-core peak assumes.  The small-token kernel does not report.  NULL disarms. */
+int qalora_profile_arm_clock(int direction, void* counts);
+int qalora_profile_wall_clock_khz(int* khz /* host */);
+
 /* Create / time / destroy timing events for qalora_profile_arm (thin wrappers over
  * hipEventCreate, hipEventElapsedTime, hipEventDestroy so that a caller without HIP
  * headers can use the aid).  elapsed_ms requires both events to have completed. */

@@ -26,6 +26,7 @@ EXPORTS = (
     "qalora_merge", "qalora_profile_arm", "qalora_profile_event_create",
     "qalora_profile_event_elapsed_ms", "qalora_profile_event_destroy", "qalora_profile_copy",
     "qalora_swiglu_forward", "qalora_swiglu_backward",
+    "qalora_profile_arm_clock", "qalora_profile_wall_clock_khz",
 )
 
 
@@ -74,6 +75,8 @@ def load() -> ctypes.CDLL:
     lib.qalora_profile_event_destroy.argtypes = [vp]
     lib.qalora_profile_copy.argtypes = [vp, vp, sz, vp]
     lib.qalora_swiglu_forward.argtypes = [vp, vp, vp, sz, vp]
+    lib.qalora_profile_arm_clock.argtypes = [ctypes.c_int, vp]
+    lib.qalora_profile_wall_clock_khz.argtypes = [ctypes.POINTER(ctypes.c_int)]
     lib.qalora_swiglu_backward.argtypes = [vp, vp, vp, vp, vp, sz, vp]
     _lib = lib
     return lib
@@ -230,11 +233,27 @@ class KernelTimer:
             _check(load().qalora_profile_event_create(ctypes.byref(b)), "event_create")
             self.pairs.append((a, b))
         self.used = 0
+        # per launch: shader cycles and wall-clock ticks at the first block's start and end
+        self.counts = torch.zeros((n, 4), dtype=torch.int64, device="cuda")
 
     def arm(self):
         a, b = self.pairs[self.used]
-        self.used += 1
         _check(load().qalora_profile_arm(self.direction, a, b), "profile_arm")
+        _check(load().qalora_profile_arm_clock(self.direction, _p(self.counts[self.used])),
+               "profile_arm_clock")
+        self.used += 1
+
+    def shader_clock_ghz(self):
+        """Average shader clock over the life of the armed kernels' first blocks (None when the
+        armed kernel was one that does not report)."""
+        khz = ctypes.c_int()
+        _check(load().qalora_profile_wall_clock_khz(ctypes.byref(khz)), "wall_clock_khz")
+        c = self.counts[: self.used].cpu().double()
+        cycles, ticks = c[:, 2] - c[:, 0], c[:, 3] - c[:, 1]
+        ok = ticks > 0
+        if not bool(ok.any()):
+            return None
+        return float((cycles[ok] / ticks[ok]).mean()) * khz.value * 1e3 / 1e9
 
     def elapsed_ms(self):
         out = []

@@ -421,8 +421,23 @@ int qalora_merge(const qalora_desc* d, const float* beta, const float* A, const 
 
 int qalora_profile_arm(int direction, void* start_event, void* stop_event) {
   if (direction != 0 && direction != 1) return QALORA_EINVAL;
-  g_profile_hook[direction] =
-      ProfileHook{static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event)};
+  g_profile_hook[direction] = ProfileHook{static_cast<hipEvent_t>(start_event),
+                                          static_cast<hipEvent_t>(stop_event), nullptr};
+  return QALORA_OK;
+}
+
+int qalora_profile_arm_clock(int direction, void* counts) {
+  if (direction != 0 && direction != 1) return QALORA_EINVAL;
+  if (counts && misaligned(counts)) return QALORA_EALIGN;
+  g_profile_hook[direction].clock_probe = static_cast<unsigned long long*>(counts);
+  return QALORA_OK;
+}
+
+int qalora_profile_wall_clock_khz(int* khz) {
+  if (!khz) return QALORA_EINVAL;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return QALORA_EHIP;
+  if (hipDeviceGetAttribute(khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess) return QALORA_EHIP;
   return QALORA_OK;
 }
 

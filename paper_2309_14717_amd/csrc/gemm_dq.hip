@@ -181,6 +181,15 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     it_begin = nk_tail;
   }
 
+  // measurement aid: the first block reports how many shader cycles and wall-clock ticks it
+  // lived for (their ratio is the clock the chip actually ran this kernel at)
+  const bool probe = HAS_MAIN && p.clock_probe != nullptr && blockIdx.x == 0 && blockIdx.y == 0 &&
+                     tid == 0;
+  if (probe) {
+    p.clock_probe[0] = (unsigned long long)clock64();
+    p.clock_probe[1] = (unsigned long long)wall_clock64();
+  }
+
   f32x16 acc[TM][TN];
 #pragma unroll
   for (int a = 0; a < TM; ++a)
@@ -797,6 +806,10 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     epilogue(std::true_type{});
   else
     epilogue(std::false_type{});
+  if (probe) {
+    p.clock_probe[2] = (unsigned long long)clock64();
+    p.clock_probe[3] = (unsigned long long)wall_clock64();
+  }
 }
 
 template <int NBITS, bool BWD, int BM, int BN, int WAVES_M, int WAVES_N, bool HAS_MAIN, bool FAST>
@@ -828,17 +841,34 @@ static hipError_t launch_dir(const GemmArgs& a, hipStream_t st) {
   return launch_cfg<NBITS, BWD, 64, 256, 1, 8, true, false>(a, ks, st);
 }
 
-// K splits of the dequantising product for token counts that leave most compute units
-// without a tile: enough slices to occupy them, at least eight K steps each.
+// K splits of the dequantising product.  One block runs per compute unit, so a launch takes
+// rounds(tiles x splits) x (steps per block + a fixed cost per block); splitting K pays when it
+// fills compute units that a short or ragged last round leaves idle (few tokens; 160 tiles on
+// 256 units) by more than the fp32 partial sums cost: `splits` copies of the output written
+// here and read again by the sum, priced at 4 TB/s against the ~2 us of a 256-row K step.
+// At least eight K steps per slice.
 int gemm_dq_ksplit(int M, int N, int K_main) {
+  constexpr int kUnits = 256;        // compute units = resident blocks
+  constexpr double kBlockSteps = 7;  // prologue + epilogue of a block, in K steps
   const int bm = M > 128 ? 256 : (M > 64 ? 128 : 64);
-  const int tiles = ceil_div(M, bm) * ceil_div(N, 256);
-  if (tiles >= 128) return 1;
-  int ks = 256 / tiles;
-  const int max_ks = ceil_div(K_main, BK) / 8;
-  if (ks > max_ks) ks = max_ks;
-  if (ks > 16) ks = 16;
-  return ks < 1 ? 1 : ks;
+  const long tiles = (long)ceil_div(M, bm) * ceil_div(N, 256);
+  const int nk = ceil_div(K_main, BK);
+  const double step_us = 2.0 * bm / 256;
+  auto cost = [&](int ks) {
+    const long rounds = (tiles * ks + kUnits - 1) / kUnits;
+    const double sum_us = ks > 1 ? (double)M * N * (8.0 * ks + 2.0) / 4e6 : 0.0;
+    return rounds * (ceil_div(nk, ks) + kBlockSteps) + sum_us / step_us;
+  };
+  int best = 1;
+  double best_cost = cost(1);
+  for (int ks = 2; ks <= 16 && nk / ks >= 8; ++ks) {
+    const double c = cost(ks);
+    if (c < best_cost) {
+      best_cost = c;
+      best = ks;
+    }
+  }
+  return best;
 }
 
 // out = sum over the K slices of the partial products, slice order, converted on the way out
@@ -855,7 +885,7 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(const float* __restri
     reinterpret_cast<f32x4*>(out)[i] = v;
 }
 
-ProfileHook g_profile_hook[2] = {{nullptr, nullptr}, {nullptr, nullptr}};
+ProfileHook g_profile_hook[2] = {{nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}};
 
 static hipError_t launch_bits(int bits, bool bwd, const GemmArgs& a, hipStream_t st) {
   if (bits == 4) return bwd ? launch_dir<4, true>(a, st) : launch_dir<4, false>(a, st);
@@ -871,7 +901,8 @@ hipError_t launch_gemm_dq(int bits, bool bwd, const GemmArgs& args, hipStream_t 
     a.out_bf16 = 0;
   }
   ProfileHook hook = g_profile_hook[bwd ? 1 : 0];
-  g_profile_hook[bwd ? 1 : 0] = ProfileHook{nullptr, nullptr};
+  g_profile_hook[bwd ? 1 : 0] = ProfileHook{nullptr, nullptr, nullptr};
+  a.clock_probe = hook.clock_probe;
   if (hook.start) (void)hipEventRecord(hook.start, st);
   hipError_t e = launch_bits(bits, bwd, a, st);
   if (e == hipSuccess && split) {

@@ -37,6 +37,8 @@ struct GemmArgs {
   int K_main;              // d_in (forward) or d_out (backward); 0 for a plain product
   int K_tail;              // multiple of 64 (zero padded), may be 0
   int d_in, d_out, group;
+  unsigned long long* clock_probe;  // measurement aid (may be null): block 0 stores its shader
+                                    // cycle and wall-clock tick counts at start and end, [4]
 };
 hipError_t launch_gemm_dq(int bits, bool bwd, const GemmArgs& a, hipStream_t st);
 // K slices the dequantising product should use for an [M x K_main] x [K_main x N] problem.
@@ -44,6 +46,7 @@ int gemm_dq_ksplit(int M, int N, int K_main);
 // Measurement aid: events recorded around the next launch_gemm_dq of each direction.
 struct ProfileHook {
   hipEvent_t start, stop;
+  unsigned long long* clock_probe;  // device, 4 x u64, or null
 };
 extern ProfileHook g_profile_hook[2];
 hipError_t launch_gemm_plain(const GemmArgs& a, int ksplit, hipStream_t st);

@@ -394,7 +394,7 @@ hipError_t launch_smallt(const SmallTArgs& args, hipStream_t st) {
   };
   // measurement aid: this kernel is the forward contraction of the small-token regime
   ProfileHook hook = g_profile_hook[0];
-  g_profile_hook[0] = ProfileHook{nullptr, nullptr};
+  g_profile_hook[0] = ProfileHook{nullptr, nullptr, nullptr};
   if (hook.start) (void)hipEventRecord(hook.start, st);
   const hipError_t e = run();
   if (hook.stop) (void)hipEventRecord(hook.stop, st);
