@@ -340,18 +340,28 @@ hipError_t launch_front_backward(const uint16_t* dy, int T, int d_out, float2* r
 constexpr int DB_BN = 128;
 constexpr int DB_DY_ROW = 136;  // bf16 per LDS row of the dy tile (128 + 8 pad)
 
+struct DbArgs {
+  const uint16_t* us_t;  // bf16 [2*rp, t_pad]: hi rows, then lo rows, of (s U)^T
+  int t_pad;
+  const uint16_t* dy;    // bf16 [T, d_out]
+  int T, d_out, rank, tsplit;
+  float* part;           // [tsplit][rank, d_out]
+};
+template <int MT>
+constexpr int db_lds_bytes() { return (32 * MT * LDS_ROW_72 + 64 * DB_DY_ROW) * 2; }
+
 template <int MT>  // number of 32-row tiles of the hi/lo operand = 2*rp/32
-__global__ __launch_bounds__(256) void db_partial_kernel(const uint16_t* __restrict__ us_t,
-                                                         int t_pad,
-                                                         const uint16_t* __restrict__ dy, int T,
-                                                         int d_out, int rank, int tsplit,
-                                                         float* __restrict__ part) {
+__device__ __forceinline__ void db_partial_block(const DbArgs& a, int bx, int z,
+                                                 unsigned char* lds) {
   constexpr int ROWS = 32 * MT;
-  __shared__ __align__(16) uint16_t us_s[ROWS * LDS_ROW_72];
-  __shared__ __align__(16) uint16_t dy_s[64 * DB_DY_ROW];
+  const uint16_t* __restrict__ us_t = a.us_t;
+  const uint16_t* __restrict__ dy = a.dy;
+  float* __restrict__ part = a.part;
+  const int t_pad = a.t_pad, T = a.T, d_out = a.d_out, rank = a.rank, tsplit = a.tsplit;
+  uint16_t* us_s = reinterpret_cast<uint16_t*>(lds);  // [ROWS][LDS_ROW_72]
+  uint16_t* dy_s = us_s + ROWS * LDS_ROW_72;          // [64][DB_DY_ROW]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int j0 = blockIdx.x * DB_BN;
-  const int z = blockIdx.y;
+  const int j0 = bx * DB_BN;
   const int steps = ceil_div(t_pad / 64, tsplit);
   const int step_begin = z * steps, step_end = min(t_pad / 64, step_begin + steps);
 
@@ -361,21 +371,42 @@ __global__ __launch_bounds__(256) void db_partial_kernel(const uint16_t* __restr
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[a][r] = 0.0f;
 
-  for (int step = step_begin; step < step_end; ++step) {
+  // The tiles of step+1 are fetched into registers while step runs on the matrix cores.
+  constexpr int US_LOADS = ROWS * 8 / 256, DY_LOADS = 64 * 16 / 256;
+  uint4 us_r[US_LOADS], dy_r[DY_LOADS];
+  auto fetch = [&](int step) {
     const int t0 = step * 64;
-    for (int idx = tid; idx < ROWS * 8; idx += 256) {
-      const int row = idx >> 3, ch = idx & 7;
-      *reinterpret_cast<uint4*>(us_s + row * LDS_ROW_72 + 8 * ch) =
-          *reinterpret_cast<const uint4*>(us_t + (size_t)row * t_pad + t0 + 8 * ch);
+#pragma unroll
+    for (int q = 0; q < US_LOADS; ++q) {
+      const int idx = tid + 256 * q, row = idx >> 3, ch = idx & 7;
+      us_r[q] = *reinterpret_cast<const uint4*>(us_t + (size_t)row * t_pad + t0 + 8 * ch);
     }
-    for (int idx = tid; idx < 64 * 16; idx += 256) {
-      const int row = idx >> 4, ch = idx & 15;
+#pragma unroll
+    for (int q = 0; q < DY_LOADS; ++q) {
+      const int idx = tid + 256 * q, row = idx >> 4, ch = idx & 15;
       const int t = t0 + row, j = j0 + 8 * ch;
-      uint4 v = {0, 0, 0, 0};
-      if (t < T && j < d_out) v = *reinterpret_cast<const uint4*>(dy + (size_t)t * d_out + j);
-      *reinterpret_cast<uint4*>(dy_s + row * DB_DY_ROW + 8 * ch) = v;
+      dy_r[q] = uint4{0, 0, 0, 0};
+      if (t < T && j < d_out) dy_r[q] = *reinterpret_cast<const uint4*>(dy + (size_t)t * d_out + j);
     }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int q = 0; q < US_LOADS; ++q) {
+      const int idx = tid + 256 * q, row = idx >> 3, ch = idx & 7;
+      *reinterpret_cast<uint4*>(us_s + row * LDS_ROW_72 + 8 * ch) = us_r[q];
+    }
+#pragma unroll
+    for (int q = 0; q < DY_LOADS; ++q) {
+      const int idx = tid + 256 * q, row = idx >> 4, ch = idx & 15;
+      *reinterpret_cast<uint4*>(dy_s + row * DB_DY_ROW + 8 * ch) = dy_r[q];
+    }
+  };
+
+  if (step_begin < step_end) fetch(step_begin);
+  for (int step = step_begin; step < step_end; ++step) {
+    stash();
     __syncthreads();
+    if (step + 1 < step_end) fetch(step + 1);
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       union {
@@ -408,18 +439,6 @@ __global__ __launch_bounds__(256) void db_partial_kernel(const uint16_t* __restr
   }
 }
 
-hipError_t launch_db_partial(const uint16_t* us_t, int t_pad, const uint16_t* dy, int T, int d_out,
-                             int rank, int tsplit, float* part, hipStream_t st) {
-  const int mt = 2 * rank_pad32(rank) / 32;
-  dim3 grid(ceil_div(d_out, DB_BN), tsplit);
-  if (mt == 2) db_partial_kernel<2><<<grid, 256, 0, st>>>(us_t, t_pad, dy, T, d_out, rank, tsplit, part);
-  else if (mt == 4) db_partial_kernel<4><<<grid, 256, 0, st>>>(us_t, t_pad, dy, T, d_out, rank, tsplit, part);
-  else if (mt == 6) db_partial_kernel<6><<<grid, 256, 0, st>>>(us_t, t_pad, dy, T, d_out, rank, tsplit, part);
-  else if (mt == 8) db_partial_kernel<8><<<grid, 256, 0, st>>>(us_t, t_pad, dy, T, d_out, rank, tsplit, part);
-  else return hipErrorInvalidValue;
-  return hipGetLastError();
-}
-
 // ---------------------------------------------------------------------------------------
 // dA = P^T dU over a token slice, fp32 on the vector units (67 MFLOP at LLaMA-7B shapes),
 // fused with the finalisation of dU: dU[t,k] = s * sum_z (raw[z][t][k] + raw[z][t][rp+k]) is
@@ -429,20 +448,33 @@ hipError_t launch_db_partial(const uint16_t* us_t, int t_pad, const uint16_t* dy
 // ---------------------------------------------------------------------------------------
 constexpr int DA_TT = 16;
 
-__global__ __launch_bounds__(256) void da_partial_kernel(const float* __restrict__ P,
-                                                         const float* __restrict__ raw,
-                                                         int ksplit, float s,
-                                                         const float2* __restrict__ rs, int T,
-                                                         int L, int rank, int tsplit,
-                                                         float* __restrict__ part,
-                                                         uint16_t* __restrict__ du_ext,
-                                                         int ktail) {
-  __shared__ float p_s[DA_TT][64];
-  __shared__ float du_s[DA_TT][128];
+struct DaArgs {
+  const float* P;    // [T, L] group averages of x
+  const float* raw;  // [ksplit][T, 2*rp] split-K partials of dy [B_hi | B_lo]^T
+  int ksplit;
+  float s;
+  const float2* rs;  // [T] row scales of dy
+  int T, L, rank, tsplit;
+  float* part;       // [tsplit][L, rank]
+  uint16_t* du_ext;  // [T, ktail]
+  int ktail;
+};
+constexpr int da_lds_bytes() { return DA_TT * (64 + 128) * 4; }
+
+__device__ __forceinline__ void da_partial_block(const DaArgs& a, int bx, int z,
+                                                 unsigned char* lds) {
+  const float* __restrict__ P = a.P;
+  const float* __restrict__ raw = a.raw;
+  const float2* __restrict__ rs = a.rs;
+  float* __restrict__ part = a.part;
+  uint16_t* __restrict__ du_ext = a.du_ext;
+  const int ksplit = a.ksplit, T = a.T, L = a.L, rank = a.rank, tsplit = a.tsplit, ktail = a.ktail;
+  const float s = a.s;
+  float (*p_s)[64] = reinterpret_cast<float (*)[64]>(lds);                        // [DA_TT][64]
+  float (*du_s)[128] = reinterpret_cast<float (*)[128]>(lds + DA_TT * 64 * 4);    // [DA_TT][128]
   const int tid = threadIdx.x;
   const int lq = tid >> 4, kq = tid & 15;
-  const int l0 = blockIdx.x * 64;
-  const int z = blockIdx.y;
+  const int l0 = bx * 64;
   const int rp = rank_pad32(rank);
   const int per = ceil_div(ceil_div(T, DA_TT), tsplit) * DA_TT;
   const int t_begin = z * per, t_end = min(T, t_begin + per);
@@ -458,28 +490,50 @@ __global__ __launch_bounds__(256) void da_partial_kernel(const float* __restrict
       const int tt = idx >> 6, l = l0 + (idx & 63);
       p_s[tt][idx & 63] = (t0 + tt < t_end && l < L) ? P[(size_t)(t0 + tt) * L + l] : 0.0f;
     }
-    for (int idx = tid; idx < DA_TT * 128; idx += 256) {
+    // dU of this thread's eight (token, rank) elements: the loads of one split-K partial are
+    // all issued before any is used (element loop unrolled inside the partial loop)
+    constexpr int DU_E = DA_TT * 128 / 256;
+    float duv[DU_E];
+#pragma unroll
+    for (int e = 0; e < DU_E; ++e) duv[e] = 0.0f;
+    for (int q0 = 0; q0 < ksplit; q0 += 4) {  // four partials' loads in flight together
+      float ld[4][DU_E][2];
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < DU_E; ++e) {
+          const int idx = tid + 256 * e;
+          const int t = t0 + (idx >> 7), k = idx & 127;
+          ld[j][e][0] = ld[j][e][1] = 0.0f;
+          if (q0 + j < ksplit && t < t_end && k < rank) {
+            const float* r = raw + ((size_t)(q0 + j) * T + t) * (2 * rp);
+            ld[j][e][0] = r[k];
+            ld[j][e][1] = r[rp + k];
+          }
+        }
+#pragma unroll
+      for (int j = 0; j < 4; ++j)  // partial order, as a plain loop over q would add them
+#pragma unroll
+        for (int e = 0; e < DU_E; ++e)
+          if (q0 + j < ksplit) duv[e] += ld[j][e][0] + ld[j][e][1];
+    }
+#pragma unroll
+    for (int e = 0; e < DU_E; ++e) {
+      const int idx = tid + 256 * e;
       const int tt = idx >> 7, k = idx & 127;
       const int t = t0 + tt;
-      float v = 0.0f;
-      if (t < t_end && k < rank) {
-        for (int q = 0; q < ksplit; ++q) {
-          const float* r = raw + ((size_t)q * T + t) * (2 * rp);
-          v += r[k] + r[rp + k];
-        }
-        v *= s;
-        if (blockIdx.x == 0) {
-          uint16_t hi, lo;
-          split_bf16(v * rs[t].x, hi, lo);  // the backward tail rides on the scaled main product
-          uint16_t* row = du_ext + (size_t)t * ktail;
-          row[k] = hi;
-          row[rank + k] = lo;
-          row[2 * rank + k] = hi;
-        }
+      const float v = duv[e] * s;
+      if (bx == 0 && t < t_end && k < rank) {
+        uint16_t hi, lo;
+        split_bf16(v * rs[t].x, hi, lo);  // the backward tail rides on the scaled main product
+        uint16_t* row = du_ext + (size_t)t * ktail;
+        row[k] = hi;
+        row[rank + k] = lo;
+        row[2 * rank + k] = hi;
       }
       du_s[tt][k] = v;
     }
-    if (blockIdx.x == 0) {
+    if (bx == 0) {
       const int npad = ktail - 3 * rank;
       for (int idx = tid; idx < DA_TT * npad; idx += 256) {
         const int t = t0 + idx / npad;
@@ -513,12 +567,39 @@ __global__ __launch_bounds__(256) void da_partial_kernel(const float* __restrict
   }
 }
 
-hipError_t launch_da_partial(const float* P, const float* raw, int ksplit, float s,
-                             const float2* rs, int T, int L, int rank, int tsplit, float* part,
-                             uint16_t* du_ext, int ktail, hipStream_t st) {
-  dim3 grid(ceil_div(L, 64), tsplit);
-  da_partial_kernel<<<grid, 256, 0, st>>>(P, raw, ksplit, s, rs, T, L, rank, tsplit, part, du_ext,
-                                          ktail);
+// Both gradient jobs in ONE launch (neither needs the other; the dB blocks, the longer job,
+// come first): blocks [0, db_blocks) are (column block, token slice) pairs of dB, the rest
+// (group block, token slice) pairs of dA.
+template <int MT>
+__global__ __launch_bounds__(256) void adapter_grads_kernel(const DbArgs db, const DaArgs da,
+                                                            int db_bx, int db_blocks, int da_bx) {
+  constexpr int kLds = db_lds_bytes<MT>() > da_lds_bytes() ? db_lds_bytes<MT>() : da_lds_bytes();
+  __shared__ __align__(16) unsigned char lds[kLds];
+  const int b = blockIdx.x;
+  if (b < db_blocks) {
+    db_partial_block<MT>(db, b % db_bx, b / db_bx, lds);
+  } else {
+    const int c = b - db_blocks;
+    da_partial_block(da, c % da_bx, c / da_bx, lds);
+  }
+}
+
+hipError_t launch_adapter_grads(const uint16_t* us_t, int t_pad, const uint16_t* dy, int T, int d_out,
+                                int rank, int tsplit_b, float* db_part, const float* P,
+                                const float* raw, int ksplit, float s, const float2* rs, int L,
+                                int tsplit_a, float* da_part, uint16_t* du_ext, int ktail,
+                                hipStream_t st) {
+  const DbArgs db{us_t, t_pad, dy, T, d_out, rank, tsplit_b, db_part};
+  const DaArgs da{P, raw, ksplit, s, rs, T, L, rank, tsplit_a, da_part, du_ext, ktail};
+  const int db_bx = ceil_div(d_out, DB_BN), db_blocks = db_bx * tsplit_b;
+  const int da_bx = ceil_div(L, 64), da_blocks = da_bx * tsplit_a;
+  const int mt = 2 * rank_pad32(rank) / 32;
+  const dim3 grid(db_blocks + da_blocks);
+  if (mt == 2) adapter_grads_kernel<2><<<grid, 256, 0, st>>>(db, da, db_bx, db_blocks, da_bx);
+  else if (mt == 4) adapter_grads_kernel<4><<<grid, 256, 0, st>>>(db, da, db_bx, db_blocks, da_bx);
+  else if (mt == 6) adapter_grads_kernel<6><<<grid, 256, 0, st>>>(db, da, db_bx, db_blocks, da_bx);
+  else if (mt == 8) adapter_grads_kernel<8><<<grid, 256, 0, st>>>(db, da, db_bx, db_blocks, da_bx);
+  else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 

@@ -76,7 +76,7 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
   }
   {
     const int blocks = ceil_div(d.d_out, 128);
-    int ts = ceil_div(512, blocks);
+    int ts = ceil_div(256, blocks);  // about one block per compute unit
     ts = ts > 32 ? 32 : ts;
     const int steps = p.t_pad / 64;
     p.tsplit_b = ts > steps ? steps : ts;
@@ -363,13 +363,11 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
     g.N = 2 * plan.rp;
     g.group = 1;
     if (launch_gemm_plain(g, plan.ksplit, st) != hipSuccess) return QALORA_EHIP;
-    // dB = (sU)^T dy (partials over token slices)
-    if (launch_db_partial(us_t, plan.t_pad, dy16, tokens, d->d_out, d->rank, plan.tsplit_b,
-                          db_part, st) != hipSuccess)
-      return QALORA_EHIP;
-    // dA = P^T dU (partials), dU finalised on the fly, du_ext for the dx tail
-    if (launch_da_partial(P, du_raw, plan.ksplit, d->s, rs, tokens, L, d->rank, plan.tsplit_a,
-                          da_part, du_ext, plan.ktail, st) != hipSuccess)
+    // dB = (sU)^T dy and dA = P^T dU as partials over token slices, one launch; the dA job
+    // finalises dU on the fly and writes du_ext for the dx tail
+    if (launch_adapter_grads(us_t, plan.t_pad, dy16, tokens, d->d_out, d->rank, plan.tsplit_b, db_part,
+                             P, du_raw, plan.ksplit, d->s, rs, L, plan.tsplit_a, da_part, du_ext,
+                             plan.ktail, st) != hipSuccess)
       return QALORA_EHIP;
     if (launch_reduce2(da_part, plan.tsplit_a, (size_t)L * d->rank, dA, db_part, plan.tsplit_b,
                        (size_t)d->rank * d->d_out, dB, accumulate, st) != hipSuccess)

@@ -99,15 +99,16 @@ hipError_t launch_front_backward(const uint16_t* dy, int T, int d_out, float2* r
                                  const float* B, float s, int g, int rank, float* P,
                                  uint16_t* us_t, int t_pad, uint16_t* b_hl, uint16_t* a_ext_t,
                                  int ktail, hipStream_t st);
-// dB partials over token slices: part[z][rank][d_out] = sum_{t in slice z} sU[t,:]^T dy[t,:]
-hipError_t launch_db_partial(const uint16_t* us_t, int t_pad, const uint16_t* dy, int T, int d_out,
-                             int rank, int tsplit, float* part, hipStream_t st);
-// dA partials over token slices, part[z][L][rank] = sum_{t in slice z} P[t,:]^T dU[t,:], with
-// dU = s * sum_q (raw[q][:, :rp] + raw[q][:, rp:]) rebuilt from the split-K partials of the dU
-// product; also writes du_ext bf16 [T, ktail] = [hi | lo | hi | 0] of dU * rs[t].x
-hipError_t launch_da_partial(const float* P, const float* raw, int ksplit, float s,
-                             const float2* rs, int T, int L, int rank, int tsplit, float* part,
-                             uint16_t* du_ext, int ktail, hipStream_t st);
+// Both adapter-gradient jobs in one launch (neither depends on the other):
+//   dB partials over token slices: db_part[z][rank][d_out] = sum_{t in slice z} sU[t,:]^T dy[t,:]
+//   dA partials over token slices: da_part[z][L][rank] = sum_{t in slice z} P[t,:]^T dU[t,:], with
+//   dU = s * sum_q (raw[q][:, :rp] + raw[q][:, rp:]) rebuilt from the split-K partials of the dU
+//   product; that job also writes du_ext bf16 [T, ktail] = [hi | lo | hi | 0] of dU * rs[t].x
+hipError_t launch_adapter_grads(const uint16_t* us_t, int t_pad, const uint16_t* dy, int T, int d_out,
+                                int rank, int tsplit_b, float* db_part, const float* P,
+                                const float* raw, int ksplit, float s, const float2* rs, int L,
+                                int tsplit_a, float* da_part, uint16_t* du_ext, int ktail,
+                                hipStream_t st);
 // out = (accumulate ? out : 0) + sum_z part[z], fixed order, for two outputs in one launch
 hipError_t launch_reduce2(const float* part_a, int nparts_a, size_t n_a, float* out_a,
                           const float* part_b, int nparts_b, size_t n_b, float* out_b,
