@@ -38,8 +38,11 @@
  *     are detected on the host before anything is launched; no partial work is
  *     enqueued in that case.  Nothing throws.
  *   - Supported shapes: bits in {2,3,4}; group dividing d_in and a multiple of 8 (4-bit),
- *     16 (2-bit) or 32 (3-bit); d_out a multiple of 8; rank at most 128.  Anything else
- *     that is well-formed returns QALORA_EUNSUPPORTED -- there is no fallback path.
+ *     16 (2-bit) or 32 (3-bit); d_out a multiple of 8; rank at most 128; for forward and
+ *     backward, the packed codes, alpha (beta), and tokens (rounded up to 256) x
+ *     max(d_in, d_out) x 2 bytes each below 0xf0000000 bytes (the kernels use 32-bit byte
+ *     offsets).  Anything else that is well-formed returns QALORA_EUNSUPPORTED -- there is
+ *     no fallback path.
  *   - Results are deterministic: a rerun on the same inputs is bit-identical.
  */
 #ifndef QALORA_H_

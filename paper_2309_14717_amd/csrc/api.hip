@@ -111,13 +111,25 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
+// The contraction kernels address their operands through buffer resources with 32-bit byte
+// offsets (and keep a range of offsets above kAddressable for "reads as zero"): the packed
+// planes, the factor matrices and the fp16 copy of the activations must each stay below it.
+constexpr size_t kAddressable = 0xf0000000ull;
+inline bool addressable(const qalora_desc& d, int tokens) {
+  const size_t L = (size_t)(d.d_in / d.group);
+  const size_t wide = (size_t)(d.d_in > d.d_out ? d.d_in : d.d_out);
+  return plane0_words(d.bits, d.d_in, d.d_out) * 4 < kAddressable &&
+         L * (size_t)d.d_out * 4 < kAddressable &&
+         (size_t)round_up(tokens, 256) * wide * 2 < kAddressable;
+}
+
 // The small-token streaming path covers INT4 with groups of 32, 64 or 128 rows, input widths
 // that are whole 128-row chunks, and operands its 32-bit buffer offsets can address.
 inline bool use_smallt(const qalora_desc& d, int tokens) {
   if (tokens > 16 || d.bits != 4) return false;
   if (d.group != 32 && d.group != 64 && d.group != 128) return false;
   if (d.d_in % 128 != 0) return false;
-  return (size_t)d.d_in / 8 * (size_t)d.d_out * 4 < 0xf0000000ull;
+  return (size_t)d.d_in / 8 * (size_t)d.d_out * 4 < kAddressable;
 }
 
 // Workspace of the small-token path: one flag and one [16 x slab] fp32 partial per block.
@@ -228,6 +240,7 @@ int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* 
   if (misaligned(x) || misaligned(packed) || misaligned(alpha) || misaligned(beta) ||
       misaligned(A) || misaligned(B) || misaligned(y) || misaligned(ws))
     return QALORA_EALIGN;
+  if (!addressable(*d, tokens)) return QALORA_EUNSUPPORTED;
   const bool adapter = A && B && d->rank > 0;
   if (!adapter && use_smallt(*d, tokens)) {
     // memory-bound regime: stream the weight once on the exact-operand path
@@ -312,6 +325,7 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
       misaligned(beta) || misaligned(A) || misaligned(B) || misaligned(dx) || misaligned(dA) ||
       misaligned(dB) || misaligned(ws))
     return QALORA_EALIGN;
+  if (!addressable(*d, tokens)) return QALORA_EUNSUPPORTED;
   BwdPlan plan = plan_backward(*d, tokens);
   if (!adapter) {
     plan.rs = 0;

@@ -96,6 +96,11 @@ def test_argument_errors_are_caught_before_launch(lib):
     assert lib.qalora_pack(ref, P(good), P(odd), None) == api.EALIGN
     bad = api.make_desc(1024, 1004, 4, 32, 16, 2.0)
     assert lib.qalora_forward(ctypes.byref(bad), 64, P(good), P(good), P(good), P(good), None, None, P(good), 0, None, 0, None) == api.EUNSUPPORTED
+    # operands beyond the kernels' 32-bit byte offsets are refused, not wrapped around
+    huge = api.make_desc(65536, 65536, 4, 32, 0, 0.0)
+    big_ws = 1 << 44
+    assert lib.qalora_forward(ctypes.byref(huge), 1 << 16, P(good), P(good), P(good), P(good), None, None, P(good), 0, P(good), big_ws, None) == api.EUNSUPPORTED
+    assert lib.qalora_backward(ctypes.byref(huge), 1 << 16, P(good), P(good), P(good), P(good), P(good), None, None, P(good), 0, None, None, 0, P(good), big_ws, None) == api.EUNSUPPORTED
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
