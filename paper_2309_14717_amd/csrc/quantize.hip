@@ -2,9 +2,11 @@
 // consecutive rows of each column, Sec. 3.3), and pack / unpack between the canonical
 // one-code-per-byte matrix and the private bit-packed format.
 //
-// HBM-bound, one pass over W plus a second pass that hits L2: a thread owns one
-// (group, column) pair, adjacent threads own adjacent columns, so every load and store
-// is coalesced along D_out.
+// HBM-bound, one pass over W plus a second pass that hits L2: a thread owns four adjacent
+// columns of one group, adjacent threads own adjacent column quads, so every load and store
+// is a coalesced 16-byte access along D_out.
+#include <type_traits>
+
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -12,59 +14,107 @@ namespace qalora {
 
 // The arithmetic below is the fp32 recipe of the C ABI, operation by operation, with
 // explicit round-to-nearest intrinsics so that no contraction or reciprocal sneaks in.
-template <int NBITS>
+// A thread owns four adjacent columns of one group: 16-byte loads and stores, and four
+// independent min/max and code chains per thread to keep loads in flight.
+// GKEEP = 32: the group has 32 rows and they stay in registers between the two passes (W is
+// then read exactly once); GKEEP = 0: any group size, the code pass reads the rows again.
+template <int NBITS, int GKEEP>
 __global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__ W,
                                                        uint32_t* __restrict__ plane0,
                                                        uint32_t* __restrict__ plane1,
                                                        float* __restrict__ alpha,
                                                        float* __restrict__ beta, int d_in,
                                                        int d_out, int g) {
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const int j = 4 * (blockIdx.x * blockDim.x + threadIdx.x);  // d_out is a multiple of 8
   const int l = blockIdx.y;
   if (j >= d_out) return;
   const int i0 = l * g;
   const float* col = W + (size_t)i0 * d_out + j;
-  float mn = col[0];
-  float mx = mn;
-  for (int q = 1; q < g; ++q) {
-    const float w = col[(size_t)q * d_out];
-    if (w < mn) mn = w;
-    if (w > mx) mx = w;
+  f32x4 mn = *reinterpret_cast<const f32x4*>(col);
+  f32x4 mx = mn;
+  constexpr int KEEP_N = GKEEP > 0 ? GKEEP : 1;
+  f32x4 keep[KEEP_N];
+  if constexpr (GKEEP > 0) {
+#pragma unroll
+    for (int q = 0; q < GKEEP; ++q) keep[q] = *reinterpret_cast<const f32x4*>(col + (size_t)q * d_out);
+#pragma unroll
+    for (int q = 0; q < GKEEP; ++q)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        if (keep[q][c] < mn[c]) mn[c] = keep[q][c];
+        if (keep[q][c] > mx[c]) mx[c] = keep[q][c];
+      }
+  } else {
+    for (int q0 = 0; q0 < g; q0 += 8) {  // g is a multiple of 8: eight rows' loads in flight
+      f32x4 w[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        w[u] = *reinterpret_cast<const f32x4*>(col + (size_t)(q0 + u) * d_out);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          if (w[u][c] < mn[c]) mn[c] = w[u][c];
+          if (w[u][c] > mx[c]) mx[c] = w[u][c];
+        }
+    }
   }
   constexpr int QMAX = (1 << NBITS) - 1;
-  const float range = __fsub_rn(mx, mn);
-  float a = __fdiv_rn(range, (float)QMAX);
-  const bool degenerate = !(a > 0.0f);
-  if (degenerate) a = 1.0f;
-  alpha[(size_t)l * d_out + j] = a;
-  beta[(size_t)l * d_out + j] = mn;
+  f32x4 a;
+  bool degenerate[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const float range = __fsub_rn(mx[c], mn[c]);
+    a[c] = __fdiv_rn(range, (float)QMAX);
+    degenerate[c] = !(a[c] > 0.0f);
+    if (degenerate[c]) a[c] = 1.0f;
+  }
+  *reinterpret_cast<f32x4*>(alpha + (size_t)l * d_out + j) = a;
+  *reinterpret_cast<f32x4*>(beta + (size_t)l * d_out + j) = mn;
 
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   constexpr int RB0 = PackFmt<NBITS>::kRowsPerWord0;
   constexpr int LOW_BITS = (NBITS == 3) ? 2 : NBITS;
   constexpr int ROWS = (NBITS == 3) ? 32 : RB0;  // rows handled per outer step
-  for (int q0 = 0; q0 < g; q0 += ROWS) {
-    uint32_t hiword = 0;
+  auto code_rows = [&](int q0, auto in_regs) {
+    u32x4 hiword = {0, 0, 0, 0};
 #pragma unroll
     for (int h = 0; h < ROWS / RB0; ++h) {
-      uint32_t word = 0;
+      u32x4 word = {0, 0, 0, 0};
 #pragma unroll
       for (int p = 0; p < RB0; ++p) {
-        int c = 0;
-        if (!degenerate) {
-          const float d = __fsub_rn(col[(size_t)(q0 + h * RB0 + p) * d_out], mn);
-          const float r = rintf(__fdiv_rn(d, a));
-          c = (int)r;
-          c = c < 0 ? 0 : (c > QMAX ? QMAX : c);
-        }
-        word |= (uint32_t)(c & ((1 << LOW_BITS) - 1)) << (LOW_BITS * (p >> 1) + 16 * (p & 1));
-        if constexpr (NBITS == 3) {
-          const int pp = h * RB0 + p;
-          hiword |= (uint32_t)(c >> 2) << ((pp >> 1) + 16 * (pp & 1));
+        f32x4 w;
+        if constexpr (decltype(in_regs)::value)
+          w = keep[q0 + h * RB0 + p];  // a constant index once the caller's loop is unrolled
+        else
+          w = *reinterpret_cast<const f32x4*>(col + (size_t)(q0 + h * RB0 + p) * d_out);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          int code = 0;
+          if (!degenerate[c]) {
+            const float d = __fsub_rn(w[c], mn[c]);
+            const float r = rintf(__fdiv_rn(d, a[c]));
+            code = (int)r;
+            code = code < 0 ? 0 : (code > QMAX ? QMAX : code);
+          }
+          word[c] |= (uint32_t)(code & ((1 << LOW_BITS) - 1)) << (LOW_BITS * (p >> 1) + 16 * (p & 1));
+          if constexpr (NBITS == 3) {
+            const int pp = h * RB0 + p;
+            hiword[c] |= (uint32_t)(code >> 2) << ((pp >> 1) + 16 * (pp & 1));
+          }
         }
       }
-      plane0[(size_t)((i0 + q0) / RB0 + h) * d_out + j] = word;
+      *reinterpret_cast<u32x4*>(plane0 + (size_t)((i0 + q0) / RB0 + h) * d_out + j) = word;
     }
-    if constexpr (NBITS == 3) plane1[(size_t)((i0 + q0) / 32) * d_out + j] = hiword;
+    if constexpr (NBITS == 3)
+      *reinterpret_cast<u32x4*>(plane1 + (size_t)((i0 + q0) / 32) * d_out + j) = hiword;
+  };
+  if constexpr (GKEEP > 0) {
+    static_assert(GKEEP % ROWS == 0 || GKEEP == 0, "whole words");
+#pragma unroll
+    for (int w = 0; w < GKEEP / ROWS; ++w) code_rows(w * ROWS, std::true_type{});
+  } else {
+    for (int q0 = 0; q0 < g; q0 += ROWS) code_rows(q0, std::false_type{});
   }
 }
 
@@ -119,8 +169,11 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint8_t* __restrict__ c
 template <int NBITS>
 static void quantize_n(const float* W, uint32_t* p0, uint32_t* p1, float* alpha, float* beta,
                        int d_in, int d_out, int g, hipStream_t st) {
-  dim3 grid(ceil_div(d_out, 256), d_in / g);
-  quantize_kernel<NBITS><<<grid, 256, 0, st>>>(W, p0, p1, alpha, beta, d_in, d_out, g);
+  dim3 grid(ceil_div(d_out, 4 * 256), d_in / g);
+  if (g == 32)
+    quantize_kernel<NBITS, 32><<<grid, 256, 0, st>>>(W, p0, p1, alpha, beta, d_in, d_out, g);
+  else
+    quantize_kernel<NBITS, 0><<<grid, 256, 0, st>>>(W, p0, p1, alpha, beta, d_in, d_out, g);
 }
 template <int NBITS>
 static void unpack_n(const uint32_t* p0, const uint32_t* p1, uint8_t* codes, int d_in, int d_out,
