@@ -648,38 +648,60 @@ hipError_t launch_reduce2(const float* part_a, int nparts_a, size_t n_a, float* 
 // ---------------------------------------------------------------------------------------
 // Merge (Alg. 1 merge / App. B.3 in Eq. 1's zero-factor convention):
 //   beta'[l,j] = beta[l,j] + (s/g) sum_k A[l,k] B[k,j]
-// One thread per (group, 4 columns); row l of A is uniform over the block.
+// One thread per (GL groups, 4 columns): a row of B fetched for one k serves GL groups, so the
+// L2 traffic for B is 1/GL of what one group per thread would draw; the GL rows of A are
+// uniform over the block.  The sum over k runs in k order for every output.
 // ---------------------------------------------------------------------------------------
+template <int GL>
 __global__ __launch_bounds__(256) void merge_kernel(const float* beta,  // may alias beta_out
                                                     const float* __restrict__ A,
-                                                    const float* __restrict__ B, int d_out,
+                                                    const float* __restrict__ B, int L, int d_out,
                                                     int rank, float scale, float* beta_out) {
-  const int l = blockIdx.y;
+  const int l0 = blockIdx.y * GL;
   const int j = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (j >= d_out) return;  // d_out is a multiple of 8
-  const float* a = A + (size_t)l * rank;
-  f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-  for (int k = 0; k < rank; ++k) {
-    const float av = a[k];
-    const f32x4 b = *reinterpret_cast<const f32x4*>(B + (size_t)k * d_out + j);
-    acc.x = __builtin_fmaf(av, b.x, acc.x);
-    acc.y = __builtin_fmaf(av, b.y, acc.y);
-    acc.z = __builtin_fmaf(av, b.z, acc.z);
-    acc.w = __builtin_fmaf(av, b.w, acc.w);
+  f32x4 acc[GL];
+#pragma unroll
+  for (int u = 0; u < GL; ++u) acc[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  auto step = [&](int k, const f32x4 b) {
+#pragma unroll
+    for (int u = 0; u < GL; ++u) {
+      const int l = min(l0 + u, L - 1);  // rows past the end repeat the last one, unused
+      const float av = A[(size_t)l * rank + k];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[u][c] = __builtin_fmaf(av, b[c], acc[u][c]);
+    }
+  };
+  int k = 0;
+  for (; k + 8 <= rank; k += 8) {  // eight rows of B in flight
+    f32x4 b[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) b[q] = *reinterpret_cast<const f32x4*>(B + (size_t)(k + q) * d_out + j);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) step(k + q, b[q]);
   }
-  const f32x4 bt = *reinterpret_cast<const f32x4*>(beta + (size_t)l * d_out + j);
-  f32x4 o;
-  o.x = __builtin_fmaf(scale, acc.x, bt.x);
-  o.y = __builtin_fmaf(scale, acc.y, bt.y);
-  o.z = __builtin_fmaf(scale, acc.z, bt.z);
-  o.w = __builtin_fmaf(scale, acc.w, bt.w);
-  *reinterpret_cast<f32x4*>(beta_out + (size_t)l * d_out + j) = o;
+  for (; k < rank; ++k) step(k, *reinterpret_cast<const f32x4*>(B + (size_t)k * d_out + j));
+#pragma unroll
+  for (int u = 0; u < GL; ++u) {
+    const int l = l0 + u;
+    if (l >= L) break;
+    const f32x4 bt = *reinterpret_cast<const f32x4*>(beta + (size_t)l * d_out + j);
+    f32x4 o;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) o[c] = __builtin_fmaf(scale, acc[u][c], bt[c]);
+    *reinterpret_cast<f32x4*>(beta_out + (size_t)l * d_out + j) = o;
+  }
 }
 
 hipError_t launch_merge(const float* beta, const float* A, const float* B, int L, int d_out,
                         int rank, int g, float s, float* beta_out, hipStream_t st) {
-  dim3 grid(ceil_div(d_out / 4, 256), L);
-  merge_kernel<<<grid, 256, 0, st>>>(beta, A, B, d_out, rank, s / (float)g, beta_out);
+  const int bx = ceil_div(d_out / 4, 256);
+  const float scale = s / (float)g;
+  if (bx * ceil_div(L, 8) >= 200) {  // enough blocks for the chip at eight groups per thread
+    merge_kernel<8><<<dim3(bx, ceil_div(L, 8)), 256, 0, st>>>(beta, A, B, L, d_out, rank, scale, beta_out);
+  } else {
+    merge_kernel<2><<<dim3(bx, ceil_div(L, 2)), 256, 0, st>>>(beta, A, B, L, d_out, rank, scale, beta_out);
+  }
   return hipGetLastError();
 }
 
