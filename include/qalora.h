@@ -131,7 +131,7 @@ int qalora_pack(const qalora_desc* desc, const uint8_t* codes, void* packed, voi
  * fp16), W~ is rounded to fp16 (11 significant bits) before the matrix cores, accumulation
  * is fp32; the adapter branch is evaluated to about 2^-16 relative.  Without an adapter, for
  * tokens <= 16, 4-bit codes, group 32/64/128 and d_in a multiple of 128, a streaming kernel
- * takes over whose operands are exact (only the fp32 accumulation order differs from the
+ * (one tile shape for tokens <= 4, another up to 16) takes over whose operands are exact (only the fp32 accumulation order differs from the
  * definition); its cross-block sum waits on flags with a bound -- should a wait ever run out
  * (another kernel holding the compute units for ~0.3 s) the affected outputs are NaN. */
 int qalora_forward(const qalora_desc* desc, int tokens, const void* x, const void* packed,

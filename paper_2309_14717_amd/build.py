@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqalora_hip.so")
-SOURCES = ["api.hip", "quantize.hip", "gemm_dq.hip", "adapter.hip", "smallt.hip", "glue.hip"]
+SOURCES = ["api.hip", "quantize.hip", "gemm_dq.hip", "adapter.hip", "smallt.hip", "smallt4.hip", "glue.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -25,7 +25,7 @@ FLAGS = [
 
 # Kernels whose waits on outstanding memory operations are counted by hand: a register spill
 # would add scratch traffic to the same counter, so they must compile with zero scratch.
-NO_SCRATCH = {"gemm_dq.hip": "gemm_dq_kernel", "smallt.hip": "smallt_kernel"}
+NO_SCRATCH = {"gemm_dq.hip": "gemm_dq_kernel", "smallt.hip": "smallt_kernel", "smallt4.hip": "smallt4_kernel"}
 
 
 def _check_no_scratch(src: str, remarks: str) -> None:
@@ -58,7 +58,7 @@ def _compile(src: str, extra) -> str:
 
 def build(verbose: bool = False, extra_flags=()) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(6, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(7, len(SOURCES))) as ex:
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
     tmp = LIB + ".tmp%d" % os.getpid()
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])

@@ -134,9 +134,8 @@ inline bool use_smallt(const qalora_desc& d, int tokens) {
 
 // Workspace of the small-token path: one flag and one [16 x slab] fp32 partial per block.
 inline size_t smallt_workspace(const qalora_desc& d, int tokens) {
-  (void)tokens;
-  return align_up((size_t)ST_MAX_BLOCKS * 8) +
-         align_up((size_t)smallt_plan(d.d_in, d.d_out).blocks * ST_PARTIAL_FLOATS * 4);
+  const int blocks = tokens <= 4 ? smallt4_plan(d.d_in, d.d_out).blocks : smallt_plan(d.d_in, d.d_out).blocks;
+  return align_up((size_t)ST_MAX_BLOCKS * 8) + align_up((size_t)blocks * ST_PARTIAL_FLOATS * 4);
 }
 
 }  // namespace

@@ -73,7 +73,10 @@ struct SmallTPlan {
   int halves, slab_cols, slabs, parts, blocks;
 };
 SmallTPlan smallt_plan(int d_in, int d_out);
-hipError_t launch_smallt(const SmallTArgs& a, hipStream_t st);
+hipError_t launch_smallt(const SmallTArgs& a, hipStream_t st);  // dispatches on T
+// --- smallt4.hip: the same for T <= 4 (one column per lane on the 4x4x4 MFMA) ----------
+SmallTPlan smallt4_plan(int d_in, int d_out);
+hipError_t launch_smallt4(const SmallTArgs& a, hipStream_t st);  // nonce set by the caller
 
 // --- adapter.hip --------------------------------------------------------------------
 // Tail width of the adapter operands: three bf16 sections of `rank` columns, zero padded

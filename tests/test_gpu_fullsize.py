@@ -99,3 +99,27 @@ def test_config5_post_merge_inference(gpu_api, name):
     err = rel_err(y256[torch.from_numpy(rows).cuda()].cpu().numpy(), ref)
     record(f"fullsize {name} post-merge T=256", y=err)
     assert err <= TOL
+
+
+def test_small_token_share_longer_than_one_staged_piece(gpu_api):
+    """8448 x 32768: 128 slabs of 256 columns leave two parts of 33 chunks each, one more than a
+    block stages of x at a time -- the only way to reach the second-piece path of the two
+    streaming kernels with the part count the launch planner picks (T = 3: one-column-per-lane
+    kernel, T = 9: sixteen-token kernel).  Seeded codes and factors are uploaded as given (the
+    quantizer is not what this test is about)."""
+    d_in, d_out, g = 8448, 32768, 32
+    rng = np.random.default_rng(77)
+    codes = rng.integers(0, 16, size=(d_in, d_out), dtype=np.uint8)
+    alpha = (rng.random((d_in // g, d_out), dtype=np.float32) * 0.01 + 0.001).astype(np.float32)
+    beta = (-rng.random((d_in // g, d_out), dtype=np.float32) * 0.05).astype(np.float32)
+    x = torch.from_numpy(rng.standard_normal((9, d_in)).astype(np.float32)).to(torch.bfloat16)
+    x64 = x.float().numpy().astype(np.float64)
+    desc = gpu_api.make_desc(d_in, d_out, 4, g)
+    packed = gpu_api.pack(desc, dev(codes))
+    ga, gb = dev(alpha), dev(beta)
+    ref = oracle.forward(x64, codes, alpha, beta, g)
+    for T in (3, 9):
+        y = gpu_api.forward(desc, x[:T].contiguous().cuda(), packed, ga, gb)
+        err = rel_err(y.cpu().numpy(), ref[:T])
+        record(f"fullsize two-piece share T={T} {d_in}x{d_out}", y=err)
+        assert err <= 1e-5

@@ -220,6 +220,26 @@ def test_small_token_forward(gpu_api, tokens, group, d_in, d_out):
     assert torch.equal(y, y2)
 
 
+@pytest.mark.parametrize("tokens,group,d_in,d_out", [
+    (2, 64, 2048, 8704),    # 512-column slabs win: 17 slabs x 15 parts, two-way split inside a block
+    (4, 32, 1536, 22528),   # 1024-column slabs win: 22 slabs x 11 parts, no split inside a block
+    (1, 128, 1024, 264),    # 256-column slabs, ragged second slab, four-way split inside a block
+])
+def test_small_token_decode_kernel_variants(gpu_api, tokens, group, d_in, d_out):
+    """T <= 4 runs on the one-column-per-lane kernel; these shapes select each of its slab
+    widths and a ragged slab."""
+    cfg = synth.LayerConfig("st4", tokens, d_in, d_out, 4, group, 8, 0.5, seed=13)
+    L = layer_on_gpu(gpu_api, cfg)
+    y = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"])
+    ref = oracle.forward(L["np"]["x"], L["codes"], L["alpha"], L["beta"], cfg.group)
+    err = rel_err(y.cpu().numpy(), ref)
+    record(f"small_token decode T={tokens} g={group} {d_in}x{d_out}", y=err)
+    assert err <= 1e-5
+    assert torch.equal(y, gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"]))
+    yb = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"], out_dtype=torch.bfloat16)
+    assert torch.equal(yb, y.to(torch.bfloat16))
+
+
 def test_small_token_wide_slab_path(gpu_api):
     """A shape for which the 512-column slabs fill more compute units than the 256-column ones
     (13312 columns: 26 slabs x 9 parts against 52 x 4), so the other kernel variant and a
