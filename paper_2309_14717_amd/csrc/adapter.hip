@@ -371,59 +371,61 @@ __device__ __forceinline__ void db_partial_block(const DbArgs& a, int bx, int z,
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[a][r] = 0.0f;
 
-  // The tiles of step+1 are fetched into registers while step runs on the matrix cores.
+  // The tiles of step+1 are fetched into registers while step runs on the matrix cores (one
+  // loop body with the three phases guarded, so that each phase is written once and the
+  // staging registers stay plain registers).
   constexpr int US_LOADS = ROWS * 8 / 256, DY_LOADS = 64 * 16 / 256;
-  uint4 us_r[US_LOADS], dy_r[DY_LOADS];
-  auto fetch = [&](int step) {
-    const int t0 = step * 64;
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 us_r[US_LOADS], dy_r[DY_LOADS];
+  for (int step = step_begin - 1; step < step_end; ++step) {
+    const bool have = step >= step_begin;  // registers hold the tiles of `step`
+    if (have) {
 #pragma unroll
-    for (int q = 0; q < US_LOADS; ++q) {
-      const int idx = tid + 256 * q, row = idx >> 3, ch = idx & 7;
-      us_r[q] = *reinterpret_cast<const uint4*>(us_t + (size_t)row * t_pad + t0 + 8 * ch);
+      for (int q = 0; q < US_LOADS; ++q) {
+        const int idx = tid + 256 * q, row = idx >> 3, ch = idx & 7;
+        *reinterpret_cast<u32x4*>(us_s + row * LDS_ROW_72 + 8 * ch) = us_r[q];
+      }
+#pragma unroll
+      for (int q = 0; q < DY_LOADS; ++q) {
+        const int idx = tid + 256 * q, row = idx >> 4, ch = idx & 15;
+        *reinterpret_cast<u32x4*>(dy_s + row * DB_DY_ROW + 8 * ch) = dy_r[q];
+      }
+      __syncthreads();
     }
+    if (step + 1 < step_end) {
+      const int t0 = (step + 1) * 64;
 #pragma unroll
-    for (int q = 0; q < DY_LOADS; ++q) {
-      const int idx = tid + 256 * q, row = idx >> 4, ch = idx & 15;
-      const int t = t0 + row, j = j0 + 8 * ch;
-      dy_r[q] = uint4{0, 0, 0, 0};
-      if (t < T && j < d_out) dy_r[q] = *reinterpret_cast<const uint4*>(dy + (size_t)t * d_out + j);
-    }
-  };
-  auto stash = [&]() {
+      for (int q = 0; q < US_LOADS; ++q) {
+        const int idx = tid + 256 * q, row = idx >> 3, ch = idx & 7;
+        us_r[q] = *reinterpret_cast<const u32x4*>(us_t + (size_t)row * t_pad + t0 + 8 * ch);
+      }
 #pragma unroll
-    for (int q = 0; q < US_LOADS; ++q) {
-      const int idx = tid + 256 * q, row = idx >> 3, ch = idx & 7;
-      *reinterpret_cast<uint4*>(us_s + row * LDS_ROW_72 + 8 * ch) = us_r[q];
-    }
-#pragma unroll
-    for (int q = 0; q < DY_LOADS; ++q) {
-      const int idx = tid + 256 * q, row = idx >> 4, ch = idx & 15;
-      *reinterpret_cast<uint4*>(dy_s + row * DB_DY_ROW + 8 * ch) = dy_r[q];
-    }
-  };
-
-  if (step_begin < step_end) fetch(step_begin);
-  for (int step = step_begin; step < step_end; ++step) {
-    stash();
-    __syncthreads();
-    if (step + 1 < step_end) fetch(step + 1);
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      union {
-        bf16x8 v;
-        uint16_t h[8];
-      } bfrag;
-      const uint16_t* src = dy_s + (kk * 16 + 8 * (lane >> 5)) * DB_DY_ROW + 32 * wave + (lane & 31);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) bfrag.h[e] = src[e * DB_DY_ROW];
-#pragma unroll
-      for (int a = 0; a < MT; ++a) {
-        const bf16x8 af = *reinterpret_cast<const bf16x8*>(
-            us_s + (32 * a + (lane & 31)) * LDS_ROW_72 + kk * 16 + 8 * (lane >> 5));
-        acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfrag.v, acc[a], 0, 0, 0);
+      for (int q = 0; q < DY_LOADS; ++q) {
+        const int idx = tid + 256 * q, row = idx >> 4, ch = idx & 15;
+        const int t = t0 + row, j = j0 + 8 * ch;
+        dy_r[q] = u32x4{0, 0, 0, 0};
+        if (t < T && j < d_out) dy_r[q] = *reinterpret_cast<const u32x4*>(dy + (size_t)t * d_out + j);
       }
     }
-    __syncthreads();
+    if (have) {
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        // B fragment: eight tokens of one column, gathered with 16-bit reads and packed in pairs
+        const uint16_t* src = dy_s + (kk * 16 + 8 * (lane >> 5)) * DB_DY_ROW + 32 * wave + (lane & 31);
+        uint32_t h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = src[e * DB_DY_ROW];
+        const u32x4 packed = {h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+        const bf16x8 bfrag = __builtin_bit_cast(bf16x8, packed);
+#pragma unroll
+        for (int a = 0; a < MT; ++a) {
+          const bf16x8 af = *reinterpret_cast<const bf16x8*>(
+              us_s + (32 * a + (lane & 31)) * LDS_ROW_72 + kk * 16 + 8 * (lane >> 5));
+          acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfrag, acc[a], 0, 0, 0);
+        }
+      }
+      __syncthreads();
+    }
   }
 
   const int j = j0 + 32 * wave + (lane & 31);
@@ -476,6 +478,14 @@ __device__ __forceinline__ void da_partial_block(const DaArgs& a, int bx, int z,
   const int lq = tid >> 4, kq = tid & 15;
   const int l0 = bx * 64;
   const int rp = rank_pad32(rank);
+  // The split-K partials are read through a buffer resource: the lane offset is fixed per
+  // (token, rank) element and the partial index lives in the scalar offset, so the four
+  // partials' loads in flight together cost no address registers.  (The host refuses token
+  // counts for which the partials exceed 32-bit byte offsets.)
+  constexpr uint32_t kDaOob = 0xffff0000u;
+  const uint32_t q_stride = (uint32_t)T * (uint32_t)(2 * rp) * 4u;
+  const __amdgpu_buffer_rsrc_t rs_raw = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float*>(raw), 0, (int)((uint32_t)ksplit * q_stride), 0x00020000);
   const int per = ceil_div(ceil_div(T, DA_TT), tsplit) * DA_TT;
   const int t_begin = z * per, t_end = min(T, t_begin + per);
 
@@ -494,23 +504,29 @@ __device__ __forceinline__ void da_partial_block(const DaArgs& a, int bx, int z,
     // all issued before any is used (element loop unrolled inside the partial loop)
     constexpr int DU_E = DA_TT * 128 / 256;
     float duv[DU_E];
+    uint32_t voff[DU_E];  // byte offset of (t, k) inside one split-K partial; elements that do
+                          // not exist point past the buffer and read as zero
 #pragma unroll
-    for (int e = 0; e < DU_E; ++e) duv[e] = 0.0f;
+    for (int e = 0; e < DU_E; ++e) {
+      const int idx = tid + 256 * e;
+      const int t = t0 + (idx >> 7), k = idx & 127;
+      duv[e] = 0.0f;
+      voff[e] = (t < t_end && k < rank) ? ((uint32_t)t * (uint32_t)(2 * rp) + (uint32_t)k) * 4u : kDaOob;
+    }
     for (int q0 = 0; q0 < ksplit; q0 += 4) {  // four partials' loads in flight together
       float ld[4][DU_E][2];
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < 4; ++j) {
+        const bool live = q0 + j < ksplit;  // uniform
+        const uint32_t so = live ? (uint32_t)(q0 + j) * q_stride : 0u;
 #pragma unroll
         for (int e = 0; e < DU_E; ++e) {
-          const int idx = tid + 256 * e;
-          const int t = t0 + (idx >> 7), k = idx & 127;
-          ld[j][e][0] = ld[j][e][1] = 0.0f;
-          if (q0 + j < ksplit && t < t_end && k < rank) {
-            const float* r = raw + ((size_t)(q0 + j) * T + t) * (2 * rp);
-            ld[j][e][0] = r[k];
-            ld[j][e][1] = r[rp + k];
-          }
+          const uint32_t v = live ? voff[e] : kDaOob;
+          ld[j][e][0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_raw, (int)v, (int)so, 0));
+          ld[j][e][1] = __builtin_bit_cast(
+              float, __builtin_amdgcn_raw_buffer_load_b32(rs_raw, (int)v, (int)(so + (uint32_t)rp * 4u), 0));
         }
+      }
 #pragma unroll
       for (int j = 0; j < 4; ++j)  // partial order, as a plain loop over q would add them
 #pragma unroll

@@ -326,6 +326,8 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
     return QALORA_EALIGN;
   if (!addressable(*d, tokens)) return QALORA_EUNSUPPORTED;
   BwdPlan plan = plan_backward(*d, tokens);
+  if (adapter && (size_t)plan.ksplit * tokens * 2 * plan.rp * 4 >= kAddressable)
+    return QALORA_EUNSUPPORTED;  // the split-K partials of dU are read with 32-bit byte offsets
   if (!adapter) {
     plan.rs = 0;
     plan.a16 = align_up((size_t)tokens * sizeof(float2));
