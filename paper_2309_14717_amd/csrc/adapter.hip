@@ -513,10 +513,11 @@ __device__ __forceinline__ void da_partial_block(const DaArgs& a, int bx, int z,
       duv[e] = 0.0f;
       voff[e] = (t < t_end && k < rank) ? ((uint32_t)t * (uint32_t)(2 * rp) + (uint32_t)k) * 4u : kDaOob;
     }
-    for (int q0 = 0; q0 < ksplit; q0 += 4) {  // four partials' loads in flight together
-      float ld[4][DU_E][2];
+    constexpr int QB = 2;  // split-K partials whose loads are in flight together
+    for (int q0 = 0; q0 < ksplit; q0 += QB) {
+      float ld[QB][DU_E][2];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < QB; ++j) {
         const bool live = q0 + j < ksplit;  // uniform
         const uint32_t so = live ? (uint32_t)(q0 + j) * q_stride : 0u;
 #pragma unroll
@@ -528,7 +529,7 @@ __device__ __forceinline__ void da_partial_block(const DaArgs& a, int bx, int z,
         }
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j)  // partial order, as a plain loop over q would add them
+      for (int j = 0; j < QB; ++j)  // partial order, as a plain loop over q would add them
 #pragma unroll
         for (int e = 0; e < DU_E; ++e)
           if (q0 + j < ksplit) duv[e] += ld[j][e][0] + ld[j][e][1];
@@ -586,8 +587,10 @@ __device__ __forceinline__ void da_partial_block(const DaArgs& a, int bx, int z,
 // Both gradient jobs in ONE launch (neither needs the other; the dB blocks, the longer job,
 // come first): blocks [0, db_blocks) are (column block, token slice) pairs of dB, the rest
 // (group block, token slice) pairs of dA.
+// (Three wavefronts per SIMD fit in registers up to rank 64; the larger ranks' accumulators
+// need the room of one.)
 template <int MT>
-__global__ __launch_bounds__(256) void adapter_grads_kernel(const DbArgs db, const DaArgs da,
+__global__ __launch_bounds__(256, MT <= 4 ? 3 : 1) void adapter_grads_kernel(const DbArgs db, const DaArgs da,
                                                             int db_bx, int db_blocks, int da_bx) {
   constexpr int kLds = db_lds_bytes<MT>() > da_lds_bytes() ? db_lds_bytes<MT>() : da_lds_bytes();
   __shared__ __align__(16) unsigned char lds[kLds];
