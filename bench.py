@@ -392,7 +392,8 @@ def main():
             # reported beside it.)
             k_avg = ms_per_step / 2.0
             ach = by_step / 2.0 / k_avg / 1e6
-            roofline = {"bound": "hbm", "kernel": "smallt_kernel (8192x22016 and 22016x8192 alternating)",
+            kname = "smallt4_kernel" if T <= 4 else "smallt_kernel"
+            roofline = {"bound": "hbm", "kernel": f"{kname} (8192x22016 and 22016x8192 alternating)",
                         "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": round(ach / PEAK_HBM_GBS, 4), "avg_kernel_ms": round(k_avg, 5),
                         "event_bracketed_ms_8192x22016": round(k, 5),
