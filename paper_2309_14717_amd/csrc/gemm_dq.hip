@@ -918,7 +918,7 @@ hipError_t launch_gemm_dq(int bits, bool bwd, const GemmArgs& args, hipStream_t 
 // Plain bf16 x bf16^T product  out[z][M][N] = a_tail[M, Kz] . b_tail[N, Kz]^T  with the K
 // range split over `ksplit` slices (partial sums, reduced by the caller in a fixed order).
 hipError_t launch_gemm_plain(const GemmArgs& a, int ksplit, hipStream_t st) {
-  return launch_cfg<4, false, 64, 128, 2, 4, false, false>(a, ksplit, st);
+  return launch_cfg<4, false, 128, 128, 2, 4, false, false>(a, ksplit, st);
 }
 
 }  // namespace qalora
