@@ -73,7 +73,9 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
     const int nk = ceil_div(d.d_out, 64);
     int ks = ceil_div(256, tiles);
     ks = ks < 1 ? 1 : (ks > 16 ? 16 : ks);
-    p.ksplit = ks > nk ? nk : ks;
+    const int by_steps = nk / 12;  // a slice shorter than about twelve K steps is all prologue
+    if (ks > by_steps) ks = by_steps < 1 ? 1 : by_steps;
+    p.ksplit = ks;
   }
   {
     const int blocks = ceil_div(d.d_out, 128);
