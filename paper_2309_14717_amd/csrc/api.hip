@@ -66,10 +66,11 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
     }
     return p;
   }
-  // dU product: [T, 2rp] output tiles of 128 x 128 (measured faster than 64 x 128: half the K
-  // steps per block for the same number of blocks); split K = d_out to fill the chip.
+  // dU product: [T, 2rp] output tiles of plain_tile_rows x 128 (the taller tile pays when K is
+  // long: half the K steps per block for the same number of blocks); split K = d_out to fill
+  // the chip.
   {
-    const int tiles = ceil_div(T, 128) * ceil_div(2 * p.rp, 128);
+    const int tiles = ceil_div(T, gemm_plain_tile_rows(d.d_out)) * ceil_div(2 * p.rp, 128);
     const int nk = ceil_div(d.d_out, 64);
     int ks = ceil_div(256, tiles);
     ks = ks < 1 ? 1 : (ks > 16 ? 16 : ks);

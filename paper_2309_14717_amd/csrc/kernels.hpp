@@ -50,6 +50,7 @@ struct ProfileHook {
 };
 extern ProfileHook g_profile_hook[2];
 hipError_t launch_gemm_plain(const GemmArgs& a, int ksplit, hipStream_t st);
+int gemm_plain_tile_rows(int K);  // row tile launch_gemm_plain uses for a K of this length
 
 // --- smallt.hip ---------------------------------------------------------------------
 // Adapter-free forward for T <= 16 tokens, INT4, group 32 / 64 / 128 (memory-bound path).
