@@ -50,10 +50,9 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, si
   const uint32_t n = bytes > 0xffffffffull ? 0xffffffffu : (uint32_t)bytes;
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)n, 0x00020000);
 }
-__device__ __forceinline__ uint4 buf_load128(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
-  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
-  return uint4{v.x, v.y, v.z, v.w};
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));  // register-resident 128-bit values
+__device__ __forceinline__ u32x4_t buf_load128(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
 }
 constexpr uint32_t kOobOffset = 0xffff0000u;  // past any buffer (also after a small add): reads zero
 
@@ -285,9 +284,9 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
 
   // Two register sets: the set of step it+1 is being dequantised while the set of step it+2
   // is loading (its loads then have a whole K step to land).
-  uint4 bregs[2][6];   // fwd: codes, alpha, beta, plane-1 codes | bwd: 2 codes, 2 alpha, 2 beta
-  uint4 bregs1[2][2];  // bwd, N = 3: plane-1 words
-  uint4 btail[B_CHUNKS];
+  u32x4_t bregs[2][6];   // fwd: codes, alpha, beta, plane-1 codes | bwd: 2 codes, 2 alpha, 2 beta
+  u32x4_t bregs1[2][2];  // bwd, N = 3: plane-1 words
+  u32x4_t btail[B_CHUNKS];
   using Set0 = std::integral_constant<int, 0>;
   using Set1 = std::integral_constant<int, 1>;
 
@@ -307,16 +306,14 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
       fb_voff_ab_c = n_valid ? ((uint32_t)(b_i0 / p.group) * p.d_out + 8 * b_u0) * 4u : kOobOffset;
     }
   }
-  auto buf_load128_s = [&](__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0);
-    return uint4{v.x, v.y, v.z, v.w};
+  auto buf_load128_s = [&](__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) -> u32x4_t {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0);
   };
 
   auto gload_b = [&](auto kind, int it, auto set, bool live) {
     constexpr bool kMain = decltype(kind)::value == 0;
-    uint4(&breg)[6] = bregs[decltype(set)::value];
-    uint4(&breg1)[2] = bregs1[decltype(set)::value];
+    u32x4_t(&breg)[6] = bregs[decltype(set)::value];
+    u32x4_t(&breg1)[2] = bregs1[decltype(set)::value];
     if constexpr (kMain && FAST) {
       const uint32_t km = (uint32_t)(it - nk_tail);  // main step index (uniform)
       const uint32_t dead = live ? 0u : kOobOffset;   // branch-free, as for the A tile
@@ -417,8 +414,8 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
   auto store_b = [&](auto kind, int it, uint16_t* b_dst, auto set, auto piece_c) {
     constexpr bool kMain = decltype(kind)::value == 0;
     constexpr int piece = decltype(piece_c)::value;
-    uint4(&breg)[6] = bregs[decltype(set)::value];
-    uint4(&breg1)[2] = bregs1[decltype(set)::value];
+    u32x4_t(&breg)[6] = bregs[decltype(set)::value];
+    u32x4_t(&breg1)[2] = bregs1[decltype(set)::value];
     char* bs = reinterpret_cast<char*>(b_dst);
     if constexpr (kMain) {
       if constexpr (!BWD) {
@@ -484,7 +481,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
       for (int q = 0; q < B_CHUNKS; ++q) {
         const int idx = tid + NT * q;
         const int row = idx >> 3, ch = idx & 7;
-        if (row < BN) *reinterpret_cast<uint4*>(bs + swz_offset(row, ch)) = btail[q];
+        if (row < BN) *reinterpret_cast<u32x4_t*>(bs + swz_offset(row, ch)) = btail[q];
       }
     }
   };
