@@ -56,12 +56,12 @@ def forward_bytes(cfg, tokens, out_bytes=2):
     return codes + factors + tokens * cfg.d_in * 2 + tokens * cfg.d_out * out_bytes
 
 
-def read_traffic(name):
+def read_traffic(name, key="traffic_bytes_per_launch"):
     """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary."""
     path = os.path.join(ROOT, "profiles", name)
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
+            if line.startswith(key + ":"):
                 return float(line.split(":", 1)[1])
     except OSError:
         pass
@@ -135,6 +135,9 @@ def timed(torch, fn, n=20, warm=2):
     return s.elapsed_time(e) / n
 
 
+KERNEL_STATS = {}  # direction -> median / min / count of the armed kernel durations of the last run
+
+
 def run_steps(torch, api, step, steps, warmup, directions=(0, 1), arm_every=4):
     """Warm up, then time exactly `steps` steps; per-direction kernel times from events armed
     around the dense kernel on every `arm_every`-th step of the timed region (an armed launch
@@ -154,6 +157,10 @@ def run_steps(torch, api, step, steps, warmup, directions=(0, 1), arm_every=4):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     kms = {d: float(np.mean(t.elapsed_ms())) for d, t in timers.items()}
+    for d, t in timers.items():  # median and minimum of the same samples, for the record
+        ms = np.asarray(t.elapsed_ms())
+        KERNEL_STATS[d] = {"median_ms": round(float(np.median(ms)), 5), "min_ms": round(float(ms.min()), 5),
+                           "samples": int(ms.size)}
     clk = {d: t.shader_clock_ghz() for d, t in timers.items()}
     for t in timers.values():
         t.close()
@@ -277,6 +284,10 @@ def main():
                     "fwd_kernel_ms": round(kf, 4), "bwd_kernel_ms": round(kb, 4),
                     "traffic": read_traffic(f"gemm_dq_{args.workload}_pmc.txt")}
         roofline.update(clock_fields(clk[0 if dom[0] == "fwd" else 1], achieved))
+        st = KERNEL_STATS.get(0 if dom[0] == "fwd" else 1)
+        if st:
+            roofline.update({"kernel_ms_median": st["median_ms"], "kernel_ms_min": st["min_ms"],
+                             "kernel_samples": st["samples"]})
         workload = (f"{cfg.name}: QA-LoRA linear fwd+bwd, T={cfg.tokens}, {cfg.d_in}x{cfg.d_out}, "
                     f"INT{cfg.bits} g={cfg.group}, rank {cfg.rank}, s={cfg.s}, x/dy bf16, outputs {args.out_dtype}")
         if not args.no_extras:
@@ -343,7 +354,8 @@ def main():
         roofline = {"bound": "mfma", "kernel": f"gemm_dq_kernel<4,{dom[0]}>", "achieved": round(achieved, 2),
                     "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_TFLOPS, 4),
                     "avg_kernel_ms": round(dom[1], 4), "gate_fwd_kernel_ms": round(kf, 4),
-                    "down_bwd_kernel_ms": round(kb, 4), "traffic": read_traffic("gemm_dq_c3_pmc.txt")}
+                    "down_bwd_kernel_ms": round(kb, 4),
+                    "traffic": read_traffic("gemm_dq_c3_pmc.txt", "traffic_bytes_per_launch_" + dom[0][:3])}
         roofline.update(clock_fields(clk[0 if dom[0].startswith("fwd") else 1], achieved))
         workload = ("c3: LLaMA-7B SwiGLU MLP block fwd+bwd, T=4096, gate/up 4096x11008 + down 11008x4096, "
                     f"INT4 g=32, rank 64, s=0.25, bf16 activations, outputs {args.out_dtype}; SwiGLU glue fused (one kernel each way)")
