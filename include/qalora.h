@@ -130,9 +130,10 @@ int qalora_pack(const qalora_desc* desc, const uint8_t* codes, void* packed, voi
  * Precision: x is used exactly (each token row is scaled by a power of two and converted to
  * fp16), W~ is rounded to fp16 (11 significant bits) before the matrix cores, accumulation
  * is fp32; the adapter branch is evaluated to about 2^-16 relative.  Without an adapter, for
- * tokens <= 16, 4-bit codes, group 32/64/128 and d_in a multiple of 128, a streaming kernel
- * (one tile shape for tokens <= 4, another up to 16) takes over whose operands are exact (only the fp32 accumulation order differs from the
- * definition); its cross-block sum waits on flags with a bound -- should a wait ever run out
+ * tokens <= 16, group 32/64/128 and d_in a multiple of 128, a streaming kernel takes over
+ * (one column per lane for tokens <= 4 and for the 2- and 3-bit codes, a sixteen-token tile
+ * for 4-bit codes beyond four tokens) whose operands are exact (only the fp32 accumulation
+ * order differs from the definition); its cross-block sum waits on flags with a bound -- should a wait ever run out
  * (another kernel holding the compute units for ~0.3 s) the affected outputs are NaN. */
 int qalora_forward(const qalora_desc* desc, int tokens, const void* x, const void* packed,
                    const float* alpha, const float* beta, const float* A, const float* B,

@@ -127,18 +127,20 @@ inline bool addressable(const qalora_desc& d, int tokens) {
          (size_t)round_up(tokens, 256) * wide * 2 < kAddressable;
 }
 
-// The small-token streaming path covers INT4 with groups of 32, 64 or 128 rows, input widths
-// that are whole 128-row chunks, and operands its 32-bit buffer offsets can address.
+// The small-token streaming path covers groups of 32, 64 or 128 rows, input widths that are
+// whole 128-row chunks, and operands its 32-bit buffer offsets can address: every code width
+// up to sixteen tokens.
 inline bool use_smallt(const qalora_desc& d, int tokens) {
-  if (tokens > 16 || d.bits != 4) return false;
+  if (tokens > 16) return false;
   if (d.group != 32 && d.group != 64 && d.group != 128) return false;
   if (d.d_in % 128 != 0) return false;
-  return (size_t)d.d_in / 8 * (size_t)d.d_out * 4 < kAddressable;
+  return plane0_words(d.bits, d.d_in, d.d_out) * 4 < kAddressable;
 }
 
 // Workspace of the small-token path: one flag and one [16 x slab] fp32 partial per block.
 inline size_t smallt_workspace(const qalora_desc& d, int tokens) {
-  const int blocks = tokens <= 4 ? smallt4_plan(d.d_in, d.d_out).blocks : smallt_plan(d.d_in, d.d_out).blocks;
+  const int blocks = (tokens <= 4 || d.bits != 4) ? smallt4_plan(d.d_in, d.d_out, tokens).blocks
+                                                  : smallt_plan(d.d_in, d.d_out).blocks;
   return align_up((size_t)ST_MAX_BLOCKS * 8) + align_up((size_t)blocks * ST_PARTIAL_FLOATS * 4);
 }
 
@@ -252,6 +254,8 @@ int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* 
     SmallTArgs a{};
     a.x = static_cast<const uint16_t*>(x);
     a.plane0 = static_cast<const uint32_t*>(packed);
+    a.plane1 = a.plane0 + plane0_words(d->bits, d->d_in, d->d_out);
+    a.bits = d->bits;
     a.alpha = alpha;
     a.beta = beta;
     a.out = y;

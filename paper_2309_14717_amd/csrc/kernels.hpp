@@ -58,7 +58,8 @@ constexpr int ST_MAX_BLOCKS = 256; // one block per compute unit
 constexpr int ST_PARTIAL_FLOATS = 16 * 512;  // one [16 tokens x widest slab] tile per block
 struct SmallTArgs {
   const uint16_t* x;       // bf16 [T, d_in]
-  const uint32_t* plane0;  // packed INT4 codes
+  const uint32_t* plane0;  // packed codes (INT3: the low two bits)
+  const uint32_t* plane1;  // INT3: the plane of high bits; otherwise unused
   const float* alpha;      // [L, d_out]
   const float* beta;       // [L, d_out]
   void* out;               // [T, d_out] fp32 or bf16
@@ -67,6 +68,7 @@ struct SmallTArgs {
   unsigned long long nonce;   // filled in by the launcher, unique per call
   int out_bf16;
   int T, d_in, d_out, group;
+  int bits;  // 4, 3 or 2
 };
 // Launch shape: blocks = slabs * parts; `halves` (1 or 2) is how many ways a block splits its
 // own chunks, which sets the slab width (512 or 256 columns).
@@ -75,8 +77,9 @@ struct SmallTPlan {
 };
 SmallTPlan smallt_plan(int d_in, int d_out);
 hipError_t launch_smallt(const SmallTArgs& a, hipStream_t st);  // dispatches on T
-// --- smallt4.hip: the same for T <= 4 (one column per lane on the 4x4x4 MFMA) ----------
-SmallTPlan smallt4_plan(int d_in, int d_out);
+// --- smallt4.hip: one column per lane on the 4x4x4 MFMA: T <= 4 for every code width, and
+// INT3 / INT2 up to sixteen tokens -------------------------------------------------------
+SmallTPlan smallt4_plan(int d_in, int d_out, int tokens);
 hipError_t launch_smallt4(const SmallTArgs& a, hipStream_t st);  // nonce set by the caller
 
 // --- adapter.hip --------------------------------------------------------------------

@@ -381,7 +381,8 @@ hipError_t launch_smallt(const SmallTArgs& args, hipStream_t st) {
   const SmallTPlan pl = smallt_plan(a.d_in, a.d_out);
   const int sub = a.group / 32;
   auto run = [&]() -> hipError_t {
-    if (a.T <= 4) return launch_smallt4(a, st);  // decode shape: the one-column-per-lane kernel
+    // decode shapes and the narrower codes: the one-column-per-lane kernel
+    if (a.T <= 4 || a.bits != 4) return launch_smallt4(a, st);
     if (pl.halves == 2) {
       if (sub == 1) return launch_sub<1, 2>(a, pl.blocks, st);
       if (sub == 2) return launch_sub<2, 2>(a, pl.blocks, st);

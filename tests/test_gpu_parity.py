@@ -240,6 +240,34 @@ def test_small_token_decode_kernel_variants(gpu_api, tokens, group, d_in, d_out)
     assert torch.equal(yb, y.to(torch.bfloat16))
 
 
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("tokens,group,d_in,d_out", [
+    (1, 32, 1536, 22528),   # 1024-column slabs, no split inside a block
+    (3, 64, 2048, 8704),    # 512-column slabs, two-way split inside a block
+    (4, 128, 1024, 264),    # 256-column slabs, ragged second slab, four-way split
+    (2, 32, 4224, 1000),    # 33 chunks: more than one staged piece of x, ragged slab
+    (6, 32, 1536, 22528),   # two groups of four tokens, 1024-column slabs
+    (8, 64, 2048, 8704),    # two full groups, 512-column slabs
+    (12, 128, 1024, 264),   # four groups (three in use), 256-column slabs, ragged
+    (16, 32, 4224, 13312),  # four groups, 512-column slabs (the 1024-column one is ruled out), two staged pieces
+    (9, 64, 2048, 22528),   # four groups, nine tokens
+])
+def test_small_token_decode_low_bit(gpu_api, bits, tokens, group, d_in, d_out):
+    """Up to sixteen tokens of INT2 and INT3 weights stream the packed planes once as well: the
+    same exact-operand arithmetic with the code bits placed higher in the bf16 mantissa, one
+    column per lane, the tokens in groups of four that share a lane's code operand."""
+    cfg = synth.LayerConfig("st4lb", tokens, d_in, d_out, bits, group, 8, 0.5, seed=17 + bits)
+    L = layer_on_gpu(gpu_api, cfg)
+    y = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"])
+    ref = oracle.forward(L["np"]["x"], L["codes"], L["alpha"], L["beta"], cfg.group)
+    err = rel_err(y.cpu().numpy(), ref)
+    record(f"small_token decode INT{bits} T={tokens} g={group} {d_in}x{d_out}", y=err)
+    assert err <= 1e-5
+    assert torch.equal(y, gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"]))
+    yb = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"], out_dtype=torch.bfloat16)
+    assert torch.equal(yb, y.to(torch.bfloat16))
+
+
 def test_small_token_wide_slab_path(gpu_api):
     """A shape for which the 512-column slabs fill more compute units than the 256-column ones
     (13312 columns: 26 slabs x 9 parts against 52 x 4), so the other kernel variant and a
