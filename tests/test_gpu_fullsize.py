@@ -101,6 +101,21 @@ def test_config5_post_merge_inference(gpu_api, name):
     assert err <= TOL
 
 
+@pytest.mark.parametrize("name,bits", [("c5_up", 2), ("c5_up", 3), ("c5_down", 3)])
+def test_config5_shapes_low_bit_small_token(gpu_api, name, bits):
+    """The c5 shapes at INT2 / INT3: the streaming kernel at T in {1, 4, 8, 16} (one, two and
+    four groups of four tokens) against the full oracle."""
+    cfg = synth.CONFIGS[name].scaled(tokens=16, bits=bits)
+    L = layer_on_gpu(gpu_api, cfg)
+    d = L["np"]
+    ref16 = oracle.forward(d["x"], L["codes"], L["alpha"], L["beta"], cfg.group)
+    for T in (1, 4, 8, 16):
+        y = gpu_api.forward(L["desc"], L["x"][:T].contiguous(), L["packed"], L["g_alpha"], L["g_beta"])
+        err = rel_err(y.cpu().numpy(), ref16[:T])
+        record(f"fullsize {name} INT{bits} small-token T={T}", y=err)
+        assert err <= 1e-5
+
+
 def test_small_token_share_longer_than_one_staged_piece(gpu_api):
     """8448 x 32768: 128 slabs of 256 columns leave two parts of 33 chunks each, one more than a
     block stages of x at a time -- the only way to reach the second-piece path of the two

@@ -21,10 +21,11 @@ def fresh(like, seed, scale=1.0):
     return (torch.randn(like.shape, generator=g) * scale).to(like.dtype).cuda()
 
 
-@pytest.mark.parametrize("tokens", [4, 9])  # the decode kernel and the sixteen-token kernel
-def test_graph_replay_small_token_forward(gpu_api, tokens):
+# the decode kernel, the sixteen-token kernel, and the decode kernel's several-token-group form
+@pytest.mark.parametrize("tokens,bits", [(4, 4), (9, 4), (3, 2), (11, 3)])
+def test_graph_replay_small_token_forward(gpu_api, tokens, bits):
     # 2 slabs x 16 parts: fifteen flags per slab are raised and consumed in every launch
-    cfg = synth.LayerConfig("graph_st", tokens, 2048, 512, 4, 32, 8, 0.5, seed=31)
+    cfg = synth.LayerConfig("graph_st", tokens, 2048, 512, bits, 32, 8, 0.5, seed=31)
     L = layer_on_gpu(gpu_api, cfg)
     x = L["x"].clone()
     y = torch.empty((cfg.tokens, cfg.d_out), dtype=torch.float32, device="cuda")
