@@ -177,9 +177,9 @@ def clock_fields(clk_ghz, achieved_tflops):
             "frac_at_measured_clock": round(achieved_tflops / (PEAK_MFMA_TFLOPS * clk_ghz / NOMINAL_CLOCK_GHZ), 4)}
 
 
-def small_token_sets(torch, api, synth, name, n_sets, odt):
+def small_token_sets(torch, api, synth, name, n_sets, odt, bits=4):
     """`n_sets` merged layers of one c5 shape (distinct weights, same distribution)."""
-    cfg = synth.CONFIGS[name].scaled(tokens=256)
+    cfg = synth.CONFIGS[name].scaled(tokens=256, bits=bits)
     gen = torch.Generator(device="cuda").manual_seed(1000 + cfg.seed)
     sets = []
     for i in range(n_sets):
@@ -228,7 +228,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
-    ap.add_argument("--bits", type=int, default=4, help="c4: code width")
+    ap.add_argument("--bits", type=int, default=4, help="c4, c5: code width (c5 is defined at 4)")
     ap.add_argument("--group", type=int, default=32, help="c4: group size")
     ap.add_argument("--tokens", type=int, default=16, help="c5: tokens per call")
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
@@ -376,8 +376,8 @@ def main():
     else:  # c5
         T = args.tokens
         n_sets = 8
-        cfg_u, ups = small_token_sets(torch, api, synth, "c5_up", n_sets, odt)
-        cfg_d, downs = small_token_sets(torch, api, synth, "c5_down", n_sets, odt)
+        cfg_u, ups = small_token_sets(torch, api, synth, "c5_up", n_sets, odt, args.bits)
+        cfg_d, downs = small_token_sets(torch, api, synth, "c5_down", n_sets, odt, args.bits)
         xu, xd = ups[0].x[:T].contiguous(), downs[0].x[:T].contiguous()
         yu = torch.empty((T, cfg_u.d_out), dtype=odt, device="cuda")
         yd = torch.empty((T, cfg_d.d_out), dtype=odt, device="cuda")
@@ -404,22 +404,22 @@ def main():
             # reported beside it.)
             k_avg = ms_per_step / 2.0
             ach = by_step / 2.0 / k_avg / 1e6
-            kname = "smallt4_kernel" if T <= 4 else "smallt_kernel"
+            kname = "smallt4_kernel" if (T <= 4 or args.bits != 4) else "smallt_kernel"
             roofline = {"bound": "hbm", "kernel": f"{kname} (8192x22016 and 22016x8192 alternating)",
                         "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": round(ach / PEAK_HBM_GBS, 4), "avg_kernel_ms": round(k_avg, 5),
                         "event_bracketed_ms_8192x22016": round(k, 5),
-                        "traffic": read_traffic("smallt_c5_pmc.txt")}
+                        "traffic": read_traffic("smallt_c5_pmc.txt") if args.bits == 4 else None}
         else:
             ach = 2.0 * T * cfg_u.d_in * cfg_u.d_out / (k * 1e-3) / 1e12
-            roofline = {"bound": "mfma", "kernel": "gemm_dq_kernel<4,fwd> (8192x22016)", "achieved": round(ach, 2),
+            roofline = {"bound": "mfma", "kernel": f"gemm_dq_kernel<{args.bits},fwd> (8192x22016)", "achieved": round(ach, 2),
                         "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_MFMA_TFLOPS, 4),
                         "avg_kernel_ms": round(k, 5), "hbm_GB/s": round(by_u / k / 1e6, 1), "traffic": None}
             roofline.update(clock_fields(clk[0], ach))
         extras = {"GB/s_whole_step": round(by_step / ms_per_step / 1e6, 1),
                   "frac_hbm_whole_step": round(by_step / ms_per_step / 1e6 / PEAK_HBM_GBS, 4),
                   "bytes_per_step": by_step, "weight_sets": n_sets}
-        workload = (f"c5: post-merge forward, T={T}, 8192x22016 then 22016x8192, INT4 g=32, merged beta, "
+        workload = (f"c5: post-merge forward, T={T}, 8192x22016 then 22016x8192, INT{args.bits} g=32, merged beta, "
                     f"x bf16, outputs {args.out_dtype}, {n_sets} weight sets rotated")
         cfg = cfg_u
         if not args.no_cpu_baseline:
