@@ -29,7 +29,7 @@ FLAGS = [
 # unnoticed (a local array the compiler does not promote to registers costs a round trip to
 # memory per element).
 NO_SCRATCH = {"gemm_dq.hip": "gemm_dq_kernel", "smallt.hip": "smallt_kernel", "smallt4.hip": "smallt4_kernel",
-              "adapter.hip": ("adapter_grads_kernel", "front_kernel")}
+              "adapter.hip": ("adapter_grads_kernel", "front_kernel", "front_wide_kernel")}
 
 
 def _as_tuple(v):

@@ -280,7 +280,51 @@ __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
   }
 }
 
+// Few rows, no adapter work (the post-merge forward of a small batch): with one wavefront per
+// row the launch is a handful of wavefronts walking 16-44 KB each, batch after batch, at the
+// latency of a single wavefront.  Here a whole block takes a row: every thread holds its share
+// of it in registers (up to WIDE_BATCH 16-byte pieces: rows of up to 32768 elements), the four
+// wavefronts' maxima meet in LDS, and the row is converted from the registers -- one pass, one
+// memory round trip.  Same scale and same conversion as process_row, bit for bit.
+constexpr int WIDE_BATCH = 16;
+constexpr int kWideRows = 1024;  // beyond this the one-wavefront-per-row launch fills the chip
+__global__ __launch_bounds__(256) void front_wide_kernel(const uint16_t* __restrict__ src, int cols,
+                                                         float2* __restrict__ rs,
+                                                         uint16_t* __restrict__ dst16) {
+  __shared__ uint32_t wave_amax[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const size_t row = (size_t)blockIdx.x * cols;
+  const int nch = cols / 8;
+  uint4 v[WIDE_BATCH];
+#pragma unroll
+  for (int c = 0; c < WIDE_BATCH; ++c) {
+    const int ch = c * 256 + tid;
+    v[c] = ch < nch ? *reinterpret_cast<const uint4*>(src + row + 8 * ch) : uint4{0, 0, 0, 0};
+  }
+  uint32_t amax = 0;
+#pragma unroll
+  for (int c = 0; c < WIDE_BATCH; ++c) amax = max_abs_bits(v[c], amax);
+  amax = wave_max_u32(amax);
+  if (lane == 0) wave_amax[wave] = amax;
+  __syncthreads();
+  amax = max(max(wave_amax[0], wave_amax[1]), max(wave_amax[2], wave_amax[3]));
+  const float2 sc = scale_from_maxbits(amax);
+  if (tid == 0 && rs) rs[blockIdx.x] = sc;
+  if (dst16) {
+#pragma unroll
+    for (int c = 0; c < WIDE_BATCH; ++c) {
+      const int ch = c * 256 + tid;
+      if (ch < nch) *reinterpret_cast<uint4*>(dst16 + row + 8 * ch) = bf16x8_to_f16x8_scaled(v[c], sc.x);
+    }
+  }
+}
+
 static hipError_t launch_front(FrontArgs a, hipStream_t st) {
+  if (a.x && !a.A && !a.y && !a.b_ext_t && !a.b_hl && !a.us_t && a.T <= kWideRows && a.d_in % 8 == 0 &&
+      a.d_in <= 256 * 8 * WIDE_BATCH) {
+    front_wide_kernel<<<a.T, 256, 0, st>>>(a.x, a.d_in, a.rs_x, a.x16);
+    return hipGetLastError();
+  }
   a.nb_rows1 = a.x ? ceil_div(a.us_t ? a.t_pad : a.T, ROWS_PER_BLOCK) : 0;
   a.nb_rows2 = a.y ? ceil_div(a.Ty, ROWS_PER_BLOCK) : 0;
   size_t nprep = 0;

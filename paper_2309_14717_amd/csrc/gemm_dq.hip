@@ -828,13 +828,17 @@ static hipError_t launch_cfg(const GemmArgs& a, int ksplit, hipStream_t st) {
 template <int NBITS, bool BWD>
 static hipError_t launch_dir(const GemmArgs& a, hipStream_t st) {
   const int ks = a.ksplit > 1 ? a.ksplit : 1;
+  const bool fast = a.a_main_padded_rows >= round_up(a.M, 256) && a.K_main % BK == 0 &&
+                    (BK % a.group == 0 || a.group % BK == 0);
   if (a.M > 128) {
-    const bool fast = a.a_main_padded_rows >= round_up(a.M, 256) && a.K_main % BK == 0 &&
-                      (BK % a.group == 0 || a.group % BK == 0);
     if (fast) return launch_cfg<NBITS, BWD, 256, 256, 2, 4, true, true>(a, ks, st);
     return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, false>(a, ks, st);
   }
-  if (a.M > 64) return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, false>(a, ks, st);
+  if (a.M > 64) {
+    if (fast) return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, true>(a, ks, st);
+    return launch_cfg<NBITS, BWD, 128, 256, 2, 4, true, false>(a, ks, st);
+  }
+  if (fast) return launch_cfg<NBITS, BWD, 64, 256, 1, 8, true, true>(a, ks, st);
   return launch_cfg<NBITS, BWD, 64, 256, 1, 8, true, false>(a, ks, st);
 }
 
