@@ -333,12 +333,13 @@ static hipError_t launch_front(FrontArgs a, hipStream_t st) {
   a.nb_prep = (int)((nprep + 255) / 256);
   const size_t smem =
       a.A ? ((size_t)ROWS_PER_BLOCK * (a.d_in / a.g) + 4 * ROWS_PER_BLOCK * 128) * sizeof(float) : 0;
-  static size_t smem_limit = 48 * 1024;
-  if (smem > smem_limit) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(front_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    smem_limit = smem;
+  constexpr size_t kFrontLdsMax = 160 * 1024;  // a compute unit's LDS
+  if (smem > kFrontLdsMax) return hipErrorInvalidValue;
+  if (smem > 48 * 1024) {
+    static std::atomic<uint64_t> granted{0};
+    if (hipError_t e = grant_dynamic_lds(reinterpret_cast<const void*>(front_kernel), (int)kFrontLdsMax, granted);
+        e != hipSuccess)
+      return e;
   }
   const int nblocks = a.nb_rows1 + a.nb_rows2 + a.nb_prep;
   if (nblocks == 0) return hipSuccess;

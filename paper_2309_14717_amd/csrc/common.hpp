@@ -4,7 +4,23 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace qalora {
+
+// Dynamic LDS beyond 48 KB has to be granted to a kernel once per device.  `granted` (one
+// per kernel instantiation) remembers the devices that have it, so that the library works on
+// whichever device is current and from any thread.
+inline hipError_t grant_dynamic_lds(const void* kernel, int bytes, std::atomic<uint64_t>& granted) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (granted.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) granted.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));

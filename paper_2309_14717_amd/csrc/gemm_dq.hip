@@ -813,13 +813,9 @@ template <int NBITS, bool BWD, int BM, int BN, int WAVES_M, int WAVES_N, bool HA
 static hipError_t launch_cfg(const GemmArgs& a, int ksplit, hipStream_t st) {
   auto kern = gemm_dq_kernel<NBITS, BWD, BM, BN, WAVES_M, WAVES_N, HAS_MAIN, FAST>;
   const size_t smem = (size_t)(3 * BM + 2 * BN) * 64 * sizeof(uint16_t);
-  static bool attr_set = false;  // per instantiation
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> granted{0};  // per instantiation
+  if (hipError_t e = grant_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, granted); e != hipSuccess)
+    return e;
   dim3 grid(ceil_div(a.M, BM) * ceil_div(a.N, BN), ksplit);
   kern<<<grid, NT, smem, st>>>(a);
   return hipGetLastError();

@@ -360,13 +360,10 @@ SmallTPlan smallt_plan(int d_in, int d_out) {
 template <int SUB, int KH>
 static hipError_t launch_sub(const SmallTArgs& a, int grid, hipStream_t st) {
   const size_t smem = 16 * ST_XROW;
-  static bool attr_set = false;  // per instantiation
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(smallt_kernel<SUB, KH>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> granted{0};  // per instantiation
+  if (hipError_t e = grant_dynamic_lds(reinterpret_cast<const void*>(smallt_kernel<SUB, KH>), (int)smem, granted);
+      e != hipSuccess)
+    return e;
   smallt_kernel<SUB, KH><<<grid, ST_THREADS, smem, st>>>(a);
   return hipGetLastError();
 }

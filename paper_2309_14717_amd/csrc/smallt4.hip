@@ -435,14 +435,11 @@ SmallTPlan smallt4_plan(int d_in, int d_out, int tokens) {
 
 template <int NBITS, int SUB, int KH, int TG>
 static hipError_t launch_sub4(const SmallTArgs& a, int grid, hipStream_t st) {
-  static bool attr_set = false;  // per instantiation
+  static std::atomic<uint64_t> granted{0};  // per instantiation
   constexpr int lds = s4_lds_bytes(TG);
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(smallt4_kernel<NBITS, SUB, KH, TG>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  if (hipError_t e = grant_dynamic_lds(reinterpret_cast<const void*>(smallt4_kernel<NBITS, SUB, KH, TG>), lds, granted);
+      e != hipSuccess)
+    return e;
   smallt4_kernel<NBITS, SUB, KH, TG><<<grid, S4_THREADS, lds, st>>>(a);
   return hipGetLastError();
 }
