@@ -15,7 +15,7 @@ _REPORT = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__)
 
 
 def record(case, **errs):
-    """Append measured parity numbers to gpurun_out/parity_report.txt (best effort)."""
+    """Append measured parity numbers to the report file of the run (best effort)."""
     try:
         os.makedirs(os.path.dirname(_REPORT), exist_ok=True)
         with open(_REPORT, "a") as f:
