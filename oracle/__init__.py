@@ -179,6 +179,24 @@ def merge_zp_sum(z, alpha, A, B, s_sum: float):
     return out
 
 
+def beta_from_zero_point(alpha, z):
+    """beta = -alpha z: the zero factor of Eq. 1 that names the same weights as the zero
+    point z of App. B.1 / Alg. 1 (fp64)."""
+    alpha = _f32(alpha)
+    z = np.ascontiguousarray(z, np.float64)
+    out = np.empty(alpha.shape, np.float64)
+    _load().qo_beta_from_zero_point(_ptr(alpha), _ptr(z), ctypes.c_size_t(alpha.size), _ptr(out))
+    return out
+
+
+def zero_point_from_beta(alpha, beta):
+    """z = -beta / alpha (fp64): Eq. 1's zero factor as a zero point in code units."""
+    alpha, beta = _f32(alpha), _f32(beta)
+    out = np.empty(alpha.shape, np.float64)
+    _load().qo_zero_point_from_beta(_ptr(alpha), _ptr(beta), ctypes.c_size_t(alpha.size), _ptr(out))
+    return out
+
+
 def adapter_params(d_in: int, d_out: int, group: int, rank: int) -> int:
     return int(_load().qo_adapter_params(d_in, d_out, group, rank))
 

@@ -323,6 +323,15 @@ void qo_merge_zp_sum(const double* z, const float* alpha, const float* A, const 
     }
 }
 
+/* The two zero conventions name the same weight: alpha (code - z) = alpha code  */
+/* + beta  iff  beta = -alpha z  (App. B.1 against Eq. 1).  Interchange in fp64. */
+void qo_beta_from_zero_point(const float* alpha, const double* z, size_t n, double* beta) {
+  for (size_t i = 0; i < n; ++i) beta[i] = -(double)alpha[i] * z[i];
+}
+void qo_zero_point_from_beta(const float* alpha, const float* beta, size_t n, double* z) {
+  for (size_t i = 0; i < n; ++i) z[i] = -(double)beta[i] / (double)alpha[i];
+}
+
 /* Storage bookkeeping of Sec. 3.3: a QA-LoRA linear carries L*D_out pairs of   */
 /* quantization factors and L*r + r*D_out adapter parameters (ordinary LoRA:    */
 /* D_in*r + r*D_out).                                                           */

@@ -200,6 +200,32 @@ def test_zero_point_sum_convention_twin():
     np.testing.assert_allclose(sum_pool / g, oracle.pool(x, g), rtol=1e-14)
 
 
+def test_zero_point_interchange():
+    """beta = -alpha z names the same weights as the zero point z (App. B.1 against Eq. 1):
+    a layer given as (codes, alpha, integer z) -- the form post-training quantizers emit --
+    must give the same output through either forward; the reverse map restores z; and the
+    textbook case alpha = 1, z = c0 shifts every code by c0."""
+    g = 8
+    d_in, d_out, T = 32, 10, 6
+    x, dy, codes, alpha, beta, A, B = tiny_case(71, T=T, d_in=d_in, d_out=d_out, g=g, r=2)
+    rng = np.random.default_rng(5)
+    z_int = rng.integers(0, 16, size=alpha.shape).astype(np.float64)
+    beta_z = oracle.beta_from_zero_point(alpha, z_int)
+    y_zp = oracle.forward_zp_sum(x, codes, alpha, z_int, g)
+    # definition written out: W~ = alpha (c - z), no beta anywhere
+    W = alpha.astype(np.float64).repeat(g, 0) * (codes - z_int.repeat(g, 0))
+    np.testing.assert_allclose(y_zp, x.astype(np.float64) @ W, rtol=1e-12, atol=1e-13)
+    b32 = beta_z.astype(np.float32)
+    y_beta = oracle.forward(x, codes, alpha, b32, g)
+    assert np.abs(y_beta - y_zp).max() <= 1e-6 * np.abs(y_zp).max()  # fp32 storage of beta
+    z_back = oracle.zero_point_from_beta(alpha, b32)
+    np.testing.assert_allclose(z_back, z_int, rtol=0, atol=2e-6)
+    ones = np.ones_like(alpha)
+    assert np.array_equal(oracle.beta_from_zero_point(ones, np.full(alpha.shape, 3.0)), np.full(alpha.shape, -3.0))
+    assert np.array_equal(oracle.zero_point_from_beta(ones * 2, np.full(alpha.shape, -3.0, np.float32)),
+                          np.full(alpha.shape, 1.5))
+
+
 def test_declared_precision_mode_close_to_definition():
     """Rounding W~ to bf16 moves y by about 2^-9 relative per term; the two modes must agree
     to a few 1e-3 of max|y| and must differ (the flag is wired)."""
