@@ -160,6 +160,21 @@ int qalora_backward(const qalora_desc* desc, int tokens, const void* dy, const v
 int qalora_merge(const qalora_desc* desc, const float* beta, const float* A, const float* B,
                  float* beta_out, void* stream);
 
+/* Zero-point interchange.  Alg. 1 (`pre_quantization`, `merge_with_quantization`) and App. B.1
+ * write the de-quantized weight as W~ = alpha (code - z) with a zero POINT z in code units
+ * (an integer out of a post-training quantizer, real-valued after a merge); this library
+ * keeps Eq. 1's zero FACTOR beta, W~ = alpha code + beta.  They name the same weights iff
+ *   beta = -(alpha z)          (qalora_beta_from_zero_point: import a (codes, scales, zeros) model)
+ *   z    = -(beta / alpha)     (qalora_zero_point_from_beta: export; applied to the beta' of
+ *                               qalora_merge it yields App. B.3's z' = z - (s/g) (A B) / alpha)
+ * one IEEE fp32 operation per element, so import then export returns z to within 2 ulp.
+ * in / out: fp32 [L, d_out]; the output may alias the input it is computed from.
+ * alpha = 0 gives a non-finite z (qalora_quantize never produces it).  No workspace. */
+int qalora_beta_from_zero_point(const qalora_desc* desc, const float* alpha, const float* z,
+                                float* beta, void* stream);
+int qalora_zero_point_from_beta(const qalora_desc* desc, const float* alpha, const float* beta,
+                                float* z, void* stream);
+
 /* Measurement aid (used by the benchmark, not part of the layer): arm a pair of HIP events
  * (hipEvent_t passed as void*, created by the caller with timing enabled).  The next dense
  * contraction kernel of the given direction (0 = the y = x W~ kernel of qalora_forward,

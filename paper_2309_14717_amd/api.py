@@ -27,6 +27,7 @@ EXPORTS = (
     "qalora_profile_event_elapsed_ms", "qalora_profile_event_destroy", "qalora_profile_copy",
     "qalora_swiglu_forward", "qalora_swiglu_backward",
     "qalora_profile_arm_clock", "qalora_profile_wall_clock_khz",
+    "qalora_beta_from_zero_point", "qalora_zero_point_from_beta",
 )
 
 
@@ -78,6 +79,8 @@ def load() -> ctypes.CDLL:
     lib.qalora_profile_arm_clock.argtypes = [ctypes.c_int, vp]
     lib.qalora_profile_wall_clock_khz.argtypes = [ctypes.POINTER(ctypes.c_int)]
     lib.qalora_swiglu_backward.argtypes = [vp, vp, vp, vp, vp, sz, vp]
+    lib.qalora_beta_from_zero_point.argtypes = [cp, vp, vp, vp, vp]
+    lib.qalora_zero_point_from_beta.argtypes = [cp, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -190,6 +193,24 @@ def merge(desc: Desc, beta, A, B, out=None):
         out = torch.empty_like(beta)
     _check(load().qalora_merge(ctypes.byref(desc), _p(beta), _p(A), _p(B), _p(out), _stream()),
            "qalora_merge")
+    return out
+
+
+def beta_from_zero_point(desc: Desc, alpha, z, out=None):
+    """beta = -(alpha z): import a zero point (code units) as the zero factor of Eq. 1."""
+    if out is None:
+        out = torch.empty_like(alpha)
+    _check(load().qalora_beta_from_zero_point(ctypes.byref(desc), _p(alpha), _p(z), _p(out), _stream()),
+           "qalora_beta_from_zero_point")
+    return out
+
+
+def zero_point_from_beta(desc: Desc, alpha, beta, out=None):
+    """z = -(beta / alpha): export the zero factor as a zero point in code units."""
+    if out is None:
+        out = torch.empty_like(alpha)
+    _check(load().qalora_zero_point_from_beta(ctypes.byref(desc), _p(alpha), _p(beta), _p(out), _stream()),
+           "qalora_zero_point_from_beta")
     return out
 
 

@@ -769,4 +769,36 @@ hipError_t launch_merge(const float* beta, const float* A, const float* B, int L
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// Zero-point interchange (App. B.1 / Alg. 1 write W~ = alpha (code - z); Eq. 1 writes
+// W~ = alpha code + beta): beta = -(alpha z), z = -(beta / alpha), one IEEE operation each.
+// ---------------------------------------------------------------------------------------
+template <bool TO_ZERO_POINT>
+__global__ __launch_bounds__(256) void zero_point_kernel(const f32x4* __restrict__ alpha,
+                                                         const f32x4* __restrict__ in,
+                                                         f32x4* __restrict__ out, size_t n4) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n4) return;
+  const f32x4 a = alpha[i], v = in[i];
+  f32x4 o;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) o[c] = TO_ZERO_POINT ? -__fdiv_rn(v[c], a[c]) : -__fmul_rn(a[c], v[c]);
+  out[i] = o;
+}
+
+hipError_t launch_zero_point(const float* alpha, const float* in, float* out, size_t n, bool to_zero_point,
+                             hipStream_t st) {
+  const size_t n4 = n / 4;  // d_out is a multiple of 8
+  const unsigned blocks = (unsigned)((n4 + 255) / 256);
+  if (to_zero_point)
+    zero_point_kernel<true><<<blocks, 256, 0, st>>>(reinterpret_cast<const f32x4*>(alpha),
+                                                    reinterpret_cast<const f32x4*>(in),
+                                                    reinterpret_cast<f32x4*>(out), n4);
+  else
+    zero_point_kernel<false><<<blocks, 256, 0, st>>>(reinterpret_cast<const f32x4*>(alpha),
+                                                     reinterpret_cast<const f32x4*>(in),
+                                                     reinterpret_cast<f32x4*>(out), n4);
+  return hipGetLastError();
+}
+
 }  // namespace qalora

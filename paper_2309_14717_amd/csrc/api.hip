@@ -440,6 +440,26 @@ int qalora_merge(const qalora_desc* d, const float* beta, const float* A, const 
              : QALORA_EHIP;
 }
 
+int qalora_beta_from_zero_point(const qalora_desc* d, const float* alpha, const float* z, float* beta,
+                                void* stream) {
+  const int rc = qalora_check_desc(d);
+  if (rc != QALORA_OK) return rc;
+  if (!alpha || !z || !beta) return QALORA_EINVAL;
+  if (misaligned(alpha) || misaligned(z) || misaligned(beta)) return QALORA_EALIGN;
+  const size_t n = (size_t)(d->d_in / d->group) * d->d_out;
+  return launch_zero_point(alpha, z, beta, n, false, as_stream(stream)) == hipSuccess ? QALORA_OK : QALORA_EHIP;
+}
+
+int qalora_zero_point_from_beta(const qalora_desc* d, const float* alpha, const float* beta, float* z,
+                                void* stream) {
+  const int rc = qalora_check_desc(d);
+  if (rc != QALORA_OK) return rc;
+  if (!alpha || !beta || !z) return QALORA_EINVAL;
+  if (misaligned(alpha) || misaligned(beta) || misaligned(z)) return QALORA_EALIGN;
+  const size_t n = (size_t)(d->d_in / d->group) * d->d_out;
+  return launch_zero_point(alpha, beta, z, n, true, as_stream(stream)) == hipSuccess ? QALORA_OK : QALORA_EHIP;
+}
+
 int qalora_profile_arm(int direction, void* start_event, void* stop_event) {
   if (direction != 0 && direction != 1) return QALORA_EINVAL;
   g_profile_hook[direction] = ProfileHook{static_cast<hipEvent_t>(start_event),

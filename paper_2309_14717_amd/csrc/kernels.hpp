@@ -124,6 +124,10 @@ hipError_t launch_reduce2(const float* part_a, int nparts_a, size_t n_a, float* 
 hipError_t launch_merge(const float* beta, const float* A, const float* B, int L, int d_out,
                         int rank, int g, float s, float* beta_out, hipStream_t st);
 
+// out = -(alpha * in) (zero point -> zero factor) or -(in / alpha) (the reverse), n elements
+hipError_t launch_zero_point(const float* alpha, const float* in, float* out, size_t n, bool to_zero_point,
+                             hipStream_t st);
+
 // --- glue.hip (benchmark-harness glue, not part of the layer) --------------------------
 // h = silu(gate) * up over n bf16 elements (n a multiple of 8), and its backward.
 hipError_t launch_swiglu_forward(const void* gate, const void* up, void* h, size_t n, hipStream_t st);

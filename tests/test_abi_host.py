@@ -92,6 +92,10 @@ def test_argument_errors_are_caught_before_launch(lib):
     assert lib.qalora_quantize(ref, None, P(good), P(good), P(good), None, 0, None) == api.EINVAL
     assert lib.qalora_quantize(ref, P(good), P(good), P(odd), P(good), None, 0, None) == api.EALIGN
     assert lib.qalora_merge(ref, P(good), None, P(good), P(good), None) == api.EINVAL
+    assert lib.qalora_beta_from_zero_point(ref, P(good), None, P(good), None) == api.EINVAL
+    assert lib.qalora_beta_from_zero_point(ref, P(good), P(odd), P(good), None) == api.EALIGN
+    assert lib.qalora_zero_point_from_beta(ref, None, P(good), P(good), None) == api.EINVAL
+    assert lib.qalora_zero_point_from_beta(ref, P(good), P(good), P(odd), None) == api.EALIGN
     assert lib.qalora_unpack(ref, None, P(good), None) == api.EINVAL
     assert lib.qalora_pack(ref, P(good), P(odd), None) == api.EALIGN
     bad = api.make_desc(1024, 1004, 4, 32, 16, 2.0)

@@ -282,3 +282,37 @@ def test_small_token_wide_slab_path(gpu_api):
     yb = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"], out_dtype=torch.bfloat16)
     assert torch.equal(yb, y.to(torch.bfloat16))
     assert torch.equal(y, gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"]))
+
+
+@pytest.mark.parametrize("bits,group", [(4, 32), (3, 64), (2, 16)])
+def test_zero_point_interchange(gpu_api, bits, group):
+    """A layer handed over in zero-point form (codes, scales, integer zeros: what post-training
+    quantizers emit, App. B.1) runs after beta = -(alpha z); the merged layer goes back out as
+    App. B.3's real-valued z' = z - (s/g) (A B) / alpha.  The references are the oracle's
+    zero-point twins, which never see a beta."""
+    cfg = synth.LayerConfig("zp", 48, 512, 264, bits, group, 8, 0.5, seed=40 + bits)
+    d = synth.make_inputs(cfg)
+    rng = np.random.default_rng(cfg.seed)
+    L = cfg.d_in // group
+    codes = rng.integers(0, 1 << bits, size=(cfg.d_in, cfg.d_out), dtype=np.uint8)
+    alpha = (rng.random((L, cfg.d_out), dtype=np.float32) * 0.01 + 0.002).astype(np.float32)
+    z = rng.integers(0, 1 << bits, size=(L, cfg.d_out)).astype(np.float64)
+    desc = gpu_api.make_desc(cfg.d_in, cfg.d_out, bits, group, cfg.rank, cfg.s)
+    packed = gpu_api.pack(desc, dev(codes))
+    g_alpha, g_z = dev(alpha), dev(z.astype(np.float32))
+    beta = gpu_api.beta_from_zero_point(desc, g_alpha, g_z)
+    ref_beta = oracle.beta_from_zero_point(alpha, z)
+    assert np.array_equal(beta.cpu().numpy(), ref_beta.astype(np.float32))  # one fp32 product each
+    x, A, B = dev(d["x"]).to(torch.bfloat16), dev(d["A"]), dev(d["B"])
+    y = gpu_api.forward(desc, x, packed, g_alpha, beta, A, B)
+    ref = oracle.forward_zp_sum(d["x"], codes, alpha, z, group, d["A"], d["B"], cfg.s / group)
+    err = rel_err(y.cpu().numpy(), ref)
+    record(f"zero-point import N={bits} g={group}", y=err)
+    assert err <= TOL
+    beta_m = gpu_api.merge(desc, beta, A, B)
+    z_m = gpu_api.zero_point_from_beta(desc, g_alpha, beta_m)
+    ref_z = oracle.merge_zp_sum(z, alpha, d["A"], d["B"], cfg.s / group)
+    assert rel_err(z_m.cpu().numpy(), ref_z) <= 1e-6
+    # round trip without a merge: within 2 ulp of the integer zeros
+    z_back = gpu_api.zero_point_from_beta(desc, g_alpha, beta).cpu().numpy()
+    assert np.abs(z_back - z).max() <= 2 * np.spacing(np.float32(max(1.0, z.max())))
