@@ -81,7 +81,8 @@ enum qalora_op {
   QALORA_OP_QUANTIZE = 0,
   QALORA_OP_FORWARD = 1,
   QALORA_OP_BACKWARD = 2,
-  QALORA_OP_MERGE = 3
+  QALORA_OP_MERGE = 3,
+  QALORA_OP_FORWARD_FACTORS16 = 4
 };
 
 /* Human-readable name of a status code (static string, host). */
@@ -159,6 +160,24 @@ int qalora_backward(const qalora_desc* desc, int tokens, const void* dy, const v
  * beta_out may alias beta.  Needs no workspace. */
 int qalora_merge(const qalora_desc* desc, const float* beta, const float* A, const float* B,
                  float* beta_out, void* stream);
+
+/* 16-bit storage of the quantization factors for inference on the merged model, where every
+ * call streams the whole weight (Sec. 3.3 deployment; App. B.3): one 32-bit word per
+ * (group, column), fp16(alpha) in the low half and fp16(beta) in the high half, each rounded to
+ * nearest even.  At INT4, g = 32 this takes a quarter off the bytes of a call.  It is a lossy
+ * re-encoding of the layer (11 significant bits per factor): the layer it defines is
+ * W~ = fp16(alpha) code + fp16(beta), and that is what qalora_forward_factors16 computes.
+ * in : alpha, beta fp32 [L, d_out]      out: factors16, 4 * L * d_out bytes. */
+int qalora_pack_factors16(const qalora_desc* desc, const float* alpha, const float* beta,
+                          void* factors16, void* stream);
+
+/* Adapter-free forward y = x W~ of a layer whose factors are stored as above; otherwise as
+ * qalora_forward with A = B = NULL.  Up to 16 tokens (conditions as for qalora_forward) the
+ * streaming kernel reads the 16-bit factors directly; beyond that they are expanded to fp32
+ * in the workspace first.  Workspace: qalora_workspace_bytes(.., QALORA_OP_FORWARD_FACTORS16). */
+int qalora_forward_factors16(const qalora_desc* desc, int tokens, const void* x,
+                             const void* packed, const void* factors16, void* y, int y_dtype,
+                             void* ws, size_t ws_bytes, void* stream);
 
 /* Zero-point interchange.  Alg. 1 (`pre_quantization`, `merge_with_quantization`) and App. B.1
  * write the de-quantized weight as W~ = alpha (code - z) with a zero POINT z in code units

@@ -18,7 +18,7 @@ LIB_PATH = os.environ.get("QALORA_LIB") or os.path.join(_HERE, "libqalora_hip.so
 
 OK, EINVAL, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
-OP_QUANTIZE, OP_FORWARD, OP_BACKWARD, OP_MERGE = 0, 1, 2, 3
+OP_QUANTIZE, OP_FORWARD, OP_BACKWARD, OP_MERGE, OP_FORWARD_FACTORS16 = 0, 1, 2, 3, 4
 
 EXPORTS = (
     "qalora_status_string", "qalora_check_desc", "qalora_packed_bytes", "qalora_workspace_bytes",
@@ -28,6 +28,7 @@ EXPORTS = (
     "qalora_swiglu_forward", "qalora_swiglu_backward",
     "qalora_profile_arm_clock", "qalora_profile_wall_clock_khz",
     "qalora_beta_from_zero_point", "qalora_zero_point_from_beta",
+    "qalora_pack_factors16", "qalora_forward_factors16",
 )
 
 
@@ -79,6 +80,8 @@ def load() -> ctypes.CDLL:
     lib.qalora_profile_arm_clock.argtypes = [ctypes.c_int, vp]
     lib.qalora_profile_wall_clock_khz.argtypes = [ctypes.POINTER(ctypes.c_int)]
     lib.qalora_swiglu_backward.argtypes = [vp, vp, vp, vp, vp, sz, vp]
+    lib.qalora_pack_factors16.argtypes = [cp, vp, vp, vp, vp]
+    lib.qalora_forward_factors16.argtypes = [cp, i, vp, vp, vp, vp, i, vp, sz, vp]
     lib.qalora_beta_from_zero_point.argtypes = [cp, vp, vp, vp, vp]
     lib.qalora_zero_point_from_beta.argtypes = [cp, vp, vp, vp, vp]
     _lib = lib
@@ -163,6 +166,29 @@ def forward(desc: Desc, x, packed, alpha, beta, A=None, B=None, out_dtype=torch.
                                _p(B), _p(y), BF16 if y.dtype == torch.bfloat16 else F32, _p(ws),
                                ws_bytes, _stream())
     _check(rc, "qalora_forward")
+    return y
+
+
+def pack_factors16(desc: Desc, alpha, beta, out=None):
+    """One int32 word per (group, column): fp16(alpha) | fp16(beta) << 16."""
+    if out is None:
+        out = torch.empty(alpha.shape, dtype=torch.int32, device=alpha.device)
+    _check(load().qalora_pack_factors16(ctypes.byref(desc), _p(alpha), _p(beta), _p(out), _stream()),
+           "qalora_pack_factors16")
+    return out
+
+
+def forward_factors16(desc: Desc, x, packed, factors16, out_dtype=torch.float32, ws=None, y=None):
+    """Adapter-free y = x W~ with the factors stored in 16 bits (see pack_factors16)."""
+    assert x.dtype == torch.bfloat16 and x.is_contiguous()
+    T = x.shape[0]
+    if y is None:
+        y = torch.empty((T, desc.d_out), dtype=out_dtype, device=x.device)
+    ws, ws_bytes = _workspace(desc, T, OP_FORWARD_FACTORS16, ws)
+    rc = load().qalora_forward_factors16(ctypes.byref(desc), T, _p(x), _p(packed), _p(factors16), _p(y),
+                                         BF16 if y.dtype == torch.bfloat16 else F32, _p(ws), ws_bytes,
+                                         _stream())
+    _check(rc, "qalora_forward_factors16")
     return y
 
 

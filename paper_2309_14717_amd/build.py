@@ -13,7 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqalora_hip.so")
-SOURCES = ["api.hip", "quantize.hip", "gemm_dq.hip", "adapter.hip", "smallt.hip", "smallt4.hip", "glue.hip"]
+SOURCES = ["api.hip", "quantize.hip", "gemm_dq.hip", "adapter.hip", "smallt.hip", "smallt4.hip", "smallt4_f16.hip",
+           "glue.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -28,7 +29,7 @@ FLAGS = [
 # counter), and the adapter-gradient kernel, whose staging arrays once ended up in scratch
 # unnoticed (a local array the compiler does not promote to registers costs a round trip to
 # memory per element).
-NO_SCRATCH = {"gemm_dq.hip": "gemm_dq_kernel", "smallt.hip": "smallt_kernel", "smallt4.hip": "smallt4_kernel",
+NO_SCRATCH = {"gemm_dq.hip": "gemm_dq_kernel", "smallt.hip": "smallt_kernel", "smallt4.hip": "smallt4_kernel", "smallt4_f16.hip": "smallt4_kernel",
               "adapter.hip": ("adapter_grads_kernel", "front_kernel", "front_wide_kernel")}
 
 
@@ -66,7 +67,7 @@ def _compile(src: str, extra) -> str:
 
 def build(verbose: bool = False, extra_flags=()) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(7, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
     tmp = LIB + ".tmp%d" % os.getpid()
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])

@@ -198,6 +198,15 @@ size_t qalora_workspace_bytes(const qalora_desc* d, int tokens, int op) {
       }
       return need;
     }
+    case QALORA_OP_FORWARD_FACTORS16: {
+      if (tokens <= 0) return 0;
+      if (use_smallt(*d, tokens)) return smallt_workspace(*d, tokens);
+      // matrix path: the adapter-free forward's workspace, then alpha and beta expanded to fp32
+      qalora_desc plain = *d;
+      plain.rank = 0;
+      return align_up(qalora_workspace_bytes(&plain, tokens, QALORA_OP_FORWARD)) +
+             2 * align_up((size_t)(d->d_in / d->group) * d->d_out * 4);
+    }
     case QALORA_OP_BACKWARD: return tokens > 0 ? plan_backward(*d, tokens).total : 0;
     default: return 0;
   }
@@ -438,6 +447,58 @@ int qalora_merge(const qalora_desc* d, const float* beta, const float* A, const 
                       as_stream(stream)) == hipSuccess
              ? QALORA_OK
              : QALORA_EHIP;
+}
+
+int qalora_pack_factors16(const qalora_desc* d, const float* alpha, const float* beta, void* factors16,
+                          void* stream) {
+  const int rc = qalora_check_desc(d);
+  if (rc != QALORA_OK) return rc;
+  if (!alpha || !beta || !factors16) return QALORA_EINVAL;
+  if (misaligned(alpha) || misaligned(beta) || misaligned(factors16)) return QALORA_EALIGN;
+  const size_t n = (size_t)(d->d_in / d->group) * d->d_out;
+  return launch_pack_factors(alpha, beta, factors16, n, as_stream(stream)) == hipSuccess ? QALORA_OK
+                                                                                          : QALORA_EHIP;
+}
+
+int qalora_forward_factors16(const qalora_desc* d, int tokens, const void* x, const void* packed,
+                             const void* factors16, void* y, int y_dtype, void* ws, size_t ws_bytes,
+                             void* stream) {
+  const int rc = qalora_check_desc(d);
+  if (rc != QALORA_OK) return rc;
+  if (tokens <= 0 || !x || !packed || !factors16 || !y) return QALORA_EINVAL;
+  if (y_dtype != QALORA_F32 && y_dtype != QALORA_BF16) return QALORA_EINVAL;
+  if (misaligned(x) || misaligned(packed) || misaligned(factors16) || misaligned(y) || misaligned(ws))
+    return QALORA_EALIGN;
+  if (!addressable(*d, tokens)) return QALORA_EUNSUPPORTED;
+  const size_t need = qalora_workspace_bytes(d, tokens, QALORA_OP_FORWARD_FACTORS16);
+  if (!ws || ws_bytes < need) return QALORA_EWORKSPACE;
+  if (use_smallt(*d, tokens)) {
+    SmallTArgs a{};
+    a.x = static_cast<const uint16_t*>(x);
+    a.plane0 = static_cast<const uint32_t*>(packed);
+    a.plane1 = a.plane0 + plane0_words(d->bits, d->d_in, d->d_out);
+    a.bits = d->bits;
+    a.fac16 = static_cast<const uint32_t*>(factors16);
+    a.out = y;
+    a.flags = static_cast<unsigned long long*>(ws);
+    a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + align_up((size_t)ST_MAX_BLOCKS * 8));
+    a.out_bf16 = (y_dtype == QALORA_BF16);
+    a.T = tokens;
+    a.d_in = d->d_in;
+    a.d_out = d->d_out;
+    a.group = d->group;
+    return launch_smallt(a, as_stream(stream)) == hipSuccess ? QALORA_OK : QALORA_EHIP;
+  }
+  // matrix path: expand the factors behind the forward's own workspace and run it
+  qalora_desc plain = *d;
+  plain.rank = 0;
+  const size_t fwd_ws = align_up(qalora_workspace_bytes(&plain, tokens, QALORA_OP_FORWARD));
+  const size_t n = (size_t)(d->d_in / d->group) * d->d_out;
+  float* alpha = reinterpret_cast<float*>(static_cast<char*>(ws) + fwd_ws);
+  float* beta = reinterpret_cast<float*>(static_cast<char*>(ws) + fwd_ws + align_up(n * 4));
+  if (launch_unpack_factors(factors16, alpha, beta, n, as_stream(stream)) != hipSuccess) return QALORA_EHIP;
+  return qalora_forward(&plain, tokens, x, packed, alpha, beta, nullptr, nullptr, y, y_dtype, ws, fwd_ws,
+                        stream);
 }
 
 int qalora_beta_from_zero_point(const qalora_desc* d, const float* alpha, const float* z, float* beta,

@@ -11,6 +11,9 @@ void launch_quantize(int bits, const float* W, void* packed, float* alpha, float
                      int d_out, int g, hipStream_t st);
 void launch_unpack(int bits, const void* packed, uint8_t* codes, int d_in, int d_out,
                    hipStream_t st);
+// fac16[i] = fp16(alpha[i]) | fp16(beta[i]) << 16 over n = L * d_out elements, and back
+hipError_t launch_pack_factors(const float* alpha, const float* beta, void* fac16, size_t n, hipStream_t st);
+hipError_t launch_unpack_factors(const void* fac16, float* alpha, float* beta, size_t n, hipStream_t st);
 void launch_pack(int bits, const uint8_t* codes, void* packed, int d_in, int d_out,
                  hipStream_t st);
 
@@ -62,6 +65,7 @@ struct SmallTArgs {
   const uint32_t* plane1;  // INT3: the plane of high bits; otherwise unused
   const float* alpha;      // [L, d_out]
   const float* beta;       // [L, d_out]
+  const uint32_t* fac16;   // or, instead of both: [L, d_out] words fp16 alpha | fp16 beta << 16
   void* out;               // [T, d_out] fp32 or bf16
   float* partial;          // [blocks][ST_PARTIAL_FLOATS] fp32, accumulator-register layout: runs that end inside a slab
   unsigned long long* flags;  // [blocks]: set to `nonce` once the block's partial is complete
@@ -81,6 +85,7 @@ hipError_t launch_smallt(const SmallTArgs& a, hipStream_t st);  // dispatches on
 // INT3 / INT2 up to sixteen tokens -------------------------------------------------------
 SmallTPlan smallt4_plan(int d_in, int d_out, int tokens);
 hipError_t launch_smallt4(const SmallTArgs& a, hipStream_t st);  // nonce set by the caller
+hipError_t launch_smallt4_f16(const SmallTArgs& a, hipStream_t st);  // the 16-bit-factor instantiations
 
 // --- adapter.hip --------------------------------------------------------------------
 // Tail width of the adapter operands: three bf16 sections of `rank` columns, zero padded

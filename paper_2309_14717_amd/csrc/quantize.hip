@@ -216,4 +216,55 @@ void launch_pack(int bits, const uint8_t* codes, void* packed, int d_in, int d_o
   else pack_n<2>(codes, p0, p1, d_in, d_out, st);
 }
 
+// ---------------------------------------------------------------------------------------
+// 16-bit storage of the factors for the memory-bound forward: one word per (group, column),
+// fp16(alpha) | fp16(beta) << 16, round-to-nearest-even; and back to two fp32 matrices.
+// ---------------------------------------------------------------------------------------
+typedef uint32_t qz_u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void pack_factors_kernel(const f32x4* __restrict__ alpha,
+                                                           const f32x4* __restrict__ beta,
+                                                           qz_u32x4* __restrict__ out, size_t n4) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n4) return;
+  const f32x4 a = alpha[i], b = beta[i];
+  qz_u32x4 o;
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+    o[c] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)a[c]) |
+           ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)b[c]) << 16);
+  out[i] = o;
+}
+
+__global__ __launch_bounds__(256) void unpack_factors_kernel(const qz_u32x4* __restrict__ in,
+                                                             f32x4* __restrict__ alpha,
+                                                             f32x4* __restrict__ beta, size_t n4) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n4) return;
+  const qz_u32x4 w = in[i];
+  f32x4 a, b;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    a[c] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[c] & 0xffffu));
+    b[c] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[c] >> 16));
+  }
+  alpha[i] = a;
+  beta[i] = b;
+}
+
+hipError_t launch_pack_factors(const float* alpha, const float* beta, void* fac16, size_t n, hipStream_t st) {
+  const size_t n4 = n / 4;  // d_out is a multiple of 8
+  pack_factors_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, st>>>(
+      reinterpret_cast<const f32x4*>(alpha), reinterpret_cast<const f32x4*>(beta),
+      static_cast<qz_u32x4*>(fac16), n4);
+  return hipGetLastError();
+}
+
+hipError_t launch_unpack_factors(const void* fac16, float* alpha, float* beta, size_t n, hipStream_t st) {
+  const size_t n4 = n / 4;
+  unpack_factors_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, st>>>(
+      static_cast<const qz_u32x4*>(fac16), reinterpret_cast<f32x4*>(alpha), reinterpret_cast<f32x4*>(beta), n4);
+  return hipGetLastError();
+}
+
 }  // namespace qalora

@@ -74,7 +74,8 @@ __device__ __forceinline__ void lds_barrier() {
 // SUB : 32-row steps per quantization group (group = 32 * SUB; 1, 2 or 4)
 // KH  : ways a block splits its own chunks (1: sixteen column groups, slab of 512 columns;
 //       2: eight column groups x two halves, slab of 256 columns)
-template <int SUB, int KH>
+// F16 : the factors of a (group, column) come as ONE word, fp16 alpha | fp16 beta << 16
+template <int SUB, int KH, bool F16>
 __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) {
   extern __shared__ __align__(16) unsigned char xs[];  // [16][ST_XROW]
   __shared__ int poison;
@@ -95,8 +96,9 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
 
   const __amdgpu_buffer_rsrc_t rs_w = st_rsrc(p.plane0, (size_t)(p.d_in / 8) * p.d_out * 4);
   const __amdgpu_buffer_rsrc_t rs_x = st_rsrc(p.x, (size_t)p.T * p.d_in * 2);
-  const __amdgpu_buffer_rsrc_t rs_al = st_rsrc(p.alpha, (size_t)L * p.d_out * 4);
-  const __amdgpu_buffer_rsrc_t rs_be = st_rsrc(p.beta, (size_t)L * p.d_out * 4);
+  const __amdgpu_buffer_rsrc_t rs_al = st_rsrc(F16 ? (const void*)p.fac16 : (const void*)p.alpha, (size_t)L * p.d_out * 4);
+  const __amdgpu_buffer_rsrc_t rs_be = st_rsrc(p.beta, F16 ? 0 : (size_t)L * p.d_out * 4);
+  constexpr int NLOADS = F16 ? 5 : 6;  // vector-memory loads of one chunk
   const uint32_t step_w = 4u * p.d_out * 4u;  // four packed rows per 32-row step
   const uint32_t row_ab = (uint32_t)p.d_out * 4u;
   // Mask and bias live in registers (not literals) so that "(w >> k) & mask | bias" is one
@@ -128,7 +130,7 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
                                                         (int)((uint32_t)(4 * c + st) * step_w), ST_NT);
       const uint32_t so = (uint32_t)(4 * c / SUB) * row_ab;
       ch.al = __builtin_amdgcn_raw_buffer_load_b64(rs_al, (int)vab, (int)so, ST_NT);
-      ch.be = __builtin_amdgcn_raw_buffer_load_b64(rs_be, (int)vab, (int)so, ST_NT);
+      if constexpr (!F16) ch.be = __builtin_amdgcn_raw_buffer_load_b64(rs_be, (int)vab, (int)so, ST_NT);
     };
 
     f32x4 acc[CW];
@@ -162,8 +164,15 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
           const int src = (n + 16 * (st / SUB)) * 4;  // the lane group holding this group's factors
 #pragma unroll
           for (int q = 0; q < CW; ++q) {
-            const float al = __int_as_float(__builtin_amdgcn_ds_bpermute(src, (int)ch.al[q]));
-            const float be = __int_as_float(__builtin_amdgcn_ds_bpermute(src, (int)ch.be[q]));
+            float al, be;
+            if constexpr (F16) {
+              const uint32_t ab = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)ch.al[q]);
+              al = (float)__builtin_bit_cast(_Float16, (uint16_t)(ab & 0xffffu));
+              be = (float)__builtin_bit_cast(_Float16, (uint16_t)(ab >> 16));
+            } else {
+              al = __int_as_float(__builtin_amdgcn_ds_bpermute(src, (int)ch.al[q]));
+              be = __int_as_float(__builtin_amdgcn_ds_bpermute(src, (int)ch.be[q]));
+            }
             const float bp = __builtin_fmaf(-128.0f, al, be);  // codes carry a +128 offset
 #pragma unroll
             for (int r = 0; r < 4; ++r)
@@ -204,9 +213,9 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
             *reinterpret_cast<u32x4*>(xs + wave * ST_XROW + o * 16) = u32x4{0, 0, 0, 0};
         }
       }
-      // twelve weight loads were issued after the copies: once at most twelve are outstanding,
+      // two chunks of weight loads were issued after the copies: once at most that many are outstanding,
       // the copies have landed
-      asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NLOADS) : "memory");
       lds_barrier();
 
       int c = wa;
@@ -357,14 +366,14 @@ SmallTPlan smallt_plan(int d_in, int d_out) {
   return best;
 }
 
-template <int SUB, int KH>
+template <int SUB, int KH, bool F16>
 static hipError_t launch_sub(const SmallTArgs& a, int grid, hipStream_t st) {
   const size_t smem = 16 * ST_XROW;
   static std::atomic<uint64_t> granted{0};  // per instantiation
-  if (hipError_t e = grant_dynamic_lds(reinterpret_cast<const void*>(smallt_kernel<SUB, KH>), (int)smem, granted);
+  if (hipError_t e = grant_dynamic_lds(reinterpret_cast<const void*>(smallt_kernel<SUB, KH, F16>), (int)smem, granted);
       e != hipSuccess)
     return e;
-  smallt_kernel<SUB, KH><<<grid, ST_THREADS, smem, st>>>(a);
+  smallt_kernel<SUB, KH, F16><<<grid, ST_THREADS, smem, st>>>(a);
   return hipGetLastError();
 }
 
@@ -381,13 +390,13 @@ hipError_t launch_smallt(const SmallTArgs& args, hipStream_t st) {
     // decode shapes and the narrower codes: the one-column-per-lane kernel
     if (a.T <= 4 || a.bits != 4) return launch_smallt4(a, st);
     if (pl.halves == 2) {
-      if (sub == 1) return launch_sub<1, 2>(a, pl.blocks, st);
-      if (sub == 2) return launch_sub<2, 2>(a, pl.blocks, st);
-      if (sub == 4) return launch_sub<4, 2>(a, pl.blocks, st);
+      if (sub == 1) return a.fac16 ? launch_sub<1, 2, true>(a, pl.blocks, st) : launch_sub<1, 2, false>(a, pl.blocks, st);
+      if (sub == 2) return a.fac16 ? launch_sub<2, 2, true>(a, pl.blocks, st) : launch_sub<2, 2, false>(a, pl.blocks, st);
+      if (sub == 4) return a.fac16 ? launch_sub<4, 2, true>(a, pl.blocks, st) : launch_sub<4, 2, false>(a, pl.blocks, st);
     } else {
-      if (sub == 1) return launch_sub<1, 1>(a, pl.blocks, st);
-      if (sub == 2) return launch_sub<2, 1>(a, pl.blocks, st);
-      if (sub == 4) return launch_sub<4, 1>(a, pl.blocks, st);
+      if (sub == 1) return a.fac16 ? launch_sub<1, 1, true>(a, pl.blocks, st) : launch_sub<1, 1, false>(a, pl.blocks, st);
+      if (sub == 2) return a.fac16 ? launch_sub<2, 1, true>(a, pl.blocks, st) : launch_sub<2, 1, false>(a, pl.blocks, st);
+      if (sub == 4) return a.fac16 ? launch_sub<4, 1, true>(a, pl.blocks, st) : launch_sub<4, 1, false>(a, pl.blocks, st);
     }
     return hipErrorInvalidValue;
   };

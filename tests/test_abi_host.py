@@ -22,7 +22,7 @@ def lib():
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "qalora.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(qalora_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(qalora_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_exports_every_declared_symbol(lib):
@@ -96,6 +96,18 @@ def test_argument_errors_are_caught_before_launch(lib):
     assert lib.qalora_beta_from_zero_point(ref, P(good), P(odd), P(good), None) == api.EALIGN
     assert lib.qalora_zero_point_from_beta(ref, None, P(good), P(good), None) == api.EINVAL
     assert lib.qalora_zero_point_from_beta(ref, P(good), P(good), P(odd), None) == api.EALIGN
+    assert lib.qalora_pack_factors16(ref, P(good), None, P(good), None) == api.EINVAL
+    assert lib.qalora_pack_factors16(ref, P(good), P(good), P(odd), None) == api.EALIGN
+    assert lib.qalora_forward_factors16(ref, 0, P(good), P(good), P(good), P(good), 0, P(good), 1 << 30, None) == api.EINVAL
+    assert lib.qalora_forward_factors16(ref, 4, P(good), P(good), None, P(good), 0, P(good), 1 << 30, None) == api.EINVAL
+    assert lib.qalora_forward_factors16(ref, 4, P(good), P(good), P(good), P(good), 7, P(good), 1 << 30, None) == api.EINVAL
+    assert lib.qalora_forward_factors16(ref, 4, P(odd), P(good), P(good), P(good), 0, P(good), 1 << 30, None) == api.EALIGN
+    assert lib.qalora_forward_factors16(ref, 4, P(good), P(good), P(good), P(good), 0, P(good), 16, None) == api.EWORKSPACE
+    assert lib.qalora_forward_factors16(ref, 400, P(good), P(good), P(good), P(good), 0, None, 0, None) == api.EWORKSPACE
+    # the matrix path of the 16-bit-factor forward needs room for the expanded factors on top
+    fwd = lib.qalora_workspace_bytes(ref, 400, api.OP_FORWARD)
+    assert lib.qalora_workspace_bytes(ref, 400, api.OP_FORWARD_FACTORS16) >= 2 * (1024 // 32) * 1024 * 4
+    assert lib.qalora_workspace_bytes(ref, 4, api.OP_FORWARD_FACTORS16) > 0 and fwd > 0
     assert lib.qalora_unpack(ref, None, P(good), None) == api.EINVAL
     assert lib.qalora_pack(ref, P(good), P(odd), None) == api.EALIGN
     bad = api.make_desc(1024, 1004, 4, 32, 16, 2.0)

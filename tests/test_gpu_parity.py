@@ -316,3 +316,35 @@ def test_zero_point_interchange(gpu_api, bits, group):
     # round trip without a merge: within 2 ulp of the integer zeros
     z_back = gpu_api.zero_point_from_beta(desc, g_alpha, beta).cpu().numpy()
     assert np.abs(z_back - z).max() <= 2 * np.spacing(np.float32(max(1.0, z.max())))
+
+
+@pytest.mark.parametrize("bits,group,d_in,d_out", [(4, 32, 1536, 2304), (3, 64, 1024, 8704), (2, 128, 2048, 520)])
+def test_forward_with_16bit_factors(gpu_api, bits, group, d_in, d_out):
+    """alpha, beta stored as fp16 pairs: the packing is the IEEE round-to-nearest-even
+    conversion bit for bit, and the layer W~ = fp16(alpha) c + fp16(beta) runs on the streaming
+    kernels (T <= 16, exact operands) and on the matrix path (T > 16) like any other layer."""
+    cfg = synth.LayerConfig("f16fac", 300, d_in, d_out, bits, group, 8, 0.5, seed=60 + bits)
+    L = layer_on_gpu(gpu_api, cfg)
+    fac = gpu_api.pack_factors16(L["desc"], L["g_alpha"], L["g_beta"])
+    a16, b16 = L["alpha"].astype(np.float16), L["beta"].astype(np.float16)
+    want = a16.view(np.uint16).astype(np.uint32) | (b16.view(np.uint16).astype(np.uint32) << 16)
+    assert np.array_equal(fac.cpu().numpy().view(np.uint32), want)
+    al, be = a16.astype(np.float32), b16.astype(np.float32)
+    ref = oracle.forward(L["np"]["x"], L["codes"], al, be, group)
+    for T in (1, 3, 4, 7, 16):
+        y = gpu_api.forward_factors16(L["desc"], L["x"][:T].contiguous(), L["packed"], fac)
+        err = rel_err(y.cpu().numpy(), ref[:T])
+        record(f"16-bit factors N={bits} g={group} T={T}", y=err)
+        assert err <= 1e-5
+        # the same layer through the fp32-factor entry point: same kernel arithmetic, same bits
+        y32 = gpu_api.forward(L["desc"], L["x"][:T].contiguous(), L["packed"], dev(al), dev(be))
+        assert torch.equal(y, y32)
+        yb = gpu_api.forward_factors16(L["desc"], L["x"][:T].contiguous(), L["packed"], fac,
+                                       out_dtype=torch.bfloat16)
+        assert torch.equal(yb, y.to(torch.bfloat16))
+    for T in (40, 300):
+        y = gpu_api.forward_factors16(L["desc"], L["x"][:T].contiguous(), L["packed"], fac)
+        err = rel_err(y.cpu().numpy(), ref[:T])
+        record(f"16-bit factors N={bits} g={group} T={T}", y=err)
+        assert err <= TOL
+        assert torch.equal(y, gpu_api.forward(L["desc"], L["x"][:T].contiguous(), L["packed"], dev(al), dev(be)))
