@@ -49,10 +49,10 @@ def layer_flops(cfg, adapter=True):
                 bwd_kernel=main + 2.0 * T * L * r)           # dy W~^T + dU A^T (unpooled)
 
 
-def forward_bytes(cfg, tokens, out_bytes=2):
+def forward_bytes(cfg, tokens, out_bytes=2, factor_bytes=4):
     """Algorithmic HBM bytes of one adapter-free forward: every operand once."""
     codes = cfg.d_in * cfg.d_out * cfg.bits // 8
-    factors = 2 * cfg.groups * cfg.d_out * 4
+    factors = 2 * cfg.groups * cfg.d_out * factor_bytes
     return codes + factors + tokens * cfg.d_in * 2 + tokens * cfg.d_out * out_bytes
 
 
@@ -94,6 +94,7 @@ class Layer:
         self.W = W
         self.packed, self.alpha, self.beta = api.quantize(self.desc, W)
         self.beta_m = api.merge(self.desc, self.beta, self.A, self.B) if merged else None
+        self.fac16 = None
         T = cfg.tokens
         self.y = torch.empty((T, cfg.d_out), dtype=odt, device=dev)
         self.ws_f = torch.empty(max(16, api.workspace_bytes(self.desc, T, api.OP_FORWARD)), dtype=torch.uint8, device=dev)
@@ -112,6 +113,9 @@ class Layer:
 
     def forward_merged(self, x=None, y=None, ws=None):
         a = self.api
+        if self.fac16 is not None:  # factors of the merged layer stored as fp16 pairs
+            return a.forward_factors16(self.desc, self.x if x is None else x, self.packed, self.fac16,
+                                       ws=self.ws_f if ws is None else ws, y=self.y if y is None else y)
         return a.forward(self.desc, self.x if x is None else x, self.packed, self.alpha, self.beta_m,
                          ws=self.ws_f if ws is None else ws, y=self.y if y is None else y)
 
@@ -231,6 +235,8 @@ def main():
     ap.add_argument("--bits", type=int, default=4, help="c4, c5: code width (c5 is defined at 4)")
     ap.add_argument("--group", type=int, default=32, help="c4: group size")
     ap.add_argument("--tokens", type=int, default=16, help="c5: tokens per call")
+    ap.add_argument("--factors16", action="store_true",
+                    help="c5: alpha, beta of the merged layers stored as fp16 pairs (the configuration itself has fp32)")
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
@@ -378,11 +384,16 @@ def main():
         n_sets = 8
         cfg_u, ups = small_token_sets(torch, api, synth, "c5_up", n_sets, odt, args.bits)
         cfg_d, downs = small_token_sets(torch, api, synth, "c5_down", n_sets, odt, args.bits)
+        fb = 2 if args.factors16 else 4
+        if args.factors16:
+            for Lr in ups + downs:
+                Lr.fac16 = api.pack_factors16(Lr.desc, Lr.alpha, Lr.beta_m)
         xu, xd = ups[0].x[:T].contiguous(), downs[0].x[:T].contiguous()
         yu = torch.empty((T, cfg_u.d_out), dtype=odt, device="cuda")
         yd = torch.empty((T, cfg_d.d_out), dtype=odt, device="cuda")
-        ws_u = torch.empty(api.workspace_bytes(ups[0].desc, T, api.OP_FORWARD), dtype=torch.uint8, device="cuda")
-        ws_d = torch.empty(api.workspace_bytes(downs[0].desc, T, api.OP_FORWARD), dtype=torch.uint8, device="cuda")
+        op = api.OP_FORWARD_FACTORS16 if args.factors16 else api.OP_FORWARD
+        ws_u = torch.empty(api.workspace_bytes(ups[0].desc, T, op), dtype=torch.uint8, device="cuda")
+        ws_d = torch.empty(api.workspace_bytes(downs[0].desc, T, op), dtype=torch.uint8, device="cuda")
         counter = [0]
 
         def step():
@@ -393,8 +404,8 @@ def main():
 
         ms_per_step, kms, clk = run_steps(torch, api, step, args.steps, max(args.warmup, n_sets), directions=(0,), arm_every=7)
         total_flops = 2.0 * T * (cfg_u.d_in * cfg_u.d_out + cfg_d.d_in * cfg_d.d_out)
-        by_u = forward_bytes(cfg_u, T, yu.element_size())
-        by_step = by_u + forward_bytes(cfg_d, T, yd.element_size())
+        by_u = forward_bytes(cfg_u, T, yu.element_size(), fb)
+        by_step = by_u + forward_bytes(cfg_d, T, yd.element_size(), fb)
         k = kms[0]
         if T <= 16:
             # A step is two launches of the streaming kernel with (to 0.1 %) the same algorithmic
@@ -409,7 +420,7 @@ def main():
                         "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": round(ach / PEAK_HBM_GBS, 4), "avg_kernel_ms": round(k_avg, 5),
                         "event_bracketed_ms_8192x22016": round(k, 5),
-                        "traffic": read_traffic("smallt_c5_pmc.txt") if args.bits == 4 else None}
+                        "traffic": read_traffic("smallt_c5_pmc.txt") if (args.bits == 4 and not args.factors16) else None}
         else:
             ach = 2.0 * T * cfg_u.d_in * cfg_u.d_out / (k * 1e-3) / 1e12
             roofline = {"bound": "mfma", "kernel": f"gemm_dq_kernel<{args.bits},fwd> (8192x22016)", "achieved": round(ach, 2),
@@ -420,7 +431,8 @@ def main():
                   "frac_hbm_whole_step": round(by_step / ms_per_step / 1e6 / PEAK_HBM_GBS, 4),
                   "bytes_per_step": by_step, "weight_sets": n_sets}
         workload = (f"c5: post-merge forward, T={T}, 8192x22016 then 22016x8192, INT{args.bits} g=32, merged beta, "
-                    f"x bf16, outputs {args.out_dtype}, {n_sets} weight sets rotated")
+                    f"x bf16, outputs {args.out_dtype}, {n_sets} weight sets rotated"
+                    + (", alpha and beta stored as fp16 pairs" if args.factors16 else ""))
         cfg = cfg_u
         if not args.no_cpu_baseline:
             import oracle
