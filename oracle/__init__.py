@@ -43,6 +43,7 @@ def _load():
         _lib.qo_adapter_params.restype = ctypes.c_longlong
         _lib.qo_lora_params.restype = ctypes.c_longlong
         _lib.qo_quant_factor_pairs.restype = ctypes.c_longlong
+        _lib.qo_sum_squares.restype = ctypes.c_double
     return _lib
 
 
@@ -195,6 +196,38 @@ def zero_point_from_beta(alpha, beta):
     out = np.empty(alpha.shape, np.float64)
     _load().qo_zero_point_from_beta(_ptr(alpha), _ptr(beta), ctypes.c_size_t(alpha.size), _ptr(out))
     return out
+
+
+def grad_norm(grads) -> float:
+    """Joint L2 norm of all gradient tensors (fp64)."""
+    lib = _load()
+    total = 0.0
+    for g in grads:
+        g = _f32(g)
+        total += float(lib.qo_sum_squares(_ptr(g), ctypes.c_size_t(g.size)))
+    return float(np.sqrt(total))
+
+
+def adamw_step(params, grads, exp_avg, exp_avg_sq, step: int, lr: float, beta1: float = 0.9,
+               beta2: float = 0.999, eps: float = 1e-8, weight_decay: float = 0.0,
+               max_grad_norm: float = 0.0):
+    """One AdamW step on a list of tensors with a joint gradient-norm clip (Sec. 4.1's recipe;
+    max_grad_norm <= 0: no clip).  The clip factor is min(1, max / (norm + 1e-6)), the form the
+    usual training loops apply.  Returns (params, exp_avg, exp_avg_sq) as fp64 lists and the norm."""
+    lib = _load()
+    norm = grad_norm(grads)
+    clip = min(1.0, max_grad_norm / (norm + 1e-6)) if max_grad_norm > 0 else 1.0
+    outs = ([], [], [])
+    for p, g, m, v in zip(params, grads, exp_avg, exp_avg_sq):
+        p, g, m, v = _f32(p), _f32(g), _f32(m), _f32(v)
+        po, mo, vo = (np.empty(p.shape, np.float64) for _ in range(3))
+        lib.qo_adamw_update(_ptr(p), _ptr(g), _ptr(m), _ptr(v), ctypes.c_size_t(p.size),
+                            ctypes.c_double(clip), ctypes.c_double(lr), ctypes.c_double(beta1),
+                            ctypes.c_double(beta2), ctypes.c_double(eps), ctypes.c_double(weight_decay),
+                            int(step), _ptr(po), _ptr(mo), _ptr(vo))
+        for o, t in zip(outs, (po, mo, vo)):
+            o.append(t)
+    return outs[0], outs[1], outs[2], norm
 
 
 def adapter_params(d_in: int, d_out: int, group: int, rank: int) -> int:

@@ -332,6 +332,37 @@ void qo_zero_point_from_beta(const float* alpha, const float* beta, size_t n, do
   for (size_t i = 0; i < n; ++i) z[i] = -(double)beta[i] / (double)alpha[i];
 }
 
+/* ------------------------------------------------------------------------- */
+/* The optimiser step that follows the backward in the fine-tuning recipe      */
+/* (Sec. 4.1, training details: AdamW, a maximum gradient norm, a constant     */
+/* learning rate; only A and B are parameters, Sec. 3.1).  AdamW is Adam with  */
+/* decoupled weight decay; the clip rescales ALL gradients by one factor when  */
+/* their joint L2 norm exceeds the maximum.  fp64 from fp32 inputs.            */
+/* ------------------------------------------------------------------------- */
+double qo_sum_squares(const float* g, size_t n) {
+  double acc = 0.0;
+  for (size_t i = 0; i < n; ++i) acc += (double)g[i] * (double)g[i];
+  return acc;
+}
+
+/* step counts from 1.  clip is the factor applied to the raw gradient.         */
+void qo_adamw_update(const float* p, const float* g, const float* m, const float* v, size_t n,
+                     double clip, double lr, double beta1, double beta2, double eps,
+                     double weight_decay, int step, double* p_out, double* m_out, double* v_out) {
+  const double bias1 = 1.0 - pow(beta1, (double)step);
+  const double bias2 = 1.0 - pow(beta2, (double)step);
+  for (size_t i = 0; i < n; ++i) {
+    const double gi = clip * (double)g[i];
+    const double mi = beta1 * (double)m[i] + (1.0 - beta1) * gi;        /* first moment  */
+    const double vi = beta2 * (double)v[i] + (1.0 - beta2) * gi * gi;   /* second moment */
+    const double decayed = (double)p[i] * (1.0 - lr * weight_decay);    /* decoupled decay */
+    const double m_hat = mi / bias1, v_hat = vi / bias2;
+    p_out[i] = decayed - lr * m_hat / (sqrt(v_hat) + eps);
+    m_out[i] = mi;
+    v_out[i] = vi;
+  }
+}
+
 /* Storage bookkeeping of Sec. 3.3: a QA-LoRA linear carries L*D_out pairs of   */
 /* quantization factors and L*r + r*D_out adapter parameters (ordinary LoRA:    */
 /* D_in*r + r*D_out).                                                           */
