@@ -213,6 +213,27 @@ def small_token_table(torch, api, synth, odt, n_sets=8, tokens=(1, 4, 16, 256), 
     return rows
 
 
+def adamw_layer_timing(torch, api, d=4096, ff=11008, g=32, r=64):
+    """The fused optimiser step over the adapters of one LLaMA-7B decoder layer (seven linears,
+    fourteen tensors; AdamW with the 0.3 norm clip of the paper's recipe).  Algorithmic bytes:
+    the gradient once for the norm, then p, g, m, v read and p, m, v written = 32 B/parameter."""
+    shapes = []
+    for d_in, d_out in ((d, d),) * 4 + ((d, ff), (d, ff), (ff, d)):
+        shapes += [(d_in // g, r), (r, d_out)]
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    p = [torch.randn(s, device="cuda", generator=gen) * 0.02 for s in shapes]
+    gr = [torch.randn(s, device="cuda", generator=gen) for s in shapes]
+    m = [torch.zeros_like(x) for x in p]
+    v = [torch.zeros_like(x) for x in p]
+    hp = api.AdamW(2e-5, 0.9, 0.999, 1e-8, 0.0, 0.3)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    it = iter(range(1, 10 ** 9))
+    ms = timed(torch, lambda: api.adamw_step(hp, next(it), p, gr, m, v, ws=ws), n=50, warm=5)
+    n = sum(x.numel() for x in p)
+    return {"parameters": n, "tensors": len(p), "us": round(ms * 1e3, 2), "GB/s": round(32.0 * n / ms / 1e6, 1),
+            "frac_hbm": round(32.0 * n / ms / 1e6 / PEAK_HBM_GBS, 4)}
+
+
 def cpu_oracle_baseline(fn_flops_pairs, label):
     """Time the oracle (as it stands) on the host: list of (callable, flops)."""
     import oracle
@@ -310,6 +331,7 @@ def main():
             }
             if args.workload == "c2":
                 L.drop_w()
+                extras["adamw_step_decoder_layer"] = adamw_layer_timing(torch, api)
                 extras["small_token_post_merge_forward"] = small_token_table(torch, api, synth, odt)
         if not args.no_cpu_baseline:
             import oracle

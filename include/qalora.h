@@ -194,6 +194,30 @@ int qalora_beta_from_zero_point(const qalora_desc* desc, const float* alpha, con
 int qalora_zero_point_from_beta(const qalora_desc* desc, const float* alpha, const float* beta,
                                 float* z, void* stream);
 
+/* The optimiser step that follows qalora_backward in the fine-tuning loop (Sec. 4.1, training
+ * details: AdamW, a maximum gradient norm of 0.3, a constant learning rate; only A and B are
+ * parameters, Sec. 3.1), fused over up to QALORA_ADAMW_MAX_TENSORS tensors -- e.g. the A and B
+ * of every linear of a decoder layer -- in two launches.  With t = step (counted from 1):
+ *   norm = joint L2 norm of all grads;  clip = min(1, max_grad_norm / (norm + 1e-6)), or 1 if
+ *   max_grad_norm <= 0;  g = clip * grad;
+ *   m = beta1 m + (1 - beta1) g;   v = beta2 v + (1 - beta2) g^2;
+ *   p = p (1 - lr weight_decay) - lr (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps).
+ * params, grads, exp_avg, exp_avg_sq: HOST arrays of n_tensors DEVICE pointers (fp32, numel[i]
+ * elements each, 16-byte aligned); params, exp_avg, exp_avg_sq are updated in place; grads are
+ * read, and set to zero afterwards if zero_grads != 0 (so that the next qalora_backward can
+ * accumulate).  grad_norm: optional device float receiving the norm before clipping.
+ * ws: qalora_adamw_workspace_bytes(n_tensors, numel) bytes (needed when clipping or when the
+ * norm is asked for).  fp32 arithmetic, sums in a fixed order: a step is bit-reproducible. */
+#define QALORA_ADAMW_MAX_TENSORS 32
+typedef struct qalora_adamw {
+  float lr, beta1, beta2, eps, weight_decay, max_grad_norm;
+} qalora_adamw;
+size_t qalora_adamw_workspace_bytes(int n_tensors, const size_t* numel);
+int qalora_adamw_step(const qalora_adamw* hp, int step, int n_tensors, float* const* params,
+                      float* const* grads, float* const* exp_avg, float* const* exp_avg_sq,
+                      const size_t* numel, int zero_grads, float* grad_norm, void* ws,
+                      size_t ws_bytes, void* stream);
+
 /* Measurement aid (used by the benchmark, not part of the layer): arm a pair of HIP events
  * (hipEvent_t passed as void*, created by the caller with timing enabled).  The next dense
  * contraction kernel of the given direction (0 = the y = x W~ kernel of qalora_forward,

@@ -29,6 +29,7 @@ EXPORTS = (
     "qalora_profile_arm_clock", "qalora_profile_wall_clock_khz",
     "qalora_beta_from_zero_point", "qalora_zero_point_from_beta",
     "qalora_pack_factors16", "qalora_forward_factors16",
+    "qalora_adamw_workspace_bytes", "qalora_adamw_step",
 )
 
 
@@ -82,6 +83,9 @@ def load() -> ctypes.CDLL:
     lib.qalora_swiglu_backward.argtypes = [vp, vp, vp, vp, vp, sz, vp]
     lib.qalora_pack_factors16.argtypes = [cp, vp, vp, vp, vp]
     lib.qalora_forward_factors16.argtypes = [cp, i, vp, vp, vp, vp, i, vp, sz, vp]
+    lib.qalora_adamw_workspace_bytes.restype = sz
+    lib.qalora_adamw_workspace_bytes.argtypes = [i, vp]
+    lib.qalora_adamw_step.argtypes = [vp, i, i, vp, vp, vp, vp, vp, i, vp, vp, sz, vp]
     lib.qalora_beta_from_zero_point.argtypes = [cp, vp, vp, vp, vp]
     lib.qalora_zero_point_from_beta.argtypes = [cp, vp, vp, vp, vp]
     _lib = lib
@@ -238,6 +242,26 @@ def zero_point_from_beta(desc: Desc, alpha, beta, out=None):
     _check(load().qalora_zero_point_from_beta(ctypes.byref(desc), _p(alpha), _p(beta), _p(out), _stream()),
            "qalora_zero_point_from_beta")
     return out
+
+
+class AdamW(ctypes.Structure):
+    """Mirror of ``qalora_adamw``."""
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float), ("max_grad_norm", ctypes.c_float)]
+
+
+def adamw_step(hp: AdamW, step: int, params, grads, exp_avg, exp_avg_sq, zero_grads=False, grad_norm=None,
+               ws=None):
+    """One fused AdamW step with a joint gradient-norm clip over lists of fp32 device tensors
+    (updated in place).  ``grad_norm``: optional one-element fp32 device tensor for the norm."""
+    n = len(params)
+    ptrs = [(ctypes.c_void_p * n)(*[t.data_ptr() for t in ts]) for ts in (params, grads, exp_avg, exp_avg_sq)]
+    numel = (ctypes.c_size_t * n)(*[t.numel() for t in params])
+    if ws is None:
+        ws = torch.empty(max(load().qalora_adamw_workspace_bytes(n, numel), 16), dtype=torch.uint8, device="cuda")
+    rc = load().qalora_adamw_step(ctypes.byref(hp), int(step), n, ptrs[0], ptrs[1], ptrs[2], ptrs[3], numel,
+                                  1 if zero_grads else 0, _p(grad_norm), _p(ws), ws.numel(), _stream())
+    _check(rc, "qalora_adamw_step")
 
 
 def profile_copy(dst: torch.Tensor, src: torch.Tensor):

@@ -5,6 +5,8 @@
 #include "common.hpp"
 #include "kernels.hpp"
 
+#include <cmath>
+
 using namespace qalora;
 
 namespace {
@@ -519,6 +521,70 @@ int qalora_zero_point_from_beta(const qalora_desc* d, const float* alpha, const 
   if (misaligned(alpha) || misaligned(beta) || misaligned(z)) return QALORA_EALIGN;
   const size_t n = (size_t)(d->d_in / d->group) * d->d_out;
   return launch_zero_point(alpha, beta, z, n, true, as_stream(stream)) == hipSuccess ? QALORA_OK : QALORA_EHIP;
+}
+
+namespace {
+// Block table of a tensor list; false if the list is not acceptable.
+bool adamw_table(int n, const size_t* numel, OptTensors& t) {
+  if (n < 1 || n > OPT_MAX_TENSORS || !numel) return false;
+  unsigned long long blocks = 0;
+  for (int i = 0; i < n; ++i) {
+    if (numel[i] == 0) return false;
+    t.numel[i] = numel[i];
+    t.chunk_start[i] = (unsigned)blocks;
+    blocks += (numel[i] + OPT_CHUNK - 1) / OPT_CHUNK;
+    if (blocks > 0x7fffffffull) return false;
+  }
+  t.chunk_start[n] = (unsigned)blocks;
+  t.n = n;
+  return true;
+}
+}  // namespace
+
+size_t qalora_adamw_workspace_bytes(int n_tensors, const size_t* numel) {
+  OptTensors t{};
+  if (!adamw_table(n_tensors, numel, t)) return 0;
+  return align_up((size_t)t.chunk_start[t.n] * sizeof(float));
+}
+
+int qalora_adamw_step(const qalora_adamw* hp, int step, int n_tensors, float* const* params,
+                      float* const* grads, float* const* exp_avg, float* const* exp_avg_sq,
+                      const size_t* numel, int zero_grads, float* grad_norm, void* ws, size_t ws_bytes,
+                      void* stream) {
+  if (!hp || step < 1 || !params || !grads || !exp_avg || !exp_avg_sq) return QALORA_EINVAL;
+  if (!(hp->beta1 >= 0.0f && hp->beta1 < 1.0f && hp->beta2 >= 0.0f && hp->beta2 < 1.0f) ||
+      !(hp->eps >= 0.0f) || !(hp->lr >= 0.0f) || !(hp->weight_decay >= 0.0f))
+    return QALORA_EINVAL;
+  OptTensors t{};
+  if (!adamw_table(n_tensors, numel, t)) return QALORA_EINVAL;
+  for (int i = 0; i < n_tensors; ++i) {
+    if (!params[i] || !grads[i] || !exp_avg[i] || !exp_avg_sq[i]) return QALORA_EINVAL;
+    if (misaligned(params[i]) || misaligned(grads[i]) || misaligned(exp_avg[i]) || misaligned(exp_avg_sq[i]))
+      return QALORA_EALIGN;
+    t.p[i] = params[i];
+    t.g[i] = grads[i];
+    t.m[i] = exp_avg[i];
+    t.v[i] = exp_avg_sq[i];
+  }
+  if (misaligned(grad_norm) || misaligned(ws)) return QALORA_EALIGN;
+  const bool need_norm = hp->max_grad_norm > 0.0f || grad_norm;
+  if (need_norm && (!ws || ws_bytes < (size_t)t.chunk_start[t.n] * sizeof(float))) return QALORA_EWORKSPACE;
+  OptHyper h{};
+  const double b1 = hp->beta1, b2 = hp->beta2;
+  h.beta1 = hp->beta1;
+  h.one_minus_beta1 = (float)(1.0 - b1);
+  h.beta2 = hp->beta2;
+  h.one_minus_beta2 = (float)(1.0 - b2);
+  h.eps = hp->eps;
+  h.decay = (float)(1.0 - (double)hp->lr * (double)hp->weight_decay);
+  h.step_size = (float)((double)hp->lr / (1.0 - pow(b1, (double)step)));
+  h.inv_sqrt_bias2 = (float)(1.0 / sqrt(1.0 - pow(b2, (double)step)));
+  h.max_norm = hp->max_grad_norm;
+  h.zero_grads = zero_grads ? 1 : 0;
+  return launch_adamw(t, h, need_norm ? static_cast<float*>(ws) : nullptr, grad_norm, as_stream(stream)) ==
+                 hipSuccess
+             ? QALORA_OK
+             : QALORA_EHIP;
 }
 
 int qalora_profile_arm(int direction, void* start_event, void* stop_event) {

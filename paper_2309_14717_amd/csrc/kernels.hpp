@@ -133,6 +133,28 @@ hipError_t launch_merge(const float* beta, const float* A, const float* B, int L
 hipError_t launch_zero_point(const float* alpha, const float* in, float* out, size_t n, bool to_zero_point,
                              hipStream_t st);
 
+// --- optim.hip: fused AdamW step with a joint gradient-norm clip over up to 32 tensors ----
+constexpr int OPT_MAX_TENSORS = 32;
+constexpr int OPT_CHUNK = 4096;  // elements per block; a block never straddles two tensors
+struct OptTensors {
+  float* p[OPT_MAX_TENSORS];
+  float* g[OPT_MAX_TENSORS];
+  float* m[OPT_MAX_TENSORS];
+  float* v[OPT_MAX_TENSORS];
+  unsigned long long numel[OPT_MAX_TENSORS];
+  unsigned chunk_start[OPT_MAX_TENSORS + 1];  // first block of each tensor; [n] = blocks in all
+  int n;
+};
+struct OptHyper {
+  float beta1, one_minus_beta1, beta2, one_minus_beta2, eps;
+  float decay;           // 1 - lr * weight_decay
+  float step_size;       // lr / (1 - beta1^t)
+  float inv_sqrt_bias2;  // 1 / sqrt(1 - beta2^t)
+  float max_norm;
+  int zero_grads;
+};
+hipError_t launch_adamw(const OptTensors& t, const OptHyper& h, float* partial, float* norm_out, hipStream_t st);
+
 // --- glue.hip (benchmark-harness glue, not part of the layer) --------------------------
 // h = silu(gate) * up over n bf16 elements (n a multiple of 8), and its backward.
 hipError_t launch_swiglu_forward(const void* gate, const void* up, void* h, size_t n, hipStream_t st);

@@ -124,3 +124,30 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(api, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         api.load()
+
+
+def test_adamw_argument_errors(lib):
+    """The fused optimiser step checks its tensor table on the host (fake pointers, no launch)."""
+    P = ctypes.c_void_p
+    hp = api.AdamW(2e-5, 0.9, 0.999, 1e-8, 0.0, 0.3)
+    good, odd = 0x10000, 0x10004
+    arr = lambda v, n=2: (ctypes.c_void_p * n)(*([v] * n))
+    numel = (ctypes.c_size_t * 2)(4096, 1000)
+    assert lib.qalora_adamw_workspace_bytes(2, numel) >= 2 * 4
+    assert lib.qalora_adamw_workspace_bytes(0, numel) == 0
+    assert lib.qalora_adamw_workspace_bytes(33, numel) == 0
+    call = lambda **kw: lib.qalora_adamw_step(
+        kw.get("hp", ctypes.byref(hp)), kw.get("step", 1), kw.get("n", 2), kw.get("p", arr(good)), arr(good),
+        kw.get("m", arr(good)), arr(good), kw.get("numel", numel), 0, None, kw.get("ws", P(good)),
+        kw.get("ws_bytes", 1 << 20), None)
+    assert call(hp=None) == api.EINVAL
+    assert call(step=0) == api.EINVAL
+    assert call(n=0) == api.EINVAL
+    assert call(n=33) == api.EINVAL
+    assert call(p=arr(None)) == api.EINVAL
+    assert call(m=arr(odd)) == api.EALIGN
+    assert call(numel=(ctypes.c_size_t * 2)(4096, 0)) == api.EINVAL
+    assert call(ws=None, ws_bytes=0) == api.EWORKSPACE   # clipping needs the block sums
+    assert call(ws_bytes=4) == api.EWORKSPACE
+    bad = api.AdamW(2e-5, 1.0, 0.999, 1e-8, 0.0, 0.3)
+    assert call(hp=ctypes.byref(bad)) == api.EINVAL
