@@ -348,3 +348,17 @@ def test_forward_with_16bit_factors(gpu_api, bits, group, d_in, d_out):
         record(f"16-bit factors N={bits} g={group} T={T}", y=err)
         assert err <= TOL
         assert torch.equal(y, gpu_api.forward(L["desc"], L["x"][:T].contiguous(), L["packed"], dev(al), dev(be)))
+
+
+def test_forward_with_16bit_factors_off_the_streaming_shapes(gpu_api):
+    """A few tokens of a layer the streaming kernels do not take (group 16, input width not a
+    multiple of 128): the 16-bit factors are expanded and the matrix path runs."""
+    cfg = synth.LayerConfig("f16fac_m", 6, 528, 264, 2, 16, 8, 0.5, seed=66)
+    L = layer_on_gpu(gpu_api, cfg)
+    fac = gpu_api.pack_factors16(L["desc"], L["g_alpha"], L["g_beta"])
+    al = L["alpha"].astype(np.float16).astype(np.float32)
+    be = L["beta"].astype(np.float16).astype(np.float32)
+    ref = oracle.forward(L["np"]["x"], L["codes"], al, be, cfg.group)
+    y = gpu_api.forward_factors16(L["desc"], L["x"], L["packed"], fac)
+    assert rel_err(y.cpu().numpy(), ref) <= TOL
+    assert torch.equal(y, gpu_api.forward(L["desc"], L["x"], L["packed"], dev(al), dev(be)))
