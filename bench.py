@@ -234,6 +234,16 @@ def adamw_layer_timing(torch, api, d=4096, ff=11008, g=32, r=64):
             "frac_hbm": round(32.0 * n / ms / 1e6 / PEAK_HBM_GBS, 4)}
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_oracle_baseline(fn_flops_pairs, label):
     """Time the oracle (as it stands) on the host: list of (callable, flops)."""
     import oracle
@@ -244,7 +254,7 @@ def cpu_oracle_baseline(fn_flops_pairs, label):
         flops += fl
     dt = time.perf_counter() - tc
     return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "sample": f"{label}, fp64, {dt:.1f} s"}
+            "kind": "oracle", "sample": f"{label}, fp64, {dt:.1f} s", "cpu_model": cpu_model()}
 
 
 def main():
