@@ -60,3 +60,31 @@ def test_random_layer(gpu_api, case):
     errs["y_factors16"] = rel_err(y16.cpu().numpy(), oracle.forward(d["x"], L["codes"], a16, b16, cfg.group))
     record(f"random N={cfg.bits} g={cfg.group} {cfg.d_in}x{cfg.d_out} T={cfg.tokens} r={cfg.rank}", **errs)
     assert max(errs.values()) <= TOL, errs
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_random_small_token_layer(gpu_api, case):
+    """The streaming kernels on drawn shapes: up to sixteen tokens, every code width, 1 to 70
+    chunks of input rows, output widths that end anywhere inside a slab; fp32 and 16-bit
+    factors; exact operands, so the bar is 1e-5; reruns bit-identical."""
+    from helpers import dev
+    rng = np.random.default_rng(9000 + case)
+    bits, group = int(rng.choice([2, 3, 4])), int(rng.choice([32, 64, 128]))
+    d_in, d_out, T = 128 * int(rng.integers(1, 70)), 8 * int(rng.integers(1, 1500)), int(rng.integers(1, 17))
+    L = d_in // group
+    codes = rng.integers(0, 1 << bits, size=(d_in, d_out), dtype=np.uint8)
+    alpha = (rng.random((L, d_out), dtype=np.float32) * 0.01 + 0.001).astype(np.float32)
+    beta = (-rng.random((L, d_out), dtype=np.float32) * 0.05).astype(np.float32)
+    x = torch.from_numpy(rng.standard_normal((T, d_in)).astype(np.float32)).to(torch.bfloat16)
+    x64 = x.float().numpy().astype(np.float64)
+    desc = gpu_api.make_desc(d_in, d_out, bits, group)
+    packed, ga, gb, xd = gpu_api.pack(desc, dev(codes)), dev(alpha), dev(beta), x.cuda()
+    y = gpu_api.forward(desc, xd, packed, ga, gb)
+    e32 = rel_err(y.cpu().numpy(), oracle.forward(x64, codes, alpha, beta, group))
+    assert torch.equal(y, gpu_api.forward(desc, xd, packed, ga, gb))
+    fac = gpu_api.pack_factors16(desc, ga, gb)
+    a16, b16 = (v.astype(np.float16).astype(np.float32) for v in (alpha, beta))
+    y16 = gpu_api.forward_factors16(desc, xd, packed, fac)
+    e16 = rel_err(y16.cpu().numpy(), oracle.forward(x64, codes, a16, b16, group))
+    record(f"random small-token N={bits} g={group} {d_in}x{d_out} T={T}", y=e32, y_factors16=e16)
+    assert max(e32, e16) <= 1e-5
