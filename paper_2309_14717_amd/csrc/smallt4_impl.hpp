@@ -333,30 +333,46 @@ __global__ __launch_bounds__(S4_THREADS) void smallt4_kernel(const SmallTArgs p)
   }
 
   // ---- hand over, or finish the slab (wavefronts of share 0 hold the sums) ------------------
-  // A partial is [column group][row pair][lane] x 8 bytes: every store and load is 512
-  // contiguous bytes.  Row pairs that hold no token are neither written nor read.
-  const int npairs = (p.T + 1) / 2;
-  if (part < m - 1) {
-    // The partial and the flag are written with device-scope atomic stores (write-through to
-    // the level all compute units share), so no cache write-back or invalidate is needed.
-    unsigned long long* dst =
-        reinterpret_cast<unsigned long long*>(p.partial + (size_t)b * ST_PARTIAL_FLOATS) + cg * (2 * TG * 64) + lane;
-    if (kh == 0) {
+  // The block's sums are first laid out in LDS as a [token][column] tile, so that they travel
+  // as 16-byte accesses, one (token, four columns) item per thread: a partial leaves the block
+  // in a quarter of the memory instructions the one-column-per-lane registers would need, and
+  // the cost of the hand-over goes with the number of these cache-bypassing accesses.
+  // They carry the cache policy of a device-scope atomic (coherent at the level all compute
+  // units share), so no cache write-back or invalidate is needed.
+  float* tile = reinterpret_cast<float*>(xs);  // [NTOK][SLAB_COLS]
+  constexpr int kDeviceCoherent = 16;          // "sc1"
+  constexpr int C4 = SLAB_COLS / 4;            // items per token row
+  constexpr int ITEMS_PER_THREAD = (NTOK * C4 + S4_THREADS - 1) / S4_THREADS;
+  static_assert(NTOK * SLAB_COLS <= ST_PARTIAL_FLOATS, "a partial holds the whole tile");
+  lds_barrier();  // x and the meeting area of the shares are no longer needed
+  if (kh == 0) {
 #pragma unroll
-      for (int q = 0; q < 2 * TG; ++q)
-        if (q < npairs)
-          __hip_atomic_store(dst + 64 * q,
-                             __builtin_bit_cast(unsigned long long, f32x2{acc[q >> 1][2 * (q & 1)], acc[q >> 1][2 * (q & 1) + 1]}),
-                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int t = 0; t < TG; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) tile[(4 * t + r) * SLAB_COLS + cg * S4_WCOLS + lane] = acc[t][r];
+  }
+  lds_barrier();
+  const int items = p.T * C4;
+  const __amdgpu_buffer_rsrc_t rs_p = s4_rsrc(p.partial, (size_t)gridDim.x * ST_PARTIAL_FLOATS * 4);
+  if (part < m - 1) {
+#pragma unroll
+    for (int k = 0; k < ITEMS_PER_THREAD; ++k) {
+      const int it = tid + k * S4_THREADS;
+      if (it < items) {
+        const int r = it / C4, c4 = it - r * C4;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(tile + r * SLAB_COLS + 4 * c4);
+        __builtin_amdgcn_raw_buffer_store_b128(v, rs_p, (r * SLAB_COLS + 4 * c4) * 4,
+                                               (int)((uint32_t)b * (ST_PARTIAL_FLOATS * 4u)), kDeviceCoherent);
+      }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // every store of this wavefront has landed
     __syncthreads();
     if (tid == 0)
       __hip_atomic_store(p.flags + b, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   } else {
-    f32x2 tot[2 * TG];
+    f32x4 tot[ITEMS_PER_THREAD];
 #pragma unroll
-    for (int q = 0; q < 2 * TG; ++q) tot[q] = f32x2{0.0f, 0.0f};
+    for (int k = 0; k < ITEMS_PER_THREAD; ++k) tot[k] = zero4;
     if (m > 1) {
       const int bf = b - (m - 1);  // block of part 0 of this slab
       // one thread per flag, all polling at once
@@ -375,41 +391,44 @@ __global__ __launch_bounds__(S4_THREADS) void smallt4_kernel(const SmallTArgs p)
       }
       __syncthreads();
       // partials in part order, PB blocks' loads in flight at a time
-      constexpr int PB = 8 / TG;
-      if (kh == 0) {
-        for (int i0 = 0; i0 < m - 1; i0 += PB) {
-          f32x2 v[PB][2 * TG];
+      constexpr int PB = 8 / ITEMS_PER_THREAD;
 #pragma unroll
-          for (int i = 0; i < PB; ++i) {
-            const unsigned long long* src =
-                reinterpret_cast<const unsigned long long*>(p.partial + (size_t)(bf + i0 + i) * ST_PARTIAL_FLOATS) +
-                cg * (2 * TG * 64) + lane;
+      for (int k = 0; k < ITEMS_PER_THREAD; ++k) {
+        const int it = tid + k * S4_THREADS;
+        if (it < items) {
+          const int r = it / C4, c4 = it - r * C4;
+          for (int i0 = 0; i0 < m - 1; i0 += PB) {
+            u32x4 v[PB];
 #pragma unroll
-            for (int q = 0; q < 2 * TG; ++q) {
-              v[i][q] = f32x2{0.0f, 0.0f};
-              if (i0 + i < m - 1 && q < npairs)
-                v[i][q] = __builtin_bit_cast(
-                    f32x2, __hip_atomic_load(src + 64 * q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            for (int i = 0; i < PB; ++i) {
+              v[i] = u32x4{0, 0, 0, 0};
+              if (i0 + i < m - 1)
+                v[i] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rs_p, (r * SLAB_COLS + 4 * c4) * 4,
+                    (int)((uint32_t)(bf + i0 + i) * (ST_PARTIAL_FLOATS * 4u)), kDeviceCoherent);
             }
+#pragma unroll
+            for (int i = 0; i < PB; ++i) tot[k] += __builtin_bit_cast(f32x4, v[i]);
           }
-#pragma unroll
-          for (int i = 0; i < PB; ++i)
-#pragma unroll
-            for (int q = 0; q < 2 * TG; ++q) tot[q] += v[i][q];
         }
       }
     }
     const bool bad = (m > 1) && poison != 0;
-    if (kh == 0 && col_ok) {
 #pragma unroll
-      for (int r = 0; r < NTOK; ++r) {
-        float v = tot[r >> 1][r & 1] + acc[r >> 2][r & 3];
-        if (bad) v = __builtin_nanf("");  // a wait ran out: make it loud
-        if (r < p.T) {
+    for (int k = 0; k < ITEMS_PER_THREAD; ++k) {
+      const int it = tid + k * S4_THREADS;
+      if (it < items) {
+        const int r = it / C4, c4 = it - r * C4;
+        const int jj = s * SLAB_COLS + 4 * c4;  // d_out is a multiple of 8: four columns are all in or all out
+        if (jj < p.d_out) {
+          f32x4 v = tot[k] + *reinterpret_cast<const f32x4*>(tile + r * SLAB_COLS + 4 * c4);
+          if (bad) v = f32x4{__builtin_nanf(""), __builtin_nanf(""), __builtin_nanf(""), __builtin_nanf("")};  // a wait ran out: make it loud
+          const size_t o = (size_t)r * p.d_out + jj;
           if (p.out_bf16)
-            static_cast<uint16_t*>(p.out)[(size_t)r * p.d_out + j] = f32_to_bf16_bits(v);
+            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(p.out) + o) =
+                u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
           else
-            static_cast<float*>(p.out)[(size_t)r * p.d_out + j] = v;
+            *reinterpret_cast<f32x4*>(static_cast<float*>(p.out) + o) = v;
         }
       }
     }
