@@ -258,30 +258,48 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
     }
 
     // ---- hand over, or finish the slab (wavefronts of the first half hold the sums) --------
-    // D layout: lane (n, kb) holds rows 4*kb + r of columns 2n, 2n+1.  A partial keeps that
-    // layout, [column group][r][lane] x 8 bytes: every store and load is 512 contiguous bytes.
-    if (part < m - 1) {
-      // The partial and the flag are written with device-scope atomic stores (write-through to
-      // the level all compute units share), so no cache write-back or invalidate is needed --
-      // those walk a whole L2 and cost far more than the few KB moved here.
-      unsigned long long* dst =
-          reinterpret_cast<unsigned long long*>(p.partial + (size_t)b * ST_PARTIAL_FLOATS) + cg * 256 + lane;
-      if (kh == 0) {
+    // D layout: lane (n, kb) holds rows 4*kb + r of columns 2n, 2n+1.  The block's sums are
+    // first laid out in LDS as a [token][column] tile, so that they travel as 16-byte accesses,
+    // one (token, four columns) item per thread: a partial leaves the block in far fewer memory
+    // instructions than the accumulator layout would need, and the cost of the hand-over goes
+    // with the number of these cache-bypassing accesses.  They carry the cache policy of a
+    // device-scope atomic (coherent at the level all compute units share), so no cache
+    // write-back or invalidate is needed -- those walk a whole L2 and cost far more than the
+    // few KB moved here.
+    float* tile = reinterpret_cast<float*>(xs);  // [16][ST_SLAB_COLS]
+    constexpr int kDeviceCoherent = 16;          // "sc1"
+    constexpr int C4 = ST_SLAB_COLS / 4;         // items per token row
+    constexpr int ITEMS_PER_THREAD = (16 * C4 + ST_THREADS - 1) / ST_THREADS;
+    static_assert(16 * ST_SLAB_COLS <= ST_PARTIAL_FLOATS, "a partial holds the whole tile");
+    lds_barrier();  // x and the meeting area of the halves are no longer needed
+    if (kh == 0) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (4 * kb + r < p.T)
-            __hip_atomic_store(dst + r * 64,
-                               __builtin_bit_cast(unsigned long long, f32x2{acc[0][r], acc[1][r]}),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      for (int r = 0; r < 4; ++r)
+        *reinterpret_cast<f32x2*>(tile + (4 * kb + r) * ST_SLAB_COLS + cg * ST_WCOLS + CW * n) =
+            f32x2{acc[0][r], acc[1][r]};
+    }
+    lds_barrier();
+    const int items = p.T * C4;
+    const __amdgpu_buffer_rsrc_t rs_p = st_rsrc(p.partial, (size_t)gridDim.x * ST_PARTIAL_FLOATS * 4);
+    if (part < m - 1) {
+#pragma unroll
+      for (int k = 0; k < ITEMS_PER_THREAD; ++k) {
+        const int it = tid + k * ST_THREADS;
+        if (it < items) {
+          const int r = it / C4, c4 = it - r * C4;
+          const u32x4 v = *reinterpret_cast<const u32x4*>(tile + r * ST_SLAB_COLS + 4 * c4);
+          __builtin_amdgcn_raw_buffer_store_b128(v, rs_p, (r * ST_SLAB_COLS + 4 * c4) * 4,
+                                                 (int)((uint32_t)b * (ST_PARTIAL_FLOATS * 4u)), kDeviceCoherent);
+        }
       }
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // every store of this wavefront has landed
       __syncthreads();
       if (tid == 0)
         __hip_atomic_store(p.flags + b, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     } else {
-      f32x2 tot[4];
+      f32x4 tot[ITEMS_PER_THREAD];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) tot[r] = f32x2{0.0f, 0.0f};
+      for (int k = 0; k < ITEMS_PER_THREAD; ++k) tot[k] = zero4;
       if (m > 1) {
         const int bf = b - (m - 1);  // block of part 0 of this slab
         // one thread per flag, all polling at once
@@ -299,43 +317,45 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
           __hip_atomic_store(p.flags + bf + i, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __syncthreads();
-        // partials in part order, eight blocks' loads in flight at a time
-        if (kh == 0) {
-          for (int i0 = 0; i0 < m - 1; i0 += 8) {
-            f32x2 v[8][4];
+        // partials in part order, PB blocks' loads in flight at a time
+        constexpr int PB = 8 / ITEMS_PER_THREAD;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-              const unsigned long long* src =
-                  reinterpret_cast<const unsigned long long*>(p.partial + (size_t)(bf + i0 + i) * ST_PARTIAL_FLOATS) +
-                  cg * 256 + lane;
+        for (int k = 0; k < ITEMS_PER_THREAD; ++k) {
+          const int it = tid + k * ST_THREADS;
+          if (it < items) {
+            const int r = it / C4, c4 = it - r * C4;
+            for (int i0 = 0; i0 < m - 1; i0 += PB) {
+              u32x4 v[PB];
 #pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                v[i][r] = f32x2{0.0f, 0.0f};
-                if (i0 + i < m - 1 && 4 * kb + r < p.T)
-                  v[i][r] = __builtin_bit_cast(
-                      f32x2, __hip_atomic_load(src + r * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+              for (int i = 0; i < PB; ++i) {
+                v[i] = u32x4{0, 0, 0, 0};
+                if (i0 + i < m - 1)
+                  v[i] = __builtin_amdgcn_raw_buffer_load_b128(
+                      rs_p, (r * ST_SLAB_COLS + 4 * c4) * 4,
+                      (int)((uint32_t)(bf + i0 + i) * (ST_PARTIAL_FLOATS * 4u)), kDeviceCoherent);
               }
+#pragma unroll
+              for (int i = 0; i < PB; ++i) tot[k] += __builtin_bit_cast(f32x4, v[i]);
             }
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-#pragma unroll
-              for (int r = 0; r < 4; ++r) tot[r] += v[i][r];
           }
         }
       }
       const bool bad = (m > 1) && poison != 0;
-      if (kh == 0) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int row = 4 * kb + r;
-          f32x2 v = tot[r] + f32x2{acc[0][r], acc[1][r]};
-          if (bad) v = f32x2{__builtin_nanf(""), __builtin_nanf("")};  // a wait ran out: make it loud
-          if (row < p.T && col_ok) {
+      for (int k = 0; k < ITEMS_PER_THREAD; ++k) {
+        const int it = tid + k * ST_THREADS;
+        if (it < items) {
+          const int r = it / C4, c4 = it - r * C4;
+          const int jj = s * ST_SLAB_COLS + 4 * c4;  // d_out is a multiple of 8: four columns are all in or all out
+          if (jj < p.d_out) {
+            f32x4 v = tot[k] + *reinterpret_cast<const f32x4*>(tile + r * ST_SLAB_COLS + 4 * c4);
+            if (bad) v = f32x4{__builtin_nanf(""), __builtin_nanf(""), __builtin_nanf(""), __builtin_nanf("")};  // a wait ran out: make it loud
+            const size_t o = (size_t)r * p.d_out + jj;
             if (p.out_bf16)
-              *reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(p.out) + (size_t)row * p.d_out + j0) =
-                  pack_bf16x2(v[0], v[1]);
+              *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(p.out) + o) =
+                  u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
             else
-              *reinterpret_cast<f32x2*>(static_cast<float*>(p.out) + (size_t)row * p.d_out + j0) = v;
+              *reinterpret_cast<f32x4*>(static_cast<float*>(p.out) + o) = v;
           }
         }
       }
