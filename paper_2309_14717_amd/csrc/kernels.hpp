@@ -67,7 +67,7 @@ struct SmallTArgs {
   const float* beta;       // [L, d_out]
   const uint32_t* fac16;   // or, instead of both: [L, d_out] words fp16 alpha | fp16 beta << 16
   void* out;               // [T, d_out] fp32 or bf16
-  float* partial;          // [blocks][ST_PARTIAL_FLOATS] fp32, accumulator-register layout: runs that end inside a slab
+  float* partial;          // [blocks][ST_PARTIAL_FLOATS] fp32: each block's [token][slab column] tile
   unsigned long long* flags;  // [blocks]: set to `nonce` once the block's partial is complete
   unsigned long long nonce;   // filled in by the launcher, unique per call
   int out_bf16;
