@@ -26,6 +26,7 @@
 #include "kernels.hpp"
 
 #include <atomic>
+#include <type_traits>
 
 namespace qalora {
 
@@ -78,6 +79,16 @@ struct Chunk4 {
   uint32_t al[4 / SUB], be[4 / SUB];
 };
 
+// f(integral_constant<I>), ..., f(integral_constant<N - 1>): a loop whose index is a constant
+// expression (instruction immediates need one)
+template <int I, int N, typename Fn>
+__device__ __forceinline__ void s4_static_for(Fn&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    s4_static_for<I + 1, N>(f);
+  }
+}
+
 // word << sh for sh >= 0, word >> -sh otherwise (sh is a compile-time constant at every use)
 __device__ __forceinline__ uint32_t shift_to(uint32_t word, int sh) { return sh >= 0 ? word << sh : word >> -sh; }
 
@@ -126,7 +137,13 @@ __global__ __launch_bounds__(S4_THREADS) void smallt4_kernel(const SmallTArgs p)
   asm volatile("v_mov_b32 %0, 0x43004300" : "=v"(kBias));
   const f32x4 zero4 = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
   // MFMA A operand: lane supplies four k values of token (lane & 3)
-  const unsigned char* xs_lane = xs + (lane & 3) * S4_XROW;  // token group t: + 4 t rows
+  // MFMA A operand.  The sixteen 4 x 4 blocks of an instruction all multiply the same tokens,
+  // so only one block has to supply them: with the broadcast controls (CBSZ = 4, ABID = i) the
+  // A rows held by the four lanes of block i serve every block.  Lane l therefore keeps the
+  // 8-row slice l / 4 of token l % 4 -- ONE 16-byte LDS read per chunk and token group holds all
+  // sixteen slices of the chunk across the wavefront, and slice i is used with ABID = i.
+  // (Layout checked on the device: D[lane l][r] = sum_k A(lane 4 ABID + r)[k] B(lane l)[k].)
+  const unsigned char* xs_lane = xs + (lane & 3) * S4_XROW + (lane >> 2) * 16;  // token group t: + 4 t rows
   const unsigned char* gs = xs + NTOK * S4_XROW;             // [chunk][group][NTOK] fp32
 
   const int j = s * SLAB_COLS + cg * S4_WCOLS + lane;  // this lane's column
@@ -172,31 +189,28 @@ __global__ __launch_bounds__(S4_THREADS) void smallt4_kernel(const SmallTArgs p)
 
   // xrel: chunk index relative to the staged piece
   auto compute_chunk = [&](const Chunk4<NBITS, SUB>& ch, int xrel) {
+    u32x4 xa[TG];  // the chunk's x: slice lane / 4 of token lane % 4 (+ 4 t)
 #pragma unroll
-    for (int u = 0; u < NG; ++u) {
+    for (int t = 0; t < TG; ++t)
+      xa[t] = *reinterpret_cast<const u32x4*>(xs_lane + 4 * t * S4_XROW + xrel * 256);
+    s4_static_for<0, NG>([&](auto u_c) {
+      constexpr int u = decltype(u_c)::value;
       f32x4 d[TG];
 #pragma unroll
       for (int t = 0; t < TG; ++t) d[t] = zero4;
+      s4_static_for<0, 4 * SUB>([&](auto i_c) {
+        constexpr int ks = u * 4 * SUB + decltype(i_c)::value;  // 8-row slice of the chunk
+        constexpr int st = ks / 4, k = ks % 4;                  // 32-row step, slice inside it
+        const u32x2 b01 = {pair_bits(ch, st, k, 0), pair_bits(ch, st, k, 1)};
+        const u32x2 b23 = {pair_bits(ch, st, k, 2), pair_bits(ch, st, k, 3)};
 #pragma unroll
-      for (int ss = 0; ss < SUB; ++ss) {
-        const int st = u * SUB + ss;  // 32-row step of the chunk
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {  // rows 32 st + 8 k .. + 7
-          const u32x2 b01 = {pair_bits(ch, st, k, 0), pair_bits(ch, st, k, 1)};
-          const u32x2 b23 = {pair_bits(ch, st, k, 2), pair_bits(ch, st, k, 3)};
-#pragma unroll
-          for (int t = 0; t < TG; ++t) {
-            const u32x4 xa = *reinterpret_cast<const u32x4*>(xs_lane + 4 * t * S4_XROW + xrel * 256 + st * 64 + k * 16);
-            d[t] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4_bits, u32x2{xa.x, xa.y}),
-                                                          __builtin_bit_cast(bf16x4_bits, b01), d[t], 0, 0, 0);
-            d[t] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4_bits, u32x2{xa.z, xa.w}),
-                                                          __builtin_bit_cast(bf16x4_bits, b23), d[t], 0, 0, 0);
-          }
+        for (int t = 0; t < TG; ++t) {
+          d[t] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4_bits, u32x2{xa[t].x, xa[t].y}),
+                                                        __builtin_bit_cast(bf16x4_bits, b01), d[t], 4, ks, 0);
+          d[t] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4_bits, u32x2{xa[t].z, xa[t].w}),
+                                                        __builtin_bit_cast(bf16x4_bits, b23), d[t], 4, ks, 0);
         }
-        // sixteen tokens of INT3: keep the scheduler from hoisting the next step's operand
-        // reads over this one's (the register budget of 128 would not hold them)
-        if constexpr (NBITS == 3 && TG == 4) __builtin_amdgcn_sched_barrier(0);
-      }
+      });
       // sum x code = d * kInvStep - kOff * sum x  (the operand was 128 + code / kInvStep)
       float a0, b0;
       if constexpr (F16) {
@@ -214,7 +228,7 @@ __global__ __launch_bounds__(S4_THREADS) void smallt4_kernel(const SmallTArgs p)
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc[t][r] = __builtin_fmaf(al, d[t][r], __builtin_fmaf(bp, sx[r], acc[t][r]));
       }
-    }
+    });
   };
 
   for (int pa = ca; pa < ce; pa += S4_XCHUNKS) {  // pieces of at most S4_XCHUNKS chunks
