@@ -5,14 +5,20 @@
 namespace qalora {
 
 // Launch shape: slabs x parts with parts chosen to fill the compute units (at least one chunk
-// per part); of the slab widths, the one that occupies most compute units (ties: the narrower
-// slab, which has fewer partials to add).  A partial holds at most ST_PARTIAL_FLOATS values, so
-// more than eight tokens rule out the 1024-column slab.
+// per part).  Of the slab widths, the one with the fewest parts to add among those that keep at
+// least kEnoughBlocks compute units streaming -- HBM is saturated from about four fifths of the
+// chip on, and every further part costs a hand-over (measured at 8192 x 22016, one token:
+// 242 blocks x 11 parts 27.1 us, 215 x 5 26.2 us, 172 x 2 26.2 us; but the vector-bound 2- and
+// 3-bit forms lose on 172) -- otherwise the one that occupies most compute units.  (A third
+// width, 1024 columns with no split inside the block, never won once the hand-over had become
+// cheap, and is no longer built.)
 SmallTPlan smallt4_plan(int d_in, int d_out, int tokens) {
+  constexpr int kEnoughBlocks = 200;
   const int chunks = d_in / 128;
   const int tg = tokens <= 4 ? 1 : (tokens <= 8 ? 2 : 4);
   SmallTPlan best{};
-  for (int halves = 4; halves >= 1; halves /= 2) {
+  bool have = false;
+  for (int halves = 4; halves >= 2; halves /= 2) {
     SmallTPlan pl;
     pl.halves = halves;
     pl.slab_cols = (S4_WAVES / halves) * S4_WCOLS;
@@ -25,7 +31,16 @@ SmallTPlan smallt4_plan(int d_in, int d_out, int tokens) {
     pl.blocks = pl.slabs * m;
     const int busy = pl.blocks < ST_MAX_BLOCKS ? pl.blocks : ST_MAX_BLOCKS;
     const int best_busy = best.blocks < ST_MAX_BLOCKS ? best.blocks : ST_MAX_BLOCKS;
-    if (halves == 4 || busy > best_busy) best = pl;
+    bool better;
+    if (!have) better = true;
+    else if (busy >= kEnoughBlocks && best_busy >= kEnoughBlocks)
+      better = pl.parts < best.parts || (pl.parts == best.parts && busy > best_busy);
+    else
+      better = busy > best_busy;
+    if (better) {
+      best = pl;
+      have = true;
+    }
   }
   return best;
 }

@@ -18,8 +18,8 @@
 // 128 + 16 c; the per-group update undoes the scale and the bias exactly (powers of two).
 //
 // Decomposition, partial sums, flags and their bounded waits are those of the sixteen-token
-// kernel: slabs of 1024, 512 or 256 columns (sixteen, eight or four 64-column wavefronts, the
-// block's chunks split over the remaining factor of wavefronts) x m parts of the 128-row
+// kernel: slabs of 512 or 256 columns (eight or four 64-column wavefronts, the block's chunks
+// split two or four ways over the remaining factor of wavefronts) x m parts of the 128-row
 // chunks; parts 0 .. m-2 publish a partial and a flag, the last part adds them in part order.
 #pragma once
 #include "common.hpp"
@@ -96,7 +96,7 @@ __device__ __forceinline__ uint32_t shift_to(uint32_t word, int sh) { return sh 
 
 // NBITS : code width (4, 3, 2)
 // SUB   : 32-row steps per quantization group (group = 32 * SUB; 1, 2 or 4)
-// KH    : ways a block splits its own chunks (1, 2, 4: slab of 1024, 512, 256 columns)
+// KH    : ways a block splits its own chunks (2, 4: slab of 512, 256 columns)
 // TG    : groups of four tokens (1, 2, 4): every group reuses the code operand a lane has built,
 //         with its own rows of x and its own accumulators
 // F16   : the factors of a (group, column) come as ONE word, fp16 alpha | fp16 beta << 16
@@ -464,7 +464,6 @@ template <int NBITS, int SUB, int TG, bool F16>
 static hipError_t launch_halves4(const SmallTArgs& a, const SmallTPlan& pl, hipStream_t st) {
   if (pl.halves == 4) return launch_sub4<NBITS, SUB, 4, TG, F16>(a, pl.blocks, st);
   if (pl.halves == 2) return launch_sub4<NBITS, SUB, 2, TG, F16>(a, pl.blocks, st);
-  if constexpr (TG <= 2) return launch_sub4<NBITS, SUB, 1, TG, F16>(a, pl.blocks, st);
   return hipErrorInvalidValue;
 }
 

@@ -221,12 +221,12 @@ def test_small_token_forward(gpu_api, tokens, group, d_in, d_out):
 
 
 @pytest.mark.parametrize("tokens,group,d_in,d_out", [
-    (2, 64, 2048, 8704),    # 512-column slabs win: 17 slabs x 15 parts, two-way split inside a block
-    (4, 32, 1536, 22528),   # 1024-column slabs win: 22 slabs x 11 parts, no split inside a block
+    (2, 64, 2048, 8704),    # 256-column slabs: 34 slabs x 7 parts (fewer parts than 17 x 15), four-way split in a block
+    (4, 32, 1536, 22528),   # 512-column slabs: 44 slabs x 5 parts (88 x 2 would leave too many units idle), two-way split
     (1, 128, 1024, 264),    # 256-column slabs, ragged second slab, four-way split inside a block
 ])
 def test_small_token_decode_kernel_variants(gpu_api, tokens, group, d_in, d_out):
-    """T <= 4 runs on the one-column-per-lane kernel; these shapes select each of its slab
+    """T <= 4 runs on the one-column-per-lane kernel; these shapes select both of its slab
     widths and a ragged slab."""
     cfg = synth.LayerConfig("st4", tokens, d_in, d_out, 4, group, 8, 0.5, seed=13)
     L = layer_on_gpu(gpu_api, cfg)
@@ -242,14 +242,14 @@ def test_small_token_decode_kernel_variants(gpu_api, tokens, group, d_in, d_out)
 
 @pytest.mark.parametrize("bits", [2, 3])
 @pytest.mark.parametrize("tokens,group,d_in,d_out", [
-    (1, 32, 1536, 22528),   # 1024-column slabs, no split inside a block
-    (3, 64, 2048, 8704),    # 512-column slabs, two-way split inside a block
-    (4, 128, 1024, 264),    # 256-column slabs, ragged second slab, four-way split
+    (1, 32, 1536, 22528),   # 512-column slabs, two-way split inside a block
+    (3, 64, 2048, 8704),    # 256-column slabs, four-way split inside a block
+    (4, 128, 1024, 264),    # 256-column slabs, ragged second slab
     (2, 32, 4224, 1000),    # 33 chunks: more than one staged piece of x, ragged slab
-    (6, 32, 1536, 22528),   # two groups of four tokens, 1024-column slabs
-    (8, 64, 2048, 8704),    # two full groups, 512-column slabs
+    (6, 32, 1536, 22528),   # two groups of four tokens, 512-column slabs
+    (8, 64, 2048, 8704),    # two full groups, 256-column slabs
     (12, 128, 1024, 264),   # four groups (three in use), 256-column slabs, ragged
-    (16, 32, 4224, 13312),  # four groups, 512-column slabs (the 1024-column one is ruled out), two staged pieces
+    (16, 32, 4224, 13312),  # four groups, two staged pieces
     (9, 64, 2048, 22528),   # four groups, nine tokens
 ])
 def test_small_token_decode_low_bit(gpu_api, bits, tokens, group, d_in, d_out):
