@@ -452,7 +452,8 @@ def main():
                         "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": round(ach / PEAK_HBM_GBS, 4), "avg_kernel_ms": round(k_avg, 5),
                         "event_bracketed_ms_8192x22016": round(k, 5),
-                        "traffic": read_traffic("smallt_c5_pmc.txt") if (args.bits == 4 and not args.factors16) else None}
+                        "traffic": (read_traffic("smallt4_c5_pmc.txt" if T <= 4 else "smallt_c5_pmc.txt")
+                                    if (args.bits == 4 and not args.factors16) else None)}
         else:
             ach = 2.0 * T * cfg_u.d_in * cfg_u.d_out / (k * 1e-3) / 1e12
             roofline = {"bound": "mfma", "kernel": f"gemm_dq_kernel<{args.bits},fwd> (8192x22016)", "achieved": round(ach, 2),
