@@ -6,9 +6,11 @@
 // (Eq. 1 per group pulled out of the inner sum.)  The inner sums run on the matrix cores with
 // EXACT operands: x is bf16 already, and a 4-bit code c becomes the bf16 number 128 + c by
 // OR-ing it into the mantissa of 0x4300 -- no int->float conversion, no rounding.  The extra
-// 128 * sum(x) is folded into beta.  One more MFMA against a matrix of ones yields the group
-// sums of x in exactly the accumulator layout the update needs.  alpha and beta are applied in
-// fp32 once per group, so this path is more accurate than the large-T one.
+// 128 * sum(x) is folded into beta.  alpha is applied in fp32 once per group; the beta term of a
+// chunk, sum_groups beta'[group, col] sum(x)[token, group], is a small product of its own and
+// runs on the fp32 matrix instruction, with the group sums of x taken from a table made when x
+// is staged.  Nothing is rounded before the fp32 accumulation, so this path is more accurate
+// than the large-T one.
 //
 // Decomposition.  The weight is cut into slabs of 256 or 512 output columns, and the 128-row
 // chunks of each slab into m equal parts, m chosen so that slabs x m fills the 256 compute units
@@ -106,9 +108,10 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
   uint32_t kMask, kBias;
   asm volatile("s_mov_b32 %0, 0x000f000f" : "=s"(kMask));
   asm volatile("v_mov_b32 %0, 0x43004300" : "=v"(kBias));
-  const bf16x8 ones = __builtin_bit_cast(bf16x8, u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
   const f32x4 zero4 = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
   const unsigned char* xs_lane = xs + n * ST_XROW + 16 * kb;
+  constexpr int NG = 4 / SUB;  // quantization groups per chunk
+  float* gs = reinterpret_cast<float*>(xs + 16 * ST_XROW);  // [chunk of the piece][group][16 tokens]
 
   {
     const int jw = cg * ST_WCOLS + CW * n;  // column inside the slab
@@ -143,7 +146,26 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
 #pragma unroll
       for (int st = 0; st < 4; ++st)
         xa[st] = *reinterpret_cast<const u32x4*>(xs_lane + xrel * 256 + st * 64);
-      f32x4 d[CW], dsx;
+      // The beta term of the whole chunk, sum_groups beta'[group, col] * sum(x)[token, group], is
+      // itself a small product [16 tokens x 4 groups] x [4 groups x columns]: one fp32 MFMA per
+      // 16 columns.  Its B operand wants lane (n, kb) to supply beta' of group kb for column n --
+      // exactly how the factors were LOADED (lane group kb fetched group kb), so beta needs no
+      // hand-round at all; its A operand is the table of group sums made when x was staged.
+      const float sx = kb < NG ? gs[(xrel * NG + kb) * 16 + n] : 0.0f;
+#pragma unroll
+      for (int q = 0; q < CW; ++q) {
+        float al_own, be_own;  // group kb of the chunk (zero for kb >= NG: the loads aimed outside)
+        if constexpr (F16) {
+          al_own = (float)__builtin_bit_cast(_Float16, (uint16_t)(ch.al[q] & 0xffffu));
+          be_own = (float)__builtin_bit_cast(_Float16, (uint16_t)(ch.al[q] >> 16));
+        } else {
+          al_own = __uint_as_float(ch.al[q]);
+          be_own = __uint_as_float(ch.be[q]);
+        }
+        const float bp = __builtin_fmaf(-128.0f, al_own, be_own);  // codes carry a +128 offset
+        acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(sx, bp, acc[q], 0, 0, 0);
+      }
+      f32x4 d[CW];
 #pragma unroll
       for (int st = 0; st < 4; ++st) {
         const bool first = (st % SUB) == 0, last = (st % SUB) == SUB - 1;
@@ -159,24 +181,14 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
           d[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bv),
                                                          first ? zero4 : d[q], 0, 0, 0);
         }
-        dsx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ones, first ? zero4 : dsx, 0, 0, 0);
         if (last) {
           const int src = (n + 16 * (st / SUB)) * 4;  // the lane group holding this group's factors
 #pragma unroll
           for (int q = 0; q < CW; ++q) {
-            float al, be;
-            if constexpr (F16) {
-              const uint32_t ab = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)ch.al[q]);
-              al = (float)__builtin_bit_cast(_Float16, (uint16_t)(ab & 0xffffu));
-              be = (float)__builtin_bit_cast(_Float16, (uint16_t)(ab >> 16));
-            } else {
-              al = __int_as_float(__builtin_amdgcn_ds_bpermute(src, (int)ch.al[q]));
-              be = __int_as_float(__builtin_amdgcn_ds_bpermute(src, (int)ch.be[q]));
-            }
-            const float bp = __builtin_fmaf(-128.0f, al, be);  // codes carry a +128 offset
+            const uint32_t ab = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)ch.al[q]);
+            const float al = F16 ? (float)__builtin_bit_cast(_Float16, (uint16_t)(ab & 0xffffu)) : __uint_as_float(ab);
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-              acc[q][r] = __builtin_fmaf(al, d[q][r], __builtin_fmaf(bp, dsx[r], acc[q][r]));
+            for (int r = 0; r < 4; ++r) acc[q][r] = __builtin_fmaf(al, d[q][r], acc[q][r]);
           }
         }
       }
@@ -216,6 +228,23 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
       // two chunks of weight loads were issued after the copies: once at most that many are outstanding,
       // the copies have landed
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NLOADS) : "memory");
+      lds_barrier();
+      // group sums of x for the piece, one (group, token) pair per thread, element order
+      for (int idx = tid; idx < (pe - pa) * NG * 16; idx += ST_THREADS) {
+        const int grp = idx >> 4, tok = idx & 15;
+        const unsigned char* src = xs + tok * ST_XROW + grp * (64 * SUB);
+        float sum = 0.0f;
+#pragma unroll
+        for (int q = 0; q < 4 * SUB; ++q) {
+          const u32x4 v = *reinterpret_cast<const u32x4*>(src + 16 * q);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            sum += __uint_as_float(v[e] << 16);
+            sum += __uint_as_float(v[e] & 0xffff0000u);
+          }
+        }
+        gs[grp * 16 + tok] = sum;
+      }
       lds_barrier();
 
       int c = wa;
@@ -388,7 +417,7 @@ SmallTPlan smallt_plan(int d_in, int d_out) {
 
 template <int SUB, int KH, bool F16>
 static hipError_t launch_sub(const SmallTArgs& a, int grid, hipStream_t st) {
-  const size_t smem = 16 * ST_XROW;
+  const size_t smem = 16 * ST_XROW + ST_XCHUNKS * 4 * 16 * sizeof(float);
   static std::atomic<uint64_t> granted{0};  // per instantiation
   if (hipError_t e = grant_dynamic_lds(reinterpret_cast<const void*>(smallt_kernel<SUB, KH, F16>), (int)smem, granted);
       e != hipSuccess)
