@@ -131,9 +131,10 @@ int qalora_pack(const qalora_desc* desc, const uint8_t* codes, void* packed, voi
  * Precision: x is used exactly (each token row is scaled by a power of two and converted to
  * fp16), W~ is rounded to fp16 (11 significant bits) before the matrix cores, accumulation
  * is fp32; the adapter branch is evaluated to about 2^-16 relative.  Without an adapter, for
- * tokens <= 16, group 32/64/128 and d_in a multiple of 128, a streaming kernel takes over
- * (one column per lane for tokens <= 4 and for the 2- and 3-bit codes, a sixteen-token tile
- * for 4-bit codes beyond four tokens) whose operands are exact (only the fp32 accumulation
+ * tokens <= 16 (<= 32 for 4-bit codes), group 32/64/128 and d_in a multiple of 128, a
+ * streaming kernel takes over (one column per lane for tokens <= 4 and for the 2- and 3-bit
+ * codes, a sixteen-token tile -- two of them beyond sixteen tokens -- for 4-bit codes) whose
+ * operands are exact (only the fp32 accumulation
  * order differs from the definition); its cross-block sum waits on flags with a bound -- should a wait ever run out
  * (another kernel holding the compute units for ~0.3 s) the affected outputs are NaN. */
 int qalora_forward(const qalora_desc* desc, int tokens, const void* x, const void* packed,
@@ -172,7 +173,7 @@ int qalora_pack_factors16(const qalora_desc* desc, const float* alpha, const flo
                           void* factors16, void* stream);
 
 /* Adapter-free forward y = x W~ of a layer whose factors are stored as above; otherwise as
- * qalora_forward with A = B = NULL.  Up to 16 tokens (conditions as for qalora_forward) the
+ * qalora_forward with A = B = NULL.  In the few-token regime (conditions as for qalora_forward) the
  * streaming kernel reads the 16-bit factors directly; beyond that they are expanded to fp32
  * in the workspace first.  Workspace: qalora_workspace_bytes(.., QALORA_OP_FORWARD_FACTORS16). */
 int qalora_forward_factors16(const qalora_desc* desc, int tokens, const void* x,

@@ -131,9 +131,9 @@ inline bool addressable(const qalora_desc& d, int tokens) {
 
 // The small-token streaming path covers groups of 32, 64 or 128 rows, input widths that are
 // whole 128-row chunks, and operands its 32-bit buffer offsets can address: every code width
-// up to sixteen tokens.
+// up to sixteen tokens, 4-bit codes up to thirty-two.
 inline bool use_smallt(const qalora_desc& d, int tokens) {
-  if (tokens > 16) return false;
+  if (tokens > (d.bits == 4 ? 32 : 16)) return false;
   if (d.group != 32 && d.group != 64 && d.group != 128) return false;
   if (d.d_in % 128 != 0) return false;
   return plane0_words(d.bits, d.d_in, d.d_out) * 4 < kAddressable;
@@ -142,7 +142,7 @@ inline bool use_smallt(const qalora_desc& d, int tokens) {
 // Workspace of the small-token path: one flag and one [16 x slab] fp32 partial per block.
 inline size_t smallt_workspace(const qalora_desc& d, int tokens) {
   const int blocks = (tokens <= 4 || d.bits != 4) ? smallt4_plan(d.d_in, d.d_out, tokens).blocks
-                                                  : smallt_plan(d.d_in, d.d_out).blocks;
+                                                  : smallt_plan(d.d_in, d.d_out, tokens).blocks;
   return align_up((size_t)ST_MAX_BLOCKS * 8) + align_up((size_t)blocks * ST_PARTIAL_FLOATS * 4);
 }
 

@@ -79,7 +79,7 @@ struct SmallTArgs {
 struct SmallTPlan {
   int halves, slab_cols, slabs, parts, blocks;
 };
-SmallTPlan smallt_plan(int d_in, int d_out);
+SmallTPlan smallt_plan(int d_in, int d_out, int tokens);
 hipError_t launch_smallt(const SmallTArgs& a, hipStream_t st);  // dispatches on T
 // --- smallt4.hip: one column per lane on the 4x4x4 MFMA: T <= 4 for every code width, and
 // INT3 / INT2 up to sixteen tokens -------------------------------------------------------

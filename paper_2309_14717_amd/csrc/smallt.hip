@@ -44,9 +44,10 @@ constexpr int ST_WAVES = 16;
 constexpr int ST_THREADS = 64 * ST_WAVES;
 constexpr int ST_CW = 2;                         // columns per lane
 constexpr int ST_WCOLS = 16 * ST_CW;             // columns per wavefront
-constexpr int ST_XCHUNKS = 32;                   // chunks of x staged in LDS at a time
-constexpr int ST_XROW = ST_XCHUNKS * 256 + 16;   // bytes per token row in LDS (+16: bank spread)
-constexpr int ST_XPIECES = ST_XCHUNKS * 16 / 64; // 1 KB wavefront copies per staged token row
+// tgs = groups of sixteen tokens (1 or 2): chunks of x staged in LDS at a time, and the bytes
+// per token row in LDS (+16: bank spread)
+constexpr int st_xchunks(int tgs) { return 32 / tgs; }
+constexpr int st_xrow(int tgs) { return st_xchunks(tgs) * 256 + 16; }
 constexpr uint32_t ST_SPIN_LIMIT = 1u << 18;     // bounded wait: the kernel always terminates
 constexpr uint32_t kStOob = 0xffff0000u;         // beyond every buffer: the range check returns zero
 constexpr int ST_NT = 2;                         // cache policy "nontemporal": streamed once
@@ -77,11 +78,17 @@ __device__ __forceinline__ void lds_barrier() {
 // KH  : ways a block splits its own chunks (1: sixteen column groups, slab of 512 columns;
 //       2: eight column groups x two halves, slab of 256 columns)
 // F16 : the factors of a (group, column) come as ONE word, fp16 alpha | fp16 beta << 16
-template <int SUB, int KH, bool F16>
+// TGS : groups of sixteen tokens (1, 2): the second group reuses the code operand a lane has
+//       built, with its own rows of x and its own accumulators
+template <int SUB, int KH, bool F16, int TGS>
 __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) {
-  extern __shared__ __align__(16) unsigned char xs[];  // [16][ST_XROW]
+  extern __shared__ __align__(16) unsigned char xs[];  // [NTOK][ST_XROW], then the group sums
   __shared__ int poison;
   constexpr int CW = ST_CW;
+  constexpr int NTOK = 16 * TGS;
+  constexpr int ST_XCHUNKS = st_xchunks(TGS), ST_XROW = st_xrow(TGS);
+  constexpr int ST_XPIECES = ST_XCHUNKS * 16 / 64;  // 1 KB wavefront copies per staged token row
+  constexpr int NBUF = TGS == 1 ? 3 : 2;            // chunk buffers in rotation (registers)
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, kb = lane >> 4;
@@ -111,7 +118,7 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
   const f32x4 zero4 = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
   const unsigned char* xs_lane = xs + n * ST_XROW + 16 * kb;
   constexpr int NG = 4 / SUB;  // quantization groups per chunk
-  float* gs = reinterpret_cast<float*>(xs + 16 * ST_XROW);  // [chunk of the piece][group][16 tokens]
+  float* gs = reinterpret_cast<float*>(xs + NTOK * ST_XROW);  // [chunk of the piece][group][NTOK tokens]
 
   {
     const int jw = cg * ST_WCOLS + CW * n;  // column inside the slab
@@ -136,22 +143,22 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
       if constexpr (!F16) ch.be = __builtin_amdgcn_raw_buffer_load_b64(rs_be, (int)vab, (int)so, ST_NT);
     };
 
-    f32x4 acc[CW];
+    f32x4 acc[TGS][CW];
 #pragma unroll
-    for (int q = 0; q < CW; ++q) acc[q] = zero4;
+    for (int tg = 0; tg < TGS; ++tg)
+#pragma unroll
+      for (int q = 0; q < CW; ++q) acc[tg][q] = zero4;
 
     // xrel: chunk index relative to the staged piece
     auto compute_chunk = [&](const Chunk& ch, int xrel) {
-      u32x4 xa[4];
-#pragma unroll
-      for (int st = 0; st < 4; ++st)
-        xa[st] = *reinterpret_cast<const u32x4*>(xs_lane + xrel * 256 + st * 64);
       // The beta term of the whole chunk, sum_groups beta'[group, col] * sum(x)[token, group], is
       // itself a small product [16 tokens x 4 groups] x [4 groups x columns]: one fp32 MFMA per
       // 16 columns.  Its B operand wants lane (n, kb) to supply beta' of group kb for column n --
       // exactly how the factors were LOADED (lane group kb fetched group kb), so beta needs no
       // hand-round at all; its A operand is the table of group sums made when x was staged.
-      const float sx = kb < NG ? gs[(xrel * NG + kb) * 16 + n] : 0.0f;
+      float sx[TGS];
+#pragma unroll
+      for (int tg = 0; tg < TGS; ++tg) sx[tg] = kb < NG ? gs[(xrel * NG + kb) * NTOK + 16 * tg + n] : 0.0f;
 #pragma unroll
       for (int q = 0; q < CW; ++q) {
         float al_own, be_own;  // group kb of the chunk (zero for kb >= NG: the loads aimed outside)
@@ -163,13 +170,18 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
           be_own = __uint_as_float(ch.be[q]);
         }
         const float bp = __builtin_fmaf(-128.0f, al_own, be_own);  // codes carry a +128 offset
-        acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(sx, bp, acc[q], 0, 0, 0);
+#pragma unroll
+        for (int tg = 0; tg < TGS; ++tg)
+          acc[tg][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(sx[tg], bp, acc[tg][q], 0, 0, 0);
       }
-      f32x4 d[CW];
+      f32x4 d[TGS][CW];
 #pragma unroll
       for (int st = 0; st < 4; ++st) {
         const bool first = (st % SUB) == 0, last = (st % SUB) == SUB - 1;
-        const bf16x8 a = __builtin_bit_cast(bf16x8, xa[st]);
+        u32x4 xa[TGS];  // x of this 32-row step (read here, not a chunk ahead: registers)
+#pragma unroll
+        for (int tg = 0; tg < TGS; ++tg)
+          xa[tg] = *reinterpret_cast<const u32x4*>(xs_lane + tg * 16 * ST_XROW + xrel * 256 + st * 64);
 #pragma unroll
         for (int q = 0; q < CW; ++q) {
           const uint32_t w = ch.w[st][q];
@@ -178,8 +190,11 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
           bv.y = ((w >> 4) & kMask) | kBias;
           bv.z = ((w >> 8) & kMask) | kBias;
           bv.w = ((w >> 12) & kMask) | kBias;
-          d[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bv),
-                                                         first ? zero4 : d[q], 0, 0, 0);
+#pragma unroll
+          for (int tg = 0; tg < TGS; ++tg)
+            d[tg][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa[tg]),
+                                                               __builtin_bit_cast(bf16x8, bv),
+                                                               first ? zero4 : d[tg][q], 0, 0, 0);
         }
         if (last) {
           const int src = (n + 16 * (st / SUB)) * 4;  // the lane group holding this group's factors
@@ -188,7 +203,9 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
             const uint32_t ab = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)ch.al[q]);
             const float al = F16 ? (float)__builtin_bit_cast(_Float16, (uint16_t)(ab & 0xffffu)) : __uint_as_float(ab);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) acc[q][r] = __builtin_fmaf(al, d[q][r], acc[q][r]);
+            for (int tg = 0; tg < TGS; ++tg)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) acc[tg][q][r] = __builtin_fmaf(al, d[tg][q][r], acc[tg][q][r]);
           }
         }
       }
@@ -198,40 +215,49 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
       const int pe = min(ce, pa + ST_XCHUNKS);
       const int np = (pe - pa) * 16;  // 16-byte pieces per token row
       if (pa != ca) lds_barrier();  // every wavefront is done reading the previous piece
-      // x of this piece: wavefront w copies token row w straight into LDS (no registers).  The
-      // copies are issued BEFORE the weight prefetch, so waiting for them leaves it in flight.
-      if (wave < p.T) {
-        const uint32_t xoff = ((uint32_t)wave * p.d_in + (uint32_t)pa * 128) * 2u + lane * 16u;
+      // x of this piece: wavefront w copies token rows w (and w + 16) straight into LDS (no
+      // registers).  The copies are issued BEFORE the weight prefetch, so waiting for them
+      // leaves it in flight.
 #pragma unroll
-        for (int k = 0; k < ST_XPIECES; ++k)
-          if (lane + 64 * k < np)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rs_x, (__attribute__((address_space(3))) void*)(xs + wave * ST_XROW + k * 1024), 16,
-                (int)xoff, k * 1024, 0, 0);
+      for (int tg = 0; tg < TGS; ++tg) {
+        const int row = wave + 16 * tg;
+        if (row < p.T) {
+          const uint32_t xoff = ((uint32_t)row * p.d_in + (uint32_t)pa * 128) * 2u + lane * 16u;
+#pragma unroll
+          for (int k = 0; k < ST_XPIECES; ++k)
+            if (lane + 64 * k < np)
+              __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                  rs_x, (__attribute__((address_space(3))) void*)(xs + row * ST_XROW + k * 1024), 16,
+                  (int)xoff, k * 1024, 0, 0);
+        }
       }
       // this wavefront's share of the piece: the first or the second half of its chunks
       const int pm = KH == 2 ? pa + (pe - pa + 1) / 2 : pe;
       const int wa = kh ? pm : pa, we = kh ? pe : pm;
-      Chunk b0, b1, b2;
+      Chunk b0, b1, b2;  // b2 unused with two buffers
       load_chunk(b0, wa, we);
-      load_chunk(b1, wa + 1, we);
+      if constexpr (NBUF == 3) load_chunk(b1, wa + 1, we);
       __builtin_amdgcn_sched_barrier(0);
       if (pa == ca) {
         // first piece: with the loads above already in flight, clear what must start at zero --
         // the token rows that do not exist (they stay zero for the whole kernel)
         if (tid == 0) poison = 0;
-        if (wave >= p.T) {
-          for (int o = lane; o < ST_XROW / 16; o += 64)
-            *reinterpret_cast<u32x4*>(xs + wave * ST_XROW + o * 16) = u32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int tg = 0; tg < TGS; ++tg) {
+          const int row = wave + 16 * tg;
+          if (row >= p.T) {
+            for (int o = lane; o < ST_XROW / 16; o += 64)
+              *reinterpret_cast<u32x4*>(xs + row * ST_XROW + o * 16) = u32x4{0, 0, 0, 0};
+          }
         }
       }
       // two chunks of weight loads were issued after the copies: once at most that many are outstanding,
       // the copies have landed
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NLOADS) : "memory");
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NBUF - 1) * NLOADS) : "memory");
       lds_barrier();
       // group sums of x for the piece, one (group, token) pair per thread, element order
-      for (int idx = tid; idx < (pe - pa) * NG * 16; idx += ST_THREADS) {
-        const int grp = idx >> 4, tok = idx & 15;
+      for (int idx = tid; idx < (pe - pa) * NG * NTOK; idx += ST_THREADS) {
+        const int grp = idx / NTOK, tok = idx % NTOK;
         const unsigned char* src = xs + tok * ST_XROW + grp * (64 * SUB);
         float sum = 0.0f;
 #pragma unroll
@@ -243,46 +269,65 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
             sum += __uint_as_float(v[e] & 0xffff0000u);
           }
         }
-        gs[grp * 16 + tok] = sum;
+        gs[grp * NTOK + tok] = sum;
       }
       lds_barrier();
 
       int c = wa;
+      if constexpr (NBUF == 3) {
 #pragma nounroll
-      for (; c + 2 < we; c += 3) {
-        load_chunk(b2, c + 2, we);
-        __builtin_amdgcn_sched_barrier(0);
-        compute_chunk(b0, c - pa);
-        __builtin_amdgcn_sched_barrier(0);
-        load_chunk(b0, c + 3, we);
-        __builtin_amdgcn_sched_barrier(0);
-        compute_chunk(b1, c + 1 - pa);
-        __builtin_amdgcn_sched_barrier(0);
-        load_chunk(b1, c + 4, we);
-        __builtin_amdgcn_sched_barrier(0);
-        compute_chunk(b2, c + 2 - pa);
-        __builtin_amdgcn_sched_barrier(0);
+        for (; c + 2 < we; c += 3) {
+          load_chunk(b2, c + 2, we);
+          __builtin_amdgcn_sched_barrier(0);
+          compute_chunk(b0, c - pa);
+          __builtin_amdgcn_sched_barrier(0);
+          load_chunk(b0, c + 3, we);
+          __builtin_amdgcn_sched_barrier(0);
+          compute_chunk(b1, c + 1 - pa);
+          __builtin_amdgcn_sched_barrier(0);
+          load_chunk(b1, c + 4, we);
+          __builtin_amdgcn_sched_barrier(0);
+          compute_chunk(b2, c + 2 - pa);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (c < we) compute_chunk(b0, c - pa);
+        if (c + 1 < we) compute_chunk(b1, c + 1 - pa);
+      } else {
+#pragma nounroll
+        for (; c + 1 < we; c += 2) {
+          load_chunk(b1, c + 1, we);
+          __builtin_amdgcn_sched_barrier(0);
+          compute_chunk(b0, c - pa);
+          __builtin_amdgcn_sched_barrier(0);
+          load_chunk(b0, c + 2, we);
+          __builtin_amdgcn_sched_barrier(0);
+          compute_chunk(b1, c + 1 - pa);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (c < we) compute_chunk(b0, c - pa);
       }
-      if (c < we) compute_chunk(b0, c - pa);
-      if (c + 1 < we) compute_chunk(b1, c + 1 - pa);
     }
 
     // ---- the two halves of the block meet in LDS (fixed order: first half + second half) ----
     if constexpr (KH == 2) {
-      float* red = reinterpret_cast<float*>(xs);  // [8 column groups][8 registers][64 lanes]
+      float* red = reinterpret_cast<float*>(xs);  // [8 column groups][8 TGS registers][64 lanes]
       lds_barrier();                              // x is no longer needed
       if (kh == 1) {
 #pragma unroll
-        for (int q = 0; q < CW; ++q)
+        for (int tg = 0; tg < TGS; ++tg)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) red[(cg * 8 + 4 * q + r) * 64 + lane] = acc[q][r];
+          for (int q = 0; q < CW; ++q)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) red[((cg * TGS + tg) * 8 + 4 * q + r) * 64 + lane] = acc[tg][q][r];
       }
       lds_barrier();
       if (kh == 0) {
 #pragma unroll
-        for (int q = 0; q < CW; ++q)
+        for (int tg = 0; tg < TGS; ++tg)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) acc[q][r] += red[(cg * 8 + 4 * q + r) * 64 + lane];
+          for (int q = 0; q < CW; ++q)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[tg][q][r] += red[((cg * TGS + tg) * 8 + 4 * q + r) * 64 + lane];
       }
     }
 
@@ -295,17 +340,19 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
     // device-scope atomic (coherent at the level all compute units share), so no cache
     // write-back or invalidate is needed -- those walk a whole L2 and cost far more than the
     // few KB moved here.
-    float* tile = reinterpret_cast<float*>(xs);  // [16][ST_SLAB_COLS]
+    float* tile = reinterpret_cast<float*>(xs);  // [NTOK][ST_SLAB_COLS]
     constexpr int kDeviceCoherent = 16;          // "sc1"
     constexpr int C4 = ST_SLAB_COLS / 4;         // items per token row
-    constexpr int ITEMS_PER_THREAD = (16 * C4 + ST_THREADS - 1) / ST_THREADS;
-    static_assert(16 * ST_SLAB_COLS <= ST_PARTIAL_FLOATS, "a partial holds the whole tile");
+    constexpr int ITEMS_PER_THREAD = (NTOK * C4 + ST_THREADS - 1) / ST_THREADS;
+    static_assert(NTOK * ST_SLAB_COLS <= ST_PARTIAL_FLOATS, "a partial holds the whole tile");
     lds_barrier();  // x and the meeting area of the halves are no longer needed
     if (kh == 0) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-        *reinterpret_cast<f32x2*>(tile + (4 * kb + r) * ST_SLAB_COLS + cg * ST_WCOLS + CW * n) =
-            f32x2{acc[0][r], acc[1][r]};
+      for (int tg = 0; tg < TGS; ++tg)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          *reinterpret_cast<f32x2*>(tile + (16 * tg + 4 * kb + r) * ST_SLAB_COLS + cg * ST_WCOLS + CW * n) =
+              f32x2{acc[tg][0][r], acc[tg][1][r]};
     }
     lds_barrier();
     const int items = p.T * C4;
@@ -393,12 +440,17 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
 }
 
 // Launch shape: slabs x parts with parts chosen to fill the compute units (at least one chunk
-// per part); of the two slab widths, the one that occupies more compute units (ties: the
-// narrower slab, which has fewer partials to add).
-SmallTPlan smallt_plan(int d_in, int d_out) {
+// per part).  Of the two slab widths, the one with fewer parts to add if both keep at least
+// kEnoughBlocks compute units streaming (HBM is saturated from about four fifths of the chip
+// on, and every further part costs a hand-over: 4096 x 11008 at sixteen tokens takes 18.6 us
+// as 22 slabs x 11 parts and 14.8 us as 43 x 5), otherwise the one that occupies more units.
+SmallTPlan smallt_plan(int d_in, int d_out, int tokens) {
+  constexpr int kEnoughBlocks = 200;
   const int chunks = d_in / 128;
   SmallTPlan best{};
-  for (int halves = 2; halves >= 1; --halves) {
+  bool have = false;
+  // more than sixteen tokens: a partial holds the [32 x 256] tile of the narrower slab only
+  for (int halves = 2; halves >= (tokens > 16 ? 2 : 1); --halves) {
     SmallTPlan pl;
     pl.halves = halves;
     pl.slab_cols = (ST_WAVES / halves) * ST_WCOLS;
@@ -410,20 +462,37 @@ SmallTPlan smallt_plan(int d_in, int d_out) {
     pl.blocks = pl.slabs * m;
     const int busy = pl.blocks < ST_MAX_BLOCKS ? pl.blocks : ST_MAX_BLOCKS;
     const int best_busy = best.blocks < ST_MAX_BLOCKS ? best.blocks : ST_MAX_BLOCKS;
-    if (halves == 2 || busy > best_busy) best = pl;
+    bool better;
+    if (!have) better = true;
+    else if (busy >= kEnoughBlocks && best_busy >= kEnoughBlocks)
+      better = pl.parts < best.parts || (pl.parts == best.parts && busy > best_busy);
+    else
+      better = busy > best_busy;
+    if (better) {
+      best = pl;
+      have = true;
+    }
   }
   return best;
 }
 
-template <int SUB, int KH, bool F16>
-static hipError_t launch_sub(const SmallTArgs& a, int grid, hipStream_t st) {
-  const size_t smem = 16 * ST_XROW + ST_XCHUNKS * 4 * 16 * sizeof(float);
+template <int SUB, int KH, bool F16, int TGS>
+static hipError_t launch_tgs(const SmallTArgs& a, int grid, hipStream_t st) {
+  constexpr size_t smem = 16 * TGS * st_xrow(TGS) + st_xchunks(TGS) * 4 * 16 * TGS * sizeof(float);
   static std::atomic<uint64_t> granted{0};  // per instantiation
-  if (hipError_t e = grant_dynamic_lds(reinterpret_cast<const void*>(smallt_kernel<SUB, KH, F16>), (int)smem, granted);
+  if (hipError_t e = grant_dynamic_lds(reinterpret_cast<const void*>(smallt_kernel<SUB, KH, F16, TGS>), (int)smem, granted);
       e != hipSuccess)
     return e;
-  smallt_kernel<SUB, KH, F16><<<grid, ST_THREADS, smem, st>>>(a);
+  smallt_kernel<SUB, KH, F16, TGS><<<grid, ST_THREADS, smem, st>>>(a);
   return hipGetLastError();
+}
+
+// seventeen to thirty-two tokens take the two-group form, which exists for the narrower slab
+template <int SUB, int KH, bool F16>
+static hipError_t launch_sub(const SmallTArgs& a, int grid, hipStream_t st) {
+  if (a.T <= 16) return launch_tgs<SUB, KH, F16, 1>(a, grid, st);
+  if constexpr (KH == 2) return launch_tgs<SUB, KH, F16, 2>(a, grid, st);
+  return hipErrorInvalidValue;
 }
 
 hipError_t launch_smallt(const SmallTArgs& args, hipStream_t st) {
@@ -433,7 +502,7 @@ hipError_t launch_smallt(const SmallTArgs& args, hipStream_t st) {
   unsigned long long z = (calls.fetch_add(1) + 1) * 0x9e3779b97f4a7c15ull;
   z ^= z >> 31;  // both steps are bijections that fix zero, and the count is never zero
   a.nonce = z;
-  const SmallTPlan pl = smallt_plan(a.d_in, a.d_out);
+  const SmallTPlan pl = smallt_plan(a.d_in, a.d_out, a.T);
   const int sub = a.group / 32;
   auto run = [&]() -> hipError_t {
     // decode shapes and the narrower codes: the one-column-per-lane kernel

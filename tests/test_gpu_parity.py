@@ -269,15 +269,16 @@ def test_small_token_decode_low_bit(gpu_api, bits, tokens, group, d_in, d_out):
 
 
 def test_small_token_wide_slab_path(gpu_api):
-    """A shape for which the 512-column slabs fill more compute units than the 256-column ones
-    (13312 columns: 26 slabs x 9 parts against 52 x 4), so the other kernel variant and a
-    nine-way cross-block sum are exercised; bf16 output equals the rounded fp32 output."""
-    cfg = synth.LayerConfig("stw", 5, 1152, 13312, 4, 64, 8, 0.5, seed=12)
+    """A shape for which only the 512-column slabs keep enough compute units busy (16640
+    columns: 33 slabs x 7 parts = 231 blocks against 65 x 3 = 195), so the sixteen-token
+    kernel's other variant and a seven-way cross-block sum are exercised; bf16 output equals
+    the rounded fp32 output."""
+    cfg = synth.LayerConfig("stw", 5, 1152, 16640, 4, 64, 8, 0.5, seed=12)
     L = layer_on_gpu(gpu_api, cfg)
     y = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"])
     ref = oracle.forward(L["np"]["x"], L["codes"], L["alpha"], L["beta"], cfg.group)
     err = rel_err(y.cpu().numpy(), ref)
-    record("small_token wide slab T=5 g=64 1152x13312", y=err)
+    record("small_token wide slab T=5 g=64 1152x16640", y=err)
     assert err <= 1e-5
     yb = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"], out_dtype=torch.bfloat16)
     assert torch.equal(yb, y.to(torch.bfloat16))
@@ -362,3 +363,28 @@ def test_forward_with_16bit_factors_off_the_streaming_shapes(gpu_api):
     y = gpu_api.forward_factors16(L["desc"], L["x"], L["packed"], fac)
     assert rel_err(y.cpu().numpy(), ref) <= TOL
     assert torch.equal(y, gpu_api.forward(L["desc"], L["x"], L["packed"], dev(al), dev(be)))
+
+
+@pytest.mark.parametrize("tokens,group,d_in,d_out", [
+    (17, 32, 1536, 2304),    # one token into the second group of sixteen
+    (24, 64, 2048, 8704),    # 34 slabs of 256 columns x 7 parts
+    (32, 128, 4224, 1000),   # both groups full, two staged pieces of x (16 chunks each), ragged slab
+    (31, 32, 1024, 264),
+])
+def test_small_token_up_to_thirty_two(gpu_api, tokens, group, d_in, d_out):
+    """Seventeen to thirty-two tokens of an INT4 layer stay on the streaming kernel: two groups
+    of sixteen tokens share the code operand a lane has built."""
+    cfg = synth.LayerConfig("st32", tokens, d_in, d_out, 4, group, 8, 0.5, seed=70 + tokens)
+    L = layer_on_gpu(gpu_api, cfg)
+    y = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"])
+    ref = oracle.forward(L["np"]["x"], L["codes"], L["alpha"], L["beta"], cfg.group)
+    err = rel_err(y.cpu().numpy(), ref)
+    record(f"small_token T={tokens} g={group} {d_in}x{d_out}", y=err)
+    assert err <= 1e-5
+    assert torch.equal(y, gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"]))
+    yb = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"], out_dtype=torch.bfloat16)
+    assert torch.equal(yb, y.to(torch.bfloat16))
+    fac = gpu_api.pack_factors16(L["desc"], L["g_alpha"], L["g_beta"])
+    a16, b16 = (L[k].astype(np.float16).astype(np.float32) for k in ("alpha", "beta"))
+    y16 = gpu_api.forward_factors16(L["desc"], L["x"], L["packed"], fac)
+    assert rel_err(y16.cpu().numpy(), oracle.forward(L["np"]["x"], L["codes"], a16, b16, cfg.group)) <= 1e-5
