@@ -21,8 +21,8 @@ def fresh(like, seed, scale=1.0):
     return (torch.randn(like.shape, generator=g) * scale).to(like.dtype).cuda()
 
 
-# the decode kernel, the sixteen-token kernel, and the decode kernel's several-token-group form
-@pytest.mark.parametrize("tokens,bits", [(4, 4), (9, 4), (3, 2), (11, 3)])
+# the decode kernel, the sixteen-token kernel (one and two groups of sixteen), and the decode kernel's several-token-group form
+@pytest.mark.parametrize("tokens,bits", [(4, 4), (9, 4), (24, 4), (3, 2), (11, 3)])
 def test_graph_replay_small_token_forward(gpu_api, tokens, bits):
     # 2 slabs x 16 parts: fifteen flags per slab are raised and consumed in every launch
     cfg = synth.LayerConfig("graph_st", tokens, 2048, 512, bits, 32, 8, 0.5, seed=31)
