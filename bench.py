@@ -439,7 +439,7 @@ def main():
         by_u = forward_bytes(cfg_u, T, yu.element_size(), fb)
         by_step = by_u + forward_bytes(cfg_d, T, yd.element_size(), fb)
         k = kms[0]
-        if T <= 16:
+        if T <= (32 if args.bits == 4 else 16):  # the streaming kernels' range
             # A step is two launches of the streaming kernel with (to 0.1 %) the same algorithmic
             # bytes, back to back on one stream, so the average launch duration over the timed
             # region is half the step.  (An event pair around a single 30 us launch reads 3-5 us
@@ -482,7 +482,7 @@ def main():
     out = {
         "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f16" if args.workload != "c5" or args.tokens > 16 else "bf16",
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16" if args.workload != "c5" or args.tokens > (32 if args.bits == 4 else 16) else "bf16",
         "data": "synthetic",
         "config": {"workload": workload, "flops_per_step": total_flops,
                    "frac_of_mfma_peak": round(value / PEAK_MFMA_TFLOPS, 4)},
