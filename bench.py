@@ -453,7 +453,7 @@ def main():
                         "frac": round(ach / PEAK_HBM_GBS, 4), "avg_kernel_ms": round(k_avg, 5),
                         "event_bracketed_ms_8192x22016": round(k, 5),
                         "traffic": (read_traffic("smallt4_c5_pmc.txt" if T <= 4 else "smallt_c5_pmc.txt")
-                                    if (args.bits == 4 and not args.factors16) else None)}
+                                    if (args.bits == 4 and not args.factors16 and T <= 16) else None)}
         else:
             ach = 2.0 * T * cfg_u.d_in * cfg_u.d_out / (k * 1e-3) / 1e12
             roofline = {"bound": "mfma", "kernel": f"gemm_dq_kernel<{args.bits},fwd> (8192x22016)", "achieved": round(ach, 2),
