@@ -143,7 +143,8 @@ inline bool use_smallt(const qalora_desc& d, int tokens) {
 inline size_t smallt_workspace(const qalora_desc& d, int tokens) {
   const int blocks = (tokens <= 4 || d.bits != 4) ? smallt4_plan(d.d_in, d.d_out, tokens).blocks
                                                   : smallt_plan(d.d_in, d.d_out, tokens).blocks;
-  return align_up((size_t)ST_MAX_BLOCKS * 8) + align_up((size_t)blocks * ST_PARTIAL_FLOATS * 4);
+  const size_t per_block = (size_t)(tokens > 16 ? 2 : 1) * ST_PARTIAL_FLOATS;  // two groups of sixteen tokens
+  return align_up((size_t)ST_MAX_BLOCKS * 8) + align_up((size_t)blocks * per_block * 4);
 }
 
 }  // namespace

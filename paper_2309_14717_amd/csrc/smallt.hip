@@ -344,7 +344,8 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
     constexpr int kDeviceCoherent = 16;          // "sc1"
     constexpr int C4 = ST_SLAB_COLS / 4;         // items per token row
     constexpr int ITEMS_PER_THREAD = (NTOK * C4 + ST_THREADS - 1) / ST_THREADS;
-    static_assert(NTOK * ST_SLAB_COLS <= ST_PARTIAL_FLOATS, "a partial holds the whole tile");
+    constexpr int PART_FLOATS = TGS * ST_PARTIAL_FLOATS;  // a block's partial: the [NTOK][512] tile at most
+    static_assert(NTOK * ST_SLAB_COLS <= PART_FLOATS, "a partial holds the whole tile");
     lds_barrier();  // x and the meeting area of the halves are no longer needed
     if (kh == 0) {
 #pragma unroll
@@ -356,7 +357,7 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
     }
     lds_barrier();
     const int items = p.T * C4;
-    const __amdgpu_buffer_rsrc_t rs_p = st_rsrc(p.partial, (size_t)gridDim.x * ST_PARTIAL_FLOATS * 4);
+    const __amdgpu_buffer_rsrc_t rs_p = st_rsrc(p.partial, (size_t)gridDim.x * PART_FLOATS * 4);
     if (part < m - 1) {
 #pragma unroll
       for (int k = 0; k < ITEMS_PER_THREAD; ++k) {
@@ -365,7 +366,7 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
           const int r = it / C4, c4 = it - r * C4;
           const u32x4 v = *reinterpret_cast<const u32x4*>(tile + r * ST_SLAB_COLS + 4 * c4);
           __builtin_amdgcn_raw_buffer_store_b128(v, rs_p, (r * ST_SLAB_COLS + 4 * c4) * 4,
-                                                 (int)((uint32_t)b * (ST_PARTIAL_FLOATS * 4u)), kDeviceCoherent);
+                                                 (int)((uint32_t)b * (PART_FLOATS * 4u)), kDeviceCoherent);
         }
       }
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // every store of this wavefront has landed
@@ -408,7 +409,7 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
                 if (i0 + i < m - 1)
                   v[i] = __builtin_amdgcn_raw_buffer_load_b128(
                       rs_p, (r * ST_SLAB_COLS + 4 * c4) * 4,
-                      (int)((uint32_t)(bf + i0 + i) * (ST_PARTIAL_FLOATS * 4u)), kDeviceCoherent);
+                      (int)((uint32_t)(bf + i0 + i) * (PART_FLOATS * 4u)), kDeviceCoherent);
               }
 #pragma unroll
               for (int i = 0; i < PB; ++i) tot[k] += __builtin_bit_cast(f32x4, v[i]);
@@ -449,8 +450,8 @@ SmallTPlan smallt_plan(int d_in, int d_out, int tokens) {
   const int chunks = d_in / 128;
   SmallTPlan best{};
   bool have = false;
-  // more than sixteen tokens: a partial holds the [32 x 256] tile of the narrower slab only
-  for (int halves = 2; halves >= (tokens > 16 ? 2 : 1); --halves) {
+  (void)tokens;  // both widths serve every token count (a partial of the two-group form is twice the size)
+  for (int halves = 2; halves >= 1; --halves) {
     SmallTPlan pl;
     pl.halves = halves;
     pl.slab_cols = (ST_WAVES / halves) * ST_WCOLS;
@@ -487,12 +488,11 @@ static hipError_t launch_tgs(const SmallTArgs& a, int grid, hipStream_t st) {
   return hipGetLastError();
 }
 
-// seventeen to thirty-two tokens take the two-group form, which exists for the narrower slab
+// seventeen to thirty-two tokens take the two-group form
 template <int SUB, int KH, bool F16>
 static hipError_t launch_sub(const SmallTArgs& a, int grid, hipStream_t st) {
   if (a.T <= 16) return launch_tgs<SUB, KH, F16, 1>(a, grid, st);
-  if constexpr (KH == 2) return launch_tgs<SUB, KH, F16, 2>(a, grid, st);
-  return hipErrorInvalidValue;
+  return launch_tgs<SUB, KH, F16, 2>(a, grid, st);
 }
 
 hipError_t launch_smallt(const SmallTArgs& args, hipStream_t st) {
