@@ -106,7 +106,7 @@ size_t qalora_workspace_bytes(const qalora_desc* desc, int tokens, int op);
  * of each column (Sec. 3.3).  In fp32, in this order:
  *   beta = min, alpha = (max - min) / (2^N - 1)   (one subtract, one IEEE divide),
  *   code = clamp(rint((w - beta) / alpha), 0, 2^N - 1)   (ties to even);
- *   a group whose alpha is not > 0 (constant group) gets alpha = 1 and codes 0.
+ *   a group whose alpha is not > 0 (constant group) gets alpha = 2^-60 and codes 0.
  * in : W      fp32 [d_in, d_out]
  * out: packed  qalora_packed_bytes(desc) bytes
  *      alpha, beta  fp32 [L, d_out]

@@ -64,7 +64,10 @@ static double round_to_bf16(double v) {
 /*   mn, mx  : running strict-compare min / max down the group's rows         */
 /*   beta    = mn                                                             */
 /*   alpha   = (mx - mn) / (2^N - 1)      one subtract, one IEEE divide       */
-/*   alpha not > 0 (constant group, or underflow): alpha = 1, all codes 0     */
+/*   alpha not > 0 (constant group, or underflow): alpha = 2^-60, all codes 0 */
+/*     (Eq. 1 gives alpha = 0 and 0/0 codes there; any alpha > 0 with codes 0  */
+/*     dequantises to beta exactly, and one far below every real step keeps   */
+/*     alpha * code negligible however the product is later evaluated)        */
 /*   code    = clamp(rint((w - beta) / alpha), 0, 2^N - 1)   ties to even     */
 /* Returns 0, or -1 on bad arguments.                                         */
 /* ------------------------------------------------------------------------- */
@@ -89,7 +92,7 @@ int qo_quantize(const float* W, int d_in, int d_out, int bits, int g,
       const float range = mx - mn;
       float a = range / levels;
       const int degenerate = !(a > 0.0f);
-      if (degenerate) a = 1.0f;
+      if (degenerate) a = 0x1p-60f;
       alpha[(size_t)l * d_out + j] = a;
       beta[(size_t)l * d_out + j] = mn;
       for (int i = i0; i < i0 + g; ++i) {

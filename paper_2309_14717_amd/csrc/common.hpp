@@ -137,9 +137,10 @@ __device__ __forceinline__ uint32_t patch_code(uint32_t w0s, uint32_t w1s, int p
   }
 }
 
-// The codes of rows 2m and 2m+1 (m = 0..3) of the patch, for one column, as an exact pair
-// of fp16 integers (low half = even row).  0x6400 is fp16 1024.0, whose mantissa unit is 1,
-// so (0x6400 | c) - 1024 == c for c < 1024 without any int->float conversion.
+// The codes of rows 2m and 2m+1 (m = 0..3) of the patch, for one column, less the mid code
+// 2^(N-1), as an exact pair of fp16 integers (low half = even row).  0x6400 is fp16 1024.0, whose
+// mantissa unit is 1, so (0x6400 | c) - (1024 + mid) == c - mid for c < 1024 without any
+// int->float conversion.  The caller adds mid * alpha to beta (code_center<NBITS>()).
 // `mask` and `magic` are the constants (2^LB - 1) * 0x00010001 and 0x64006400 handed in by the
 // caller: a kernel that keeps them in registers gets "(w >> k) & mask | magic" as one shift and
 // one v_and_or_b32 (a VOP3 instruction cannot carry a 32-bit literal on gfx9-class targets).
@@ -154,8 +155,13 @@ __device__ __forceinline__ f16x2 patch_code_pair_f16(uint32_t w0s, uint32_t w1s,
   } else {
     u = ((w0s >> (LB * m)) & mask) | magic;
   }
-  const f16x2 k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
-  return __builtin_bit_cast(f16x2, u) - k1024;
+  constexpr float kOff = 1024.0f + float(1 << (NBITS - 1));
+  const f16x2 off = {(_Float16)kOff, (_Float16)kOff};
+  return __builtin_bit_cast(f16x2, u) - off;
+}
+template <int NBITS>
+__host__ __device__ constexpr float code_center() {
+  return float(1 << (NBITS - 1));
 }
 template <int NBITS>
 __host__ __device__ constexpr uint32_t patch_code_mask() {

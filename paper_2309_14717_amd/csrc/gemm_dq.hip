@@ -389,9 +389,14 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     }
   };
 
-  // alpha * code + beta for the row pair m of one column, as a packed fp16 pair
+  // The fp16 factors of one (group, column): W~ = alpha * (c - mid) + (beta + mid * alpha) with
+  // mid = 2^(N-1).  Written around the mid code, the constant term is the group's mid value
+  // instead of its minimum: it is several times smaller for a group that straddles zero, and so
+  // is its fp16 rounding error, the one error of this path that is the same for every row of a
+  // group and therefore adds up along K instead of averaging out.
   auto ab_pair = [&](uint32_t a_bits, uint32_t b_bits) {
-    const f32x2 abf = {__uint_as_float(a_bits), __uint_as_float(b_bits)};
+    const float al_f = __uint_as_float(a_bits);
+    const f32x2 abf = {al_f, fmaf(code_center<NBITS>(), al_f, __uint_as_float(b_bits))};
     return __builtin_convertvector(abf, f16x2);
   };
   // extraction constants held in registers (see patch_code_pair_f16)

@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__
     const float range = __fsub_rn(mx[c], mn[c]);
     a[c] = __fdiv_rn(range, (float)QMAX);
     degenerate[c] = !(a[c] > 0.0f);
-    if (degenerate[c]) a[c] = 1.0f;
+    if (degenerate[c]) a[c] = 0x1p-60f;
   }
   *reinterpret_cast<f32x4*>(alpha + (size_t)l * d_out + j) = a;
   *reinterpret_cast<f32x4*>(beta + (size_t)l * d_out + j) = mn;

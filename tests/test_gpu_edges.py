@@ -53,6 +53,46 @@ def test_one_group_per_column(gpu_api, bits):
     assert max(errs.values()) <= TOL
 
 
+def test_one_short_group_per_column(gpu_api):
+    """K = 64 in a single group: the roundings of a column's one (alpha, beta) pair act on all of
+    its terms alike.  The matrix path evaluates alpha * (c - mid) + (beta + mid * alpha), whose
+    constant term is small, and stays well inside the bar (about 4e-4 here)."""
+    cfg = cfg_of(bits=4, d_in=64, group=64, d_out=776, tokens=257, rank=64, s=1.0, seed=32136)
+    L, got, ref = run_both(gpu_api, cfg)
+    errs = {k: rel_err(got[k], ref[k]) for k in got}
+    bm = gpu_api.merge(L["desc"], L["g_beta"], L["A"], L["B"])
+    ym = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], bm)
+    errs["y_merged"] = rel_err(ym.cpu().numpy(), ref["y"])
+    record("edge L=1 K=64", **errs)
+    assert max(errs.values()) <= 0.5 * TOL
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_constant_groups_through_matrix_path(gpu_api, bits):
+    """Groups whose weights are all equal (codes 0, the placeholder step) among ordinary ones.
+    One-hot token rows read W~ back row by row: a constant group must come back as its value to
+    fp16 rounding (2^-11 relative), whatever form the kernel evaluates alpha * c + beta in."""
+    cfg = cfg_of(bits=bits, d_in=256, group=32, d_out=72, tokens=256, rank=0)
+    d = synth.make_inputs(cfg)
+    vals = np.array([0.0237, -0.4161, 3.3e-3, 117.3, -0.0, 1.0], np.float32)
+    for n, v in enumerate(vals):
+        d["W"][32 * n:32 * (n + 1), 5 * n + 1] = v
+    d["x"] = np.eye(256, dtype=np.float32)
+    L = layer_on_gpu(gpu_api, cfg, inputs=d)
+    assert all(L["alpha"][n, 5 * n + 1] == np.float32(2.0 ** -60) for n in range(len(vals)))
+    y = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"]).cpu().numpy()
+    dx = gpu_api.backward(L["desc"], L["x"][:, :72].contiguous(), L["x"], L["packed"], L["g_alpha"],
+                          L["g_beta"])[0].cpu().numpy()
+    Wt = oracle.dequantize(L["codes"], L["alpha"], L["beta"], cfg.group)
+    assert rel_err(y, Wt) <= TOL
+    for n, v in enumerate(vals):
+        got = y[32 * n:32 * (n + 1), 5 * n + 1].astype(np.float64)
+        assert np.abs(got - float(v)).max() <= 2.0 ** -11 * abs(float(v)), (n, v, got[:4])
+        # dy = the first 72 one-hot rows: dx[j, :] = W~[:, j], the same weights through the backward
+        got_b = dx[5 * n + 1, 32 * n:32 * (n + 1)].astype(np.float64)
+        assert np.abs(got_b - float(v)).max() <= 2.0 ** -11 * abs(float(v)), (n, v, got_b[:4])
+
+
 def test_largest_rank(gpu_api):
     cfg = cfg_of(rank=128, tokens=150, d_out=520)
     _, got, ref = run_both(gpu_api, cfg)

@@ -114,13 +114,13 @@ def test_requantize_round_trip(bits):
 
 
 def test_degenerate_group_and_column_wise():
-    """max == min: alpha := 1, codes 0, beta = the value, so W~ = W.  g = D_in is
+    """max == min: alpha := 2^-60, codes 0, beta = the value, so W~ = W.  g = D_in is
     column-wise quantization (one pair of factors per column, Sec. 3.1)."""
     W = np.full((16, 4), 0.375, np.float32)
     W[:, 1] = np.linspace(-1, 1, 16, dtype=np.float32)
     c, a, b = oracle.quantize(W, 4, 16)
     assert a.shape == (1, 4)
-    assert a[0, 0] == 1.0 and b[0, 0] == np.float32(0.375) and np.all(c[:, 0] == 0)
+    assert a[0, 0] == np.float32(2.0 ** -60) and b[0, 0] == np.float32(0.375) and np.all(c[:, 0] == 0)
     assert np.array_equal(oracle.dequantize(c, a, b, 16)[:, 0], W[:, 0].astype(np.float64))
     assert c[0, 1] == 0 and c[-1, 1] == 15
     assert a[0, 1] == np.float32(np.float32(2.0) / np.float32(15.0))
