@@ -71,6 +71,8 @@ def read_traffic(name, key="traffic_bytes_per_launch"):
 class Layer:
     """One quantized layer on the device, with adapters and preallocated outputs / workspace."""
 
+    keep = True   # training steps: the forward keeps pool(x) and U for the backward (--no-keep: re-read x)
+
     def __init__(self, api, torch, cfg, odt, gen=None, want_bwd=True, merged=False):
         self.api, self.cfg = api, cfg
         from paper_2309_14717_amd import synth
@@ -102,12 +104,16 @@ class Layer:
             self.dx = torch.empty((T, cfg.d_in), dtype=odt, device=dev)
             self.dA, self.dB = torch.zeros_like(self.A), torch.zeros_like(self.B)
             self.ws_b = torch.empty(api.workspace_bytes(self.desc, T, api.OP_BACKWARD), dtype=torch.uint8, device=dev)
+            self.kept = torch.empty(max(16, api.kept_bytes(self.desc, T)), dtype=torch.uint8, device=dev)
 
     def drop_w(self):
         self.W = None
 
     def forward(self, x=None):
         a = self.api
+        if self.keep and self.dy is not None:
+            return a.forward_keep(self.desc, self.x if x is None else x, self.packed, self.alpha, self.beta,
+                                  self.A, self.B, ws=self.ws_f, y=self.y, kept=self.kept)[0]
         return a.forward(self.desc, self.x if x is None else x, self.packed, self.alpha, self.beta,
                          self.A, self.B, ws=self.ws_f, y=self.y)
 
@@ -121,6 +127,10 @@ class Layer:
 
     def backward(self, dy=None, x=None):
         a = self.api
+        if self.keep:   # x is not read: the matching forward() left what is needed in self.kept
+            return a.backward_kept(self.desc, self.dy if dy is None else dy, self.kept, self.packed,
+                                   self.alpha, self.beta, self.A, self.B, dA=self.dA, dB=self.dB,
+                                   ws=self.ws_b, dx=self.dx)
         return a.backward(self.desc, self.dy if dy is None else dy, self.x if x is None else x,
                           self.packed, self.alpha, self.beta, self.A, self.B, dA=self.dA, dB=self.dB,
                           ws=self.ws_b, dx=self.dx)
@@ -269,6 +279,8 @@ def main():
     ap.add_argument("--factors16", action="store_true",
                     help="c5: alpha, beta of the merged layers stored as fp16 pairs (the configuration itself has fp32)")
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
+    ap.add_argument("--no-keep", action="store_true",
+                    help="backward re-reads x instead of the pooled activations the forward kept")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
@@ -281,6 +293,7 @@ def main():
               "all-reduce of dA/dB per step; no multi-GPU path is built). Use --gpus 1.",
               file=sys.stderr)
         sys.exit(2)
+    Layer.keep = not args.no_keep
 
     import torch
     from paper_2309_14717_amd import api, synth
@@ -485,7 +498,9 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f16" if args.workload != "c5" or args.tokens > (32 if args.bits == 4 else 16) else "bf16",
         "data": "synthetic",
         "config": {"workload": workload, "flops_per_step": total_flops,
-                   "frac_of_mfma_peak": round(value / PEAK_MFMA_TFLOPS, 4)},
+                   "frac_of_mfma_peak": round(value / PEAK_MFMA_TFLOPS, 4),
+                   "backward_reads": ("n/a" if args.workload == "c5" else
+                                      ("pooled activations kept by the forward" if Layer.keep else "x"))},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "extras": extras,
     }
     print(json.dumps(out))

@@ -155,6 +155,26 @@ int qalora_backward(const qalora_desc* desc, int tokens, const void* dy, const v
                     const float* A, const float* B, void* dx, int dx_dtype, float* dA,
                     float* dB, int accumulate, void* ws, size_t ws_bytes, void* stream);
 
+/* The pair above for training loops that keep the pooled activations instead of x.  The
+ * backward needs x only through P = pool_g(x) and U = P A (Alg. 1; App. B.2: the adapter sees
+ * the group averages, never x itself), which are g times smaller than x.
+ * qalora_forward_keep is qalora_forward (adapter required) that also leaves them in `kept`:
+ * device memory of qalora_kept_bytes(desc, tokens) bytes, 16-byte aligned, contents private to
+ * the library and valid for a backward call with the same desc, tokens, A and B.
+ * qalora_backward_kept is qalora_backward reading `kept` in place of x: same results bit for
+ * bit, one read of x less, and the caller may release x after the forward.
+ * qalora_kept_bytes returns 0 for an invalid descriptor, tokens <= 0 or rank 0.
+ * Workspace sizes are those of QALORA_OP_FORWARD and QALORA_OP_BACKWARD. */
+size_t qalora_kept_bytes(const qalora_desc* desc, int tokens);
+int qalora_forward_keep(const qalora_desc* desc, int tokens, const void* x, const void* packed,
+                        const float* alpha, const float* beta, const float* A, const float* B,
+                        void* y, int y_dtype, void* kept, void* ws, size_t ws_bytes,
+                        void* stream);
+int qalora_backward_kept(const qalora_desc* desc, int tokens, const void* dy, const void* kept,
+                         const void* packed, const float* alpha, const float* beta,
+                         const float* A, const float* B, void* dx, int dx_dtype, float* dA,
+                         float* dB, int accumulate, void* ws, size_t ws_bytes, void* stream);
+
 /* Merge the adapter into the zero factors (Alg. 1 merge, App. B.3, in Eq. 1's
  * convention):  beta_out[l,j] = beta[l,j] + (s/g) * sum_k A[l,k] B[k,j].
  * Codes and alpha are untouched, so the merged layer is still N-bit.

@@ -30,6 +30,7 @@ EXPORTS = (
     "qalora_beta_from_zero_point", "qalora_zero_point_from_beta",
     "qalora_pack_factors16", "qalora_forward_factors16",
     "qalora_adamw_workspace_bytes", "qalora_adamw_step",
+    "qalora_kept_bytes", "qalora_forward_keep", "qalora_backward_kept",
 )
 
 
@@ -72,6 +73,10 @@ def load() -> ctypes.CDLL:
     lib.qalora_forward.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
     lib.qalora_backward.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, vp, i, vp, vp, i, vp, sz, vp]
     lib.qalora_merge.argtypes = [cp, vp, vp, vp, vp, vp]
+    lib.qalora_kept_bytes.restype = sz
+    lib.qalora_kept_bytes.argtypes = [cp, i]
+    lib.qalora_forward_keep.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, i, vp, vp, sz, vp]
+    lib.qalora_backward_kept.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, vp, i, vp, vp, i, vp, sz, vp]
     lib.qalora_profile_arm.argtypes = [i, vp, vp]
     lib.qalora_profile_event_create.argtypes = [ctypes.POINTER(vp)]
     lib.qalora_profile_event_elapsed_ms.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float)]
@@ -214,6 +219,47 @@ def backward(desc: Desc, dy, x, packed, alpha, beta, A=None, B=None, want_dx=Tru
                                 _p(beta), _p(A), _p(B), _p(dx), dxd, _p(dA), _p(dB),
                                 1 if accumulate else 0, _p(ws), ws_bytes, _stream())
     _check(rc, "qalora_backward")
+    return dx, dA, dB
+
+
+def kept_bytes(desc: Desc, tokens: int) -> int:
+    return int(load().qalora_kept_bytes(ctypes.byref(desc), tokens))
+
+
+def forward_keep(desc: Desc, x, packed, alpha, beta, A, B, out_dtype=torch.float32, ws=None, y=None,
+                 kept=None):
+    """forward() that also leaves the pooled activations the backward needs.  Returns (y, kept)."""
+    assert x.dtype == torch.bfloat16 and x.is_contiguous()
+    T = x.shape[0]
+    if y is None:
+        y = torch.empty((T, desc.d_out), dtype=out_dtype, device=x.device)
+    if kept is None:
+        kept = torch.empty(max(kept_bytes(desc, T), 16), dtype=torch.uint8, device=x.device)
+    ws, ws_bytes = _workspace(desc, T, OP_FORWARD, ws)
+    rc = load().qalora_forward_keep(ctypes.byref(desc), T, _p(x), _p(packed), _p(alpha), _p(beta), _p(A),
+                                    _p(B), _p(y), BF16 if y.dtype == torch.bfloat16 else F32, _p(kept),
+                                    _p(ws), ws_bytes, _stream())
+    _check(rc, "qalora_forward_keep")
+    return y, kept
+
+
+def backward_kept(desc: Desc, dy, kept, packed, alpha, beta, A, B, want_dx=True,
+                  dx_dtype=torch.float32, dA=None, dB=None, accumulate=False, ws=None, dx=None):
+    """backward() from what forward_keep() left instead of x.  Returns (dx, dA, dB)."""
+    assert dy.dtype == torch.bfloat16 and dy.is_contiguous()
+    T = dy.shape[0]
+    if want_dx and dx is None:
+        dx = torch.empty((T, desc.d_in), dtype=dx_dtype, device=dy.device)
+    if dA is None:
+        dA = torch.zeros_like(A)
+    if dB is None:
+        dB = torch.zeros_like(B)
+    ws, ws_bytes = _workspace(desc, T, OP_BACKWARD, ws)
+    dxd = BF16 if (dx is not None and dx.dtype == torch.bfloat16) else F32
+    rc = load().qalora_backward_kept(ctypes.byref(desc), T, _p(dy), _p(kept), _p(packed), _p(alpha),
+                                     _p(beta), _p(A), _p(B), _p(dx), dxd, _p(dA), _p(dB),
+                                     1 if accumulate else 0, _p(ws), ws_bytes, _stream())
+    _check(rc, "qalora_backward_kept")
     return dx, dA, dB
 
 

@@ -62,6 +62,7 @@ __device__ __forceinline__ uint4 bf16x8_to_f16x8_scaled(uint4 v, float sc) {
 // ---------------------------------------------------------------------------------------
 constexpr int ROWS_PER_BLOCK = 4;  // one wavefront each
 constexpr int ROW_BATCH = 8;       // 128-bit chunks per lane held in registers (4096 elements)
+constexpr int TR_TOK = 32;         // tokens per block of the transpose job
 
 struct FrontArgs {
   // rows job 1 (x)
@@ -77,6 +78,9 @@ struct FrontArgs {
   int ktail;
   uint16_t* us_t;       // optional [2*rp, t_pad]
   int t_pad;
+  float* u_keep;        // optional [T, rank]: s U in fp32, for a later launch's transpose job
+  // transpose job: us_t from the [T, rank] fp32 rows an earlier launch kept (then x is not needed)
+  const float* u_kept;
   // rows job 2 (dy): scale + convert only
   const uint16_t* y;
   int Ty, d_y;
@@ -88,7 +92,7 @@ struct FrontArgs {
   uint16_t* b_ext_t;    // forward: [d_out, ktail]
   uint16_t* b_hl;       // backward: [2*rp, d_out]
   uint16_t* a_ext_t;    // backward: [L, ktail]
-  int nb_rows1, nb_rows2, nb_prep;
+  int nb_rows1, nb_rows2, nb_tr, nb_prep;
 };
 
 // One wavefront processes one bf16 row: returns the row scale; optionally writes the fp16
@@ -202,6 +206,7 @@ __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
           u *= a.s;
         }
         uint16_t hi, lo;
+        if (a.u_keep && k < a.rank) a.u_keep[(size_t)t * a.rank + k] = u;
         if (a.u_ext && k < a.rank) {
           // the forward tail shares the accumulator of the scaled main product
           split_bf16(u * sc.x, hi, lo);
@@ -236,6 +241,40 @@ __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
     return;
   }
   bid -= a.nb_rows2;
+  if (bid < a.nb_tr) {
+    // ---- transpose job: TR_TOK tokens of the kept s U -> token-contiguous hi/lo rows --------
+    // (the same values and the same split as rows job 1 writes when it computes U itself).
+    // The loads go out in batches of eight per thread before any is used: the launch is
+    // memory-saturated by the row jobs, and a round trip per element would outlast them.
+    float* tile = P_all;  // [TR_TOK][rank + 1]
+    const int t0 = bid * TR_TOK, rank = a.rank, rp = rank_pad32(rank), ld = rank + 1;
+    const int n = TR_TOK * rank;
+    for (int e0 = 0; e0 < n; e0 += 8 * 256) {
+      float r[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int e = e0 + j * 256 + tid;
+        const int t = e / rank;
+        r[j] = (e < n && t0 + t < a.T) ? a.u_kept[(size_t)t0 * rank + e] : 0.0f;
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int e = e0 + j * 256 + tid;
+        const int t = e / rank;
+        if (e < n) tile[t * ld + (e - t * rank)] = r[j];
+      }
+    }
+    __syncthreads();
+    const int tl = lane & (TR_TOK - 1);
+    for (int k = 2 * wave + (lane >> 5); k < rp; k += 8) {
+      uint16_t hi, lo;
+      split_bf16(k < rank ? tile[tl * ld + k] : 0.0f, hi, lo);  // zero for padding rows and tokens
+      a.us_t[(size_t)k * a.t_pad + t0 + tl] = hi;
+      a.us_t[(size_t)(rp + k) * a.t_pad + t0 + tl] = lo;
+    }
+    return;
+  }
+  bid -= a.nb_tr;
   // ---- prep job: elementwise hi/lo splits ------------------------------------------------
   const size_t idx = (size_t)bid * 256 + tid;
   const int rp = rank_pad32(a.rank);
@@ -331,8 +370,11 @@ static hipError_t launch_front(FrontArgs a, hipStream_t st) {
   if (a.b_ext_t) nprep = (size_t)a.d_out * a.ktail;
   else if (a.b_hl) nprep = (size_t)2 * rank_pad32(a.rank) * a.d_out + (size_t)a.L * a.ktail;
   a.nb_prep = (int)((nprep + 255) / 256);
-  const size_t smem =
+  a.nb_tr = a.u_kept ? a.t_pad / TR_TOK : 0;
+  size_t smem =
       a.A ? ((size_t)ROWS_PER_BLOCK * (a.d_in / a.g) + 4 * ROWS_PER_BLOCK * 128) * sizeof(float) : 0;
+  const size_t tr_smem = (size_t)TR_TOK * (a.rank + 1) * sizeof(float);
+  if (a.nb_tr > 0 && smem < tr_smem) smem = tr_smem;
   constexpr size_t kFrontLdsMax = 160 * 1024;  // a compute unit's LDS
   if (smem > kFrontLdsMax) return hipErrorInvalidValue;
   if (smem > 48 * 1024) {
@@ -341,7 +383,7 @@ static hipError_t launch_front(FrontArgs a, hipStream_t st) {
         e != hipSuccess)
       return e;
   }
-  const int nblocks = a.nb_rows1 + a.nb_rows2 + a.nb_prep;
+  const int nblocks = a.nb_rows1 + a.nb_rows2 + a.nb_tr + a.nb_prep;
   if (nblocks == 0) return hipSuccess;
   front_kernel<<<nblocks, 256, smem, st>>>(a);
   return hipGetLastError();
@@ -350,12 +392,14 @@ static hipError_t launch_front(FrontArgs a, hipStream_t st) {
 hipError_t launch_front_forward(const uint16_t* x, int T, int d_in, float2* rs, uint16_t* x16,
                                 const float* A, const float* B, float s, int g, int rank,
                                 int d_out, uint16_t* u_ext, uint16_t* b_ext_t, int ktail,
-                                hipStream_t st) {
+                                float* P_keep, float* u_keep, hipStream_t st) {
   FrontArgs a{};
   a.x = x; a.T = T; a.d_in = d_in; a.rs_x = rs; a.x16 = x16;
   if (A && rank > 0) {
     a.A = A; a.s = s; a.g = g; a.rank = rank; a.u_ext = u_ext; a.ktail = ktail;
     a.B = B; a.d_out = d_out; a.b_ext_t = b_ext_t;
+    a.P_out = P_keep;  // what the backward needs of x, when the caller keeps it
+    a.u_keep = u_keep;
   }
   return launch_front(a, st);
 }
@@ -364,11 +408,13 @@ hipError_t launch_front_backward(const uint16_t* dy, int T, int d_out, float2* r
                                  uint16_t* dy16, const uint16_t* x, int d_in, const float* A,
                                  const float* B, float s, int g, int rank, float* P,
                                  uint16_t* us_t, int t_pad, uint16_t* b_hl, uint16_t* a_ext_t,
-                                 int ktail, hipStream_t st) {
+                                 int ktail, const float* u_kept, hipStream_t st) {
   FrontArgs a{};
   a.y = dy; a.Ty = T; a.d_y = d_out; a.rs_y = rs_dy; a.y16 = dy16;
   if (A && rank > 0) {
-    a.x = x; a.T = T; a.d_in = d_in; a.A = A; a.s = s; a.g = g; a.rank = rank;
+    a.x = u_kept ? nullptr : x;  // with the kept rows, P is the caller's and us_t is a transpose
+    a.u_kept = u_kept;
+    a.T = T; a.d_in = d_in; a.A = A; a.s = s; a.g = g; a.rank = rank;
     a.P_out = P; a.us_t = us_t; a.t_pad = t_pad; a.ktail = ktail;
     a.B = B; a.d_out = d_out; a.L = d_in / g; a.b_hl = b_hl; a.a_ext_t = a_ext_t;
   }

@@ -246,16 +246,79 @@ int qalora_pack(const qalora_desc* d, const uint8_t* codes, void* packed, void* 
   return hipGetLastError() == hipSuccess ? QALORA_OK : QALORA_EHIP;
 }
 
+namespace {
+
+// What the forward leaves for the backward when asked to: P = pool_g(x) [T, L] and
+// s P A [T, rank], both fp32.
+struct KeptLayout {
+  size_t P, U, total;
+};
+KeptLayout kept_layout(const qalora_desc& d, int T) {
+  KeptLayout k{};
+  k.P = 0;
+  k.U = align_up((size_t)T * (d.d_in / d.group) * 4);
+  k.total = k.U + align_up((size_t)T * d.rank * 4);
+  return k;
+}
+
+int forward_impl(const qalora_desc* d, int tokens, const void* x, const void* packed,
+                 const float* alpha, const float* beta, const float* A, const float* B, void* y,
+                 int y_dtype, void* kept, bool keep, void* ws, size_t ws_bytes, void* stream);
+int backward_impl(const qalora_desc* d, int tokens, const void* dy, const void* x, const void* kept,
+                  bool use_kept, const void* packed, const float* alpha, const float* beta,
+                  const float* A, const float* B, void* dx, int dx_dtype, float* dA, float* dB,
+                  int accumulate, void* ws, size_t ws_bytes, void* stream);
+
+}  // namespace
+
 int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* packed,
                    const float* alpha, const float* beta, const float* A, const float* B, void* y,
                    int y_dtype, void* ws, size_t ws_bytes, void* stream) {
+  return forward_impl(d, tokens, x, packed, alpha, beta, A, B, y, y_dtype, nullptr, false, ws, ws_bytes,
+                      stream);
+}
+
+size_t qalora_kept_bytes(const qalora_desc* d, int tokens) {
+  if (qalora_check_desc(d) != QALORA_OK || tokens <= 0 || d->rank <= 0) return 0;
+  return kept_layout(*d, tokens).total;
+}
+
+int qalora_forward_keep(const qalora_desc* d, int tokens, const void* x, const void* packed,
+                        const float* alpha, const float* beta, const float* A, const float* B,
+                        void* y, int y_dtype, void* kept, void* ws, size_t ws_bytes, void* stream) {
+  return forward_impl(d, tokens, x, packed, alpha, beta, A, B, y, y_dtype, kept, true, ws, ws_bytes,
+                      stream);
+}
+
+int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void* x,
+                    const void* packed, const float* alpha, const float* beta, const float* A,
+                    const float* B, void* dx, int dx_dtype, float* dA, float* dB, int accumulate,
+                    void* ws, size_t ws_bytes, void* stream) {
+  return backward_impl(d, tokens, dy, x, nullptr, false, packed, alpha, beta, A, B, dx, dx_dtype, dA, dB,
+                       accumulate, ws, ws_bytes, stream);
+}
+
+int qalora_backward_kept(const qalora_desc* d, int tokens, const void* dy, const void* kept,
+                         const void* packed, const float* alpha, const float* beta, const float* A,
+                         const float* B, void* dx, int dx_dtype, float* dA, float* dB,
+                         int accumulate, void* ws, size_t ws_bytes, void* stream) {
+  return backward_impl(d, tokens, dy, nullptr, kept, true, packed, alpha, beta, A, B, dx, dx_dtype, dA,
+                       dB, accumulate, ws, ws_bytes, stream);
+}
+
+namespace {
+
+int forward_impl(const qalora_desc* d, int tokens, const void* x, const void* packed,
+                 const float* alpha, const float* beta, const float* A, const float* B, void* y,
+                 int y_dtype, void* kept, bool keep, void* ws, size_t ws_bytes, void* stream) {
   const int rc = qalora_check_desc(d);
   if (rc != QALORA_OK) return rc;
   if (tokens <= 0 || !x || !packed || !alpha || !beta || !y) return QALORA_EINVAL;
   if ((A == nullptr) != (B == nullptr)) return QALORA_EINVAL;
   if (y_dtype != QALORA_F32 && y_dtype != QALORA_BF16) return QALORA_EINVAL;
+  if (keep && (!kept || !A || !B || d->rank <= 0)) return QALORA_EINVAL;  // only an adapter has anything to keep
   if (misaligned(x) || misaligned(packed) || misaligned(alpha) || misaligned(beta) ||
-      misaligned(A) || misaligned(B) || misaligned(y) || misaligned(ws))
+      misaligned(A) || misaligned(B) || misaligned(y) || misaligned(ws) || misaligned(kept))
     return QALORA_EALIGN;
   if (!addressable(*d, tokens)) return QALORA_EUNSUPPORTED;
   const bool adapter = A && B && d->rank > 0;
@@ -315,9 +378,16 @@ int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* 
   g.partial = plan.gsplit > 1 ? reinterpret_cast<float*>(w + plan.gpart) : nullptr;
   uint16_t* u_ext = adapter ? reinterpret_cast<uint16_t*>(w + plan.u_ext) : nullptr;
   uint16_t* b_ext_t = adapter ? reinterpret_cast<uint16_t*>(w + plan.b_ext_t) : nullptr;
+  float* P_keep = nullptr;
+  float* u_keep = nullptr;
+  if (keep) {
+    const KeptLayout k = kept_layout(*d, tokens);
+    P_keep = reinterpret_cast<float*>(static_cast<char*>(kept) + k.P);
+    u_keep = reinterpret_cast<float*>(static_cast<char*>(kept) + k.U);
+  }
   if (launch_front_forward(static_cast<const uint16_t*>(x), tokens, d->d_in, rs, x16,
                            adapter ? A : nullptr, B, d->s, d->group, d->rank, d->d_out, u_ext,
-                           b_ext_t, plan.ktail, st) != hipSuccess)
+                           b_ext_t, plan.ktail, P_keep, u_keep, st) != hipSuccess)
     return QALORA_EHIP;
   if (adapter) {
     g.a_tail = u_ext;
@@ -328,16 +398,18 @@ int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* 
   return launch_gemm_dq(d->bits, false, g, st) == hipSuccess ? QALORA_OK : QALORA_EHIP;
 }
 
-int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void* x,
-                    const void* packed, const float* alpha, const float* beta, const float* A,
-                    const float* B, void* dx, int dx_dtype, float* dA, float* dB, int accumulate,
-                    void* ws, size_t ws_bytes, void* stream) {
+int backward_impl(const qalora_desc* d, int tokens, const void* dy, const void* x, const void* kept,
+                  bool use_kept, const void* packed, const float* alpha, const float* beta,
+                  const float* A, const float* B, void* dx, int dx_dtype, float* dA, float* dB,
+                  int accumulate, void* ws, size_t ws_bytes, void* stream) {
   const int rc = qalora_check_desc(d);
   if (rc != QALORA_OK) return rc;
   if (tokens <= 0 || !dy || !packed || !alpha || !beta) return QALORA_EINVAL;
   if ((A == nullptr) != (B == nullptr)) return QALORA_EINVAL;
   const bool adapter = A && B && d->rank > 0;
-  if (adapter && (!x || !dA || !dB)) return QALORA_EINVAL;
+  if (use_kept && (!kept || !adapter)) return QALORA_EINVAL;
+  if (adapter && ((!use_kept && !x) || !dA || !dB)) return QALORA_EINVAL;
+  if (misaligned(kept)) return QALORA_EALIGN;
   if (dx && dx_dtype != QALORA_F32 && dx_dtype != QALORA_BF16) return QALORA_EINVAL;
   if (accumulate != 0 && accumulate != 1) return QALORA_EINVAL;
   if (misaligned(dy) || misaligned(x) || misaligned(packed) || misaligned(alpha) ||
@@ -370,11 +442,18 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
   if (!adapter) {
     if (launch_front_backward(dy16, tokens, d->d_out, rs, dyh, nullptr, d->d_in, nullptr, nullptr,
                               0.0f, d->group, 0, nullptr, nullptr, 0, nullptr, nullptr, 0,
-                              st) != hipSuccess)
+                              nullptr, st) != hipSuccess)
       return QALORA_EHIP;
   } else {
     float* P = reinterpret_cast<float*>(w + plan.P);
     uint16_t* us_t = reinterpret_cast<uint16_t*>(w + plan.us_t);
+    const float* u_kept = nullptr;
+    if (use_kept) {  // written by the forward: the front launch below then skips x altogether
+      const KeptLayout k = kept_layout(*d, tokens);
+      char* kp = const_cast<char*>(static_cast<const char*>(kept));
+      P = reinterpret_cast<float*>(kp + k.P);
+      u_kept = reinterpret_cast<const float*>(kp + k.U);
+    }
     uint16_t* b_hl = reinterpret_cast<uint16_t*>(w + plan.b_hl);
     a_ext_t = reinterpret_cast<uint16_t*>(w + plan.a_ext_t);
     float* du_raw = reinterpret_cast<float*>(w + plan.du_raw);
@@ -383,9 +462,10 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
     float* da_part = reinterpret_cast<float*>(w + plan.da_part);
 
     // row scales + fp16 copy of dy; P = pool(x), sU^T hi/lo; hi/lo operands of A and B
-    if (launch_front_backward(dy16, tokens, d->d_out, rs, dyh, static_cast<const uint16_t*>(x),
+    if (launch_front_backward(dy16, tokens, d->d_out, rs, dyh,
+                              use_kept ? nullptr : static_cast<const uint16_t*>(x),
                               d->d_in, A, B, d->s, d->group, d->rank, P, us_t, plan.t_pad, b_hl,
-                              a_ext_t, plan.ktail, st) != hipSuccess)
+                              a_ext_t, plan.ktail, u_kept, st) != hipSuccess)
       return QALORA_EHIP;
     // dU = s dy B^T : plain bf16 product against the hi/lo rows of B, split over K = d_out
     GemmArgs g{};
@@ -438,6 +518,8 @@ int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void
   }
   return QALORA_OK;
 }
+
+}  // namespace
 
 int qalora_merge(const qalora_desc* d, const float* beta, const float* A, const float* B,
                  float* beta_out, void* stream) {

@@ -97,20 +97,24 @@ __host__ __device__ inline int rank_pad32(int rank) { return ((rank + 31) / 32) 
 // Forward front launch: x -> rs (row scales), x16 = fp16(x * scale), and with an adapter
 //   u_ext   bf16 [T, ktail]      = [hi | lo | hi | 0] of s (pool_g(x) A) * row scale
 //   b_ext_t bf16 [d_out, ktail]  = [hi | hi | lo | 0] of B per output column
+// and, when given, P_keep fp32 [T, L] = pool_g(x) and u_keep fp32 [T, rank] = s pool_g(x) A, from
+// which the backward front launch below can work without x (its u_kept argument).
 hipError_t launch_front_forward(const uint16_t* x, int T, int d_in, float2* rs, uint16_t* x16,
                                 const float* A, const float* B, float s, int g, int rank,
                                 int d_out, uint16_t* u_ext, uint16_t* b_ext_t, int ktail,
-                                hipStream_t st);
+                                float* P_keep, float* u_keep, hipStream_t st);
 // Backward front launch: dy -> rs_dy, dy16; and with an adapter
 //   P       fp32 [T, L]          = pool_g(x)
 //   us_t    bf16 [2*rp, t_pad]   = rows hi(sU)^T then lo(sU)^T (token-contiguous, zero padded)
 //   b_hl    bf16 [2*rp, d_out]   = hi(B) rows then lo(B) rows
 //   a_ext_t bf16 [L, ktail]      = [hi | hi | lo | 0] of A / g
+// With u_kept (the forward's u_keep) x is not read: P is not written (the caller passes the
+// forward's P_keep on to the gradient kernels) and us_t is transposed from u_kept.
 hipError_t launch_front_backward(const uint16_t* dy, int T, int d_out, float2* rs_dy,
                                  uint16_t* dy16, const uint16_t* x, int d_in, const float* A,
                                  const float* B, float s, int g, int rank, float* P,
                                  uint16_t* us_t, int t_pad, uint16_t* b_hl, uint16_t* a_ext_t,
-                                 int ktail, hipStream_t st);
+                                 int ktail, const float* u_kept, hipStream_t st);
 // Both adapter-gradient jobs in one launch (neither depends on the other):
 //   dB partials over token slices: db_part[z][rank][d_out] = sum_{t in slice z} sU[t,:]^T dy[t,:]
 //   dA partials over token slices: da_part[z][L][rank] = sum_{t in slice z} P[t,:]^T dU[t,:], with

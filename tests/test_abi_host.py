@@ -108,6 +108,18 @@ def test_argument_errors_are_caught_before_launch(lib):
     fwd = lib.qalora_workspace_bytes(ref, 400, api.OP_FORWARD)
     assert lib.qalora_workspace_bytes(ref, 400, api.OP_FORWARD_FACTORS16) >= 2 * (1024 // 32) * 1024 * 4
     assert lib.qalora_workspace_bytes(ref, 4, api.OP_FORWARD_FACTORS16) > 0 and fwd > 0
+    # the kept-activation pair: the buffer is required, and only an adapter has anything to keep
+    assert lib.qalora_kept_bytes(ref, 64) >= 64 * 32 * 4 + 64 * 16 * 4
+    assert lib.qalora_kept_bytes(ref, 0) == 0
+    assert lib.qalora_kept_bytes(ctypes.byref(api.make_desc(1024, 1024, 4, 32, 0, 0.0)), 64) == 0
+    assert lib.qalora_forward_keep(ref, 64, P(good), P(good), P(good), P(good), P(good), P(good), P(good), 0, None, P(good), 1 << 30, None) == api.EINVAL
+    assert lib.qalora_forward_keep(ref, 64, P(good), P(good), P(good), P(good), None, None, P(good), 0, P(good), P(good), 1 << 30, None) == api.EINVAL
+    assert lib.qalora_forward_keep(ref, 64, P(good), P(good), P(good), P(good), P(good), P(good), P(good), 0, P(odd), P(good), 1 << 30, None) == api.EALIGN
+    assert lib.qalora_forward_keep(ref, 64, P(good), P(good), P(good), P(good), P(good), P(good), P(good), 0, P(good), P(good), 16, None) == api.EWORKSPACE
+    assert lib.qalora_backward_kept(ref, 64, P(good), None, P(good), P(good), P(good), P(good), P(good), P(good), 0, P(good), P(good), 0, P(good), 1 << 40, None) == api.EINVAL
+    assert lib.qalora_backward_kept(ref, 64, P(good), P(good), P(good), P(good), P(good), None, None, P(good), 0, None, None, 0, P(good), 1 << 40, None) == api.EINVAL
+    assert lib.qalora_backward_kept(ref, 64, P(good), P(odd), P(good), P(good), P(good), P(good), P(good), P(good), 0, P(good), P(good), 0, P(good), 1 << 40, None) == api.EALIGN
+    assert lib.qalora_backward_kept(ref, 64, P(good), P(good), P(good), P(good), P(good), P(good), P(good), P(good), 0, P(good), P(good), 0, P(good), 16, None) == api.EWORKSPACE
     assert lib.qalora_unpack(ref, None, P(good), None) == api.EINVAL
     assert lib.qalora_pack(ref, P(good), P(odd), None) == api.EALIGN
     bad = api.make_desc(1024, 1004, 4, 32, 16, 2.0)
