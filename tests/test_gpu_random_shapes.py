@@ -49,6 +49,10 @@ def test_random_layer(gpu_api, case):
     if cfg.rank:
         errs["dA"] = rel_err(dA.cpu().numpy(), rdA)
         errs["dB"] = rel_err(dB.cpu().numpy(), rdB)
+        # the pair that keeps the pooled activations instead of x: the same bits
+        yk, kept = gpu_api.forward_keep(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"], A, B)
+        gk = gpu_api.backward_kept(L["desc"], L["dy"], kept, L["packed"], L["g_alpha"], L["g_beta"], A, B)
+        assert torch.equal(yk, y) and all(torch.equal(p, q) for p, q in zip(gk, (dx, dA, dB)))
         beta_m = gpu_api.merge(L["desc"], L["g_beta"], A, B)
         assert rel_err(beta_m.cpu().numpy(), oracle.merge(L["beta"], hA, hB, cfg.group, cfg.s)) <= 1e-5
         y_m = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], beta_m)
