@@ -51,7 +51,10 @@ def test_graph_replay_small_token_forward(gpu_api, tokens, bits):
         assert rel_err(want.cpu().numpy(), ref) <= 1e-5
 
 
-def test_graph_replay_forward_backward(gpu_api):
+@pytest.mark.parametrize("keep", [False, True], ids=["plain", "kept"])
+def test_graph_replay_forward_backward(gpu_api, keep):
+    """keep: the pair in which the forward leaves the pooled activations and the backward reads
+    them instead of x (the buffer between the two is part of the captured graph's state)."""
     cfg = synth.LayerConfig("graph_fb", 200, 384, 520, 4, 32, 16, 0.5, seed=32)
     L = layer_on_gpu(gpu_api, cfg)
     d = L["desc"]
@@ -63,9 +66,15 @@ def test_graph_replay_forward_backward(gpu_api):
     ws_b = torch.empty(gpu_api.workspace_bytes(d, cfg.tokens, gpu_api.OP_BACKWARD), dtype=torch.uint8, device="cuda")
     w = (L["packed"], L["g_alpha"], L["g_beta"], L["A"], L["B"])
 
+    kept = torch.empty(gpu_api.kept_bytes(d, cfg.tokens), dtype=torch.uint8, device="cuda")
+
     def both():
-        gpu_api.forward(d, x, *w, ws=ws_f, y=y)
-        gpu_api.backward(d, dy, x, *w, dA=dA, dB=dB, ws=ws_b, dx=dx)
+        if keep:
+            gpu_api.forward_keep(d, x, *w, ws=ws_f, y=y, kept=kept)
+            gpu_api.backward_kept(d, dy, kept, *w, dA=dA, dB=dB, ws=ws_b, dx=dx)
+        else:
+            gpu_api.forward(d, x, *w, ws=ws_f, y=y)
+            gpu_api.backward(d, dy, x, *w, dA=dA, dB=dB, ws=ws_b, dx=dx)
 
     both()
     torch.cuda.synchronize()
@@ -77,6 +86,7 @@ def test_graph_replay_forward_backward(gpu_api):
         dy.copy_(fresh(dy, 300 + rep))
         for t in (y, dx, dA, dB):
             t.fill_(float("nan"))
+        kept.fill_(0xff)
         graph.replay()
         torch.cuda.synchronize()
         got = [t.clone() for t in (y, dx, dA, dB)]
