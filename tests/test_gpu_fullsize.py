@@ -44,6 +44,11 @@ def check_layer(gpu_api, cfg, rows=None, check_grads=True):
         errs["dB"] = rel_err(dB.cpu().numpy(), rdB)
     record(f"fullsize {cfg.name} N={cfg.bits} g={cfg.group} T={cfg.tokens}", **errs)
     assert max(errs.values()) <= TOL, errs
+    # the pair the benchmark times (pooled activations kept by the forward): the same bits
+    w = (L["packed"], L["g_alpha"], L["g_beta"], L["A"], L["B"])
+    yk, kept = gpu_api.forward_keep(L["desc"], L["x"], *w)
+    gk = gpu_api.backward_kept(L["desc"], L["dy"], kept, *w)
+    assert torch.equal(yk, y) and all(torch.equal(p, q) for p, q in zip(gk, (dx, dA, dB)))
     return L
 
 
