@@ -246,14 +246,12 @@ int qalora_pack(const qalora_desc* d, const uint8_t* codes, void* packed, void* 
   return hipGetLastError() == hipSuccess ? QALORA_OK : QALORA_EHIP;
 }
 
-namespace {
-
 // What the forward leaves for the backward when asked to: P = pool_g(x) [T, L] and
 // s P A [T, rank], both fp32.
 struct KeptLayout {
   size_t P, U, total;
 };
-KeptLayout kept_layout(const qalora_desc& d, int T) {
+static KeptLayout kept_layout(const qalora_desc& d, int T) {
   KeptLayout k{};
   k.P = 0;
   k.U = align_up((size_t)T * (d.d_in / d.group) * 4);
@@ -261,15 +259,13 @@ KeptLayout kept_layout(const qalora_desc& d, int T) {
   return k;
 }
 
-int forward_impl(const qalora_desc* d, int tokens, const void* x, const void* packed,
-                 const float* alpha, const float* beta, const float* A, const float* B, void* y,
-                 int y_dtype, void* kept, bool keep, void* ws, size_t ws_bytes, void* stream);
-int backward_impl(const qalora_desc* d, int tokens, const void* dy, const void* x, const void* kept,
-                  bool use_kept, const void* packed, const float* alpha, const float* beta,
-                  const float* A, const float* B, void* dx, int dx_dtype, float* dA, float* dB,
-                  int accumulate, void* ws, size_t ws_bytes, void* stream);
-
-}  // namespace
+static int forward_impl(const qalora_desc* d, int tokens, const void* x, const void* packed,
+                        const float* alpha, const float* beta, const float* A, const float* B, void* y,
+                        int y_dtype, void* kept, bool keep, void* ws, size_t ws_bytes, void* stream);
+static int backward_impl(const qalora_desc* d, int tokens, const void* dy, const void* x,
+                         const void* kept, bool use_kept, const void* packed, const float* alpha,
+                         const float* beta, const float* A, const float* B, void* dx, int dx_dtype,
+                         float* dA, float* dB, int accumulate, void* ws, size_t ws_bytes, void* stream);
 
 int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* packed,
                    const float* alpha, const float* beta, const float* A, const float* B, void* y,
@@ -306,11 +302,9 @@ int qalora_backward_kept(const qalora_desc* d, int tokens, const void* dy, const
                        dB, accumulate, ws, ws_bytes, stream);
 }
 
-namespace {
-
-int forward_impl(const qalora_desc* d, int tokens, const void* x, const void* packed,
-                 const float* alpha, const float* beta, const float* A, const float* B, void* y,
-                 int y_dtype, void* kept, bool keep, void* ws, size_t ws_bytes, void* stream) {
+static int forward_impl(const qalora_desc* d, int tokens, const void* x, const void* packed,
+                        const float* alpha, const float* beta, const float* A, const float* B, void* y,
+                        int y_dtype, void* kept, bool keep, void* ws, size_t ws_bytes, void* stream) {
   const int rc = qalora_check_desc(d);
   if (rc != QALORA_OK) return rc;
   if (tokens <= 0 || !x || !packed || !alpha || !beta || !y) return QALORA_EINVAL;
@@ -398,10 +392,10 @@ int forward_impl(const qalora_desc* d, int tokens, const void* x, const void* pa
   return launch_gemm_dq(d->bits, false, g, st) == hipSuccess ? QALORA_OK : QALORA_EHIP;
 }
 
-int backward_impl(const qalora_desc* d, int tokens, const void* dy, const void* x, const void* kept,
-                  bool use_kept, const void* packed, const float* alpha, const float* beta,
-                  const float* A, const float* B, void* dx, int dx_dtype, float* dA, float* dB,
-                  int accumulate, void* ws, size_t ws_bytes, void* stream) {
+static int backward_impl(const qalora_desc* d, int tokens, const void* dy, const void* x,
+                         const void* kept, bool use_kept, const void* packed, const float* alpha,
+                         const float* beta, const float* A, const float* B, void* dx, int dx_dtype,
+                         float* dA, float* dB, int accumulate, void* ws, size_t ws_bytes, void* stream) {
   const int rc = qalora_check_desc(d);
   if (rc != QALORA_OK) return rc;
   if (tokens <= 0 || !dy || !packed || !alpha || !beta) return QALORA_EINVAL;
@@ -518,8 +512,6 @@ int backward_impl(const qalora_desc* d, int tokens, const void* dy, const void* 
   }
   return QALORA_OK;
 }
-
-}  // namespace
 
 int qalora_merge(const qalora_desc* d, const float* beta, const float* A, const float* B,
                  float* beta_out, void* stream) {
