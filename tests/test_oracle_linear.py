@@ -226,6 +226,26 @@ def test_zero_point_interchange():
                           np.full(alpha.shape, 1.5))
 
 
+def test_constant_group_in_zero_point_form():
+    """A constant group (Eq. 1's alpha = 0, undefined codes) is stored as codes 0, beta = the value
+    and a placeholder step: its zero-point twin must stay finite, name the same weights, and map
+    back to the same beta bit for bit; and the step must be too small to matter however
+    alpha * c + beta is evaluated (here: around the mid code, in fp32)."""
+    W = np.full((16, 3), -0.4161, np.float32)
+    W[:, 1] = 117.3
+    W[:, 2] = np.linspace(-1, 1, 16, dtype=np.float32)
+    c, a, b = oracle.quantize(W, 4, 16)
+    assert np.all(c[:, :2] == 0) and np.all(a[0, :2] > 0)
+    z = oracle.zero_point_from_beta(a, b)
+    assert np.isfinite(z).all()
+    assert np.array_equal(oracle.beta_from_zero_point(a, z).astype(np.float32), b)
+    Wz = a.astype(np.float64).repeat(16, 0) * (c - z.repeat(16, 0))      # App. B.1 form
+    assert np.array_equal(Wz[:, :2].astype(np.float32), W[:, :2])
+    mid = np.float32(8.0)
+    centred = a[0] * (c[0].astype(np.float32) - mid) + (b[0] + mid * a[0])  # fp32 throughout
+    assert np.array_equal(centred[:2], W[0, :2])
+
+
 def test_declared_precision_mode_close_to_definition():
     """Rounding W~ to bf16 moves y by about 2^-9 relative per term; the two modes must agree
     to a few 1e-3 of max|y| and must differ (the flag is wired)."""
