@@ -57,7 +57,9 @@ def forward_bytes(cfg, tokens, out_bytes=2, factor_bytes=4):
 
 
 def read_traffic(name, key="traffic_bytes_per_launch"):
-    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary."""
+    """HBM bytes per launch of the dominant kernel.  Hardware counters cannot be read from inside
+    this process, so the figure is the one of the committed rocprofv3 --pmc summary of the same
+    workload, and `traffic_source` in the output says so."""
     path = os.path.join(ROOT, "profiles", name)
     try:
         for line in open(path):
@@ -66,6 +68,13 @@ def read_traffic(name, key="traffic_bytes_per_launch"):
     except OSError:
         pass
     return None
+
+
+def traffic_fields(name, key="traffic_bytes_per_launch"):
+    t = read_traffic(name, key) if name else None
+    return {"traffic": t,
+            "traffic_source": (f"profiles/{name} (committed rocprofv3 --pmc run of this workload, not "
+                               "measured in this run)") if t is not None else None}
 
 
 class Layer:
@@ -136,6 +145,35 @@ class Layer:
                           ws=self.ws_b, dx=self.dx)
 
 
+class MlpBlock:
+    """The SwiGLU MLP block of one LLaMA-7B decoder layer (workload c3): three adapted linears
+    chained through bf16 activations, y = down(silu(gate(x)) * up(x)), and its backward."""
+
+    def __init__(self, api, torch, synth, odt):
+        self.api = api
+        self.gate = Layer(api, torch, synth.CONFIGS["c3_gate"], odt)
+        self.gate.drop_w()
+        self.up = Layer(api, torch, synth.CONFIGS["c3_up"], odt)
+        self.up.drop_w()
+        self.down = Layer(api, torch, synth.CONFIGS["c3_down"], odt)
+        self.down.drop_w()
+        self.x, self.dy = self.gate.x, self.down.dy
+        self.h = torch.empty_like(self.gate.y)
+        self.dg, self.du = torch.empty_like(self.gate.y), torch.empty_like(self.gate.y)
+
+    def step(self):
+        api, gate, up, down, x = self.api, self.gate, self.up, self.down, self.x
+        g = gate.forward(x)
+        u = up.forward(x)
+        api.swiglu_forward(g, u, out=self.h)
+        down.forward(self.h)
+        dh, _, _ = down.backward(self.dy, self.h)
+        api.swiglu_backward(dh, g, u, dgate=self.dg, dup=self.du)
+        dx1, _, _ = gate.backward(self.dg, x)
+        dx2, _, _ = up.backward(self.du, x)
+        return dx1.add_(dx2)
+
+
 def timed(torch, fn, n=20, warm=2):
     for _ in range(warm):
         fn()
@@ -152,14 +190,41 @@ def timed(torch, fn, n=20, warm=2):
 KERNEL_STATS = {}  # direction -> median / min / count of the armed kernel durations of the last run
 
 
-def run_steps(torch, api, step, steps, warmup, directions=(0, 1), arm_every=4):
+SETTLE = {}  # extra untimed warm-up the last run_steps needed before its step time was steady
+
+
+def settle(torch, step, chunk=10, tol=0.015, max_chunks=40):
+    """Untimed warm-up beyond --warmup: run chunks of `chunk` steps until two consecutive chunks
+    agree to `tol` (the chip's power management takes a while to reach the clock it then holds
+    under this load; a short run would otherwise time the transient)."""
+    prev, calm, n = None, 0, 0
+    for _ in range(max_chunks):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(chunk):
+            step()
+        torch.cuda.synchronize()
+        t = time.perf_counter() - t0
+        n += chunk
+        calm = calm + 1 if (prev is not None and abs(t - prev) <= tol * prev) else 0
+        prev = t
+        if calm >= 2:
+            break
+    return n
+
+
+def run_steps(torch, api, step, steps, warmup, directions=(0, 1), arm_every=None):
     """Warm up, then time exactly `steps` steps; per-direction kernel times from events armed
     around the dense kernel on every `arm_every`-th step of the timed region (an armed launch
     costs the stream a few microseconds of event handling, which would otherwise weigh on
-    `value` -- by 10 % for the 30 us kernels of the small-token workload)."""
+    `value` -- by 10 % for the 30 us kernels of the small-token workload).  Short runs arm every
+    step so that the kernel figure still rests on a few dozen samples."""
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    SETTLE["steps"] = settle(torch, step)
+    if arm_every is None:
+        arm_every = 1 if steps <= 50 else 4
     timers = {d: api.KernelTimer(d, (steps + arm_every - 1) // arm_every) for d in directions}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -332,7 +397,7 @@ def main():
                     "achieved": round(achieved, 2), "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_MFMA_TFLOPS, 4), "avg_kernel_ms": round(dom[1], 4),
                     "fwd_kernel_ms": round(kf, 4), "bwd_kernel_ms": round(kb, 4),
-                    "traffic": read_traffic(f"gemm_dq_{args.workload}_pmc.txt")}
+                    **traffic_fields(f"gemm_dq_{args.workload}_pmc.txt")}
         roofline.update(clock_fields(clk[0 if dom[0] == "fwd" else 1], achieved))
         st = KERNEL_STATS.get(0 if dom[0] == "fwd" else 1)
         if st:
@@ -371,28 +436,8 @@ def main():
     elif args.workload == "c3":
         if odt != torch.bfloat16:
             sys.exit("bench.py: workload c3 chains layers through bf16 activations; use --out-dtype bf16")
-        gate = Layer(api, torch, synth.CONFIGS["c3_gate"], odt)
-        gate.drop_w()
-        up = Layer(api, torch, synth.CONFIGS["c3_up"], odt)
-        up.drop_w()
-        down = Layer(api, torch, synth.CONFIGS["c3_down"], odt)
-        down.drop_w()
-        x, dy = gate.x, down.dy
-        h = torch.empty_like(gate.y)
-        dg, du = torch.empty_like(gate.y), torch.empty_like(gate.y)
-
-        def step():
-            # forward: y = down( silu(gate(x)) * up(x) )
-            g = gate.forward(x)
-            u = up.forward(x)
-            api.swiglu_forward(g, u, out=h)
-            down.forward(h)
-            # backward
-            dh, _, _ = down.backward(dy, h)
-            api.swiglu_backward(dh, g, u, dgate=dg, dup=du)
-            dx1, _, _ = gate.backward(dg, x)
-            dx2, _, _ = up.backward(du, x)
-            return dx1.add_(dx2)
+        blk = MlpBlock(api, torch, synth, odt)
+        gate, up, down, step = blk.gate, blk.up, blk.down, blk.step
 
         ms_per_step, kms, clk = run_steps(torch, api, step, args.steps, args.warmup)
         fls = [layer_flops(l.cfg) for l in (gate, up, down)]
@@ -406,7 +451,7 @@ def main():
                     "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_TFLOPS, 4),
                     "avg_kernel_ms": round(dom[1], 4), "gate_fwd_kernel_ms": round(kf, 4),
                     "down_bwd_kernel_ms": round(kb, 4),
-                    "traffic": read_traffic("gemm_dq_c3_pmc.txt", "traffic_bytes_per_launch_" + dom[0][:3])}
+                    **traffic_fields("gemm_dq_c3_pmc.txt", "traffic_bytes_per_launch_" + dom[0][:3])}
         roofline.update(clock_fields(clk[0 if dom[0].startswith("fwd") else 1], achieved))
         workload = ("c3: LLaMA-7B SwiGLU MLP block fwd+bwd, T=4096, gate/up 4096x11008 + down 11008x4096, "
                     f"INT4 g=32, rank 64, s=0.25, bf16 activations, outputs {args.out_dtype}; SwiGLU glue fused (one kernel each way)")
@@ -465,13 +510,14 @@ def main():
                         "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": round(ach / PEAK_HBM_GBS, 4), "avg_kernel_ms": round(k_avg, 5),
                         "event_bracketed_ms_8192x22016": round(k, 5),
-                        "traffic": (read_traffic("smallt4_c5_pmc.txt" if T <= 4 else "smallt_c5_pmc.txt")
-                                    if (args.bits == 4 and not args.factors16 and T <= 16) else None)}
+                        **traffic_fields(("smallt4_c5_pmc.txt" if T <= 4 else "smallt_c5_pmc.txt")
+                                         if (args.bits == 4 and not args.factors16 and T <= 16) else None)}
         else:
             ach = 2.0 * T * cfg_u.d_in * cfg_u.d_out / (k * 1e-3) / 1e12
             roofline = {"bound": "mfma", "kernel": f"gemm_dq_kernel<{args.bits},fwd> (8192x22016)", "achieved": round(ach, 2),
                         "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_MFMA_TFLOPS, 4),
-                        "avg_kernel_ms": round(k, 5), "hbm_GB/s": round(by_u / k / 1e6, 1), "traffic": None}
+                        "avg_kernel_ms": round(k, 5), "hbm_GB/s": round(by_u / k / 1e6, 1), "traffic": None,
+                        "traffic_source": None}
             roofline.update(clock_fields(clk[0], ach))
         extras = {"GB/s_whole_step": round(by_step / ms_per_step / 1e6, 1),
                   "frac_hbm_whole_step": round(by_step / ms_per_step / 1e6 / PEAK_HBM_GBS, 4),
@@ -494,7 +540,7 @@ def main():
     value = total_flops / (ms_per_step * 1e-3) / 1e12
     out = {
         "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "warmup": args.warmup, "warmup_settle_steps": SETTLE.get("steps", 0), "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f16" if args.workload != "c5" or args.tokens > (32 if args.bits == 4 else 16) else "bf16",
         "data": "synthetic",
         "config": {"workload": workload, "flops_per_step": total_flops,

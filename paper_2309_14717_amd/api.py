@@ -13,8 +13,7 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# QALORA_LIB points at an alternative build of the same library (kernel experiments)
-LIB_PATH = os.environ.get("QALORA_LIB") or os.path.join(_HERE, "libqalora_hip.so")
+LIB_PATH = os.path.join(_HERE, "libqalora_hip.so")
 
 OK, EINVAL, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
@@ -130,17 +129,76 @@ def _check(rc, where):
         raise QaloraError(int(rc), where)
 
 
-def _workspace(desc, tokens, op, ws):
+def _workspace(desc, tokens, op, ws, device="cuda"):
     # a caller-provided workspace is passed through as it is (the library checks its size)
     if ws is None:
-        ws = torch.empty(max(workspace_bytes(desc, tokens, op), 16), dtype=torch.uint8, device="cuda")
-    return ws, ws.numel()
+        ws = torch.empty(max(workspace_bytes(desc, tokens, op), 16), dtype=torch.uint8, device=device)
+    else:
+        _need(ws, "ws", device=device)
+    return ws, ws.numel() * ws.element_size()
+
+
+def _need(t, name, dtype=None, shape=None, nbytes=None, device=None, optional=False):
+    """The C ABI sees raw pointers only: a tensor of the wrong size, type or device would become
+    an out-of-bounds device access there, so every operand is checked here first."""
+    if t is None:
+        if optional:
+            return
+        raise ValueError(f"{name}: missing")
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise ValueError(f"{name}: must be a device tensor")
+    if device is not None and t.device != torch.device(device):
+        raise ValueError(f"{name}: on {t.device}, expected {device}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name}: dtype {t.dtype}, expected {dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(t.shape)}, expected {tuple(shape)}")
+    if nbytes is not None and t.numel() * t.element_size() < nbytes:
+        raise ValueError(f"{name}: {t.numel() * t.element_size()} bytes, needs at least {nbytes}")
+
+
+def _need_layer(desc, x, in_features, packed, alpha, beta, A, B, x_name="x"):
+    """Checks shared by every forward / backward entry; returns (tokens, device)."""
+    _need(x, x_name, torch.bfloat16)
+    dev = x.device
+    if check_desc(desc) != OK:  # the library rejects the call with its own status
+        return x.shape[0], dev
+    if x.dim() != 2 or x.shape[1] != in_features:
+        raise ValueError(f"{x_name}: shape {tuple(x.shape)}, expected [tokens, {in_features}]")
+    L = desc.d_in // max(desc.group, 1)
+    _need(packed, "packed", nbytes=packed_bytes(desc), device=dev)
+    _need(alpha, "alpha", torch.float32, (L, desc.d_out), device=dev)
+    if beta is not None:
+        _need(beta, "beta", torch.float32, (L, desc.d_out), device=dev)
+    if (A is None) != (B is None):
+        raise ValueError("A and B must be given together")
+    if A is not None:
+        _need(A, "A", torch.float32, (L, desc.rank), device=dev)
+        _need(B, "B", torch.float32, (desc.rank, desc.d_out), device=dev)
+    return x.shape[0], dev
+
+
+def _need_factor_pair(desc, alpha, other, other_name):
+    _need(alpha, "alpha", torch.float32)
+    shape = (desc.d_in // desc.group, desc.d_out) if check_desc(desc) == OK else tuple(alpha.shape)
+    _need(alpha, "alpha", shape=shape)
+    _need(other, other_name, torch.float32, shape, device=alpha.device)
+
+
+def _need_out(t, name, rows, cols, dev):
+    _need(t, name, shape=(rows, cols), device=dev)
+    if t.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError(f"{name}: dtype {t.dtype}, expected float32 or bfloat16")
 
 
 def quantize(desc: Desc, W: torch.Tensor):
     """W fp32 [d_in, d_out] (device) -> (packed uint8, alpha fp32 [L, d_out], beta fp32 [L, d_out])."""
-    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous()
-    L = desc.d_in // desc.group
+    _need(W, "W", torch.float32)
+    if check_desc(desc) == OK:
+        _need(W, "W", shape=(desc.d_in, desc.d_out))
+    L = desc.d_in // max(desc.group, 1)
     packed = torch.empty(packed_bytes(desc), dtype=torch.uint8, device=W.device)
     alpha = torch.empty((L, desc.d_out), dtype=torch.float32, device=W.device)
     beta = torch.empty_like(alpha)
@@ -151,13 +209,16 @@ def quantize(desc: Desc, W: torch.Tensor):
 
 
 def unpack(desc: Desc, packed: torch.Tensor) -> torch.Tensor:
+    _need(packed, "packed", nbytes=packed_bytes(desc))
     codes = torch.empty((desc.d_in, desc.d_out), dtype=torch.uint8, device=packed.device)
     _check(load().qalora_unpack(ctypes.byref(desc), _p(packed), _p(codes), _stream()), "qalora_unpack")
     return codes
 
 
 def pack(desc: Desc, codes: torch.Tensor) -> torch.Tensor:
-    assert codes.is_cuda and codes.dtype == torch.uint8 and codes.is_contiguous()
+    _need(codes, "codes", torch.uint8)
+    if check_desc(desc) == OK:
+        _need(codes, "codes", shape=(desc.d_in, desc.d_out))
     packed = torch.empty(packed_bytes(desc), dtype=torch.uint8, device=codes.device)
     _check(load().qalora_pack(ctypes.byref(desc), _p(codes), _p(packed), _stream()), "qalora_pack")
     return packed
@@ -166,11 +227,11 @@ def pack(desc: Desc, codes: torch.Tensor) -> torch.Tensor:
 def forward(desc: Desc, x, packed, alpha, beta, A=None, B=None, out_dtype=torch.float32, ws=None,
             y=None):
     """y = x W~ + s (pool(x) A) B.  x bf16 [T, d_in]; returns y [T, d_out]."""
-    assert x.dtype == torch.bfloat16 and x.is_contiguous()
-    T = x.shape[0]
+    T, dev = _need_layer(desc, x, desc.d_in, packed, alpha, beta, A, B)
     if y is None:
-        y = torch.empty((T, desc.d_out), dtype=out_dtype, device=x.device)
-    ws, ws_bytes = _workspace(desc, T, OP_FORWARD, ws)
+        y = torch.empty((T, desc.d_out), dtype=out_dtype, device=dev)
+    _need_out(y, "y", T, desc.d_out, dev)
+    ws, ws_bytes = _workspace(desc, T, OP_FORWARD, ws, dev)
     rc = load().qalora_forward(ctypes.byref(desc), T, _p(x), _p(packed), _p(alpha), _p(beta), _p(A),
                                _p(B), _p(y), BF16 if y.dtype == torch.bfloat16 else F32, _p(ws),
                                ws_bytes, _stream())
@@ -180,8 +241,12 @@ def forward(desc: Desc, x, packed, alpha, beta, A=None, B=None, out_dtype=torch.
 
 def pack_factors16(desc: Desc, alpha, beta, out=None):
     """One int32 word per (group, column): fp16(alpha) | fp16(beta) << 16."""
+    L = desc.d_in // max(desc.group, 1)
+    _need(alpha, "alpha", torch.float32, (L, desc.d_out))
+    _need(beta, "beta", torch.float32, (L, desc.d_out), device=alpha.device)
     if out is None:
         out = torch.empty(alpha.shape, dtype=torch.int32, device=alpha.device)
+    _need(out, "out", nbytes=4 * L * desc.d_out, device=alpha.device)
     _check(load().qalora_pack_factors16(ctypes.byref(desc), _p(alpha), _p(beta), _p(out), _stream()),
            "qalora_pack_factors16")
     return out
@@ -189,11 +254,16 @@ def pack_factors16(desc: Desc, alpha, beta, out=None):
 
 def forward_factors16(desc: Desc, x, packed, factors16, out_dtype=torch.float32, ws=None, y=None):
     """Adapter-free y = x W~ with the factors stored in 16 bits (see pack_factors16)."""
-    assert x.dtype == torch.bfloat16 and x.is_contiguous()
-    T = x.shape[0]
+    _need(x, "x", torch.bfloat16)
+    T, dev = x.shape[0], x.device
+    if check_desc(desc) == OK:
+        _need(x, "x", shape=(T, desc.d_in))
+        _need(packed, "packed", nbytes=packed_bytes(desc), device=dev)
+        _need(factors16, "factors16", nbytes=4 * (desc.d_in // desc.group) * desc.d_out, device=dev)
     if y is None:
-        y = torch.empty((T, desc.d_out), dtype=out_dtype, device=x.device)
-    ws, ws_bytes = _workspace(desc, T, OP_FORWARD_FACTORS16, ws)
+        y = torch.empty((T, desc.d_out), dtype=out_dtype, device=dev)
+    _need_out(y, "y", T, desc.d_out, dev)
+    ws, ws_bytes = _workspace(desc, T, OP_FORWARD_FACTORS16, ws, dev)
     rc = load().qalora_forward_factors16(ctypes.byref(desc), T, _p(x), _p(packed), _p(factors16), _p(y),
                                          BF16 if y.dtype == torch.bfloat16 else F32, _p(ws), ws_bytes,
                                          _stream())
@@ -204,16 +274,21 @@ def forward_factors16(desc: Desc, x, packed, factors16, out_dtype=torch.float32,
 def backward(desc: Desc, dy, x, packed, alpha, beta, A=None, B=None, want_dx=True,
              dx_dtype=torch.float32, dA=None, dB=None, accumulate=False, ws=None, dx=None):
     """Returns (dx, dA, dB).  dy bf16 [T, d_out], x bf16 [T, d_in]."""
-    assert dy.dtype == torch.bfloat16 and dy.is_contiguous()
-    T = dy.shape[0]
+    T, dev = _need_layer(desc, dy, desc.d_out, packed, alpha, beta, A, B, x_name="dy")
+    if A is not None or x is not None:
+        _need(x, "x", torch.bfloat16, (T, desc.d_in), device=dev)
     if want_dx and dx is None:
-        dx = torch.empty((T, desc.d_in), dtype=dx_dtype, device=dy.device)
+        dx = torch.empty((T, desc.d_in), dtype=dx_dtype, device=dev)
+    if dx is not None:
+        _need_out(dx, "dx", T, desc.d_in, dev)
     if A is not None:
         if dA is None:
             dA = torch.zeros_like(A)
         if dB is None:
             dB = torch.zeros_like(B)
-    ws, ws_bytes = _workspace(desc, T, OP_BACKWARD, ws)
+        _need(dA, "dA", torch.float32, tuple(A.shape), device=dev)
+        _need(dB, "dB", torch.float32, tuple(B.shape), device=dev)
+    ws, ws_bytes = _workspace(desc, T, OP_BACKWARD, ws, dev)
     dxd = BF16 if (dx is not None and dx.dtype == torch.bfloat16) else F32
     rc = load().qalora_backward(ctypes.byref(desc), T, _p(dy), _p(x), _p(packed), _p(alpha),
                                 _p(beta), _p(A), _p(B), _p(dx), dxd, _p(dA), _p(dB),
@@ -229,13 +304,14 @@ def kept_bytes(desc: Desc, tokens: int) -> int:
 def forward_keep(desc: Desc, x, packed, alpha, beta, A, B, out_dtype=torch.float32, ws=None, y=None,
                  kept=None):
     """forward() that also leaves the pooled activations the backward needs.  Returns (y, kept)."""
-    assert x.dtype == torch.bfloat16 and x.is_contiguous()
-    T = x.shape[0]
+    T, dev = _need_layer(desc, x, desc.d_in, packed, alpha, beta, A, B)
     if y is None:
-        y = torch.empty((T, desc.d_out), dtype=out_dtype, device=x.device)
+        y = torch.empty((T, desc.d_out), dtype=out_dtype, device=dev)
+    _need_out(y, "y", T, desc.d_out, dev)
     if kept is None:
-        kept = torch.empty(max(kept_bytes(desc, T), 16), dtype=torch.uint8, device=x.device)
-    ws, ws_bytes = _workspace(desc, T, OP_FORWARD, ws)
+        kept = torch.empty(max(kept_bytes(desc, T), 16), dtype=torch.uint8, device=dev)
+    _need(kept, "kept", nbytes=kept_bytes(desc, T), device=dev)
+    ws, ws_bytes = _workspace(desc, T, OP_FORWARD, ws, dev)
     rc = load().qalora_forward_keep(ctypes.byref(desc), T, _p(x), _p(packed), _p(alpha), _p(beta), _p(A),
                                     _p(B), _p(y), BF16 if y.dtype == torch.bfloat16 else F32, _p(kept),
                                     _p(ws), ws_bytes, _stream())
@@ -246,15 +322,19 @@ def forward_keep(desc: Desc, x, packed, alpha, beta, A, B, out_dtype=torch.float
 def backward_kept(desc: Desc, dy, kept, packed, alpha, beta, A, B, want_dx=True,
                   dx_dtype=torch.float32, dA=None, dB=None, accumulate=False, ws=None, dx=None):
     """backward() from what forward_keep() left instead of x.  Returns (dx, dA, dB)."""
-    assert dy.dtype == torch.bfloat16 and dy.is_contiguous()
-    T = dy.shape[0]
+    T, dev = _need_layer(desc, dy, desc.d_out, packed, alpha, beta, A, B, x_name="dy")
+    _need(kept, "kept", nbytes=kept_bytes(desc, T), device=dev)
     if want_dx and dx is None:
-        dx = torch.empty((T, desc.d_in), dtype=dx_dtype, device=dy.device)
+        dx = torch.empty((T, desc.d_in), dtype=dx_dtype, device=dev)
+    if dx is not None:
+        _need_out(dx, "dx", T, desc.d_in, dev)
     if dA is None:
         dA = torch.zeros_like(A)
     if dB is None:
         dB = torch.zeros_like(B)
-    ws, ws_bytes = _workspace(desc, T, OP_BACKWARD, ws)
+    _need(dA, "dA", torch.float32, tuple(A.shape), device=dev)
+    _need(dB, "dB", torch.float32, tuple(B.shape), device=dev)
+    ws, ws_bytes = _workspace(desc, T, OP_BACKWARD, ws, dev)
     dxd = BF16 if (dx is not None and dx.dtype == torch.bfloat16) else F32
     rc = load().qalora_backward_kept(ctypes.byref(desc), T, _p(dy), _p(kept), _p(packed), _p(alpha),
                                      _p(beta), _p(A), _p(B), _p(dx), dxd, _p(dA), _p(dB),
@@ -265,8 +345,15 @@ def backward_kept(desc: Desc, dy, kept, packed, alpha, beta, A, B, want_dx=True,
 
 def merge(desc: Desc, beta, A, B, out=None):
     """beta' = beta + (s/g) A B; ``out`` may be ``beta`` itself."""
+    _need(beta, "beta", torch.float32)
+    if check_desc(desc) == OK:
+        L = desc.d_in // desc.group
+        _need(beta, "beta", shape=(L, desc.d_out))
+        _need(A, "A", torch.float32, (L, desc.rank), device=beta.device)
+        _need(B, "B", torch.float32, (desc.rank, desc.d_out), device=beta.device)
     if out is None:
         out = torch.empty_like(beta)
+    _need(out, "out", torch.float32, tuple(beta.shape), device=beta.device)
     _check(load().qalora_merge(ctypes.byref(desc), _p(beta), _p(A), _p(B), _p(out), _stream()),
            "qalora_merge")
     return out
@@ -274,8 +361,10 @@ def merge(desc: Desc, beta, A, B, out=None):
 
 def beta_from_zero_point(desc: Desc, alpha, z, out=None):
     """beta = -(alpha z): import a zero point (code units) as the zero factor of Eq. 1."""
+    _need_factor_pair(desc, alpha, z, "z")
     if out is None:
         out = torch.empty_like(alpha)
+    _need(out, "out", torch.float32, tuple(alpha.shape), device=alpha.device)
     _check(load().qalora_beta_from_zero_point(ctypes.byref(desc), _p(alpha), _p(z), _p(out), _stream()),
            "qalora_beta_from_zero_point")
     return out
@@ -283,8 +372,10 @@ def beta_from_zero_point(desc: Desc, alpha, z, out=None):
 
 def zero_point_from_beta(desc: Desc, alpha, beta, out=None):
     """z = -(beta / alpha): export the zero factor as a zero point in code units."""
+    _need_factor_pair(desc, alpha, beta, "beta")
     if out is None:
         out = torch.empty_like(alpha)
+    _need(out, "out", torch.float32, tuple(alpha.shape), device=alpha.device)
     _check(load().qalora_zero_point_from_beta(ctypes.byref(desc), _p(alpha), _p(beta), _p(out), _stream()),
            "qalora_zero_point_from_beta")
     return out
@@ -301,6 +392,12 @@ def adamw_step(hp: AdamW, step: int, params, grads, exp_avg, exp_avg_sq, zero_gr
     """One fused AdamW step with a joint gradient-norm clip over lists of fp32 device tensors
     (updated in place).  ``grad_norm``: optional one-element fp32 device tensor for the norm."""
     n = len(params)
+    for ts, nm in ((params, "params"), (grads, "grads"), (exp_avg, "exp_avg"), (exp_avg_sq, "exp_avg_sq")):
+        if len(ts) != n:
+            raise ValueError(f"{nm}: {len(ts)} tensors, expected {n}")
+        for t, p0 in zip(ts, params):
+            _need(t, nm, torch.float32, tuple(p0.shape), device=params[0].device)
+    _need(grad_norm, "grad_norm", torch.float32, nbytes=4, optional=True)
     ptrs = [(ctypes.c_void_p * n)(*[t.data_ptr() for t in ts]) for ts in (params, grads, exp_avg, exp_avg_sq)]
     numel = (ctypes.c_size_t * n)(*[t.numel() for t in params])
     if ws is None:
@@ -312,15 +409,19 @@ def adamw_step(hp: AdamW, step: int, params, grads, exp_avg, exp_avg_sq, zero_gr
 
 def profile_copy(dst: torch.Tensor, src: torch.Tensor):
     """Plain copy kernel of known size (yardstick for the HBM traffic counters)."""
+    _need(src, "src")
     n = src.numel() * src.element_size()
-    assert dst.numel() * dst.element_size() == n
+    _need(dst, "dst", nbytes=n, device=src.device)
     _check(load().qalora_profile_copy(_p(dst), _p(src), n, _stream()), "qalora_profile_copy")
 
 
 def swiglu_forward(gate, up, out=None):
     """Harness glue: h = silu(gate) * up, bf16 tensors of equal shape."""
+    _need(gate, "gate", torch.bfloat16)
+    _need(up, "up", torch.bfloat16, tuple(gate.shape), device=gate.device)
     if out is None:
         out = torch.empty_like(gate)
+    _need(out, "out", torch.bfloat16, tuple(gate.shape), device=gate.device)
     _check(load().qalora_swiglu_forward(_p(gate), _p(up), _p(out), gate.numel(), _stream()),
            "qalora_swiglu_forward")
     return out
@@ -328,10 +429,15 @@ def swiglu_forward(gate, up, out=None):
 
 def swiglu_backward(dh, gate, up, dgate=None, dup=None):
     """Harness glue: gradients of h = silu(gate) * up with respect to gate and up (bf16)."""
+    _need(gate, "gate", torch.bfloat16)
+    _need(up, "up", torch.bfloat16, tuple(gate.shape), device=gate.device)
+    _need(dh, "dh", torch.bfloat16, tuple(gate.shape), device=gate.device)
     if dgate is None:
         dgate = torch.empty_like(gate)
     if dup is None:
         dup = torch.empty_like(up)
+    _need(dgate, "dgate", torch.bfloat16, tuple(gate.shape), device=gate.device)
+    _need(dup, "dup", torch.bfloat16, tuple(gate.shape), device=gate.device)
     _check(load().qalora_swiglu_backward(_p(dh), _p(gate), _p(up), _p(dgate), _p(dup), gate.numel(),
                                          _stream()), "qalora_swiglu_backward")
     return dgate, dup

@@ -1,6 +1,4 @@
 """Shared helpers of the GPU parity tests: upload seeded inputs, run the oracle, compare."""
-import os
-
 import numpy as np
 import torch
 
@@ -10,18 +8,9 @@ from paper_2309_14717_amd import synth
 TOL = 2e-3  # max|delta| / max|ref|, bf16 operands with fp32 accumulation
 
 
-_REPORT = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out",
-                       "parity_report.txt")
-
-
 def record(case, **errs):
-    """Append measured parity numbers to the report file of the run (best effort)."""
-    try:
-        os.makedirs(os.path.dirname(_REPORT), exist_ok=True)
-        with open(_REPORT, "a") as f:
-            f.write(case + " " + " ".join(f"{k}={v:.3e}" for k, v in errs.items()) + "\n")
-    except OSError:
-        pass
+    """Print the measured parity numbers of a case (shown by pytest -s / -rP)."""
+    print("parity", case, " ".join(f"{k}={v:.3e}" for k, v in errs.items()), flush=True)
 
 
 def rel_err(got, ref):

@@ -258,6 +258,32 @@ def test_declared_precision_mode_close_to_definition():
     assert 0 < rel < 5e-3
 
 
+def test_declared_precision_mode_is_the_definition_on_rounded_weights():
+    """The bf16 mode of forward AND backward is the exact mode applied to W~ rounded to bf16
+    (round to nearest even, written out here with torch's conversion): y and dx through numpy
+    matmuls on the rounded matrix; dA and dB do not depend on W~ and must not move."""
+    import torch
+    cfg = synth.LayerConfig("t", 12, 128, 40, 3, 32, 4, 0.75, seed=19)
+    d = synth.make_inputs(cfg)
+    c, a, b = oracle.quantize(d["W"], 3, 32)
+    Wt = oracle.dequantize(c, a, b, 32)
+    Wr = torch.from_numpy(Wt).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+    x, dy = d["x"].astype(np.float64), d["dy"].astype(np.float64)
+    A, B = d["A"].astype(np.float64), d["B"].astype(np.float64)
+    P = x.reshape(12, -1, 32).mean(axis=2)
+    y_ref = x @ Wr + cfg.s * (P @ A) @ B
+    dU = cfg.s * dy @ B.T
+    dx_ref = dy @ Wr.T + np.repeat(dU @ A.T, 32, axis=1) / 32
+    y = oracle.forward(d["x"], c, a, b, 32, d["A"], d["B"], cfg.s, round_wt_bf16=True)
+    dx, dA, dB = oracle.backward(d["dy"], d["x"], c, a, b, 32, d["A"], d["B"], cfg.s, round_wt_bf16=True)
+    _, dA0, dB0 = oracle.backward(d["dy"], d["x"], c, a, b, 32, d["A"], d["B"], cfg.s)
+    assert np.abs(y - y_ref).max() <= 1e-12 * np.abs(y_ref).max()
+    assert np.abs(dx - dx_ref).max() <= 1e-12 * np.abs(dx_ref).max()
+    assert np.array_equal(dA, dA0) and np.array_equal(dB, dB0)
+    dx_exact, _, _ = oracle.backward(d["dy"], d["x"], c, a, b, 32, d["A"], d["B"], cfg.s)
+    assert 0 < np.abs(dx - dx_exact).max() / np.abs(dx_exact).max() < 5e-3
+
+
 def test_table2_parameter_counts():
     """Sec. 3.3's counts L*r + r*D_out (QA-LoRA) and D_in*r + r*D_out (LoRA / QLoRA) over the
     seven linears of every decoder layer reproduce Table 2 (values in tests/golden)."""

@@ -23,8 +23,8 @@ def independent_quantize(W, bits, g):
             mn, mx = np.float32(col.min()), np.float32(col.max())
             a = np.float32(np.float32(mx - mn) / np.float32(qmax))
             beta[l, j] = mn
-            if not a > 0:
-                alpha[l, j] = 1.0
+            if not a > 0:  # constant group: Eq. 1 gives alpha = 0; placeholder step 2^-60, codes 0
+                alpha[l, j] = np.float32(2.0 ** -60)
                 continue
             alpha[l, j] = a
             q = np.rint((col - mn).astype(np.float32) / a)  # fp32 ops, ties to even
@@ -42,6 +42,23 @@ def test_brute_force_tiny(bits, g):
     assert np.array_equal(c, c2)
     assert np.array_equal(a.view(np.uint32), a2.view(np.uint32))
     assert np.array_equal(b.view(np.uint32), b2.view(np.uint32))
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_independent_agrees_on_constant_groups(bits):
+    """Constant groups (Eq. 1 gives alpha = 0 there) among ordinary ones: both implementations
+    give codes 0, beta = the value and the placeholder step, bit for bit."""
+    rng = np.random.default_rng(300 + bits)
+    W = (rng.standard_normal((16, 6)) * 0.02).astype(np.float32)
+    W[0:4, 1] = 0.25
+    W[8:12, 4] = -0.0078125
+    W[12:16, 5] = 0.0
+    c, a, b = oracle.quantize(W, bits, 4)
+    c2, a2, b2 = independent_quantize(W, bits, 4)
+    assert np.array_equal(c, c2)
+    assert np.array_equal(a.view(np.uint32), a2.view(np.uint32))
+    assert np.array_equal(b.view(np.uint32), b2.view(np.uint32))
+    assert a[0, 1] == np.float32(2.0 ** -60) and not c[0:4, 1].any() and b[0, 1] == np.float32(0.25)
 
 
 @pytest.mark.parametrize("bits,g", [(4, 32), (3, 64), (2, 128), (4, 256)])
