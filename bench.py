@@ -9,6 +9,9 @@ Workloads (``--workload``), all on seeded synthetic tensors already resident in 
   c3            the SwiGLU MLP block of one LLaMA-7B decoder layer: gate/up/down adapted linears,
                 forward and backward (dx, dA, dB of all three); the elementwise glue is torch.
   c4            one layer of the LLaMA-13B low-bit sweep at --bits / --group.
+  probe         measurement aids only (no layer): what the matrix cores sustain under the
+                instruction mixes of the contraction kernel (qalora_profile_mfma_probe) and the
+                rate of the vendor library's plain fp16 / bf16 product on the same box.
   c5            post-merge inference at --tokens (1, 4, 16 or 256): one forward of the
                 8192x22016 layer plus one of the 22016x8192 layer, rotating over eight weight
                 sets (> 1 GB) so that nothing is served from the last-level cache.
@@ -239,7 +242,7 @@ def run_steps(torch, api, step, steps, warmup, directions=(0, 1), arm_every=None
     for d, t in timers.items():  # median and minimum of the same samples, for the record
         ms = np.asarray(t.elapsed_ms())
         KERNEL_STATS[d] = {"median_ms": round(float(np.median(ms)), 5), "min_ms": round(float(ms.min()), 5),
-                           "samples": int(ms.size)}
+                           "samples": int(ms.size), "block_cycles": t.block_cycles()}
     clk = {d: t.shader_clock_ghz() for d, t in timers.items()}
     for t in timers.values():
         t.close()
@@ -309,6 +312,35 @@ def adamw_layer_timing(torch, api, d=4096, ff=11008, g=32, r=64):
             "frac_hbm": round(32.0 * n / ms / 1e6 / PEAK_HBM_GBS, 4)}
 
 
+def probe_report(torch, api):
+    """Ceilings of the dense contraction on this machine: issue interval, clock and rate of the
+    matrix instruction alone, with the operand reads from LDS, and with n vector instructions
+    behind each one (all 256 compute units busy, and 16 of them for comparison); and the vendor
+    library's plain product (torch.matmul) at two sizes."""
+    rows = []
+    for blocks in (16, 256):
+        for shape, lds, nv in ((0, 0, 0), (0, 1, 0), (0, 1, 2), (0, 1, 4), (0, 1, 6), (0, 1, 8),
+                               (1, 0, 0), (1, 1, 0), (1, 1, 2), (1, 1, 4)):
+            cyc, ghz, tf = api.mfma_probe(shape, bool(lds), nv, iters=2000, blocks=blocks)
+            rows.append({"blocks": blocks, "wavefronts_x_tiles": "8 x (4x2)" if shape == 0 else "4 x (4x4)",
+                         "lds_fragment_reads": bool(lds), "valu_per_mfma": nv,
+                         "cycles_per_mfma_per_simd": round(cyc, 2), "shader_clock_ghz": round(ghz, 3),
+                         "TFLOP/s": round(tf, 1), "frac_of_peak": round(tf / PEAK_MFMA_TFLOPS, 4)})
+    vendor = []
+    for n in (4096, 8192):
+        for dt, name in ((torch.float16, "f16"), (torch.bfloat16, "bf16")):
+            a = torch.randn((n, n), device="cuda").to(dt)
+            b = torch.randn((n, n), device="cuda").to(dt)
+            c = torch.empty((n, n), device="cuda", dtype=dt)
+            ms = timed(torch, lambda: torch.matmul(a, b, out=c), n=50, warm=10)
+            tf = 2.0 * n ** 3 / ms / 1e9
+            vendor.append({"n": n, "dtype": name, "ms": round(ms, 4), "TFLOP/s": round(tf, 1),
+                           "frac_of_peak": round(tf / PEAK_MFMA_TFLOPS, 4)})
+            del a, b, c
+    return {"workload": "probe: matrix-core issue probes and the vendor library's plain product",
+            "mfma_probe": rows, "vendor_gemm": vendor}
+
+
 def cpu_model():
     try:
         for line in open("/proc/cpuinfo"):
@@ -337,7 +369,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "probe"])
     ap.add_argument("--bits", type=int, default=4, help="c4, c5: code width (c5 is defined at 4)")
     ap.add_argument("--group", type=int, default=32, help="c4: group size")
     ap.add_argument("--tokens", type=int, default=16, help="c5: tokens per call")
@@ -377,6 +409,10 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.workload == "probe":
+        print(json.dumps(probe_report(torch, api)))
+        return
+
     if args.workload in ("c1", "c2", "c4"):
         cfg = synth.CONFIGS[args.workload]
         if args.workload == "c4":
@@ -402,7 +438,8 @@ def main():
         st = KERNEL_STATS.get(0 if dom[0] == "fwd" else 1)
         if st:
             roofline.update({"kernel_ms_median": st["median_ms"], "kernel_ms_min": st["min_ms"],
-                             "kernel_samples": st["samples"]})
+                             "kernel_samples": st["samples"],
+                             "first_block_shader_cycles": st["block_cycles"]})
         workload = (f"{cfg.name}: QA-LoRA linear fwd+bwd, T={cfg.tokens}, {cfg.d_in}x{cfg.d_out}, "
                     f"INT{cfg.bits} g={cfg.group}, rank {cfg.rank}, s={cfg.s}, x/dy bf16, outputs {args.out_dtype}")
         if not args.no_extras:

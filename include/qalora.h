@@ -135,8 +135,14 @@ int qalora_pack(const qalora_desc* desc, const uint8_t* codes, void* packed, voi
  * streaming kernel takes over (one column per lane for tokens <= 4 and for the 2- and 3-bit
  * codes, a sixteen-token tile -- two of them beyond sixteen tokens -- for 4-bit codes) whose
  * operands are exact (only the fp32 accumulation
- * order differs from the definition); its cross-block sum waits on flags with a bound -- should a wait ever run out
- * (another kernel holding the compute units for ~0.3 s) the affected outputs are NaN. */
+ * order differs from the definition); its cross-block sum waits on flags with a bound -- should a
+ * wait ever run out (another kernel holding the compute units for ~0.3 s) the affected outputs
+ * are NaN and the kernel sets the 64-bit word at byte QALORA_WS_STATUS_OFFSET of ws to a non-zero
+ * value.  The library only ever sets that word: a caller who wants the status zeroes it once
+ * (e.g. when allocating ws) and reads it after the stream has completed; after a non-zero
+ * status the first QALORA_WS_STATUS_OFFSET bytes of ws must be zeroed before ws is used again
+ * (a late flag of the failed call may still be there). */
+#define QALORA_WS_STATUS_OFFSET 2048
 int qalora_forward(const qalora_desc* desc, int tokens, const void* x, const void* packed,
                    const float* alpha, const float* beta, const float* A, const float* B,
                    void* y, int y_dtype, void* ws, size_t ws_bytes, void* stream);
@@ -269,6 +275,20 @@ int qalora_profile_event_destroy(void* event);
  * pointers 16-byte aligned, buffers must not overlap).  It reads and writes exactly `bytes` of
  * HBM once, which makes it the yardstick the hardware traffic counters are scaled by. */
 int qalora_profile_copy(void* dst, const void* src, size_t bytes, void* stream);
+
+/* Measurement aid: an issue-rate probe of the matrix cores.  `blocks` blocks each run `iters` K
+ * steps (64 deep) of the inner loop of a dense contraction with only the instruction mix left:
+ * v_mfma_f32_32x32x16_f16 on register accumulators, with (lds_reads = 1) or without the operand
+ * fragment reads from LDS, and valu_per_mfma ordinary vector instructions behind every matrix
+ * instruction.  shape 0: eight wavefronts of 4 x 2 tiles per block (valu_per_mfma in
+ * {0,2,4,6,8}; 0 only without LDS reads); shape 1: four wavefronts of 4 x 4 tiles (valu in
+ * {0,2,4}).  Other combinations return QALORA_EINVAL.  Block b stores its shader cycles and
+ * wall-clock ticks over the loop to counts[2b], counts[2b+1] (device, 16 * blocks bytes); sink
+ * is device scratch of 2048 * blocks bytes.  A block issues iters * 32 (shape 0: per wavefront,
+ * two wavefronts per SIMD; shape 1: iters * 64, one wavefront per SIMD) matrix instructions per
+ * wavefront. */
+int qalora_profile_mfma_probe(int shape, int lds_reads, int valu_per_mfma, int iters, int blocks,
+                              void* sink, void* counts, void* stream);
 
 /* Benchmark-harness glue, not part of the QA-LoRA layer: the elementwise part of a LLaMA
  * SwiGLU MLP block around three adapted linears (the MLP-block workload of the benchmark).

@@ -30,6 +30,7 @@ EXPORTS = (
     "qalora_pack_factors16", "qalora_forward_factors16",
     "qalora_adamw_workspace_bytes", "qalora_adamw_step",
     "qalora_kept_bytes", "qalora_forward_keep", "qalora_backward_kept",
+    "qalora_profile_mfma_probe",
 )
 
 
@@ -72,6 +73,7 @@ def load() -> ctypes.CDLL:
     lib.qalora_forward.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
     lib.qalora_backward.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, vp, i, vp, vp, i, vp, sz, vp]
     lib.qalora_merge.argtypes = [cp, vp, vp, vp, vp, vp]
+    lib.qalora_profile_mfma_probe.argtypes = [i, i, i, i, i, vp, vp, vp]
     lib.qalora_kept_bytes.restype = sz
     lib.qalora_kept_bytes.argtypes = [cp, i]
     lib.qalora_forward_keep.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, i, vp, vp, sz, vp]
@@ -237,6 +239,16 @@ def forward(desc: Desc, x, packed, alpha, beta, A=None, B=None, out_dtype=torch.
                                ws_bytes, _stream())
     _check(rc, "qalora_forward")
     return y
+
+
+WS_STATUS_OFFSET = 2048
+
+
+def streaming_status(ws) -> int:
+    """The status word the few-token kernels set in a forward workspace when a bounded wait ran
+    out (0 = never, provided the caller zeroed it first).  Synchronises."""
+    _need(ws, "ws", nbytes=WS_STATUS_OFFSET + 8)
+    return int(ws.view(torch.uint8)[WS_STATUS_OFFSET:WS_STATUS_OFFSET + 8].cpu().view(torch.int64).item())
 
 
 def pack_factors16(desc: Desc, alpha, beta, out=None):
@@ -415,6 +427,25 @@ def profile_copy(dst: torch.Tensor, src: torch.Tensor):
     _check(load().qalora_profile_copy(_p(dst), _p(src), n, _stream()), "qalora_profile_copy")
 
 
+def mfma_probe(shape: int, lds_reads: bool, valu_per_mfma: int, iters: int = 500, blocks: int = 256):
+    """Issue-rate probe of the matrix cores (measurement aid).  Returns (cycles per matrix
+    instruction per SIMD, shader clock in GHz, TFLOP/s) over all blocks of the launch."""
+    sink = torch.empty(blocks * 512, dtype=torch.float32, device="cuda")
+    counts = torch.zeros((blocks, 2), dtype=torch.int64, device="cuda")
+    for _ in range(2):  # the second launch runs at the clock the mix settles to
+        _check(load().qalora_profile_mfma_probe(int(shape), 1 if lds_reads else 0, int(valu_per_mfma), int(iters),
+                                                int(blocks), _p(sink), _p(counts), _stream()), "qalora_profile_mfma_probe")
+        torch.cuda.synchronize()
+    khz = ctypes.c_int()
+    _check(load().qalora_profile_wall_clock_khz(ctypes.byref(khz)), "wall_clock_khz")
+    c = counts.cpu().double()
+    cycles, ticks = c[:, 0].mean().item(), c[:, 1].mean().item()
+    per_simd = iters * 64.0  # matrix instructions per SIMD: 32 per K step per wavefront, 2 wavefronts (or 64, 1)
+    seconds = ticks / (khz.value * 1e3)
+    flops = blocks * 4 * per_simd * 2.0 * 32 * 32 * 16
+    return cycles / per_simd, cycles / ticks * khz.value * 1e3 / 1e9, flops / seconds / 1e12
+
+
 def swiglu_forward(gate, up, out=None):
     """Harness glue: h = silu(gate) * up, bf16 tensors of equal shape."""
     _need(gate, "gate", torch.bfloat16)
@@ -477,6 +508,13 @@ class KernelTimer:
         if not bool(ok.any()):
             return None
         return float((cycles[ok] / ticks[ok]).mean()) * khz.value * 1e3 / 1e9
+
+    def block_cycles(self):
+        """Mean shader cycles the armed kernels' first blocks lived for (None if not reported)."""
+        c = self.counts[: self.used].cpu().double()
+        cycles = c[:, 2] - c[:, 0]
+        ok = (c[:, 3] - c[:, 1]) > 0
+        return float(cycles[ok].mean()) if bool(ok.any()) else None
 
     def elapsed_ms(self):
         out = []

@@ -144,8 +144,10 @@ inline size_t smallt_workspace(const qalora_desc& d, int tokens) {
   const int blocks = (tokens <= 4 || d.bits != 4) ? smallt4_plan(d.d_in, d.d_out, tokens).blocks
                                                   : smallt_plan(d.d_in, d.d_out, tokens).blocks;
   const size_t per_block = (size_t)(tokens > 16 ? 2 : 1) * ST_PARTIAL_FLOATS;  // two groups of sixteen tokens
-  return align_up((size_t)ST_MAX_BLOCKS * 8) + align_up((size_t)blocks * per_block * 4);
+  return ST_HEAD_BYTES + align_up((size_t)blocks * per_block * 4);
 }
+
+static_assert(ST_STATUS_OFFSET == QALORA_WS_STATUS_OFFSET, "the header documents this offset");
 
 }  // namespace
 
@@ -329,7 +331,8 @@ static int forward_impl(const qalora_desc* d, int tokens, const void* x, const v
     a.beta = beta;
     a.out = y;
     a.flags = static_cast<unsigned long long*>(ws);
-    a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + align_up((size_t)ST_MAX_BLOCKS * 8));
+    a.status = a.flags + ST_MAX_BLOCKS;
+    a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + ST_HEAD_BYTES);
     a.out_bf16 = (y_dtype == QALORA_BF16);
     a.T = tokens;
     a.d_in = d->d_in;
@@ -558,7 +561,8 @@ int qalora_forward_factors16(const qalora_desc* d, int tokens, const void* x, co
     a.fac16 = static_cast<const uint32_t*>(factors16);
     a.out = y;
     a.flags = static_cast<unsigned long long*>(ws);
-    a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + align_up((size_t)ST_MAX_BLOCKS * 8));
+    a.status = a.flags + ST_MAX_BLOCKS;
+    a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + ST_HEAD_BYTES);
     a.out_bf16 = (y_dtype == QALORA_BF16);
     a.T = tokens;
     a.d_in = d->d_in;
@@ -713,6 +717,17 @@ int qalora_profile_copy(void* dst, const void* src, size_t bytes, void* stream) 
   profile_copy_kernel<<<blocks, 256, 0, as_stream(stream)>>>(static_cast<const uint4*>(src),
                                                               static_cast<uint4*>(dst), n16);
   return hipGetLastError() == hipSuccess ? QALORA_OK : QALORA_EHIP;
+}
+
+int qalora_profile_mfma_probe(int shape, int lds_reads, int valu_per_mfma, int iters, int blocks,
+                              void* sink, void* counts, void* stream) {
+  if (!sink || !counts || iters <= 0 || blocks <= 0 || blocks > 65536) return QALORA_EINVAL;
+  if (misaligned(sink) || misaligned(counts)) return QALORA_EALIGN;
+  const hipError_t e = launch_mfma_probe(shape, lds_reads, valu_per_mfma, static_cast<float*>(sink),
+                                         static_cast<unsigned long long*>(counts), iters, blocks,
+                                         as_stream(stream));
+  if (e == hipErrorInvalidValue) return QALORA_EINVAL;
+  return e == hipSuccess ? QALORA_OK : QALORA_EHIP;
 }
 
 int qalora_swiglu_forward(const void* gate, const void* up, void* h, size_t n, void* stream) {

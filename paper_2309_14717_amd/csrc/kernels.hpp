@@ -59,6 +59,10 @@ int gemm_plain_tile_rows(int K);  // row tile launch_gemm_plain uses for a K of 
 // Adapter-free forward for T <= 16 tokens, INT4, group 32 / 64 / 128 (memory-bound path).
 constexpr int ST_MAX_BLOCKS = 256; // one block per compute unit
 constexpr int ST_PARTIAL_FLOATS = 16 * 512;  // one [16 tokens x widest slab] tile per block
+// Head of the small-token workspace: one 64-bit flag per block, then one 64-bit status word that
+// a kernel sets (and never clears) when a bounded wait for a flag ran out; partials follow.
+constexpr size_t ST_STATUS_OFFSET = (size_t)ST_MAX_BLOCKS * 8;
+constexpr size_t ST_HEAD_BYTES = ((ST_STATUS_OFFSET + 8 + 255) / 256) * 256;
 struct SmallTArgs {
   const uint16_t* x;       // bf16 [T, d_in]
   const uint32_t* plane0;  // packed codes (INT3: the low two bits)
@@ -69,6 +73,7 @@ struct SmallTArgs {
   void* out;               // [T, d_out] fp32 or bf16
   float* partial;          // [blocks][ST_PARTIAL_FLOATS] fp32: each block's [token][slab column] tile
   unsigned long long* flags;  // [blocks]: set to `nonce` once the block's partial is complete
+  unsigned long long* status; // one word: set to a non-zero value if a wait for a flag ran out
   unsigned long long nonce;   // filled in by the launcher, unique per call
   int out_bf16;
   int T, d_in, d_out, group;
@@ -158,6 +163,10 @@ struct OptHyper {
   int zero_grads;
 };
 hipError_t launch_adamw(const OptTensors& t, const OptHyper& h, float* partial, float* norm_out, hipStream_t st);
+
+// --- probe.hip (measurement aid): issue-rate probe of the matrix cores ----------------------
+hipError_t launch_mfma_probe(int shape, int lds_reads, int valu_per_mfma, float* sink,
+                             unsigned long long* counts, int iters, int blocks, hipStream_t st);
 
 // --- glue.hip (benchmark-harness glue, not part of the layer) --------------------------
 // h = silu(gate) * up over n bf16 elements (n a multiple of 8), and its backward.

@@ -382,16 +382,23 @@ __global__ __launch_bounds__(ST_THREADS) void smallt_kernel(const SmallTArgs p) 
         // one thread per flag, all polling at once
         for (int i = tid; i < m - 1; i += ST_THREADS) {
           uint32_t spins = 0;
+          bool timed_out = false;
           while (__hip_atomic_load(p.flags + bf + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != p.nonce) {
             if (++spins > ST_SPIN_LIMIT) {
               poison = 1;
+              timed_out = true;
               break;
             }
             __builtin_amdgcn_s_sleep(8);
           }
           // Consumed: clear it, so that a replay of this very launch (a captured graph repeats
-          // the nonce) waits for its own producers instead of seeing this launch's flags.
-          __hip_atomic_store(p.flags + bf + i, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          // the nonce) waits for its own producers instead of seeing this launch's flags.  A flag
+          // that never came is left alone and reported: its producer may still write it, and a
+          // workspace in that state must be cleared by the caller before it is used again.
+          if (!timed_out)
+            __hip_atomic_store(p.flags + bf + i, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          else
+            __hip_atomic_store(p.status, p.nonce | 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __syncthreads();
         // partials in part order, PB blocks' loads in flight at a time
