@@ -147,6 +147,24 @@ int qalora_forward(const qalora_desc* desc, int tokens, const void* x, const voi
                    const float* alpha, const float* beta, const float* A, const float* B,
                    void* y, int y_dtype, void* ws, size_t ws_bytes, void* stream);
 
+/* For callers that cannot allocate or carry a workspace -- code under HIP graph capture, tight
+ * decode loops, harnesses that forbid hipMalloc: qalora_forward for the adapter-free few-token
+ * regime (A = B = NULL; tokens <= QALORA_NOALLOC_MAX_TOKENS; shapes of the streaming kernel:
+ * group 32/64/128, d_in a multiple of 128) with the flags and partial sums of the cross-block
+ * sum in a device array built into the library (QALORA_NOALLOC_SCRATCH_BYTES per GPU, held from
+ * first use until the process ends) instead of a caller workspace.  Anything beyond that
+ * returns QALORA_EUNSUPPORTED; nothing is allocated, freed or synchronised.  Same kernels and
+ * results, bit for bit, as qalora_forward.  All calls on one GPU share that array: calls that
+ * may overlap on one GPU (different streams or threads) race -- serialise them or use
+ * qalora_forward with a workspace per stream.  The first call on each device looks up the
+ * array's address (not stream work: make it outside graph capture, like the first call of any
+ * kernel here).  A wait that runs out gives NaN outputs, as above. */
+#define QALORA_NOALLOC_MAX_TOKENS 16
+#define QALORA_NOALLOC_SCRATCH_BYTES (2304 + 256 * 16 * 512 * 4)
+int qalora_forward_noalloc(const qalora_desc* desc, int tokens, const void* x, const void* packed,
+                           const float* alpha, const float* beta, void* y, int y_dtype,
+                           void* stream);
+
 /* Backward of qalora_forward with W~ frozen: only A and B are parameters (Alg. 1),
  * so with G = dy, P = pool_g(x), U = P A:
  *   dU = s G B^T,  dB = s U^T G,  dA = P^T dU,
@@ -281,8 +299,8 @@ int qalora_profile_copy(void* dst, const void* src, size_t bytes, void* stream);
  * v_mfma_f32_32x32x16_f16 on register accumulators, with (lds_reads = 1) or without the operand
  * fragment reads from LDS, and valu_per_mfma ordinary vector instructions behind every matrix
  * instruction.  shape 0: eight wavefronts of 4 x 2 tiles per block (valu_per_mfma in
- * {0,2,4,6,8}; 0 only without LDS reads); shape 1: four wavefronts of 4 x 4 tiles (valu in
- * {0,2,4}).  Other combinations return QALORA_EINVAL.  Block b stores its shader cycles and
+ * {0,2,4,6,8}; 0 only without LDS reads); shape 1: four wavefronts of 4 x 4 tiles (same
+ * choices).  Other combinations return QALORA_EINVAL.  Block b stores its shader cycles and
  * wall-clock ticks over the loop to counts[2b], counts[2b+1] (device, 16 * blocks bytes); sink
  * is device scratch of 2048 * blocks bytes.  A block issues iters * 32 (shape 0: per wavefront,
  * two wavefronts per SIMD; shape 1: iters * 64, one wavefront per SIMD) matrix instructions per

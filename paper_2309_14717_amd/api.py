@@ -30,7 +30,7 @@ EXPORTS = (
     "qalora_pack_factors16", "qalora_forward_factors16",
     "qalora_adamw_workspace_bytes", "qalora_adamw_step",
     "qalora_kept_bytes", "qalora_forward_keep", "qalora_backward_kept",
-    "qalora_profile_mfma_probe",
+    "qalora_forward_noalloc", "qalora_profile_mfma_probe",
 )
 
 
@@ -74,6 +74,7 @@ def load() -> ctypes.CDLL:
     lib.qalora_backward.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, vp, i, vp, vp, i, vp, sz, vp]
     lib.qalora_merge.argtypes = [cp, vp, vp, vp, vp, vp]
     lib.qalora_profile_mfma_probe.argtypes = [i, i, i, i, i, vp, vp, vp]
+    lib.qalora_forward_noalloc.argtypes = [cp, i, vp, vp, vp, vp, vp, i, vp]
     lib.qalora_kept_bytes.restype = sz
     lib.qalora_kept_bytes.argtypes = [cp, i]
     lib.qalora_forward_keep.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, i, vp, vp, sz, vp]
@@ -238,6 +239,18 @@ def forward(desc: Desc, x, packed, alpha, beta, A=None, B=None, out_dtype=torch.
                                _p(B), _p(y), BF16 if y.dtype == torch.bfloat16 else F32, _p(ws),
                                ws_bytes, _stream())
     _check(rc, "qalora_forward")
+    return y
+
+
+def forward_noalloc(desc: Desc, x, packed, alpha, beta, out_dtype=torch.float32, y=None):
+    """Adapter-free few-token forward on the library's built-in scratch (no workspace)."""
+    T, dev = _need_layer(desc, x, desc.d_in, packed, alpha, beta, None, None)
+    if y is None:
+        y = torch.empty((T, desc.d_out), dtype=out_dtype, device=dev)
+    _need_out(y, "y", T, desc.d_out, dev)
+    rc = load().qalora_forward_noalloc(ctypes.byref(desc), T, _p(x), _p(packed), _p(alpha), _p(beta), _p(y),
+                                       BF16 if y.dtype == torch.bfloat16 else F32, _stream())
+    _check(rc, "qalora_forward_noalloc")
     return y
 
 

@@ -149,6 +149,34 @@ inline size_t smallt_workspace(const qalora_desc& d, int tokens) {
 
 static_assert(ST_STATUS_OFFSET == QALORA_WS_STATUS_OFFSET, "the header documents this offset");
 
+// Scratch of qalora_forward_noalloc: the streaming kernels' flags, status word and per-block
+// partial sums for up to sixteen tokens.  Host code never uses this name as an address; the
+// device address is looked up once per device (scratch_on_current_device).
+constexpr size_t kScratchBytes = ST_HEAD_BYTES + (size_t)ST_MAX_BLOCKS * ST_PARTIAL_FLOATS * 4;
+static_assert(kScratchBytes == QALORA_NOALLOC_SCRATCH_BYTES, "the header documents this size");
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];  // device address of `scratch`, per device
+
+// Device address of this device's copy of the scratch array (every device holds its own, at
+// its own address); looked up on the first call with that device current.
+hipError_t scratch_on_current_device(void** out) {
+  int dev = 0;
+  if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if (hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)); e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
+  *out = ptr;
+  return hipSuccess;
+}
 }  // namespace
 
 // Plain copy of known size: the yardstick the HBM traffic counters are scaled by.
@@ -527,6 +555,38 @@ int qalora_merge(const qalora_desc* d, const float* beta, const float* A, const 
                       as_stream(stream)) == hipSuccess
              ? QALORA_OK
              : QALORA_EHIP;
+}
+
+int qalora_forward_noalloc(const qalora_desc* d, int tokens, const void* x, const void* packed,
+                           const float* alpha, const float* beta, void* y, int y_dtype, void* stream) {
+  const int rc = qalora_check_desc(d);
+  if (rc != QALORA_OK) return rc;
+  if (tokens <= 0 || !x || !packed || !alpha || !beta || !y) return QALORA_EINVAL;
+  if (y_dtype != QALORA_F32 && y_dtype != QALORA_BF16) return QALORA_EINVAL;
+  if (misaligned(x) || misaligned(packed) || misaligned(alpha) || misaligned(beta) || misaligned(y))
+    return QALORA_EALIGN;
+  // beyond what the built-in scratch holds, or outside the streaming kernels' shapes
+  if (tokens > QALORA_NOALLOC_MAX_TOKENS || !use_smallt(*d, tokens)) return QALORA_EUNSUPPORTED;
+  if (smallt_workspace(*d, tokens) > kScratchBytes) return QALORA_EUNSUPPORTED;
+  void* ptr = nullptr;
+  if (scratch_on_current_device(&ptr) != hipSuccess) return QALORA_EHIP;
+  SmallTArgs a{};
+  a.x = static_cast<const uint16_t*>(x);
+  a.plane0 = static_cast<const uint32_t*>(packed);
+  a.plane1 = a.plane0 + plane0_words(d->bits, d->d_in, d->d_out);
+  a.bits = d->bits;
+  a.alpha = alpha;
+  a.beta = beta;
+  a.out = y;
+  a.flags = static_cast<unsigned long long*>(ptr);
+  a.status = a.flags + ST_MAX_BLOCKS;
+  a.partial = reinterpret_cast<float*>(static_cast<char*>(ptr) + ST_HEAD_BYTES);
+  a.out_bf16 = (y_dtype == QALORA_BF16);
+  a.T = tokens;
+  a.d_in = d->d_in;
+  a.d_out = d->d_out;
+  a.group = d->group;
+  return launch_smallt(a, as_stream(stream)) == hipSuccess ? QALORA_OK : QALORA_EHIP;
 }
 
 int qalora_pack_factors16(const qalora_desc* d, const float* alpha, const float* beta, void* factors16,
