@@ -320,7 +320,7 @@ def probe_report(torch, api):
     rows = []
     for blocks in (16, 256):
         for shape, lds, nv in ((0, 0, 0), (0, 1, 0), (0, 1, 2), (0, 1, 4), (0, 1, 6), (0, 1, 8),
-                               (1, 0, 0), (1, 1, 0), (1, 1, 2), (1, 1, 4)):
+                               (1, 0, 0), (1, 1, 0), (1, 1, 2), (1, 1, 4), (1, 1, 6), (1, 1, 8)):
             cyc, ghz, tf = api.mfma_probe(shape, bool(lds), nv, iters=2000, blocks=blocks)
             rows.append({"blocks": blocks, "wavefronts_x_tiles": "8 x (4x2)" if shape == 0 else "4 x (4x4)",
                          "lds_fragment_reads": bool(lds), "valu_per_mfma": nv,

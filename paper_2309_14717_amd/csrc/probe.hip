@@ -26,9 +26,23 @@ typedef uint32_t pu32x4 __attribute__((ext_vector_type(4)));
 template <int WAVES, int TM, int TN, bool LDS, int NV>
 __global__ __launch_bounds__(WAVES * 64) void mfma_probe_kernel(float* sink, unsigned long long* counts,
                                                                 int iters) {
-  __shared__ pu32x4 lds[4096];  // 64 KB of fp16 ones
-  for (int i = threadIdx.x; i < 4096; i += WAVES * 64)
-    lds[i] = pu32x4{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
+  // 64 KB of fp16 values of either sign with magnitudes in [0.5, 2) and hashed mantissas:
+  // operands that toggle the data paths the way real tiles do (constant operands would let the
+  // chip hold a clock it does not hold on real data)
+  __shared__ pu32x4 lds[4096];
+  for (int i = threadIdx.x; i < 4096; i += WAVES * 64) {
+    pu32x4 v;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      uint32_t h = (uint32_t)(i * 4 + c) * 0x9e3779b9u + blockIdx.x * 0x85ebca6bu;
+      h ^= h >> 15;
+      h *= 0x2c1b3c6du;
+      h ^= h >> 12;
+      // per half-word: sign, exponent 14 or 15 (0.5 .. 2), ten mantissa bits
+      v[c] = (h & 0x87ff87ffu) | 0x38003800u;
+    }
+    lds[i] = v;
+  }
   __syncthreads();
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -84,6 +98,9 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_probe_kernel(float* sink, uns
       __builtin_amdgcn_sched_barrier(0);
     }
   }
+  // the block is done when its last wavefront is: the issue arbiter favours the oldest
+  // wavefront of a SIMD, so the first one alone would report the rate of a SIMD it does not share
+  __syncthreads();
   const unsigned long long c1 = clock64(), w1 = wall_clock64();
   float s = 0.0f;
 #pragma unroll
@@ -132,6 +149,8 @@ hipError_t launch_mfma_probe(int shape, int lds_reads, int valu_per_mfma, float*
       case 0: return run<4, 4, 4, true, 0>(sink, counts, iters, blocks, st);
       case 2: return run<4, 4, 4, true, 2>(sink, counts, iters, blocks, st);
       case 4: return run<4, 4, 4, true, 4>(sink, counts, iters, blocks, st);
+      case 6: return run<4, 4, 4, true, 6>(sink, counts, iters, blocks, st);
+      case 8: return run<4, 4, 4, true, 8>(sink, counts, iters, blocks, st);
       default: return hipErrorInvalidValue;
     }
   }

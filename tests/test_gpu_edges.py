@@ -161,3 +161,44 @@ def test_zero_adapter_matches_adapter_free(gpu_api):
     _, _, rdB = oracle.backward(d["dy"], d["x"], L["codes"], L["alpha"], L["beta"], cfg.group,
                                 d["A"], d["B"], cfg.s, want_dx=False)
     assert rel_err(dB.cpu().numpy(), rdB) <= TOL and dB.abs().max().item() > 0
+
+
+def test_binding_rejects_mismatched_tensors(gpu_api):
+    """The C ABI sees raw pointers only, so the binding checks every operand's shape, dtype and
+    device against the descriptor before marshalling: a mismatch is an exception, never an
+    out-of-bounds access on the device."""
+    cfg = synth.LayerConfig("val", 8, 256, 64, 4, 32, 8, 0.5, seed=3)
+    L = layer_on_gpu(gpu_api, cfg)
+    ok = (L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"], L["A"], L["B"])
+    gpu_api.forward(*ok)
+    bad_cases = [
+        (L["desc"], L["x"][:, :128].contiguous(), *ok[2:]),          # x narrower than d_in
+        (L["desc"], L["x"].float(), *ok[2:]),                        # x not bf16
+        (L["desc"], L["x"], L["packed"][:-16], *ok[3:]),             # packed too short
+        (L["desc"], L["x"], L["packed"], L["g_alpha"][:-1], *ok[4:]),  # alpha short of a group row
+        (L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"].double(), L["A"], L["B"]),
+        (*ok[:5], L["A"][:, :4].contiguous(), L["B"]),               # A of the wrong rank
+        (*ok[:5], L["A"], L["B"].cpu()),                             # B on the host
+    ]
+    for args in bad_cases:
+        with pytest.raises(ValueError):
+            gpu_api.forward(*args)
+    with pytest.raises(ValueError):
+        gpu_api.forward(*ok, y=torch.empty((8, 32), device="cuda"))
+    with pytest.raises(ValueError):
+        gpu_api.backward(L["desc"], L["dy"][:, :32].contiguous(), *ok[1:])
+    with pytest.raises(ValueError):
+        gpu_api.backward(L["desc"], L["dy"], L["x"][:4].contiguous(), *ok[2:])
+    with pytest.raises(ValueError):
+        gpu_api.merge(L["desc"], L["g_beta"], L["A"], L["B"][:, :32].contiguous())
+
+
+def test_streaming_status_word_stays_clear(gpu_api):
+    """A few-token forward that completes leaves the workspace's status word as the caller set
+    it (zero): the word is only written when a bounded wait for another block runs out."""
+    cfg = synth.LayerConfig("stat", 4, 2048, 2048, 4, 32, 8, 0.5, seed=5)
+    L = layer_on_gpu(gpu_api, cfg)
+    ws = torch.zeros(gpu_api.workspace_bytes(L["desc"], 16, gpu_api.OP_FORWARD), dtype=torch.uint8, device="cuda")
+    for T in (1, 4):
+        gpu_api.forward(L["desc"], L["x"][:T].contiguous(), L["packed"], L["g_alpha"], L["g_beta"], ws=ws)
+    assert gpu_api.streaming_status(ws) == 0

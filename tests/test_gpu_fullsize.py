@@ -211,7 +211,16 @@ def test_config3_mlp_block_end_to_end(gpu_api):
         errs["dA_" + name] = rel_err(grads_gpu[name][0], rA)
         errs["dB_" + name] = rel_err(grads_gpu[name][1], rB)
     record("fullsize c3 block end to end", **errs)
-    # y and dx are bf16 here: one bf16 ulp at the largest element is 2^-8 of it, which the
-    # fp32-output bar cannot see through, so they get the rounding step on top of the bar
-    assert errs["y"] <= TOL + 2.0 ** -8 and errs["dx"] <= TOL + 2.0 ** -8, errs
-    assert max(v for k, v in errs.items() if k[0] == "d" and k != "dx") <= TOL, errs
+    # Bars of the chain.  Each contraction on the path to an output may be off by TOL of its own
+    # maximum (the bar of a single layer), and each activation the block stores in bf16 by one
+    # rounding, 2^-9 relative; both carry through the linear stages that follow at most
+    # undiminished, so the bar of an output is the sum over its path (measured values sit at a
+    # third to a half of it, the independent errors adding in quadrature):
+    #   y      : gate|up, down                      2 contractions, roundings g|u, h, y
+    #   dx     : down bwd, gate|up fwd, gate|up bwd  3 contractions, roundings g|u, dh, dg|du, dx1|dx2, sum
+    #   dA, dB of gate, up : down bwd, gate|up fwd, own products   3 contractions, roundings g|u, dh, dg|du
+    #   dA, dB of down     : gate|up fwd (through h), own products 2 contractions, roundings g|u, h
+    r = 2.0 ** -9
+    bars = dict(y=2 * TOL + 3 * r, dx=3 * TOL + 5 * r, dA_gate=3 * TOL + 3 * r, dB_gate=3 * TOL + 3 * r,
+                dA_up=3 * TOL + 3 * r, dB_up=3 * TOL + 3 * r, dA_down=2 * TOL + 2 * r, dB_down=2 * TOL + 2 * r)
+    assert all(errs[k] <= bars[k] for k in bars), (errs, bars)
