@@ -221,13 +221,13 @@ def run_steps(torch, api, step, steps, warmup, directions=(0, 1), arm_every=None
     around the dense kernel on every `arm_every`-th step of the timed region (an armed launch
     costs the stream a few microseconds of event handling, which would otherwise weigh on
     `value` -- by 10 % for the 30 us kernels of the small-token workload).  Short runs arm every
-    step so that the kernel figure still rests on a few dozen samples."""
+    second step so that the kernel figure still rests on ten samples or more."""
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     SETTLE["steps"] = settle(torch, step)
     if arm_every is None:
-        arm_every = 1 if steps <= 50 else 4
+        arm_every = 2 if steps <= 50 else 4
     timers = {d: api.KernelTimer(d, (steps + arm_every - 1) // arm_every) for d in directions}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -320,9 +320,10 @@ def probe_report(torch, api):
     rows = []
     for blocks in (16, 256):
         for shape, lds, nv in ((0, 0, 0), (0, 1, 0), (0, 1, 2), (0, 1, 4), (0, 1, 6), (0, 1, 8),
-                               (1, 0, 0), (1, 1, 0), (1, 1, 2), (1, 1, 4), (1, 1, 6), (1, 1, 8)):
+                               (1, 0, 0), (1, 1, 0), (1, 1, 2), (1, 1, 4), (1, 1, 6), (1, 1, 8),
+                               (2, 0, 0), (2, 1, 0), (2, 1, 2), (2, 1, 4)):
             cyc, ghz, tf = api.mfma_probe(shape, bool(lds), nv, iters=2000, blocks=blocks)
-            rows.append({"blocks": blocks, "wavefronts_x_tiles": "8 x (4x2)" if shape == 0 else "4 x (4x4)",
+            rows.append({"blocks": blocks, "wavefronts_x_tiles": ("8 x (4x2)", "4 x (4x4)", "8 x (4x2) AGPR acc")[shape],
                          "lds_fragment_reads": bool(lds), "valu_per_mfma": nv,
                          "cycles_per_mfma_per_simd": round(cyc, 2), "shader_clock_ghz": round(ghz, 3),
                          "TFLOP/s": round(tf, 1), "frac_of_peak": round(tf / PEAK_MFMA_TFLOPS, 4)})

@@ -300,7 +300,7 @@ int qalora_profile_copy(void* dst, const void* src, size_t bytes, void* stream);
  * fragment reads from LDS, and valu_per_mfma ordinary vector instructions behind every matrix
  * instruction.  shape 0: eight wavefronts of 4 x 2 tiles per block (valu_per_mfma in
  * {0,2,4,6,8}; 0 only without LDS reads); shape 1: four wavefronts of 4 x 4 tiles (same
- * choices).  Other combinations return QALORA_EINVAL.  Block b stores its shader cycles and
+ * choices); shape 2: shape 0 with the accumulators held in AGPRs (valu in {0,2,4}).  Other combinations return QALORA_EINVAL.  Block b stores its shader cycles and
  * wall-clock ticks over the loop to counts[2b], counts[2b+1] (device, 16 * blocks bytes); sink
  * is device scratch of 2048 * blocks bytes.  A block issues iters * 32 (shape 0: per wavefront,
  * two wavefronts per SIMD; shape 1: iters * 64, one wavefront per SIMD) matrix instructions per

@@ -53,12 +53,13 @@ __device__ __forceinline__ uint4 bf16x8_to_f16x8_scaled(uint4 v, float sc) {
 // ---------------------------------------------------------------------------------------
 // The "front" launch: every row-wise and elementwise preparation step of a forward or a
 // backward call, as independent jobs of ONE kernel (the steps are tiny; launches are not).
-//   rows job 1 : x -> row scale, fp16 scaled copy (forward), P = pool_g(x), U = P A as
-//                u_ext / us_t.  One wavefront per token, the row held in registers: a single
+//   rows job 1 : x -> row scale, fp16 scaled copy (forward), P = pool_g(x), U = P A (kept for
+//                the backward, or transposed into us_t).  One wavefront per token, the row held in registers: a single
 //                sweep of 128-bit loads gives the maximum (scale), the group sums (wavefront
 //                butterfly over the g/8 lanes of a group) and the converted copy.
 //   rows job 2 : dy -> row scale + fp16 scaled copy (backward)
-//   prep job   : hi/lo splits of B (and A) into the operand layouts of the matrix kernels
+//   factor job : the adapter folded into the zero factors, as the dense kernels' factor words
+//   prep job   : hi/lo split of B into the operand layout of the dU product
 // ---------------------------------------------------------------------------------------
 constexpr int ROWS_PER_BLOCK = 4;  // one wavefront each
 constexpr int ROW_BATCH = 8;       // 128-bit chunks per lane held in registers (4096 elements)
@@ -74,8 +75,6 @@ struct FrontArgs {
   float s;
   int g, rank;
   float* P_out;         // optional [T, L]
-  uint16_t* u_ext;      // optional [T, ktail]
-  int ktail;
   uint16_t* us_t;       // optional [2*rp, t_pad]
   int t_pad;
   float* u_keep;        // optional [T, rank]: s U in fp32, for a later launch's transpose job
@@ -89,11 +88,150 @@ struct FrontArgs {
   // prep job
   const float* B;
   int d_out, L;
-  uint16_t* b_ext_t;    // forward: [d_out, ktail]
   uint16_t* b_hl;       // backward: [2*rp, d_out]
-  uint16_t* a_ext_t;    // backward: [L, ktail]
-  int nb_rows1, nb_rows2, nb_tr, nb_prep;
+  // factor job (see factor_block): the dense kernels' factor words
+  const float* f_alpha; // [L, d_out]
+  const float* f_beta;  // [L, d_out]
+  const float* f_A;     // [L, rank] or null: no adapter to fold in
+  const float* f_B;     // [rank, d_out]
+  float f_sg, f_mid;    // s / g; 2^(N-1)
+  int f_L, f_dout, f_rank, f_cols;  // f_cols: columns per block, a power of two <= 16
+  uint32_t* f_words;    // forward: [L, d_out] words at the per-column scale
+  float* f_inv;         // forward: [d_out] 1 / S of each column
+  float* f_const;       // backward: [L, d_out] beta' + mid alpha, fp32 (scaled by a later launch)
+  float* f_max;         // optional [nb_fac]: bound on |W~'| over each block's columns
+  const float* f_known; // backward, optional [nb_fac]: those bounds as an earlier launch on the
+                        // same operands left them -- the call's S is then known here, and the
+                        // words are written at once (f_words, f_inv[0]; no f_const)
+  int nb_rows1, nb_rows2, nb_tr, nb_prep, nb_fac;
 };
+
+// Power of two S = 2^e that brings a magnitude bound m to [2^13, 2^14), as (S, 1/S); (1, 1) for
+// m = 0 or a non-finite m.  Every |W~'| S then stays below 2^14 in fp16, its largest factor keeps
+// 11 significant bits, and the products with activations scaled to below 2^15 leave the fp32
+// accumulator ample room.
+__device__ __forceinline__ float2 factor_scale(float m) {
+  const int E = (int)(__float_as_uint(m) >> 23) & 255;
+  if (m == 0.0f || E == 255) return float2{1.0f, 1.0f};
+  int e = 140 - E;  // m in [2^(E-127), 2^(E-126))
+  e = e > 100 ? 100 : (e < -100 ? -100 : e);
+  return float2{__uint_as_float((uint32_t)(127 + e) << 23), __uint_as_float((uint32_t)(127 - e) << 23)};
+}
+
+// The factor job.  The adapted layer is the quantized layer with the zero factors
+//   beta'[l,j] = beta[l,j] + (s/g) sum_k A[l,k] B[k,j]                  (App. B.3)
+// so the dense kernels need no low-rank branch of their own: this job folds the adapter into
+// the zero factors for the call at hand (fp32, k in order) and hands them over in the form the
+// kernels multiply with: one word per (group, column), fp16(alpha S) | fp16(c S) << 16, where
+// c = beta' + mid alpha is the weight at the mid code mid = 2^(N-1) and S a power of two taken
+// from the bound |c| + mid |alpha| >= |W~'|.
+// A block owns f_cols columns and every group: thread (c, lg) takes column c and groups lg,
+// lg + 256 / f_cols, ...; B's columns sit in LDS, the rows of A come as broadcast loads, and c
+// is parked in LDS until the column's bound is known.  Forward: S per column, decided here.
+// Backward (the scale must not vary along the output columns, which are the contraction index
+// there): c goes out in fp32 with the block's bound, and a later launch scales by the call's S.
+__device__ __forceinline__ void factor_block(const FrontArgs& a, int bid, float* lds, int tid) {
+  const int FC = a.f_cols, NLG = 256 / FC;
+  const int c = tid & (FC - 1), lg = tid / FC;
+  const int L = a.f_L, dout = a.f_dout, rank = a.f_A ? a.f_rank : 0;
+  const int j0 = bid * FC, j = j0 + c;
+  const bool col_ok = j < dout;
+  const int bs = rank + 4;          // floats per staged column of B
+  float* tile = lds;                // [L][FC]
+  float* Bs = tile + (size_t)L * FC;  // [FC][bs]
+  float* red = Bs + FC * bs;        // [256]
+  for (int idx = tid; idx < FC * rank; idx += 256) {
+    const int cc = idx & (FC - 1), k = idx / FC;
+    Bs[cc * bs + k] = (j0 + cc < dout) ? a.f_B[(size_t)k * dout + j0 + cc] : 0.0f;
+  }
+  __syncthreads();
+  constexpr int GB = 4;  // groups per thread in flight
+  float m = 0.0f;
+  const bool vec = (rank & 3) == 0;
+  for (int lb = lg; lb < L; lb += NLG * GB) {
+    float acc[GB];
+#pragma unroll
+    for (int i = 0; i < GB; ++i) acc[i] = 0.0f;
+    if (vec) {
+#pragma unroll 2
+      for (int k = 0; k < rank; k += 4) {
+        const f32x4 b = *reinterpret_cast<const f32x4*>(Bs + c * bs + k);
+#pragma unroll
+        for (int i = 0; i < GB; ++i) {
+          const int l = min(lb + i * NLG, L - 1);  // rows past the end repeat the last one, unused
+          const f32x4 av = *reinterpret_cast<const f32x4*>(a.f_A + (size_t)l * rank + k);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) acc[i] = __builtin_fmaf(av[q], b[q], acc[i]);
+        }
+      }
+    } else {
+      for (int k = 0; k < rank; ++k) {
+        const float b = Bs[c * bs + k];
+#pragma unroll
+        for (int i = 0; i < GB; ++i) {
+          const int l = min(lb + i * NLG, L - 1);
+          acc[i] = __builtin_fmaf(a.f_A[(size_t)l * rank + k], b, acc[i]);
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < GB; ++i) {
+      const int l = lb + i * NLG;
+      if (l < L) {
+        float cst = 0.0f, bound = 0.0f;
+        if (col_ok) {
+          const float al = a.f_alpha[(size_t)l * dout + j];
+          const float bp = __builtin_fmaf(a.f_sg, acc[i], a.f_beta[(size_t)l * dout + j]);
+          cst = __builtin_fmaf(a.f_mid, al, bp);
+          bound = fabsf(cst) + a.f_mid * fabsf(al);
+        }
+        tile[(size_t)l * FC + c] = cst;
+        m = fmaxf(m, bound);
+      }
+    }
+  }
+  red[tid] = m;
+  __syncthreads();
+  float cm = 0.0f;  // bound of column c over all groups
+  for (int q = 0; q < NLG; ++q) cm = fmaxf(cm, red[q * FC + c]);
+  if (a.f_max) {  // the block's bound, for a launch that needs one scale for the whole matrix
+    __syncthreads();
+    red[tid] = cm;
+    __syncthreads();
+    if (tid == 0) {
+      float bm = 0.0f;
+      for (int q = 0; q < FC; ++q) bm = fmaxf(bm, red[q]);
+      a.f_max[bid] = bm;
+    }
+  }
+  if (a.f_known) {  // one scale for the call, from the bounds an earlier launch left
+    __syncthreads();
+    float km = 0.0f;
+    for (int i = tid; i < a.nb_fac; i += 256) km = fmaxf(km, a.f_known[i]);
+    red[tid] = km;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+      if (tid < off) red[tid] = fmaxf(red[tid], red[tid + off]);
+      __syncthreads();
+    }
+    cm = red[0];
+  }
+  if (a.f_words) {
+    const float2 sc = factor_scale(cm);
+    if (a.f_known) {
+      if (bid == 0 && tid == 0) a.f_inv[0] = sc.y;
+    } else if (lg == 0 && col_ok) {
+      a.f_inv[j] = sc.y;
+    }
+    if (col_ok)
+      for (int l = lg; l < L; l += NLG) {
+        const f32x2 v = {a.f_alpha[(size_t)l * dout + j] * sc.x, tile[(size_t)l * FC + c] * sc.x};
+        a.f_words[(size_t)l * dout + j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+      }
+  } else if (col_ok) {
+    for (int l = lg; l < L; l += NLG) a.f_const[(size_t)l * dout + j] = tile[(size_t)l * FC + c];
+  }
+}
 
 // One wavefront processes one bf16 row: returns the row scale; optionally writes the fp16
 // scaled copy and the group averages (to P_s, LDS, [L]).
@@ -161,6 +299,13 @@ __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
   extern __shared__ float P_all[];  // [ROWS_PER_BLOCK][L] when pooling
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int bid = blockIdx.x;
+  // the factor job's blocks come first: they are the longest-running ones, and started last
+  // they would finish after everything else instead of under it
+  if (bid < a.nb_fac) {
+    factor_block(a, bid, P_all, tid);
+    return;
+  }
+  bid -= a.nb_fac;
   if (bid < a.nb_rows1) {
     // ---- rows job 1: x ---------------------------------------------------------------
     const int t = bid * ROWS_PER_BLOCK + wave;
@@ -207,22 +352,12 @@ __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
         }
         uint16_t hi, lo;
         if (a.u_keep && k < a.rank) a.u_keep[(size_t)t * a.rank + k] = u;
-        if (a.u_ext && k < a.rank) {
-          // the forward tail shares the accumulator of the scaled main product
-          split_bf16(u * sc.x, hi, lo);
-          uint16_t* row = a.u_ext + (size_t)t * a.ktail;
-          row[k] = hi;
-          row[a.rank + k] = lo;
-          row[2 * a.rank + k] = hi;
-        }
         if (a.us_t) {
           split_bf16(u, hi, lo);  // zero for the padding rows k >= rank
           a.us_t[(size_t)k * a.t_pad + t] = hi;
           a.us_t[(size_t)(rp + k) * a.t_pad + t] = lo;
         }
       }
-      if (a.u_ext)
-        for (int c = 3 * a.rank + lane; c < a.ktail; c += 64) a.u_ext[(size_t)t * a.ktail + c] = 0;
     } else if (a.us_t && t < a.t_pad) {
       // token padding of the transposed operand must read as zero
       for (int k = lane; k < 2 * rp; k += 64) a.us_t[(size_t)k * a.t_pad + t] = 0;
@@ -275,27 +410,12 @@ __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
     return;
   }
   bid -= a.nb_tr;
-  // ---- prep job: elementwise hi/lo splits ------------------------------------------------
+  // ---- prep job: hi/lo split of B for the dU product -------------------------------------
   const size_t idx = (size_t)bid * 256 + tid;
   const int rp = rank_pad32(a.rank);
-  if (a.b_ext_t) {
-    // forward: b_ext_t[j][c] = [hi | hi | lo | 0] of B[:, j]
-    if (idx < (size_t)a.d_out * a.ktail) {
-      const int j = (int)(idx / a.ktail), c = (int)(idx % a.ktail);
-      uint16_t v = 0;
-      if (c < 3 * a.rank) {
-        uint16_t hi, lo;
-        split_bf16(a.B[(size_t)(c % a.rank) * a.d_out + j], hi, lo);
-        v = (c < 2 * a.rank) ? hi : lo;
-      }
-      a.b_ext_t[idx] = v;
-    }
-    return;
-  }
   const size_t nb = (size_t)2 * rp * a.d_out;
-  const size_t na = (size_t)a.L * a.ktail;
   if (idx < nb) {
-    // backward: b_hl rows = hi(B) then lo(B) (rows padded to rp with zeros)
+    // b_hl rows = hi(B) then lo(B) (rows padded to rp with zeros)
     const int row = (int)(idx / a.d_out), j = (int)(idx % a.d_out);
     const int k = row % rp;
     uint16_t v = 0;
@@ -305,17 +425,6 @@ __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
       v = (row < rp) ? hi : lo;
     }
     a.b_hl[idx] = v;
-  } else if (idx < nb + na) {
-    // backward: a_ext_t[l][c] = [hi | hi | lo | 0] of A[l, :] / g
-    const size_t o = idx - nb;
-    const int l = (int)(o / a.ktail), c = (int)(o % a.ktail);
-    uint16_t v = 0;
-    if (c < 3 * a.rank) {
-      uint16_t hi, lo;
-      split_bf16(a.A[(size_t)l * a.rank + c % a.rank] / (float)a.g, hi, lo);
-      v = (c < 2 * a.rank) ? hi : lo;
-    }
-    a.a_ext_t[o] = v;
   }
 }
 
@@ -358,23 +467,39 @@ __global__ __launch_bounds__(256) void front_wide_kernel(const uint16_t* __restr
   }
 }
 
+// Columns per block of the factor job: as many (up to 16) as keep its LDS tile of L x columns
+// fp32 values within 32 KB, so that the row jobs of the same launch keep their occupancy.
+static int factor_cols(int L) {
+  int fc = 16;
+  while (fc > 1 && (size_t)L * fc * 4 > 32 * 1024) fc >>= 1;
+  return fc;
+}
+
 static hipError_t launch_front(FrontArgs a, hipStream_t st) {
-  if (a.x && !a.A && !a.y && !a.b_ext_t && !a.b_hl && !a.us_t && a.T <= kWideRows && a.d_in % 8 == 0 &&
+  if (a.x && !a.A && !a.y && !a.b_hl && !a.us_t && a.T <= kWideRows && a.d_in % 8 == 0 &&
       a.d_in <= 256 * 8 * WIDE_BATCH) {
+    // few rows: a block per row; the factor job (if any) follows as a launch of its own
     front_wide_kernel<<<a.T, 256, 0, st>>>(a.x, a.d_in, a.rs_x, a.x16);
-    return hipGetLastError();
+    if (hipError_t e = hipGetLastError(); e != hipSuccess || !a.f_alpha) return e;
+    a.x = nullptr;
   }
   a.nb_rows1 = a.x ? ceil_div(a.us_t ? a.t_pad : a.T, ROWS_PER_BLOCK) : 0;
   a.nb_rows2 = a.y ? ceil_div(a.Ty, ROWS_PER_BLOCK) : 0;
-  size_t nprep = 0;
-  if (a.b_ext_t) nprep = (size_t)a.d_out * a.ktail;
-  else if (a.b_hl) nprep = (size_t)2 * rank_pad32(a.rank) * a.d_out + (size_t)a.L * a.ktail;
+  const size_t nprep = a.b_hl ? (size_t)2 * rank_pad32(a.rank) * a.d_out : 0;
   a.nb_prep = (int)((nprep + 255) / 256);
   a.nb_tr = a.u_kept ? a.t_pad / TR_TOK : 0;
   size_t smem =
       a.A ? ((size_t)ROWS_PER_BLOCK * (a.d_in / a.g) + 4 * ROWS_PER_BLOCK * 128) * sizeof(float) : 0;
   const size_t tr_smem = (size_t)TR_TOK * (a.rank + 1) * sizeof(float);
   if (a.nb_tr > 0 && smem < tr_smem) smem = tr_smem;
+  a.nb_fac = 0;
+  if (a.f_alpha) {
+    a.f_cols = factor_cols(a.f_L);
+    a.nb_fac = ceil_div(a.f_dout, a.f_cols);
+    const size_t f_smem =
+        ((size_t)a.f_L * a.f_cols + (size_t)a.f_cols * ((a.f_A ? a.f_rank : 0) + 4) + 256) * sizeof(float);
+    if (smem < f_smem) smem = f_smem;
+  }
   constexpr size_t kFrontLdsMax = 160 * 1024;  // a compute unit's LDS
   if (smem > kFrontLdsMax) return hipErrorInvalidValue;
   if (smem > 48 * 1024) {
@@ -383,42 +508,96 @@ static hipError_t launch_front(FrontArgs a, hipStream_t st) {
         e != hipSuccess)
       return e;
   }
-  const int nblocks = a.nb_rows1 + a.nb_rows2 + a.nb_tr + a.nb_prep;
+  const int nblocks = a.nb_rows1 + a.nb_rows2 + a.nb_tr + a.nb_fac + a.nb_prep;
   if (nblocks == 0) return hipSuccess;
   front_kernel<<<nblocks, 256, smem, st>>>(a);
   return hipGetLastError();
 }
 
+static void set_factor_job(FrontArgs& a, const FactorJob& f) {
+  a.f_alpha = f.alpha; a.f_beta = f.beta; a.f_A = f.rank > 0 ? f.A : nullptr; a.f_B = f.B;
+  a.f_sg = f.s / (float)f.g; a.f_mid = (float)(1 << (f.bits - 1));
+  a.f_L = f.L; a.f_dout = f.d_out; a.f_rank = f.rank;
+  a.f_words = f.words; a.f_inv = f.inv_scale; a.f_const = f.cst; a.f_max = f.block_max;
+  a.f_known = f.known_max;
+}
+
+int factor_job_blocks(int L, int d_out) { return ceil_div(d_out, factor_cols(L)); }
+
 hipError_t launch_front_forward(const uint16_t* x, int T, int d_in, float2* rs, uint16_t* x16,
-                                const float* A, const float* B, float s, int g, int rank,
-                                int d_out, uint16_t* u_ext, uint16_t* b_ext_t, int ktail,
-                                float* P_keep, float* u_keep, hipStream_t st) {
+                                const float* A, float s, int g, int rank, float* P_keep,
+                                float* u_keep, const FactorJob& fac, hipStream_t st) {
   FrontArgs a{};
   a.x = x; a.T = T; a.d_in = d_in; a.rs_x = rs; a.x16 = x16;
-  if (A && rank > 0) {
-    a.A = A; a.s = s; a.g = g; a.rank = rank; a.u_ext = u_ext; a.ktail = ktail;
-    a.B = B; a.d_out = d_out; a.b_ext_t = b_ext_t;
-    a.P_out = P_keep;  // what the backward needs of x, when the caller keeps it
+  if (A && rank > 0 && P_keep) {  // only a caller that keeps them needs P and s P A here
+    a.A = A; a.s = s; a.g = g; a.rank = rank;
+    a.P_out = P_keep;
     a.u_keep = u_keep;
   }
+  set_factor_job(a, fac);
   return launch_front(a, st);
 }
 
 hipError_t launch_front_backward(const uint16_t* dy, int T, int d_out, float2* rs_dy,
                                  uint16_t* dy16, const uint16_t* x, int d_in, const float* A,
                                  const float* B, float s, int g, int rank, float* P,
-                                 uint16_t* us_t, int t_pad, uint16_t* b_hl, uint16_t* a_ext_t,
-                                 int ktail, const float* u_kept, hipStream_t st) {
+                                 uint16_t* us_t, int t_pad, uint16_t* b_hl, const float* u_kept,
+                                 const FactorJob& fac, hipStream_t st) {
   FrontArgs a{};
   a.y = dy; a.Ty = T; a.d_y = d_out; a.rs_y = rs_dy; a.y16 = dy16;
   if (A && rank > 0) {
     a.x = u_kept ? nullptr : x;  // with the kept rows, P is the caller's and us_t is a transpose
     a.u_kept = u_kept;
     a.T = T; a.d_in = d_in; a.A = A; a.s = s; a.g = g; a.rank = rank;
-    a.P_out = P; a.us_t = us_t; a.t_pad = t_pad; a.ktail = ktail;
-    a.B = B; a.d_out = d_out; a.L = d_in / g; a.b_hl = b_hl; a.a_ext_t = a_ext_t;
+    a.P_out = P; a.us_t = us_t; a.t_pad = t_pad;
+    a.B = B; a.d_out = d_out; a.L = d_in / g; a.b_hl = b_hl;
   }
+  if (fac.alpha) set_factor_job(a, fac);
   return launch_front(a, st);
+}
+
+// Second stage of the backward direction's factor words: S for the call from the first
+// stage's per-block bounds (every block reduces them itself: a few hundred values), then
+// words[i] = fp16(alpha[i] S) | fp16(c[i] S) << 16.  Block 0 leaves 1 / S for the epilogue.
+__global__ __launch_bounds__(256) void factor_scale_kernel(const f32x4* __restrict__ alpha,
+                                                           const f32x4* __restrict__ cst,
+                                                           const float* __restrict__ block_max,
+                                                           int nmax, size_t n4,
+                                                           uint32_t* __restrict__ words,
+                                                           float* __restrict__ inv_scale) {
+  __shared__ float red[256];
+  float m = 0.0f;
+  for (int i = threadIdx.x; i < nmax; i += 256) m = fmaxf(m, block_max[i]);
+  red[threadIdx.x] = m;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + off]);
+    __syncthreads();
+  }
+  const float2 sc = factor_scale(red[0]);
+  if (blockIdx.x == 0 && threadIdx.x == 0) inv_scale[0] = sc.y;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+    const f32x4 al = alpha[i], c = cst[i];
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 w;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const f32x2 v = {al[q] * sc.x, c[q] * sc.x};
+      w[q] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+    }
+    reinterpret_cast<u32x4*>(words)[i] = w;
+  }
+}
+
+hipError_t launch_factor_scale(const float* alpha, const float* cst, const float* block_max, int nmax,
+                               size_t n, uint32_t* words, float* inv_scale, hipStream_t st) {
+  const size_t n4 = n / 4;  // d_out is a multiple of 8
+  const unsigned blocks = (unsigned)((n4 + 1023) / 1024 < 1024 ? (n4 + 1023) / 1024 : 1024);
+  factor_scale_kernel<<<blocks, 256, 0, st>>>(reinterpret_cast<const f32x4*>(alpha),
+                                              reinterpret_cast<const f32x4*>(cst), block_max, nmax, n4,
+                                              words, inv_scale);
+  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------
@@ -535,9 +714,8 @@ __device__ __forceinline__ void db_partial_block(const DbArgs& a, int bx, int z,
 // ---------------------------------------------------------------------------------------
 // dA = P^T dU over a token slice, fp32 on the vector units (67 MFLOP at LLaMA-7B shapes),
 // fused with the finalisation of dU: dU[t,k] = s * sum_z (raw[z][t][k] + raw[z][t][rp+k]) is
-// rebuilt from the split-K partials of the dU product while staging, and the blocks of the
-// first group tile also emit the backward tail operand du_ext = [hi | lo | hi | 0] of
-// dU * (row scale of dy).  Block = 64 groups x all ranks; thread = 4 groups x up to 8 ranks.
+// rebuilt from the split-K partials of the dU product while staging.
+// Block = 64 groups x all ranks; thread = 4 groups x up to 8 ranks.
 // ---------------------------------------------------------------------------------------
 constexpr int DA_TT = 16;
 
@@ -546,11 +724,8 @@ struct DaArgs {
   const float* raw;  // [ksplit][T, 2*rp] split-K partials of dy [B_hi | B_lo]^T
   int ksplit;
   float s;
-  const float2* rs;  // [T] row scales of dy
   int T, L, rank, tsplit;
   float* part;       // [tsplit][L, rank]
-  uint16_t* du_ext;  // [T, ktail]
-  int ktail;
 };
 constexpr int da_lds_bytes() { return DA_TT * (64 + 128) * 4; }
 
@@ -558,10 +733,8 @@ __device__ __forceinline__ void da_partial_block(const DaArgs& a, int bx, int z,
                                                  unsigned char* lds) {
   const float* __restrict__ P = a.P;
   const float* __restrict__ raw = a.raw;
-  const float2* __restrict__ rs = a.rs;
   float* __restrict__ part = a.part;
-  uint16_t* __restrict__ du_ext = a.du_ext;
-  const int ksplit = a.ksplit, T = a.T, L = a.L, rank = a.rank, tsplit = a.tsplit, ktail = a.ktail;
+  const int ksplit = a.ksplit, T = a.T, L = a.L, rank = a.rank, tsplit = a.tsplit;
   const float s = a.s;
   float (*p_s)[64] = reinterpret_cast<float (*)[64]>(lds);                        // [DA_TT][64]
   float (*du_s)[128] = reinterpret_cast<float (*)[128]>(lds + DA_TT * 64 * 4);    // [DA_TT][128]
@@ -629,24 +802,7 @@ __device__ __forceinline__ void da_partial_block(const DaArgs& a, int bx, int z,
     for (int e = 0; e < DU_E; ++e) {
       const int idx = tid + 256 * e;
       const int tt = idx >> 7, k = idx & 127;
-      const int t = t0 + tt;
-      const float v = duv[e] * s;
-      if (bx == 0 && t < t_end && k < rank) {
-        uint16_t hi, lo;
-        split_bf16(v * rs[t].x, hi, lo);  // the backward tail rides on the scaled main product
-        uint16_t* row = du_ext + (size_t)t * ktail;
-        row[k] = hi;
-        row[rank + k] = lo;
-        row[2 * rank + k] = hi;
-      }
-      du_s[tt][k] = v;
-    }
-    if (bx == 0) {
-      const int npad = ktail - 3 * rank;
-      for (int idx = tid; idx < DA_TT * npad; idx += 256) {
-        const int t = t0 + idx / npad;
-        if (t < t_end) du_ext[(size_t)t * ktail + 3 * rank + idx % npad] = 0;
-      }
+      du_s[tt][k] = duv[e] * s;
     }
     __syncthreads();
 #pragma unroll
@@ -696,11 +852,10 @@ __global__ __launch_bounds__(256, MT <= 4 ? 3 : 1) void adapter_grads_kernel(con
 
 hipError_t launch_adapter_grads(const uint16_t* us_t, int t_pad, const uint16_t* dy, int T, int d_out,
                                 int rank, int tsplit_b, float* db_part, const float* P,
-                                const float* raw, int ksplit, float s, const float2* rs, int L,
-                                int tsplit_a, float* da_part, uint16_t* du_ext, int ktail,
-                                hipStream_t st) {
+                                const float* raw, int ksplit, float s, int L, int tsplit_a,
+                                float* da_part, hipStream_t st) {
   const DbArgs db{us_t, t_pad, dy, T, d_out, rank, tsplit_b, db_part};
-  const DaArgs da{P, raw, ksplit, s, rs, T, L, rank, tsplit_a, da_part, du_ext, ktail};
+  const DaArgs da{P, raw, ksplit, s, T, L, rank, tsplit_a, da_part};
   const int db_bx = ceil_div(d_out, DB_BN), db_blocks = db_bx * tsplit_b;
   const int da_bx = ceil_div(L, 64), da_blocks = da_bx * tsplit_a;
   const int mt = 2 * rank_pad32(rank) / 32;

@@ -20,33 +20,31 @@ int row_align_for_bits(int bits) { return bits == 4 ? 8 : (bits == 2 ? 16 : 32);
 // Workspace plans.  Offsets are a pure function of (desc, tokens), so the size query and
 // the compute call always agree.
 struct FwdPlan {
-  int ktail, gsplit;
-  size_t rs, a16, u_ext, b_ext_t, gpart, total;
+  int gsplit;
+  size_t rs, a16, fac, inv, gpart, total;
 };
 struct BwdPlan {
-  int ktail, rp, t_pad, ksplit, tsplit_b, tsplit_a, gsplit;
-  size_t rs, a16, P, us_t, b_hl, a_ext_t, du_raw, du_ext, db_part, da_part, gpart, total;
+  int rp, t_pad, ksplit, tsplit_b, tsplit_a, gsplit, nmax;
+  size_t rs, a16, fac, cst, bmax, inv, P, us_t, b_hl, du_raw, db_part, da_part, gpart, total;
 };
 
+// forward workspace: row scales, the fp16 copy of x, the factor words and their column scales,
+// then the split-K partials if any.  Independent of the adapter: the factor job folds it in.
 FwdPlan plan_forward(const qalora_desc& d, int T) {
   FwdPlan p{};
-  p.ktail = adapter_ktail(d.rank);
+  const size_t L = (size_t)(d.d_in / d.group);
   size_t off = 0;
-  p.rs = off;
-  off += align_up((size_t)T * sizeof(float2));
-  p.a16 = off;
-  off += align_up((size_t)round_up(T, 256) * d.d_in * 2);
-  if (d.rank > 0) {
-    p.u_ext = off;
-    off += align_up((size_t)T * p.ktail * 2);
-    p.b_ext_t = off;
-    off += align_up((size_t)d.d_out * p.ktail * 2);
-  }
+  auto take = [&](size_t bytes) {
+    const size_t o = off;
+    off += align_up(bytes);
+    return o;
+  };
+  p.rs = take((size_t)T * sizeof(float2));
+  p.a16 = take((size_t)round_up(T, 256) * d.d_in * 2);
+  p.fac = take(L * d.d_out * 4);
+  p.inv = take((size_t)d.d_out * 4);
   p.gsplit = gemm_dq_ksplit(T, d.d_out, d.d_in);
-  if (p.gsplit > 1) {
-    p.gpart = off;
-    off += align_up((size_t)p.gsplit * T * d.d_out * 4);
-  }
+  if (p.gsplit > 1) p.gpart = take((size_t)p.gsplit * T * d.d_out * 4);
   p.total = off;
   return p;
 }
@@ -54,18 +52,25 @@ FwdPlan plan_forward(const qalora_desc& d, int T) {
 BwdPlan plan_backward(const qalora_desc& d, int T) {
   BwdPlan p{};
   const int L = d.d_in / d.group;
-  p.ktail = adapter_ktail(d.rank);
   p.rp = rank_pad32(d.rank);
   p.t_pad = round_up(T, 64);
-  if (d.rank <= 0) {  // adapter-free: only the row scales and the fp16 copy of dy
-    p.rs = 0;
-    p.a16 = align_up((size_t)T * sizeof(float2));
-    p.total = p.a16 + align_up((size_t)round_up(T, 256) * d.d_out * 2);
-    p.gsplit = gemm_dq_ksplit(T, d.d_in, d.d_out);
-    if (p.gsplit > 1) {
-      p.gpart = p.total;
-      p.total += align_up((size_t)p.gsplit * T * d.d_in * 4);
-    }
+  p.nmax = factor_job_blocks(L, d.d_out);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t o = off;
+    off += align_up(bytes);
+    return o;
+  };
+  p.rs = take((size_t)T * sizeof(float2));
+  p.a16 = take((size_t)round_up(T, 256) * d.d_out * 2);
+  p.fac = take((size_t)L * d.d_out * 4);
+  p.cst = take((size_t)L * d.d_out * 4);
+  p.bmax = take((size_t)p.nmax * 4);
+  p.inv = take(16);
+  p.gsplit = gemm_dq_ksplit(T, d.d_in, d.d_out);
+  if (p.gsplit > 1) p.gpart = take((size_t)p.gsplit * T * d.d_in * 4);
+  if (d.rank <= 0) {  // adapter-free: only dx is produced
+    p.total = off;
     return p;
   }
   // dU product: [T, 2rp] output tiles of plain_tile_rows x 128 (the taller tile pays when K is
@@ -93,24 +98,12 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
     const int steps = ceil_div(T, 16);
     p.tsplit_a = steps > 256 ? 256 : steps;
   }
-  size_t off = 0;
-  auto take = [&](size_t bytes) {
-    const size_t o = off;
-    off += align_up(bytes);
-    return o;
-  };
-  p.rs = take((size_t)T * sizeof(float2));
-  p.a16 = take((size_t)round_up(T, 256) * d.d_out * 2);
   p.P = take((size_t)T * L * 4);
   p.us_t = take((size_t)2 * p.rp * p.t_pad * 2);
   p.b_hl = take((size_t)2 * p.rp * d.d_out * 2);
-  p.a_ext_t = take((size_t)L * p.ktail * 2);
   p.du_raw = take((size_t)p.ksplit * T * 2 * p.rp * 4);
-  p.du_ext = take((size_t)T * p.ktail * 2);
   p.db_part = take((size_t)p.tsplit_b * d.rank * d.d_out * 4);
   p.da_part = take((size_t)p.tsplit_a * L * d.rank * 4);
-  p.gsplit = gemm_dq_ksplit(T, d.d_in, d.d_out);
-  if (p.gsplit > 1) p.gpart = take((size_t)p.gsplit * T * d.d_in * 4);
   p.total = off;
   return p;
 }
@@ -279,13 +272,14 @@ int qalora_pack(const qalora_desc* d, const uint8_t* codes, void* packed, void* 
 // What the forward leaves for the backward when asked to: P = pool_g(x) [T, L] and
 // s P A [T, rank], both fp32.
 struct KeptLayout {
-  size_t P, U, total;
+  size_t P, U, bmax, total;
 };
 static KeptLayout kept_layout(const qalora_desc& d, int T) {
   KeptLayout k{};
   k.P = 0;
   k.U = align_up((size_t)T * (d.d_in / d.group) * 4);
-  k.total = k.U + align_up((size_t)T * d.rank * 4);
+  k.bmax = k.U + align_up((size_t)T * d.rank * 4);
+  k.total = k.bmax + align_up((size_t)factor_job_blocks(d.d_in / d.group, d.d_out) * 4);
   return k;
 }
 
@@ -368,19 +362,42 @@ static int forward_impl(const qalora_desc* d, int tokens, const void* x, const v
     a.group = d->group;
     return launch_smallt(a, as_stream(stream)) == hipSuccess ? QALORA_OK : QALORA_EHIP;
   }
-  FwdPlan plan = plan_forward(*d, tokens);
-  if (!adapter) {  // no adapter operands: the partial sums (if any) follow the fp16 copy
-    plan.total = plan.a16 + align_up((size_t)round_up(tokens, 256) * d->d_in * 2);
-    if (plan.gsplit > 1) {
-      plan.gpart = plan.total;
-      plan.total += align_up((size_t)plan.gsplit * tokens * d->d_out * 4);
-    }
-  }
+  const FwdPlan plan = plan_forward(*d, tokens);
   if (!ws || ws_bytes < plan.total) return QALORA_EWORKSPACE;
   hipStream_t st = as_stream(stream);
   char* w = static_cast<char*>(ws);
   float2* rs = reinterpret_cast<float2*>(w + plan.rs);
   uint16_t* x16 = reinterpret_cast<uint16_t*>(w + plan.a16);
+  const int L = d->d_in / d->group;
+
+  // front launch: row scales and the fp16 copy of x; the adapter folded into the zero factors
+  // and the factor words of the dense kernel; P and s P A for the backward when asked for
+  FactorJob fj{};
+  fj.alpha = alpha;
+  fj.beta = beta;
+  fj.A = adapter ? A : nullptr;
+  fj.B = adapter ? B : nullptr;
+  fj.s = d->s;
+  fj.g = d->group;
+  fj.rank = adapter ? d->rank : 0;
+  fj.bits = d->bits;
+  fj.L = L;
+  fj.d_out = d->d_out;
+  fj.words = reinterpret_cast<uint32_t*>(w + plan.fac);
+  fj.inv_scale = reinterpret_cast<float*>(w + plan.inv);
+  float* P_keep = nullptr;
+  float* u_keep = nullptr;
+  if (keep) {
+    const KeptLayout k = kept_layout(*d, tokens);
+    P_keep = reinterpret_cast<float*>(static_cast<char*>(kept) + k.P);
+    u_keep = reinterpret_cast<float*>(static_cast<char*>(kept) + k.U);
+    // the bounds on |W~'| the factor job finds anyway: with them the backward knows its scale
+    fj.block_max = reinterpret_cast<float*>(static_cast<char*>(kept) + k.bmax);
+  }
+  if (launch_front_forward(static_cast<const uint16_t*>(x), tokens, d->d_in, rs, x16,
+                           adapter ? A : nullptr, d->s, d->group, d->rank, P_keep, u_keep, fj,
+                           st) != hipSuccess)
+    return QALORA_EHIP;
 
   GemmArgs g{};
   g.a_main = x16;
@@ -388,8 +405,8 @@ static int forward_impl(const qalora_desc* d, int tokens, const void* x, const v
   g.a_main_padded_rows = round_up(tokens, 256);
   g.plane0 = static_cast<const uint32_t*>(packed);
   g.plane1 = g.plane0 + plane0_words(d->bits, d->d_in, d->d_out);
-  g.alpha = alpha;
-  g.beta = beta;
+  g.fac = fj.words;
+  g.n_scale = fj.inv_scale;
   g.out = y;
   g.out_bf16 = (y_dtype == QALORA_BF16);
   g.M = tokens;
@@ -401,25 +418,6 @@ static int forward_impl(const qalora_desc* d, int tokens, const void* x, const v
   g.row_scale = rs;
   g.ksplit = plan.gsplit;
   g.partial = plan.gsplit > 1 ? reinterpret_cast<float*>(w + plan.gpart) : nullptr;
-  uint16_t* u_ext = adapter ? reinterpret_cast<uint16_t*>(w + plan.u_ext) : nullptr;
-  uint16_t* b_ext_t = adapter ? reinterpret_cast<uint16_t*>(w + plan.b_ext_t) : nullptr;
-  float* P_keep = nullptr;
-  float* u_keep = nullptr;
-  if (keep) {
-    const KeptLayout k = kept_layout(*d, tokens);
-    P_keep = reinterpret_cast<float*>(static_cast<char*>(kept) + k.P);
-    u_keep = reinterpret_cast<float*>(static_cast<char*>(kept) + k.U);
-  }
-  if (launch_front_forward(static_cast<const uint16_t*>(x), tokens, d->d_in, rs, x16,
-                           adapter ? A : nullptr, B, d->s, d->group, d->rank, d->d_out, u_ext,
-                           b_ext_t, plan.ktail, P_keep, u_keep, st) != hipSuccess)
-    return QALORA_EHIP;
-  if (adapter) {
-    g.a_tail = u_ext;
-    g.lda_tail = plan.ktail;
-    g.b_tail = b_ext_t;
-    g.K_tail = plan.ktail;
-  }
   return launch_gemm_dq(d->bits, false, g, st) == hipSuccess ? QALORA_OK : QALORA_EHIP;
 }
 
@@ -442,18 +440,11 @@ static int backward_impl(const qalora_desc* d, int tokens, const void* dy, const
       misaligned(dB) || misaligned(ws))
     return QALORA_EALIGN;
   if (!addressable(*d, tokens)) return QALORA_EUNSUPPORTED;
-  BwdPlan plan = plan_backward(*d, tokens);
+  qalora_desc dd = *d;
+  if (!adapter) dd.rank = 0;
+  const BwdPlan plan = plan_backward(dd, tokens);
   if (adapter && (size_t)plan.ksplit * tokens * 2 * plan.rp * 4 >= kAddressable)
     return QALORA_EUNSUPPORTED;  // the split-K partials of dU are read with 32-bit byte offsets
-  if (!adapter) {
-    plan.rs = 0;
-    plan.a16 = align_up((size_t)tokens * sizeof(float2));
-    plan.total = plan.a16 + align_up((size_t)round_up(tokens, 256) * d->d_out * 2);
-    if (plan.gsplit > 1) {
-      plan.gpart = plan.total;
-      plan.total += align_up((size_t)plan.gsplit * tokens * d->d_in * 4);
-    }
-  }
   if (!ws || ws_bytes < plan.total) return QALORA_EWORKSPACE;
   hipStream_t st = as_stream(stream);
   char* w = static_cast<char*>(ws);
@@ -462,36 +453,84 @@ static int backward_impl(const qalora_desc* d, int tokens, const void* dy, const
   float2* rs = reinterpret_cast<float2*>(w + plan.rs);
   uint16_t* dyh = reinterpret_cast<uint16_t*>(w + plan.a16);  // fp16 scaled copy of dy
 
-  uint16_t* du_ext = nullptr;
-  uint16_t* a_ext_t = nullptr;
-  if (!adapter) {
-    if (launch_front_backward(dy16, tokens, d->d_out, rs, dyh, nullptr, d->d_in, nullptr, nullptr,
-                              0.0f, d->group, 0, nullptr, nullptr, 0, nullptr, nullptr, 0,
-                              nullptr, st) != hipSuccess)
-      return QALORA_EHIP;
-  } else {
-    float* P = reinterpret_cast<float*>(w + plan.P);
-    uint16_t* us_t = reinterpret_cast<uint16_t*>(w + plan.us_t);
-    const float* u_kept = nullptr;
+  // dx = dy W~'^T with beta' = beta + (s/g) A B: the pooled-LoRA term of dx is the adapter's
+  // share of W~' (App. B.3), so the factor job folds it in and the contraction needs no extra
+  // operand.  Skipped when dx is not wanted.
+  FactorJob fj{};
+  uint32_t* words = reinterpret_cast<uint32_t*>(w + plan.fac);
+  float* inv_scale = reinterpret_cast<float*>(w + plan.inv);
+  if (dx) {
+    fj.alpha = alpha;
+    fj.beta = beta;
+    fj.A = adapter ? A : nullptr;
+    fj.B = adapter ? B : nullptr;
+    fj.s = d->s;
+    fj.g = d->group;
+    fj.rank = adapter ? d->rank : 0;
+    fj.bits = d->bits;
+    fj.L = L;
+    fj.d_out = d->d_out;
+    if (use_kept) {  // the forward left the bounds: one stage
+      const KeptLayout k = kept_layout(*d, tokens);
+      fj.known_max = reinterpret_cast<const float*>(static_cast<const char*>(kept) + k.bmax);
+      fj.words = words;
+      fj.inv_scale = inv_scale;
+    } else {
+      fj.cst = reinterpret_cast<float*>(w + plan.cst);
+      fj.block_max = reinterpret_cast<float*>(w + plan.bmax);
+    }
+  }
+  float* P = nullptr;
+  uint16_t* us_t = nullptr;
+  uint16_t* b_hl = nullptr;
+  const float* u_kept = nullptr;
+  if (adapter) {
+    P = reinterpret_cast<float*>(w + plan.P);
+    us_t = reinterpret_cast<uint16_t*>(w + plan.us_t);
+    b_hl = reinterpret_cast<uint16_t*>(w + plan.b_hl);
     if (use_kept) {  // written by the forward: the front launch below then skips x altogether
       const KeptLayout k = kept_layout(*d, tokens);
       char* kp = const_cast<char*>(static_cast<const char*>(kept));
       P = reinterpret_cast<float*>(kp + k.P);
       u_kept = reinterpret_cast<const float*>(kp + k.U);
     }
-    uint16_t* b_hl = reinterpret_cast<uint16_t*>(w + plan.b_hl);
-    a_ext_t = reinterpret_cast<uint16_t*>(w + plan.a_ext_t);
+  }
+  // row scales + fp16 copy of dy; first stage of the factor words; P = pool(x), sU^T hi/lo and
+  // the hi/lo rows of B for the adapter gradients
+  if (launch_front_backward(dy16, tokens, d->d_out, rs, dyh,
+                            (adapter && !use_kept) ? static_cast<const uint16_t*>(x) : nullptr,
+                            d->d_in, adapter ? A : nullptr, B, d->s, d->group, adapter ? d->rank : 0, P,
+                            us_t, plan.t_pad, b_hl, u_kept, fj, st) != hipSuccess)
+    return QALORA_EHIP;
+  if (dx) {
+    if (!use_kept && launch_factor_scale(alpha, fj.cst, fj.block_max, plan.nmax, (size_t)L * d->d_out,
+                                         words, inv_scale, st) != hipSuccess)
+      return QALORA_EHIP;
+    GemmArgs g{};
+    g.a_main = dyh;
+    g.lda_main = d->d_out;
+    g.a_main_padded_rows = round_up(tokens, 256);
+    g.plane0 = static_cast<const uint32_t*>(packed);
+    g.plane1 = g.plane0 + plane0_words(d->bits, d->d_in, d->d_out);
+    g.fac = words;
+    g.n_scale = inv_scale;
+    g.out = dx;
+    g.out_bf16 = (dx_dtype == QALORA_BF16);
+    g.M = tokens;
+    g.N = d->d_in;
+    g.K_main = d->d_out;
+    g.d_in = d->d_in;
+    g.d_out = d->d_out;
+    g.group = d->group;
+    g.row_scale = rs;
+    g.ksplit = plan.gsplit;
+    g.partial = plan.gsplit > 1 ? reinterpret_cast<float*>(w + plan.gpart) : nullptr;
+    if (launch_gemm_dq(d->bits, true, g, st) != hipSuccess) return QALORA_EHIP;
+  }
+  if (adapter) {
     float* du_raw = reinterpret_cast<float*>(w + plan.du_raw);
-    du_ext = reinterpret_cast<uint16_t*>(w + plan.du_ext);
     float* db_part = reinterpret_cast<float*>(w + plan.db_part);
     float* da_part = reinterpret_cast<float*>(w + plan.da_part);
-
-    // row scales + fp16 copy of dy; P = pool(x), sU^T hi/lo; hi/lo operands of A and B
-    if (launch_front_backward(dy16, tokens, d->d_out, rs, dyh,
-                              use_kept ? nullptr : static_cast<const uint16_t*>(x),
-                              d->d_in, A, B, d->s, d->group, d->rank, P, us_t, plan.t_pad, b_hl,
-                              a_ext_t, plan.ktail, u_kept, st) != hipSuccess)
-      return QALORA_EHIP;
     // dU = s dy B^T : plain bf16 product against the hi/lo rows of B, split over K = d_out
     GemmArgs g{};
     g.a_tail = dy16;
@@ -504,42 +543,13 @@ static int backward_impl(const qalora_desc* d, int tokens, const void* dy, const
     g.group = 1;
     if (launch_gemm_plain(g, plan.ksplit, st) != hipSuccess) return QALORA_EHIP;
     // dB = (sU)^T dy and dA = P^T dU as partials over token slices, one launch; the dA job
-    // finalises dU on the fly and writes du_ext for the dx tail
+    // finalises dU on the fly
     if (launch_adapter_grads(us_t, plan.t_pad, dy16, tokens, d->d_out, d->rank, plan.tsplit_b, db_part,
-                             P, du_raw, plan.ksplit, d->s, rs, L, plan.tsplit_a, da_part, du_ext,
-                             plan.ktail, st) != hipSuccess)
+                             P, du_raw, plan.ksplit, d->s, L, plan.tsplit_a, da_part, st) != hipSuccess)
       return QALORA_EHIP;
     if (launch_reduce2(da_part, plan.tsplit_a, (size_t)L * d->rank, dA, db_part, plan.tsplit_b,
                        (size_t)d->rank * d->d_out, dB, accumulate, st) != hipSuccess)
       return QALORA_EHIP;
-  }
-  if (dx) {
-    GemmArgs g{};
-    g.a_main = dyh;
-    g.lda_main = d->d_out;
-    g.a_main_padded_rows = round_up(tokens, 256);
-    g.plane0 = static_cast<const uint32_t*>(packed);
-    g.plane1 = g.plane0 + plane0_words(d->bits, d->d_in, d->d_out);
-    g.alpha = alpha;
-    g.beta = beta;
-    g.out = dx;
-    g.out_bf16 = (dx_dtype == QALORA_BF16);
-    g.M = tokens;
-    g.N = d->d_in;
-    g.K_main = d->d_out;
-    g.d_in = d->d_in;
-    g.d_out = d->d_out;
-    g.group = d->group;
-    g.row_scale = rs;
-    g.ksplit = plan.gsplit;
-    g.partial = plan.gsplit > 1 ? reinterpret_cast<float*>(w + plan.gpart) : nullptr;
-    if (adapter) {
-      g.a_tail = du_ext;
-      g.lda_tail = plan.ktail;
-      g.b_tail = a_ext_t;
-      g.K_tail = plan.ktail;
-    }
-    if (launch_gemm_dq(d->bits, true, g, st) != hipSuccess) return QALORA_EHIP;
   }
   return QALORA_OK;
 }

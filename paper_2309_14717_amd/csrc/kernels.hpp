@@ -23,14 +23,13 @@ struct GemmArgs {
                            // multiplied by its power-of-two row scale
   int lda_main;
   int a_main_padded_rows;   // rows a_main may be read for (>= M; the rest holds anything)
-  const uint16_t* a_tail;  // bf16 [M, K_tail]: hi/lo split of s*U (forward) or dU (backward),
-                           // each row pre-multiplied by its row scale
+  const uint16_t* a_tail;  // bf16 [M, K_tail]: first operand of a plain product (no main part)
   int lda_tail;
   const uint32_t* plane0;  // packed codes
   const uint32_t* plane1;
-  const float* alpha;      // [L, d_out]
-  const float* beta;       // [L, d_out]
-  const uint16_t* b_tail;  // bf16: forward [d_out, K_tail] (B~^T); backward [L, K_tail] (A~/g)
+  const uint32_t* fac;     // [L, d_out] factor words: fp16(alpha S) | fp16((beta' + mid alpha) S) << 16
+  const float* n_scale;    // 1 / S: [d_out] (forward, per column) or [1] (backward)
+  const uint16_t* b_tail;  // bf16 [N, K_tail]: second operand of a plain product
   const float2* row_scale; // [M] (scale, 1/scale): power-of-two row scales of a_main
   void* out;               // [ksplit][M, N] fp32, or [M, N] bf16
   int out_bf16;
@@ -93,43 +92,61 @@ hipError_t launch_smallt4(const SmallTArgs& a, hipStream_t st);  // nonce set by
 hipError_t launch_smallt4_f16(const SmallTArgs& a, hipStream_t st);  // the 16-bit-factor instantiations
 
 // --- adapter.hip --------------------------------------------------------------------
-// Tail width of the adapter operands: three bf16 sections of `rank` columns, zero padded
-// to a multiple of 64.
-__host__ __device__ inline int adapter_ktail(int rank) { return rank > 0 ? ((3 * rank + 63) / 64) * 64 : 0; }
 // Rows of the hi (and of the lo) section of a bf16 hi/lo split of a [rank, *] matrix.
 __host__ __device__ inline int rank_pad32(int rank) { return ((rank + 31) / 32) * 32; }
 
-// Forward front launch: x -> rs (row scales), x16 = fp16(x * scale), and with an adapter
-//   u_ext   bf16 [T, ktail]      = [hi | lo | hi | 0] of s (pool_g(x) A) * row scale
-//   b_ext_t bf16 [d_out, ktail]  = [hi | hi | lo | 0] of B per output column
-// and, when given, P_keep fp32 [T, L] = pool_g(x) and u_keep fp32 [T, rank] = s pool_g(x) A, from
-// which the backward front launch below can work without x (its u_kept argument).
+// The factor job of a front launch: folds the adapter into the zero factors for this call,
+// beta' = beta + (s/g) A B (App. B.3), and writes the dense kernels' factor words
+// fp16(alpha S) | fp16((beta' + 2^(N-1) alpha) S) << 16.
+//   forward : words + inv_scale[d_out] (S per column, decided inside the job); optionally
+//             block_max[factor_job_blocks], the per-block bounds on |W~'|
+//   backward: the scale may not vary along the contraction index, which is the column there,
+//             so one S serves the call.  Either cst fp32 [L, d_out] + block_max -- then
+//             launch_factor_scale finishes the words -- or, given known_max (the block_max of
+//             an earlier launch on the same alpha, beta, A, B), words + inv_scale[1] at once.
+struct FactorJob {
+  const float* alpha;   // [L, d_out]; null: no factor job in this launch
+  const float* beta;    // [L, d_out]
+  const float* A;       // [L, rank] or null
+  const float* B;       // [rank, d_out] or null
+  float s;
+  int g, rank, bits, L, d_out;
+  uint32_t* words;      // forward
+  float* inv_scale;     // forward
+  float* cst;           // backward, two-stage form
+  float* block_max;     // [factor_job_blocks], optional in the forward
+  const float* known_max;  // backward, one-stage form
+};
+int factor_job_blocks(int L, int d_out);
+hipError_t launch_factor_scale(const float* alpha, const float* cst, const float* block_max, int nmax,
+                               size_t n, uint32_t* words, float* inv_scale, hipStream_t st);
+
+// Forward front launch: x -> rs (row scales), x16 = fp16(x * scale), the factor job, and, when
+// given, P_keep fp32 [T, L] = pool_g(x) and u_keep fp32 [T, rank] = s pool_g(x) A, from which the
+// backward front launch below can work without x (its u_kept argument).
 hipError_t launch_front_forward(const uint16_t* x, int T, int d_in, float2* rs, uint16_t* x16,
-                                const float* A, const float* B, float s, int g, int rank,
-                                int d_out, uint16_t* u_ext, uint16_t* b_ext_t, int ktail,
-                                float* P_keep, float* u_keep, hipStream_t st);
-// Backward front launch: dy -> rs_dy, dy16; and with an adapter
+                                const float* A, float s, int g, int rank, float* P_keep,
+                                float* u_keep, const FactorJob& fac, hipStream_t st);
+// Backward front launch: dy -> rs_dy, dy16; the factor job (first stage); and with an adapter
 //   P       fp32 [T, L]          = pool_g(x)
 //   us_t    bf16 [2*rp, t_pad]   = rows hi(sU)^T then lo(sU)^T (token-contiguous, zero padded)
 //   b_hl    bf16 [2*rp, d_out]   = hi(B) rows then lo(B) rows
-//   a_ext_t bf16 [L, ktail]      = [hi | hi | lo | 0] of A / g
 // With u_kept (the forward's u_keep) x is not read: P is not written (the caller passes the
 // forward's P_keep on to the gradient kernels) and us_t is transposed from u_kept.
 hipError_t launch_front_backward(const uint16_t* dy, int T, int d_out, float2* rs_dy,
                                  uint16_t* dy16, const uint16_t* x, int d_in, const float* A,
                                  const float* B, float s, int g, int rank, float* P,
-                                 uint16_t* us_t, int t_pad, uint16_t* b_hl, uint16_t* a_ext_t,
-                                 int ktail, const float* u_kept, hipStream_t st);
+                                 uint16_t* us_t, int t_pad, uint16_t* b_hl, const float* u_kept,
+                                 const FactorJob& fac, hipStream_t st);
 // Both adapter-gradient jobs in one launch (neither depends on the other):
 //   dB partials over token slices: db_part[z][rank][d_out] = sum_{t in slice z} sU[t,:]^T dy[t,:]
 //   dA partials over token slices: da_part[z][L][rank] = sum_{t in slice z} P[t,:]^T dU[t,:], with
 //   dU = s * sum_q (raw[q][:, :rp] + raw[q][:, rp:]) rebuilt from the split-K partials of the dU
-//   product; that job also writes du_ext bf16 [T, ktail] = [hi | lo | hi | 0] of dU * rs[t].x
+//   product
 hipError_t launch_adapter_grads(const uint16_t* us_t, int t_pad, const uint16_t* dy, int T, int d_out,
                                 int rank, int tsplit_b, float* db_part, const float* P,
-                                const float* raw, int ksplit, float s, const float2* rs, int L,
-                                int tsplit_a, float* da_part, uint16_t* du_ext, int ktail,
-                                hipStream_t st);
+                                const float* raw, int ksplit, float s, int L, int tsplit_a,
+                                float* da_part, hipStream_t st);
 // out = (accumulate ? out : 0) + sum_z part[z], fixed order, for two outputs in one launch
 hipError_t launch_reduce2(const float* part_a, int nparts_a, size_t n_a, float* out_a,
                           const float* part_b, int nparts_b, size_t n_b, float* out_b,

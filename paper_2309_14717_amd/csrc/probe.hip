@@ -23,7 +23,9 @@ typedef uint32_t pu32x4 __attribute__((ext_vector_type(4)));
 //   (4, 4, 4): one wavefront per SIMD, 8 fragment reads per 16 MFMAs
 // LDS : fetch the fragments of the next K-16 slice from LDS under the current slice's MFMAs
 // NV  : vector instructions (v_and_or_b32 on private registers) issued behind every MFMA
-template <int WAVES, int TM, int TN, bool LDS, int NV>
+// ACC : keep the accumulators in the accumulation registers (AGPRs).  With eight wavefronts per
+//       block the compiler otherwise keeps them in ordinary vector registers.
+template <int WAVES, int TM, int TN, bool LDS, int NV, bool ACC = false>
 __global__ __launch_bounds__(WAVES * 64) void mfma_probe_kernel(float* sink, unsigned long long* counts,
                                                                 int iters) {
   // 64 KB of fp16 values of either sign with magnitudes in [0.5, 2) and hashed mantissas:
@@ -44,6 +46,10 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_probe_kernel(float* sink, uns
     lds[i] = v;
   }
   __syncthreads();
+  if constexpr (ACC) {  // one use of the register class makes the compiler place MFMA results there
+    float hint = 0.0f;
+    asm volatile("" : "+a"(hint));
+  }
   f32x16 acc[TM][TN];
 #pragma unroll
   for (int a = 0; a < TM; ++a)
@@ -118,15 +124,16 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_probe_kernel(float* sink, uns
   }
 }
 
-template <int WAVES, int TM, int TN, bool LDS, int NV>
+template <int WAVES, int TM, int TN, bool LDS, int NV, bool ACC = false>
 hipError_t run(float* sink, unsigned long long* counts, int iters, int blocks, hipStream_t st) {
-  mfma_probe_kernel<WAVES, TM, TN, LDS, NV><<<blocks, WAVES * 64, 0, st>>>(sink, counts, iters);
+  mfma_probe_kernel<WAVES, TM, TN, LDS, NV, ACC><<<blocks, WAVES * 64, 0, st>>>(sink, counts, iters);
   return hipGetLastError();
 }
 
 }  // namespace
 
-// shape 0: eight wavefronts x (4 x 2) tiles; shape 1: four wavefronts x (4 x 4) tiles.
+// shape 0: eight wavefronts x (4 x 2) tiles; shape 1: four wavefronts x (4 x 4) tiles; shape 2:
+// shape 0 with the accumulators in AGPRs.
 // Returns hipErrorInvalidValue for a combination that is not built.
 hipError_t launch_mfma_probe(int shape, int lds_reads, int valu_per_mfma, float* sink,
                              unsigned long long* counts, int iters, int blocks, hipStream_t st) {
@@ -151,6 +158,16 @@ hipError_t launch_mfma_probe(int shape, int lds_reads, int valu_per_mfma, float*
       case 4: return run<4, 4, 4, true, 4>(sink, counts, iters, blocks, st);
       case 6: return run<4, 4, 4, true, 6>(sink, counts, iters, blocks, st);
       case 8: return run<4, 4, 4, true, 8>(sink, counts, iters, blocks, st);
+      default: return hipErrorInvalidValue;
+    }
+  }
+  if (shape == 2) {
+    if (!lds_reads) return valu_per_mfma == 0 ? run<8, 4, 2, false, 0, true>(sink, counts, iters, blocks, st)
+                                              : hipErrorInvalidValue;
+    switch (valu_per_mfma) {
+      case 0: return run<8, 4, 2, true, 0, true>(sink, counts, iters, blocks, st);
+      case 2: return run<8, 4, 2, true, 2, true>(sink, counts, iters, blocks, st);
+      case 4: return run<8, 4, 2, true, 4, true>(sink, counts, iters, blocks, st);
       default: return hipErrorInvalidValue;
     }
   }

@@ -62,10 +62,12 @@ def test_packed_and_workspace_sizes(lib):
     assert api.workspace_bytes(d, 4096, api.OP_MERGE) == 0
     f = api.workspace_bytes(d, 4096, api.OP_FORWARD)
     b = api.workspace_bytes(d, 4096, api.OP_BACKWARD)
-    assert f >= 4096 * 192 * 2 + 4096 * 192 * 2 and b > f
+    # forward: the fp16 copy of x and one factor word per (group, column); backward: more
+    assert f >= 4096 * 4096 * 2 + 128 * 4096 * 4 and b > f
     assert api.workspace_bytes(d, 4096, 99) == 0
     d0 = api.make_desc(4096, 4096, 4, 32, 0, 0.0)
-    assert 4096 * 8 <= api.workspace_bytes(d0, 4096, api.OP_FORWARD) < f
+    # the adapter is folded into the factor words, so the forward needs the same room without one
+    assert api.workspace_bytes(d0, 4096, api.OP_FORWARD) == f
     assert 4096 * 8 <= api.workspace_bytes(d0, 4096, api.OP_BACKWARD) < b
     assert api.packed_bytes(api.make_desc(4096, 4096, 7, 32)) == 0
 

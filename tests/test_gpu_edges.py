@@ -202,3 +202,74 @@ def test_streaming_status_word_stays_clear(gpu_api):
     for T in (1, 4):
         gpu_api.forward(L["desc"], L["x"][:T].contiguous(), L["packed"], L["g_alpha"], L["g_beta"], ws=ws)
     assert gpu_api.streaming_status(ws) == 0
+
+
+@pytest.mark.parametrize("w_std", [1e-5, 1e-7, 30.0])
+def test_weights_far_from_unit_scale(gpu_api, w_std):
+    """The dense path converts the factors to fp16 only after a power-of-two scale of its own
+    (per output column forward, per call backward), so weights far below fp16's normal range
+    -- or far above the usual 0.02 -- keep the same relative accuracy."""
+    cfg = synth.LayerConfig("tiny_w", 300, 512, 264, 4, 32, 8, 0.5, seed=41, w_std=w_std, ab_std=0.02 * w_std / 0.02)
+    L = layer_on_gpu(gpu_api, cfg)
+    d = L["np"]
+    w = (L["packed"], L["g_alpha"], L["g_beta"], L["A"], L["B"])
+    y = gpu_api.forward(L["desc"], L["x"], *w)
+    dx, dA, dB = gpu_api.backward(L["desc"], L["dy"], L["x"], *w)
+    ref = oracle.forward(d["x"], L["codes"], L["alpha"], L["beta"], cfg.group, d["A"], d["B"], cfg.s)
+    rdx, rdA, rdB = oracle.backward(d["dy"], d["x"], L["codes"], L["alpha"], L["beta"], cfg.group,
+                                    d["A"], d["B"], cfg.s)
+    errs = dict(y=rel_err(y.cpu().numpy(), ref), dx=rel_err(dx.cpu().numpy(), rdx),
+                dA=rel_err(dA.cpu().numpy(), rdA), dB=rel_err(dB.cpu().numpy(), rdB))
+    record(f"weights of std {w_std:g}", **errs)
+    assert max(errs.values()) <= TOL, errs
+
+
+def test_columns_of_very_different_scale(gpu_api):
+    """Output columns whose weights differ by 2^40 in magnitude: the forward scales every
+    column on its own, so each column is accurate relative to ITS largest output."""
+    cfg = synth.LayerConfig("col_scales", 260, 256, 64, 4, 32, 0, 0.0, seed=43)
+    d = synth.make_inputs(cfg)
+    W = d["W"].copy()
+    W[:, 1::2] *= np.float32(2.0 ** -40)
+    codes, alpha, beta = oracle.quantize(W, 4, 32)
+    L = layer_on_gpu(gpu_api, cfg, inputs=d, quantized=(codes, alpha, beta))
+    y = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"]).cpu().numpy().astype(np.float64)
+    ref = oracle.forward(d["x"], codes, alpha, beta, 32)
+    per_col = np.abs(y - ref).max(axis=0) / np.abs(ref).max(axis=0)
+    record("columns 2^40 apart", worst_column=float(per_col.max()))
+    assert per_col.max() <= TOL
+
+
+def test_imported_triples_far_from_the_mid_code(gpu_api):
+    """Triples from another quantizer (through qalora_pack).  The dense path evaluates a weight
+    as alpha (c - mid) + (beta + mid alpha) with the constant rounded to fp16, so its error per
+    weight is bounded by 2^-11 |beta + mid alpha| (+ 2^-11 |alpha (c - mid)|) whatever codes the
+    group uses -- stated in include/qalora.h.
+    (a) zero-point groups alpha (c - z) with integer z anywhere in the code range, codes
+        crowded at one end: the bound is a fraction of a quantization step, parity holds;
+    (b) the degenerate encoding (codes 0, alpha = 1, beta = v): the error is bounded by
+        2^-11 (|v| + 8), checked as such, not against the 2e-3 bar."""
+    rng = np.random.default_rng(91)
+    d_in, d_out, g, T = 512, 128, 32, 260
+    x = torch.from_numpy(rng.standard_normal((T, d_in)).astype(np.float32)).to(torch.bfloat16)
+    x64 = x.float().numpy().astype(np.float64)
+    desc = gpu_api.make_desc(d_in, d_out, 4, g)
+    # (a)
+    z = rng.integers(0, 16, size=(d_in // g, d_out)).astype(np.float32)
+    alpha = (rng.random((d_in // g, d_out), dtype=np.float32) * 0.01 + 0.002).astype(np.float32)
+    lo = np.where(np.repeat(z, g, axis=0) < 8, 0, 12)
+    codes = (lo + rng.integers(0, 4, size=(d_in, d_out))).astype(np.uint8)
+    beta = oracle.beta_from_zero_point(alpha, z).astype(np.float32)
+    y = gpu_api.forward(desc, x.cuda(), gpu_api.pack(desc, dev(codes)), dev(alpha), dev(beta))
+    ref = oracle.forward(x64, codes, alpha, beta, g)
+    err = rel_err(y.cpu().numpy(), ref)
+    record("imported zero-point triples", y=err)
+    assert err <= TOL
+    # (b)
+    v = (rng.standard_normal((d_in // g, d_out)) * 0.02).astype(np.float32)
+    ones = np.ones_like(v)
+    zeros = np.zeros((d_in, d_out), np.uint8)
+    y = gpu_api.forward(desc, x.cuda(), gpu_api.pack(desc, dev(zeros)), dev(ones), dev(v))
+    ref = oracle.forward(x64, zeros, ones, v, g)
+    bound = 2.0 ** -11 * (np.abs(v).max() + 8.0) * np.abs(x64).sum(axis=1).max()
+    assert np.abs(y.cpu().numpy() - ref).max() <= bound

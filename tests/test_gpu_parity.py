@@ -97,11 +97,13 @@ def test_adapter_branch_alone(gpu_api, rank):
     y = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], L["g_beta"], L["A"], L["B"])
     ref = oracle.forward(d["x"], codes, zeros, zeros, cfg.group, d["A"], d["B"], cfg.s)
     assert np.abs(ref).max() > 1.0
-    assert rel_err(y.cpu().numpy(), ref) <= 1e-4
+    # the adapter reaches the matrix cores folded into the zero factors, beta' = (s/g) A B here,
+    # rounded to fp16 once: 2^-11 relative per weight at most
+    assert rel_err(y.cpu().numpy(), ref) <= 2.0 ** -11
     dx, dA, dB = gpu_api.backward(L["desc"], L["dy"], L["x"], L["packed"], L["g_alpha"], L["g_beta"],
                                   L["A"], L["B"])
     rdx, rdA, rdB = oracle.backward(d["dy"], d["x"], codes, zeros, zeros, cfg.group, d["A"], d["B"], cfg.s)
-    assert rel_err(dx.cpu().numpy(), rdx) <= 1e-4
+    assert rel_err(dx.cpu().numpy(), rdx) <= 2.0 ** -11  # the folded zero factors again
     assert rel_err(dA.cpu().numpy(), rdA) <= 1e-4
     assert rel_err(dB.cpu().numpy(), rdB) <= 1e-4
 
