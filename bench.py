@@ -109,6 +109,7 @@ class Layer:
         self.packed, self.alpha, self.beta = api.quantize(self.desc, W)
         self.beta_m = api.merge(self.desc, self.beta, self.A, self.B) if merged else None
         self.fac16 = None
+        self.dep = None   # deployment stream of the merged layer (decode layout)
         T = cfg.tokens
         self.y = torch.empty((T, cfg.d_out), dtype=odt, device=dev)
         self.ws_f = torch.empty(max(16, api.workspace_bytes(self.desc, T, api.OP_FORWARD)), dtype=torch.uint8, device=dev)
@@ -131,6 +132,10 @@ class Layer:
 
     def forward_merged(self, x=None, y=None, ws=None):
         a = self.api
+        xx = self.x if x is None else x
+        if self.dep is not None and xx.shape[0] <= 4:  # decode step from the deployment stream
+            return a.forward_deployed(self.desc, xx, self.dep, ws=self.ws_f if ws is None else ws,
+                                      y=self.y if y is None else y)
         if self.fac16 is not None:  # factors of the merged layer stored as fp16 pairs
             return a.forward_factors16(self.desc, self.x if x is None else x, self.packed, self.fac16,
                                        ws=self.ws_f if ws is None else ws, y=self.y if y is None else y)
@@ -259,14 +264,17 @@ def clock_fields(clk_ghz, achieved_tflops):
             "frac_at_measured_clock": round(achieved_tflops / (PEAK_MFMA_TFLOPS * clk_ghz / NOMINAL_CLOCK_GHZ), 4)}
 
 
-def small_token_sets(torch, api, synth, name, n_sets, odt, bits=4):
-    """`n_sets` merged layers of one c5 shape (distinct weights, same distribution)."""
+def small_token_sets(torch, api, synth, name, n_sets, odt, bits=4, deployed=False):
+    """`n_sets` merged layers of one c5 shape (distinct weights, same distribution); with
+    `deployed` each also holds its deployment stream (the static merged model repacked once)."""
     cfg = synth.CONFIGS[name].scaled(tokens=256, bits=bits)
     gen = torch.Generator(device="cuda").manual_seed(1000 + cfg.seed)
     sets = []
     for i in range(n_sets):
         L = Layer(api, torch, cfg, odt, gen=gen if i else None, want_bwd=False, merged=True)
         L.drop_w()
+        if deployed and bits == 4:
+            L.dep = api.deploy(L.desc, L.packed, L.alpha, L.beta_m)
         sets.append(L)
     return cfg, sets
 
@@ -274,7 +282,7 @@ def small_token_sets(torch, api, synth, name, n_sets, odt, bits=4):
 def small_token_table(torch, api, synth, odt, n_sets=8, tokens=(1, 4, 16, 256), iters=48):
     rows = []
     for name in ("c5_up", "c5_down"):
-        cfg, sets = small_token_sets(torch, api, synth, name, n_sets, odt)
+        cfg, sets = small_token_sets(torch, api, synth, name, n_sets, odt, deployed=True)
         for T in tokens:
             x = sets[0].x[:T].contiguous()
             y = torch.empty((T, cfg.d_out), dtype=odt, device="cuda")
@@ -283,7 +291,8 @@ def small_token_table(torch, api, synth, odt, n_sets=8, tokens=(1, 4, 16, 256), 
             ms = timed(torch, lambda: sets[next(it) % n_sets].forward_merged(x=x, y=y, ws=ws), n=iters, warm=n_sets)
             by = forward_bytes(cfg, T, y.element_size())
             fl = 2.0 * T * cfg.d_in * cfg.d_out
-            rows.append({"shape": f"{cfg.d_in}x{cfg.d_out}", "tokens": T, "us": round(ms * 1e3, 2),
+            rows.append({"shape": f"{cfg.d_in}x{cfg.d_out}", "tokens": T,
+                         "layout": "deployment stream" if T <= 4 else "training layout", "us": round(ms * 1e3, 2),
                          "GB/s": round(by / ms / 1e6, 1), "frac_hbm": round(by / ms / 1e6 / PEAK_HBM_GBS, 4),
                          "TFLOP/s": round(fl / ms / 1e9, 2)})
         del sets
@@ -376,6 +385,8 @@ def main():
     ap.add_argument("--tokens", type=int, default=16, help="c5: tokens per call")
     ap.add_argument("--factors16", action="store_true",
                     help="c5: alpha, beta of the merged layers stored as fp16 pairs (the configuration itself has fp32)")
+    ap.add_argument("--no-deployed", action="store_true",
+                    help="c5, up to four tokens: read the training layout instead of the deployment stream")
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
     ap.add_argument("--no-keep", action="store_true",
                     help="backward re-reads x instead of the pooled activations the forward kept")
@@ -510,8 +521,9 @@ def main():
     else:  # c5
         T = args.tokens
         n_sets = 8
-        cfg_u, ups = small_token_sets(torch, api, synth, "c5_up", n_sets, odt, args.bits)
-        cfg_d, downs = small_token_sets(torch, api, synth, "c5_down", n_sets, odt, args.bits)
+        dep = not args.no_deployed and not args.factors16
+        cfg_u, ups = small_token_sets(torch, api, synth, "c5_up", n_sets, odt, args.bits, deployed=dep)
+        cfg_d, downs = small_token_sets(torch, api, synth, "c5_down", n_sets, odt, args.bits, deployed=dep)
         fb = 2 if args.factors16 else 4
         if args.factors16:
             for Lr in ups + downs:
@@ -562,7 +574,8 @@ def main():
                   "bytes_per_step": by_step, "weight_sets": n_sets}
         workload = (f"c5: post-merge forward, T={T}, 8192x22016 then 22016x8192, INT{args.bits} g=32, merged beta, "
                     f"x bf16, outputs {args.out_dtype}, {n_sets} weight sets rotated"
-                    + (", alpha and beta stored as fp16 pairs" if args.factors16 else ""))
+                    + (", alpha and beta stored as fp16 pairs" if args.factors16 else "")
+                    + (", read from the deployment stream (qalora_deploy)" if (dep and T <= 4 and args.bits == 4) else ""))
         cfg = cfg_u
         if not args.no_cpu_baseline:
             import oracle

@@ -31,6 +31,7 @@ EXPORTS = (
     "qalora_adamw_workspace_bytes", "qalora_adamw_step",
     "qalora_kept_bytes", "qalora_forward_keep", "qalora_backward_kept",
     "qalora_forward_noalloc", "qalora_profile_mfma_probe",
+    "qalora_deployed_bytes", "qalora_deploy", "qalora_forward_deployed",
 )
 
 
@@ -73,6 +74,10 @@ def load() -> ctypes.CDLL:
     lib.qalora_forward.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
     lib.qalora_backward.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, vp, i, vp, vp, i, vp, sz, vp]
     lib.qalora_merge.argtypes = [cp, vp, vp, vp, vp, vp]
+    lib.qalora_deployed_bytes.restype = sz
+    lib.qalora_deployed_bytes.argtypes = [cp]
+    lib.qalora_deploy.argtypes = [cp, vp, vp, vp, vp, vp]
+    lib.qalora_forward_deployed.argtypes = [cp, i, vp, vp, vp, i, vp, sz, vp]
     lib.qalora_profile_mfma_probe.argtypes = [i, i, i, i, i, vp, vp, vp]
     lib.qalora_forward_noalloc.argtypes = [cp, i, vp, vp, vp, vp, vp, i, vp]
     lib.qalora_kept_bytes.restype = sz
@@ -251,6 +256,38 @@ def forward_noalloc(desc: Desc, x, packed, alpha, beta, out_dtype=torch.float32,
     rc = load().qalora_forward_noalloc(ctypes.byref(desc), T, _p(x), _p(packed), _p(alpha), _p(beta), _p(y),
                                        BF16 if y.dtype == torch.bfloat16 else F32, _stream())
     _check(rc, "qalora_forward_noalloc")
+    return y
+
+
+def deploy(desc: Desc, packed, alpha, beta):
+    """One-time repack of a (merged) 4-bit layer into the decode kernel's stream."""
+    n = int(load().qalora_deployed_bytes(ctypes.byref(desc)))
+    if n == 0:
+        raise QaloraError(EUNSUPPORTED, "qalora_deployed_bytes")
+    L = desc.d_in // desc.group
+    _need(packed, "packed", nbytes=packed_bytes(desc))
+    _need(alpha, "alpha", torch.float32, (L, desc.d_out), device=packed.device)
+    _need(beta, "beta", torch.float32, (L, desc.d_out), device=packed.device)
+    out = torch.empty(n, dtype=torch.uint8, device=packed.device)
+    _check(load().qalora_deploy(ctypes.byref(desc), _p(packed), _p(alpha), _p(beta), _p(out), _stream()),
+           "qalora_deploy")
+    return out
+
+
+def forward_deployed(desc: Desc, x, deployed, out_dtype=torch.float32, ws=None, y=None):
+    """Decode-step forward from the deployment stream (adapter-free, up to four tokens)."""
+    _need(x, "x", torch.bfloat16)
+    T, dev = x.shape[0], x.device
+    if check_desc(desc) == OK:
+        _need(x, "x", shape=(T, desc.d_in))
+        _need(deployed, "deployed", nbytes=int(load().qalora_deployed_bytes(ctypes.byref(desc))), device=dev)
+    if y is None:
+        y = torch.empty((T, desc.d_out), dtype=out_dtype, device=dev)
+    _need_out(y, "y", T, desc.d_out, dev)
+    ws, ws_bytes = _workspace(desc, min(T, 16), OP_FORWARD, ws, dev)
+    rc = load().qalora_forward_deployed(ctypes.byref(desc), T, _p(x), _p(deployed), _p(y),
+                                        BF16 if y.dtype == torch.bfloat16 else F32, _p(ws), ws_bytes, _stream())
+    _check(rc, "qalora_forward_deployed")
     return y
 
 

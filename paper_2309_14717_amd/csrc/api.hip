@@ -599,6 +599,56 @@ int qalora_forward_noalloc(const qalora_desc* d, int tokens, const void* x, cons
   return launch_smallt(a, as_stream(stream)) == hipSuccess ? QALORA_OK : QALORA_EHIP;
 }
 
+// The deployment stream covers what the one-column-per-lane streaming kernel covers at 4 bits.
+static bool deployable(const qalora_desc& d) {
+  return d.bits == 4 && (d.group == 32 || d.group == 64 || d.group == 128) && d.d_in % 128 == 0 &&
+         deploy_stream_bytes(d.d_in, d.d_out, d.group) < kAddressable;
+}
+
+size_t qalora_deployed_bytes(const qalora_desc* d) {
+  if (qalora_check_desc(d) != QALORA_OK || !deployable(*d)) return 0;
+  return deploy_stream_bytes(d->d_in, d->d_out, d->group);
+}
+
+int qalora_deploy(const qalora_desc* d, const void* packed, const float* alpha, const float* beta,
+                  void* deployed, void* stream) {
+  const int rc = qalora_check_desc(d);
+  if (rc != QALORA_OK) return rc;
+  if (!packed || !alpha || !beta || !deployed) return QALORA_EINVAL;
+  if (misaligned(packed) || misaligned(alpha) || misaligned(beta) || misaligned(deployed)) return QALORA_EALIGN;
+  if (!deployable(*d)) return QALORA_EUNSUPPORTED;
+  return launch_deploy(static_cast<const uint32_t*>(packed), alpha, beta, d->d_in, d->d_out, d->group, deployed,
+                       as_stream(stream)) == hipSuccess
+             ? QALORA_OK
+             : QALORA_EHIP;
+}
+
+int qalora_forward_deployed(const qalora_desc* d, int tokens, const void* x, const void* deployed, void* y,
+                            int y_dtype, void* ws, size_t ws_bytes, void* stream) {
+  const int rc = qalora_check_desc(d);
+  if (rc != QALORA_OK) return rc;
+  if (tokens <= 0 || !x || !deployed || !y) return QALORA_EINVAL;
+  if (y_dtype != QALORA_F32 && y_dtype != QALORA_BF16) return QALORA_EINVAL;
+  if (misaligned(x) || misaligned(deployed) || misaligned(y) || misaligned(ws)) return QALORA_EALIGN;
+  if (!deployable(*d) || tokens > QALORA_DEPLOYED_MAX_TOKENS) return QALORA_EUNSUPPORTED;
+  const size_t need = smallt_workspace(*d, tokens);
+  if (!ws || ws_bytes < need) return QALORA_EWORKSPACE;
+  SmallTArgs a{};
+  a.x = static_cast<const uint16_t*>(x);
+  a.stream = deployed;
+  a.bits = d->bits;
+  a.out = y;
+  a.flags = static_cast<unsigned long long*>(ws);
+  a.status = a.flags + ST_MAX_BLOCKS;
+  a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + ST_HEAD_BYTES);
+  a.out_bf16 = (y_dtype == QALORA_BF16);
+  a.T = tokens;
+  a.d_in = d->d_in;
+  a.d_out = d->d_out;
+  a.group = d->group;
+  return launch_smallt4_deployed(a, as_stream(stream)) == hipSuccess ? QALORA_OK : QALORA_EHIP;
+}
+
 int qalora_pack_factors16(const qalora_desc* d, const float* alpha, const float* beta, void* factors16,
                           void* stream) {
   const int rc = qalora_check_desc(d);

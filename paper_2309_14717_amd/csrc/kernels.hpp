@@ -69,6 +69,7 @@ struct SmallTArgs {
   const float* alpha;      // [L, d_out]
   const float* beta;       // [L, d_out]
   const uint32_t* fac16;   // or, instead of both: [L, d_out] words fp16 alpha | fp16 beta << 16
+  const void* stream;      // or, instead of planes and factors: the deployment stream (launch_deploy)
   void* out;               // [T, d_out] fp32 or bf16
   float* partial;          // [blocks][ST_PARTIAL_FLOATS] fp32: each block's [token][slab column] tile
   unsigned long long* flags;  // [blocks]: set to `nonce` once the block's partial is complete
@@ -85,6 +86,22 @@ struct SmallTPlan {
 };
 SmallTPlan smallt_plan(int d_in, int d_out, int tokens);
 hipError_t launch_smallt(const SmallTArgs& a, hipStream_t st);  // dispatches on T
+unsigned long long smallt_next_nonce();  // unique per call of this process, never zero
+// Deployment stream of a 4-bit layer (the static, merged model of Sec. 3.3 / App. B.3): for
+// every group of 64 columns and every 128-row chunk one contiguous record of 16-byte units,
+// unit u of lane (= column) at byte 1024 u + 16 lane: units 0..3 the column's sixteen code words
+// of the chunk in row order, then the chunk's fp32 factors -- group 32: alpha of its four
+// groups, beta of its four groups; group 64: alpha0 alpha1 beta0 beta1; group 128: alpha beta
+// 0 0.  Records are ordered [chunk][column group]: the chip's wavefronts advance through the
+// chunks together, so at any moment they sweep one contiguous region.
+__host__ __device__ constexpr int s4_dep_units(int sub) { return sub == 1 ? 6 : 5; }
+inline size_t deploy_stream_bytes(int d_in, int d_out, int group) {
+  return (size_t)((d_out + 63) / 64) * (size_t)(d_in / 128) * (size_t)s4_dep_units(group / 32) * 1024;
+}
+hipError_t launch_deploy(const uint32_t* plane0, const float* alpha, const float* beta, int d_in, int d_out,
+                         int group, void* stream_out, hipStream_t st);
+hipError_t launch_smallt4_deployed(const SmallTArgs& a, hipStream_t st);  // nonce set here
+
 // --- smallt4.hip: one column per lane on the 4x4x4 MFMA: T <= 4 for every code width, and
 // INT3 / INT2 up to sixteen tokens -------------------------------------------------------
 SmallTPlan smallt4_plan(int d_in, int d_out, int tokens);
@@ -116,6 +133,7 @@ struct FactorJob {
   float* cst;           // backward, two-stage form
   float* block_max;     // [factor_job_blocks], optional in the forward
   const float* known_max;  // backward, one-stage form
+  bool plain_beta;      // cst = beta' itself (no mid-code term): the merge of App. B.3
 };
 int factor_job_blocks(int L, int d_out);
 hipError_t launch_factor_scale(const float* alpha, const float* cst, const float* block_max, int nmax,

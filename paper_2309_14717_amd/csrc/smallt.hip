@@ -502,13 +502,17 @@ static hipError_t launch_sub(const SmallTArgs& a, int grid, hipStream_t st) {
   return launch_tgs<SUB, KH, F16, 2>(a, grid, st);
 }
 
-hipError_t launch_smallt(const SmallTArgs& args, hipStream_t st) {
+// A value no earlier call of this process has written to the flags (and never zero).
+unsigned long long smallt_next_nonce() {
   static std::atomic<unsigned long long> calls{0};
-  SmallTArgs a = args;
-  // a value no earlier call of this process has written to the flags (and never zero)
   unsigned long long z = (calls.fetch_add(1) + 1) * 0x9e3779b97f4a7c15ull;
   z ^= z >> 31;  // both steps are bijections that fix zero, and the count is never zero
-  a.nonce = z;
+  return z;
+}
+
+hipError_t launch_smallt(const SmallTArgs& args, hipStream_t st) {
+  SmallTArgs a = args;
+  a.nonce = smallt_next_nonce();
   const SmallTPlan pl = smallt_plan(a.d_in, a.d_out, a.T);
   const int sub = a.group / 32;
   auto run = [&]() -> hipError_t {

@@ -100,16 +100,22 @@ __device__ __forceinline__ uint32_t shift_to(uint32_t word, int sh) { return sh 
 // TG    : groups of four tokens (1, 2, 4): every group reuses the code operand a lane has built,
 //         with its own rows of x and its own accumulators
 // F16   : the factors of a (group, column) come as ONE word, fp16 alpha | fp16 beta << 16
-template <int NBITS, int SUB, int KH, int TG, bool F16>
+// DEP   : the weight comes as the deployment stream (see s4_dep_units): per 64 columns and
+//         128-row chunk one contiguous record of 16-byte units, a lane's four code units and its
+//         factor unit(s), so that a wavefront streams one contiguous range with 16-byte loads
+//         instead of twenty-four strided 4-byte ones (4-bit codes, fp32 factors, up to 4 tokens)
+template <int NBITS, int SUB, int KH, int TG, bool F16, bool DEP = false>
 __global__ __launch_bounds__(S4_THREADS) void smallt4_kernel(const SmallTArgs p) {
   using F = S4Fmt<NBITS>;
+  static_assert(!DEP || (NBITS == 4 && !F16 && TG == 1), "the deployment stream holds 4-bit codes and fp32 factors");
   constexpr int NTOK = 4 * TG;             // token rows held in LDS
   constexpr int WPR = S4_WAVES / NTOK;     // wavefronts that share the staging of one token row
   constexpr int NBUF = TG == 1 ? 3 : 2;    // chunk buffers in rotation
   extern __shared__ __align__(16) unsigned char xs[];  // [NTOK][S4_XROW] x, then the group sums
   __shared__ int poison;
   constexpr int NG = 4 / SUB;              // groups per chunk
-  constexpr int NLOADS = F::W0 + F::W1 + (F16 ? 1 : 2) * NG;  // vector-memory loads of one chunk
+  constexpr int DEP_UNITS = s4_dep_units(SUB);             // 16-byte units per lane and chunk
+  constexpr int NLOADS = DEP ? DEP_UNITS : F::W0 + F::W1 + (F16 ? 1 : 2) * NG;  // vector-memory loads of one chunk
   constexpr int NCG = S4_WAVES / KH;       // column groups (64 columns each)
   constexpr int SLAB_COLS = NCG * S4_WCOLS;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -123,7 +129,9 @@ __global__ __launch_bounds__(S4_THREADS) void smallt4_kernel(const SmallTArgs p)
   const int b = blockIdx.x, s = b / m, part = b - s * m;
   const int ca = (int)((long)C * part / m), ce = (int)((long)C * (part + 1) / m);
 
-  const __amdgpu_buffer_rsrc_t rs_w = s4_rsrc(p.plane0, (size_t)(p.d_in / 128) * F::W0 * p.d_out * 4);
+  const __amdgpu_buffer_rsrc_t rs_w =
+      DEP ? s4_rsrc(p.stream, (size_t)ceil_div(p.d_out, 64) * (p.d_in / 128) * (DEP_UNITS * 1024))
+          : s4_rsrc(p.plane0, (size_t)(p.d_in / 128) * F::W0 * p.d_out * 4);
   const __amdgpu_buffer_rsrc_t rs_h = s4_rsrc(p.plane1, (size_t)(p.d_in / 32) * p.d_out * 4);  // INT3 only
   const __amdgpu_buffer_rsrc_t rs_x = s4_rsrc(p.x, (size_t)p.T * p.d_in * 2);
   const __amdgpu_buffer_rsrc_t rs_al = s4_rsrc(F16 ? (const void*)p.fac16 : (const void*)p.alpha, (size_t)L * p.d_out * 4);
@@ -148,7 +156,13 @@ __global__ __launch_bounds__(S4_THREADS) void smallt4_kernel(const SmallTArgs p)
 
   const int j = s * SLAB_COLS + cg * S4_WCOLS + lane;  // this lane's column
   const bool col_ok = j < p.d_out;
-  const uint32_t voff = col_ok ? (uint32_t)j * 4u : kS4Oob;
+  const uint32_t voff = col_ok ? (DEP ? (uint32_t)lane * 16u : (uint32_t)j * 4u) : kS4Oob;
+  // deployment stream: the records of a chunk lie side by side for all column groups, so that
+  // the wavefronts of the chip, which advance through the chunks together, sweep one contiguous
+  // region at any moment (every memory channel busy) -- a wavefront's own records are one
+  // chunk row of records apart
+  const uint32_t dep_base = (uint32_t)(s * NCG + cg) * (uint32_t)(DEP_UNITS * 1024);
+  const uint32_t dep_chunk = (uint32_t)ceil_div(p.d_out, 64) * (uint32_t)(DEP_UNITS * 1024);
 
   // Loads of chunk c, or -- past the end `lim` of the wavefront's share -- the same number of
   // loads aimed outside the buffers: they return zeros without touching memory, and the
@@ -156,6 +170,24 @@ __global__ __launch_bounds__(S4_THREADS) void smallt4_kernel(const SmallTArgs p)
   auto load_chunk = [&](Chunk4<NBITS, SUB>& ch, int c, int lim) {
     const uint32_t v = c < lim ? voff : kS4Oob;
     c = min(c, C - 1);
+    if constexpr (DEP) {
+      const uint32_t rec = dep_base + (uint32_t)c * dep_chunk;
+      u32x4 q[DEP_UNITS];
+#pragma unroll
+      for (int i = 0; i < DEP_UNITS; ++i)
+        q[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, (int)v, (int)(rec + (uint32_t)i * 1024u), S4_NT);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) ch.w[i] = q[i >> 2][i & 3];
+      if constexpr (SUB == 1) {  // alpha of the four groups, then beta
+#pragma unroll
+        for (int u = 0; u < 4; ++u) ch.al[u] = q[4][u], ch.be[u] = q[5][u];
+      } else if constexpr (SUB == 2) {  // alpha0, alpha1, beta0, beta1
+        ch.al[0] = q[4][0], ch.al[1] = q[4][1], ch.be[0] = q[4][2], ch.be[1] = q[4][3];
+      } else {  // alpha, beta, -, -
+        ch.al[0] = q[4][0], ch.be[0] = q[4][1];
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < F::W0; ++i)
       ch.w[i] = __builtin_amdgcn_raw_buffer_load_b32(rs_w, (int)v, (int)((uint32_t)(F::W0 * c + i) * row_b), S4_NT);
@@ -456,15 +488,23 @@ __global__ __launch_bounds__(S4_THREADS) void smallt4_kernel(const SmallTArgs p)
   }
 }
 
-template <int NBITS, int SUB, int KH, int TG, bool F16>
+template <int NBITS, int SUB, int KH, int TG, bool F16, bool DEP = false>
 static hipError_t launch_sub4(const SmallTArgs& a, int grid, hipStream_t st) {
   static std::atomic<uint64_t> granted{0};  // per instantiation
   constexpr int lds = s4_lds_bytes(TG);
-  if (hipError_t e = grant_dynamic_lds(reinterpret_cast<const void*>(smallt4_kernel<NBITS, SUB, KH, TG, F16>), lds, granted);
+  if (hipError_t e = grant_dynamic_lds(reinterpret_cast<const void*>(smallt4_kernel<NBITS, SUB, KH, TG, F16, DEP>), lds, granted);
       e != hipSuccess)
     return e;
-  smallt4_kernel<NBITS, SUB, KH, TG, F16><<<grid, S4_THREADS, lds, st>>>(a);
+  smallt4_kernel<NBITS, SUB, KH, TG, F16, DEP><<<grid, S4_THREADS, lds, st>>>(a);
   return hipGetLastError();
+}
+
+// the deployment-stream form: 4-bit codes, fp32 factors, up to four tokens
+template <int SUB>
+static hipError_t launch_dep4(const SmallTArgs& a, const SmallTPlan& pl, hipStream_t st) {
+  if (pl.halves == 4) return launch_sub4<4, SUB, 4, 1, false, true>(a, pl.blocks, st);
+  if (pl.halves == 2) return launch_sub4<4, SUB, 2, 1, false, true>(a, pl.blocks, st);
+  return hipErrorInvalidValue;
 }
 
 template <int NBITS, int SUB, int TG, bool F16>

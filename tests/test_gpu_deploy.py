@@ -1,0 +1,58 @@
+"""The deployment stream of a merged 4-bit layer (qalora_deploy / qalora_forward_deployed): the
+repack is a permutation of (packed, alpha, beta), so the decode forward from it must equal
+qalora_forward on the original triple bit for bit, and the oracle to the exact-operand bar."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2309_14717_amd import synth
+from helpers import layer_on_gpu, record, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("group,d_in,d_out", [(32, 1024, 520), (64, 2048, 136), (128, 768, 64), (32, 4096, 4096)])
+@pytest.mark.parametrize("tokens", [1, 3, 4])
+def test_deployed_forward_small(gpu_api, group, d_in, d_out, tokens):
+    cfg = synth.LayerConfig("dep", tokens, d_in, d_out, 4, group, 8, 0.5, seed=61)
+    L = layer_on_gpu(gpu_api, cfg)
+    beta_m = gpu_api.merge(L["desc"], L["g_beta"], L["A"], L["B"])
+    dep = gpu_api.deploy(L["desc"], L["packed"], L["g_alpha"], beta_m)
+    assert dep.numel() == gpu_api.load().qalora_deployed_bytes(L["desc"])
+    for odt in (torch.float32, torch.bfloat16):
+        y = gpu_api.forward(L["desc"], L["x"], L["packed"], L["g_alpha"], beta_m, out_dtype=odt)
+        yd = gpu_api.forward_deployed(L["desc"], L["x"], dep, out_dtype=odt)
+        assert torch.equal(yd, y)
+    ref = oracle.forward(L["np"]["x"], L["codes"], L["alpha"], beta_m.cpu().numpy(), cfg.group)
+    err = rel_err(gpu_api.forward_deployed(L["desc"], L["x"], dep).cpu().numpy(), ref)
+    record(f"deployed g={group} {d_in}x{d_out} T={tokens}", y=err)
+    assert err <= 1e-5
+
+
+@pytest.mark.parametrize("name", ["c5_up", "c5_down"])
+def test_deployed_forward_config5(gpu_api, name):
+    cfg = synth.CONFIGS[name].scaled(tokens=4)
+    L = layer_on_gpu(gpu_api, cfg)
+    d = L["np"]
+    beta_m = gpu_api.merge(L["desc"], L["g_beta"], L["A"], L["B"])
+    dep = gpu_api.deploy(L["desc"], L["packed"], L["g_alpha"], beta_m)
+    ref4 = oracle.forward(d["x"], L["codes"], L["alpha"], beta_m.cpu().numpy(), cfg.group)
+    for T in (1, 4):
+        x = L["x"][:T].contiguous()
+        yd = gpu_api.forward_deployed(L["desc"], x, dep)
+        assert torch.equal(yd, gpu_api.forward(L["desc"], x, L["packed"], L["g_alpha"], beta_m))
+        err = rel_err(yd.cpu().numpy(), ref4[:T])
+        record(f"deployed {name} T={T}", y=err)
+        assert err <= 1e-5
+
+
+def test_deployed_rejects_what_it_does_not_cover(gpu_api):
+    cfg = synth.LayerConfig("dep_rej", 5, 1024, 512, 4, 32, 8, 0.5, seed=62)
+    L = layer_on_gpu(gpu_api, cfg)
+    dep = gpu_api.deploy(L["desc"], L["packed"], L["g_alpha"], L["g_beta"])
+    with pytest.raises(gpu_api.QaloraError) as e:
+        gpu_api.forward_deployed(L["desc"], L["x"], dep)   # five tokens
+    assert e.value.status == gpu_api.EUNSUPPORTED
+    with pytest.raises(gpu_api.QaloraError):
+        gpu_api.deploy(gpu_api.make_desc(1024, 512, 2, 32), L["packed"], L["g_alpha"], L["g_beta"])
