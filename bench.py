@@ -133,9 +133,10 @@ class Layer:
     def forward_merged(self, x=None, y=None, ws=None):
         a = self.api
         xx = self.x if x is None else x
-        if self.dep is not None and xx.shape[0] <= 4:  # decode step from the deployment stream
-            return a.forward_deployed(self.desc, xx, self.dep, ws=self.ws_f if ws is None else ws,
-                                      y=self.y if y is None else y)
+        if self.dep is not None and (xx.shape[0] <= 4 or xx.shape[0] > 32):
+            # the static merged layer as deployed: decode stream, or prepared factor words
+            return a.forward_deployed(self.desc, xx, self.dep, packed=self.packed,
+                                      ws=self.ws_f if ws is None else ws, y=self.y if y is None else y)
         if self.fac16 is not None:  # factors of the merged layer stored as fp16 pairs
             return a.forward_factors16(self.desc, self.x if x is None else x, self.packed, self.fac16,
                                        ws=self.ws_f if ws is None else ws, y=self.y if y is None else y)
@@ -292,7 +293,8 @@ def small_token_table(torch, api, synth, odt, n_sets=8, tokens=(1, 4, 16, 256), 
             by = forward_bytes(cfg, T, y.element_size())
             fl = 2.0 * T * cfg.d_in * cfg.d_out
             rows.append({"shape": f"{cfg.d_in}x{cfg.d_out}", "tokens": T,
-                         "layout": "deployment stream" if T <= 4 else "training layout", "us": round(ms * 1e3, 2),
+                         "layout": ("deployment stream" if T <= 4 else
+                                    ("packed codes + deployed factor words" if T > 32 else "training layout")), "us": round(ms * 1e3, 2),
                          "GB/s": round(by / ms / 1e6, 1), "frac_hbm": round(by / ms / 1e6 / PEAK_HBM_GBS, 4),
                          "TFLOP/s": round(fl / ms / 1e9, 2)})
         del sets
@@ -575,7 +577,7 @@ def main():
         workload = (f"c5: post-merge forward, T={T}, 8192x22016 then 22016x8192, INT{args.bits} g=32, merged beta, "
                     f"x bf16, outputs {args.out_dtype}, {n_sets} weight sets rotated"
                     + (", alpha and beta stored as fp16 pairs" if args.factors16 else "")
-                    + (", read from the deployment stream (qalora_deploy)" if (dep and T <= 4 and args.bits == 4) else ""))
+                    + (", deployed (qalora_deploy)" if (dep and (T <= 4 or T > 32) and args.bits == 4) else ""))
         cfg = cfg_u
         if not args.no_cpu_baseline:
             import oracle

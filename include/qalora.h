@@ -206,22 +206,29 @@ int qalora_backward_kept(const qalora_desc* desc, int tokens, const void* dy, co
 int qalora_merge(const qalora_desc* desc, const float* beta, const float* A, const float* B,
                  float* beta_out, void* stream);
 
-/* Deployment layout for decoding with the merged model (Sec. 3.3: after the merge the layer is a
- * plain N-bit layer again, and static; App. B.3).  Every decode step streams the whole weight,
- * so the layout decides the bandwidth: qalora_deploy repacks (packed, alpha, beta) of a 4-bit
- * layer once into a stream in which the codes and the fp32 factors of every 64 columns x 128
- * rows lie together, in the order the decode kernel consumes them, and qalora_forward_deployed
- * reads it with 16-byte accesses over contiguous ranges.  Same arithmetic and the same results,
- * bit for bit, as qalora_forward on the original triple (exact operands, fp32 accumulation).
- * Supported: bits 4, group 32/64/128, d_in a multiple of 128, tokens <= QALORA_DEPLOYED_MAX_TOKENS;
- * otherwise QALORA_EUNSUPPORTED (qalora_deployed_bytes returns 0).  The stream is as large as
- * packed + alpha + beta together.  Workspace and its status word as for qalora_forward. */
-#define QALORA_DEPLOYED_MAX_TOKENS 4
+/* Deployment of the merged model (Sec. 3.3: after the merge the layer is a plain N-bit layer
+ * again, and static; App. B.3).  qalora_deploy derives, once, what every later call would
+ * otherwise rebuild or gather, into `deployed` (qalora_deployed_bytes; about 1.17 x the size of
+ * packed + alpha + beta):
+ *   - a decode stream: the codes and fp32 factors of every 64 columns x 128 rows together, in
+ *     the order the decode kernel consumes them (16-byte accesses over contiguous records);
+ *   - the dense kernel's fp16 factor words and their column scales.
+ * qalora_forward_deployed is the adapter-free forward from it: up to
+ * QALORA_DEPLOYED_STREAM_TOKENS tokens the decode kernel on the stream (`packed` is not read
+ * and may be NULL; same arithmetic and results, bit for bit, as qalora_forward on the triple);
+ * beyond that the dense contraction on `packed` (required) with the prepared words (results
+ * as qalora_forward, bit for bit, without its per-call factor pass).  Five to thirty-two
+ * tokens are served faster by qalora_forward on the original triple, which has a streaming
+ * kernel for them.  Supported: bits 4, group 32/64/128, d_in a multiple of 128; otherwise
+ * QALORA_EUNSUPPORTED (qalora_deployed_bytes returns 0).  Workspace: that of
+ * QALORA_OP_FORWARD; status word as for qalora_forward. */
+#define QALORA_DEPLOYED_STREAM_TOKENS 4
 size_t qalora_deployed_bytes(const qalora_desc* desc);
 int qalora_deploy(const qalora_desc* desc, const void* packed, const float* alpha, const float* beta,
                   void* deployed, void* stream);
-int qalora_forward_deployed(const qalora_desc* desc, int tokens, const void* x, const void* deployed,
-                            void* y, int y_dtype, void* ws, size_t ws_bytes, void* stream);
+int qalora_forward_deployed(const qalora_desc* desc, int tokens, const void* x, const void* packed,
+                            const void* deployed, void* y, int y_dtype, void* ws, size_t ws_bytes,
+                            void* stream);
 
 /* 16-bit storage of the quantization factors for inference on the merged model, where every
  * call streams the whole weight (Sec. 3.3 deployment; App. B.3): one 32-bit word per

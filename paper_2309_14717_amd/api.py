@@ -77,7 +77,7 @@ def load() -> ctypes.CDLL:
     lib.qalora_deployed_bytes.restype = sz
     lib.qalora_deployed_bytes.argtypes = [cp]
     lib.qalora_deploy.argtypes = [cp, vp, vp, vp, vp, vp]
-    lib.qalora_forward_deployed.argtypes = [cp, i, vp, vp, vp, i, vp, sz, vp]
+    lib.qalora_forward_deployed.argtypes = [cp, i, vp, vp, vp, vp, i, vp, sz, vp]
     lib.qalora_profile_mfma_probe.argtypes = [i, i, i, i, i, vp, vp, vp]
     lib.qalora_forward_noalloc.argtypes = [cp, i, vp, vp, vp, vp, vp, i, vp]
     lib.qalora_kept_bytes.restype = sz
@@ -274,18 +274,21 @@ def deploy(desc: Desc, packed, alpha, beta):
     return out
 
 
-def forward_deployed(desc: Desc, x, deployed, out_dtype=torch.float32, ws=None, y=None):
-    """Decode-step forward from the deployment stream (adapter-free, up to four tokens)."""
+def forward_deployed(desc: Desc, x, deployed, packed=None, out_dtype=torch.float32, ws=None, y=None):
+    """Adapter-free forward of a deployed layer: the decode stream up to four tokens, beyond that
+    the dense kernel on ``packed`` (then required) with the prepared factor words."""
     _need(x, "x", torch.bfloat16)
     T, dev = x.shape[0], x.device
     if check_desc(desc) == OK:
         _need(x, "x", shape=(T, desc.d_in))
         _need(deployed, "deployed", nbytes=int(load().qalora_deployed_bytes(ctypes.byref(desc))), device=dev)
+        if T > 4:
+            _need(packed, "packed", nbytes=packed_bytes(desc), device=dev)
     if y is None:
         y = torch.empty((T, desc.d_out), dtype=out_dtype, device=dev)
     _need_out(y, "y", T, desc.d_out, dev)
-    ws, ws_bytes = _workspace(desc, min(T, 16), OP_FORWARD, ws, dev)
-    rc = load().qalora_forward_deployed(ctypes.byref(desc), T, _p(x), _p(deployed), _p(y),
+    ws, ws_bytes = _workspace(desc, T, OP_FORWARD, ws, dev)
+    rc = load().qalora_forward_deployed(ctypes.byref(desc), T, _p(x), _p(packed), _p(deployed), _p(y),
                                         BF16 if y.dtype == torch.bfloat16 else F32, _p(ws), ws_bytes, _stream())
     _check(rc, "qalora_forward_deployed")
     return y

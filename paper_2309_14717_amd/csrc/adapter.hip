@@ -96,6 +96,7 @@ struct FrontArgs {
   const float* f_B;     // [rank, d_out]
   float f_sg, f_mid;    // s / g; 2^(N-1)
   int f_L, f_dout, f_rank, f_cols;  // f_cols: columns per block, a power of two <= 16
+  int f_cw;             // columns per block of the adapter-free form: 32 or 64
   uint32_t* f_words;    // forward: [L, d_out] words at the per-column scale
   float* f_inv;         // forward: [d_out] 1 / S of each column
   float* f_const;       // backward: [L, d_out] beta' + mid alpha, fp32 (scaled by a later launch)
@@ -131,29 +132,30 @@ __device__ __forceinline__ float2 factor_scale(float m) {
 // Backward (the scale must not vary along the output columns, which are the contraction index
 // there): c goes out in fp32 with the block's bound, and a later launch scales by the call's S.
 // Without an adapter there is nothing to fold: the job is elementwise plus the bounds, and a
-// block takes 64 columns (256-byte runs of alpha and beta) and makes two sweeps over them, the
-// second served by the cache, instead of parking c in LDS.  It fills the same f_cols-wide slots
+// block takes 64 or 32 columns (whole 128-byte lines of alpha and beta) and makes two sweeps
+// over them, the second served by the cache, instead of parking c in LDS.  It fills the same f_cols-wide slots
 // of f_max as the folding form would.
 __device__ __forceinline__ void factor_block_plain(const FrontArgs& a, int bid, float* red, int tid) {
-  const int c = tid & 63, lg = tid >> 6;
+  const int CW = a.f_cw, NLG = 256 / CW;  // columns per block; threads per column
+  const int c = tid & (CW - 1), lg = tid / CW;
   const int L = a.f_L, dout = a.f_dout;
-  const int j = bid * 64 + c;
+  const int j = bid * CW + c;
   const bool col_ok = j < dout;
   const float mid = a.f_mid;
   float m = 0.0f;
   constexpr int NB = 8;  // rows of alpha and of beta in flight per thread
   if (col_ok) {
-    for (int l0 = lg; l0 < L; l0 += 4 * NB) {
+    for (int l0 = lg; l0 < L; l0 += NLG * NB) {
       float al[NB], be[NB];
 #pragma unroll
       for (int q = 0; q < NB; ++q) {
-        const int l = min(l0 + 4 * q, L - 1);
+        const int l = min(l0 + NLG * q, L - 1);
         al[q] = a.f_alpha[(size_t)l * dout + j];
         be[q] = a.f_beta[(size_t)l * dout + j];
       }
 #pragma unroll
       for (int q = 0; q < NB; ++q) {
-        const int l = l0 + 4 * q;
+        const int l = l0 + NLG * q;
         if (l < L) {
           const float cst = __builtin_fmaf(mid, al[q], be[q]);
           m = fmaxf(m, fabsf(cst) + mid * fabsf(al[q]));
@@ -164,12 +166,13 @@ __device__ __forceinline__ void factor_block_plain(const FrontArgs& a, int bid, 
   }
   red[tid] = m;
   __syncthreads();
-  float cm = fmaxf(fmaxf(red[c], red[64 + c]), fmaxf(red[128 + c], red[192 + c]));  // column bound
+  float cm = 0.0f;  // column bound
+  for (int q = 0; q < NLG; ++q) cm = fmaxf(cm, red[q * CW + c]);
   if (a.f_max) {
     __syncthreads();
     red[tid] = cm;
     __syncthreads();
-    const int per = 64 / a.f_cols, slots = ceil_div(dout, a.f_cols);  // f_cols-wide slots of this block
+    const int per = CW / a.f_cols, slots = ceil_div(dout, a.f_cols);  // f_cols-wide slots of this block
     if (tid < per && bid * per + tid < slots) {
       float bm = 0.0f;
       for (int q = 0; q < a.f_cols; ++q) bm = fmaxf(bm, red[tid * a.f_cols + q]);
@@ -197,17 +200,17 @@ __device__ __forceinline__ void factor_block_plain(const FrontArgs& a, int bid, 
     a.f_inv[j] = sc.y;
   }
   if (col_ok) {
-    for (int l0 = lg; l0 < L; l0 += 4 * NB) {
+    for (int l0 = lg; l0 < L; l0 += NLG * NB) {
       float al[NB], be[NB];
 #pragma unroll
       for (int q = 0; q < NB; ++q) {
-        const int l = min(l0 + 4 * q, L - 1);
+        const int l = min(l0 + NLG * q, L - 1);
         al[q] = a.f_alpha[(size_t)l * dout + j];
         be[q] = a.f_beta[(size_t)l * dout + j];
       }
 #pragma unroll
       for (int q = 0; q < NB; ++q) {
-        const int l = l0 + 4 * q;
+        const int l = l0 + NLG * q;
         if (l < L) {
           const f32x2 v = {al[q] * sc.x, __builtin_fmaf(mid, al[q], be[q]) * sc.x};
           a.f_words[(size_t)l * dout + j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
@@ -271,7 +274,7 @@ __device__ __forceinline__ void factor_block(const FrontArgs& a, int bid, float*
       if (l < L) {
         float cst = 0.0f, bound = 0.0f;
         if (col_ok) {
-          const float al = a.f_mid != 0.0f ? a.f_alpha[(size_t)l * dout + j] : 0.0f;
+          const float al = a.f_alpha[(size_t)l * dout + j];
           const float bp = __builtin_fmaf(a.f_sg, acc[i], a.f_beta[(size_t)l * dout + j]);
           cst = __builtin_fmaf(a.f_mid, al, bp);
           bound = fabsf(cst) + a.f_mid * fabsf(al);
@@ -586,7 +589,9 @@ static hipError_t launch_front(FrontArgs a, hipStream_t st) {
   a.nb_fac = 0;
   if (a.f_alpha) {
     a.f_cols = factor_cols(a.f_L);
-    a.nb_fac = a.f_A ? ceil_div(a.f_dout, a.f_cols) : ceil_div(a.f_dout, 64);
+    // adapter-free form: the widest column tile that still leaves more blocks than compute units
+    a.f_cw = a.f_dout / 64 >= 384 ? 64 : 32;
+    a.nb_fac = a.f_A ? ceil_div(a.f_dout, a.f_cols) : ceil_div(a.f_dout, a.f_cw);
     const size_t f_smem =
         a.f_A ? ((size_t)a.f_L * a.f_cols + (size_t)a.f_cols * (a.f_rank + 4) + 256) * sizeof(float)
               : 256 * sizeof(float);
@@ -608,13 +613,19 @@ static hipError_t launch_front(FrontArgs a, hipStream_t st) {
 
 static void set_factor_job(FrontArgs& a, const FactorJob& f) {
   a.f_alpha = f.alpha; a.f_beta = f.beta; a.f_A = f.rank > 0 ? f.A : nullptr; a.f_B = f.B;
-  a.f_sg = f.s / (float)f.g; a.f_mid = f.plain_beta ? 0.0f : (float)(1 << (f.bits - 1));
+  a.f_sg = f.s / (float)f.g; a.f_mid = (float)(1 << (f.bits - 1));
   a.f_L = f.L; a.f_dout = f.d_out; a.f_rank = f.rank;
   a.f_words = f.words; a.f_inv = f.inv_scale; a.f_const = f.cst; a.f_max = f.block_max;
   a.f_known = f.known_max;
 }
 
 int factor_job_blocks(int L, int d_out) { return ceil_div(d_out, factor_cols(L)); }
+
+hipError_t launch_factor_job(const FactorJob& f, hipStream_t st) {
+  FrontArgs a{};
+  set_factor_job(a, f);
+  return launch_front(a, st);
+}
 
 hipError_t launch_front_forward(const uint16_t* x, int T, int d_in, float2* rs, uint16_t* x16,
                                 const float* A, float s, int g, int rank, float* P_keep,
@@ -1005,28 +1016,61 @@ hipError_t launch_reduce2(const float* part_a, int nparts_a, size_t n_a, float* 
 // ---------------------------------------------------------------------------------------
 // Merge (Alg. 1 merge / App. B.3 in Eq. 1's zero-factor convention):
 //   beta'[l,j] = beta[l,j] + (s/g) sum_k A[l,k] B[k,j]
-// is the factor job with nothing added for the mid code and the fp32 result as its output (a
-// thread reads the element of beta it later writes, so beta_out may be beta itself).  The sum
-// over k runs in k order for every output.
+// One thread per (GL groups, 4 columns): a row of B fetched for one k serves GL groups, so the
+// L2 traffic for B is 1/GL of what one group per thread would draw; the GL rows of A are
+// uniform over the block.  The sum over k runs in k order for every output.
 // ---------------------------------------------------------------------------------------
+template <int GL>
+__global__ __launch_bounds__(256) void merge_kernel(const float* beta,  // may alias beta_out
+                                                    const float* __restrict__ A,
+                                                    const float* __restrict__ B, int L, int d_out,
+                                                    int rank, float scale, float* beta_out) {
+  const int l0 = blockIdx.y * GL;
+  const int j = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (j >= d_out) return;  // d_out is a multiple of 8
+  f32x4 acc[GL];
+#pragma unroll
+  for (int u = 0; u < GL; ++u) acc[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  auto step = [&](int k, const f32x4 b) {
+#pragma unroll
+    for (int u = 0; u < GL; ++u) {
+      const int l = min(l0 + u, L - 1);  // rows past the end repeat the last one, unused
+      const float av = A[(size_t)l * rank + k];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[u][c] = __builtin_fmaf(av, b[c], acc[u][c]);
+    }
+  };
+  int k = 0;
+  for (; k + 8 <= rank; k += 8) {  // eight rows of B in flight
+    f32x4 b[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) b[q] = *reinterpret_cast<const f32x4*>(B + (size_t)(k + q) * d_out + j);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) step(k + q, b[q]);
+  }
+  for (; k < rank; ++k) step(k, *reinterpret_cast<const f32x4*>(B + (size_t)k * d_out + j));
+#pragma unroll
+  for (int u = 0; u < GL; ++u) {
+    const int l = l0 + u;
+    if (l >= L) break;
+    const f32x4 bt = *reinterpret_cast<const f32x4*>(beta + (size_t)l * d_out + j);
+    f32x4 o;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) o[c] = __builtin_fmaf(scale, acc[u][c], bt[c]);
+    *reinterpret_cast<f32x4*>(beta_out + (size_t)l * d_out + j) = o;
+  }
+}
+
 hipError_t launch_merge(const float* beta, const float* A, const float* B, int L, int d_out,
                         int rank, int g, float s, float* beta_out, hipStream_t st) {
-  FactorJob f{};
-  f.alpha = beta;  // marks the job as present; alpha itself is not read with plain_beta
-  f.beta = beta;
-  f.A = A;
-  f.B = B;
-  f.s = s;
-  f.g = g;
-  f.rank = rank;
-  f.bits = 4;
-  f.L = L;
-  f.d_out = d_out;
-  f.cst = beta_out;
-  f.plain_beta = true;
-  FrontArgs a{};
-  set_factor_job(a, f);
-  return launch_front(a, st);
+  const int bx = ceil_div(d_out / 4, 256);
+  const float scale = s / (float)g;
+  if (bx * ceil_div(L, 8) >= 200) {  // enough blocks for the chip at eight groups per thread
+    merge_kernel<8><<<dim3(bx, ceil_div(L, 8)), 256, 0, st>>>(beta, A, B, L, d_out, rank, scale, beta_out);
+  } else {
+    merge_kernel<2><<<dim3(bx, ceil_div(L, 2)), 256, 0, st>>>(beta, A, B, L, d_out, rank, scale, beta_out);
+  }
+  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------

@@ -283,9 +283,14 @@ static KeptLayout kept_layout(const qalora_desc& d, int T) {
   return k;
 }
 
+struct PreparedFactors {  // factor words and column scales made ahead of the call (deployment)
+  const uint32_t* words;
+  const float* inv_scale;
+};
 static int forward_impl(const qalora_desc* d, int tokens, const void* x, const void* packed,
                         const float* alpha, const float* beta, const float* A, const float* B, void* y,
-                        int y_dtype, void* kept, bool keep, void* ws, size_t ws_bytes, void* stream);
+                        int y_dtype, void* kept, bool keep, void* ws, size_t ws_bytes, void* stream,
+                        const PreparedFactors* pre = nullptr);
 static int backward_impl(const qalora_desc* d, int tokens, const void* dy, const void* x,
                          const void* kept, bool use_kept, const void* packed, const float* alpha,
                          const float* beta, const float* A, const float* B, void* dx, int dx_dtype,
@@ -328,10 +333,12 @@ int qalora_backward_kept(const qalora_desc* d, int tokens, const void* dy, const
 
 static int forward_impl(const qalora_desc* d, int tokens, const void* x, const void* packed,
                         const float* alpha, const float* beta, const float* A, const float* B, void* y,
-                        int y_dtype, void* kept, bool keep, void* ws, size_t ws_bytes, void* stream) {
+                        int y_dtype, void* kept, bool keep, void* ws, size_t ws_bytes, void* stream,
+                        const PreparedFactors* pre) {
   const int rc = qalora_check_desc(d);
   if (rc != QALORA_OK) return rc;
-  if (tokens <= 0 || !x || !packed || !alpha || !beta || !y) return QALORA_EINVAL;
+  if (tokens <= 0 || !x || !packed || !y) return QALORA_EINVAL;
+  if (!pre && (!alpha || !beta)) return QALORA_EINVAL;
   if ((A == nullptr) != (B == nullptr)) return QALORA_EINVAL;
   if (y_dtype != QALORA_F32 && y_dtype != QALORA_BF16) return QALORA_EINVAL;
   if (keep && (!kept || !A || !B || d->rank <= 0)) return QALORA_EINVAL;  // only an adapter has anything to keep
@@ -340,7 +347,7 @@ static int forward_impl(const qalora_desc* d, int tokens, const void* x, const v
     return QALORA_EALIGN;
   if (!addressable(*d, tokens)) return QALORA_EUNSUPPORTED;
   const bool adapter = A && B && d->rank > 0;
-  if (!adapter && use_smallt(*d, tokens)) {
+  if (!adapter && !pre && use_smallt(*d, tokens)) {
     // memory-bound regime: stream the weight once on the exact-operand path
     const size_t need = smallt_workspace(*d, tokens);
     if (!ws || ws_bytes < need) return QALORA_EWORKSPACE;
@@ -385,6 +392,7 @@ static int forward_impl(const qalora_desc* d, int tokens, const void* x, const v
   fj.d_out = d->d_out;
   fj.words = reinterpret_cast<uint32_t*>(w + plan.fac);
   fj.inv_scale = reinterpret_cast<float*>(w + plan.inv);
+  if (pre) fj.alpha = nullptr;  // the words exist already: no factor job
   float* P_keep = nullptr;
   float* u_keep = nullptr;
   if (keep) {
@@ -405,8 +413,8 @@ static int forward_impl(const qalora_desc* d, int tokens, const void* x, const v
   g.a_main_padded_rows = round_up(tokens, 256);
   g.plane0 = static_cast<const uint32_t*>(packed);
   g.plane1 = g.plane0 + plane0_words(d->bits, d->d_in, d->d_out);
-  g.fac = fj.words;
-  g.n_scale = fj.inv_scale;
+  g.fac = pre ? pre->words : fj.words;
+  g.n_scale = pre ? pre->inv_scale : fj.inv_scale;
   g.out = y;
   g.out_bf16 = (y_dtype == QALORA_BF16);
   g.M = tokens;
@@ -605,9 +613,21 @@ static bool deployable(const qalora_desc& d) {
          deploy_stream_bytes(d.d_in, d.d_out, d.group) < kAddressable;
 }
 
+// deployed = [decode stream][dense-kernel factor words][their column scales]
+struct DeployLayout {
+  size_t words, inv, total;
+};
+static DeployLayout deploy_layout(const qalora_desc& d) {
+  DeployLayout l{};
+  l.words = align_up(deploy_stream_bytes(d.d_in, d.d_out, d.group));
+  l.inv = l.words + align_up((size_t)(d.d_in / d.group) * d.d_out * 4);
+  l.total = l.inv + align_up((size_t)d.d_out * 4);
+  return l;
+}
+
 size_t qalora_deployed_bytes(const qalora_desc* d) {
   if (qalora_check_desc(d) != QALORA_OK || !deployable(*d)) return 0;
-  return deploy_stream_bytes(d->d_in, d->d_out, d->group);
+  return deploy_layout(*d).total;
 }
 
 int qalora_deploy(const qalora_desc* d, const void* packed, const float* alpha, const float* beta,
@@ -617,20 +637,43 @@ int qalora_deploy(const qalora_desc* d, const void* packed, const float* alpha, 
   if (!packed || !alpha || !beta || !deployed) return QALORA_EINVAL;
   if (misaligned(packed) || misaligned(alpha) || misaligned(beta) || misaligned(deployed)) return QALORA_EALIGN;
   if (!deployable(*d)) return QALORA_EUNSUPPORTED;
-  return launch_deploy(static_cast<const uint32_t*>(packed), alpha, beta, d->d_in, d->d_out, d->group, deployed,
-                       as_stream(stream)) == hipSuccess
-             ? QALORA_OK
-             : QALORA_EHIP;
+  if (launch_deploy(static_cast<const uint32_t*>(packed), alpha, beta, d->d_in, d->d_out, d->group, deployed,
+                    as_stream(stream)) != hipSuccess)
+    return QALORA_EHIP;
+  // the dense kernel's factor words of the static layer, so that no call has to make them
+  const DeployLayout l = deploy_layout(*d);
+  FactorJob fj{};
+  fj.alpha = alpha;
+  fj.beta = beta;
+  fj.g = d->group;
+  fj.bits = d->bits;
+  fj.L = d->d_in / d->group;
+  fj.d_out = d->d_out;
+  fj.words = reinterpret_cast<uint32_t*>(static_cast<char*>(deployed) + l.words);
+  fj.inv_scale = reinterpret_cast<float*>(static_cast<char*>(deployed) + l.inv);
+  return launch_factor_job(fj, as_stream(stream)) == hipSuccess ? QALORA_OK : QALORA_EHIP;
 }
 
-int qalora_forward_deployed(const qalora_desc* d, int tokens, const void* x, const void* deployed, void* y,
-                            int y_dtype, void* ws, size_t ws_bytes, void* stream) {
+int qalora_forward_deployed(const qalora_desc* d, int tokens, const void* x, const void* packed,
+                            const void* deployed, void* y, int y_dtype, void* ws, size_t ws_bytes,
+                            void* stream) {
   const int rc = qalora_check_desc(d);
   if (rc != QALORA_OK) return rc;
   if (tokens <= 0 || !x || !deployed || !y) return QALORA_EINVAL;
   if (y_dtype != QALORA_F32 && y_dtype != QALORA_BF16) return QALORA_EINVAL;
-  if (misaligned(x) || misaligned(deployed) || misaligned(y) || misaligned(ws)) return QALORA_EALIGN;
-  if (!deployable(*d) || tokens > QALORA_DEPLOYED_MAX_TOKENS) return QALORA_EUNSUPPORTED;
+  if (misaligned(x) || misaligned(deployed) || misaligned(y) || misaligned(ws) || misaligned(packed))
+    return QALORA_EALIGN;
+  if (!deployable(*d)) return QALORA_EUNSUPPORTED;
+  if (tokens > QALORA_DEPLOYED_STREAM_TOKENS) {
+    // beyond the decode kernel: the dense contraction on the codes as packed, with the factor
+    // words the deployment prepared
+    if (!packed) return QALORA_EINVAL;
+    const DeployLayout l = deploy_layout(*d);
+    const PreparedFactors pre{reinterpret_cast<const uint32_t*>(static_cast<const char*>(deployed) + l.words),
+                              reinterpret_cast<const float*>(static_cast<const char*>(deployed) + l.inv)};
+    return forward_impl(d, tokens, x, packed, nullptr, nullptr, nullptr, nullptr, y, y_dtype, nullptr, false,
+                        ws, ws_bytes, stream, &pre);
+  }
   const size_t need = smallt_workspace(*d, tokens);
   if (!ws || ws_bytes < need) return QALORA_EWORKSPACE;
   SmallTArgs a{};

@@ -133,9 +133,9 @@ struct FactorJob {
   float* cst;           // backward, two-stage form
   float* block_max;     // [factor_job_blocks], optional in the forward
   const float* known_max;  // backward, one-stage form
-  bool plain_beta;      // cst = beta' itself (no mid-code term): the merge of App. B.3
 };
 int factor_job_blocks(int L, int d_out);
+hipError_t launch_factor_job(const FactorJob& f, hipStream_t st);  // the job as a launch of its own
 hipError_t launch_factor_scale(const float* alpha, const float* cst, const float* block_max, int nmax,
                                size_t n, uint32_t* words, float* inv_scale, hipStream_t st);
 
