@@ -199,6 +199,46 @@ int qalora_backward_kept(const qalora_desc* desc, int tokens, const void* dy, co
                          const float* A, const float* B, void* dx, int dx_dtype, float* dA,
                          float* dB, int accumulate, void* ws, size_t ws_bytes, void* stream);
 
+/* Several adapted linears that share their input x (q/k/v of an attention block; gate/up of a
+ * SwiGLU MLP), evaluated as ONE wide layer: one pass over x (row scales, conversion, pooling --
+ * pool_g(x) is the same for all of them), one dense launch over the concatenated columns, and
+ * in the backward one contraction dx = dy W~'^T over all of them, which IS the sum of the
+ * linears' input gradients.  Each linear keeps its own adapter (Alg. 1: A, B and s per layer),
+ * folded into its own columns of the zero factors.
+ * The wide layer: desc (d_out = sum of the parts' widths; rank and s of desc are ignored);
+ * packed, alpha, beta of the column-wise concatenation [W_0 | W_1 | ...] -- quantization is per
+ * column (Eq. 1 per group of a column), so quantizing the concatenation is concatenating the
+ * quantizations; y and dy are [tokens, d_out] with part p at columns [col0_p, col0_p + d_out_p).
+ * parts: HOST array of n_parts (1 .. QALORA_MAX_PARTS) entries; A [L, rank], B [rank, d_out],
+ * dA, dB are device pointers (dA, dB only used, and required, by the backward).  Every width
+ * must be a multiple of 32 and every rank in 1..128 (QALORA_EUNSUPPORTED otherwise); the widths
+ * must add up to desc->d_out (QALORA_EINVAL).
+ * kept: as in qalora_forward_keep / qalora_backward_kept (qalora_shared_kept_bytes); NULL in
+ * the forward keeps nothing, NULL in the backward re-reads x (then required).
+ * Results per part are those of the single-layer calls on that part, to rounding order: the
+ * forward's words are scaled per column either way (bit-identical y), the backward's one scale
+ * per call is taken over the wide layer. */
+#define QALORA_MAX_PARTS 4
+typedef struct qalora_part {
+  int32_t d_out; /* width of this linear (columns of the wide layer, in order)   */
+  int32_t rank;  /* its adapter rank                                             */
+  float s;       /* its adapter coefficient                                      */
+  const float* A;
+  const float* B;
+  float* dA;
+  float* dB;
+} qalora_part;
+size_t qalora_shared_kept_bytes(const qalora_desc* desc, int tokens, int n_parts, const qalora_part* parts);
+size_t qalora_shared_workspace_bytes(const qalora_desc* desc, int tokens, int op, int n_parts,
+                                     const qalora_part* parts);
+int qalora_forward_shared(const qalora_desc* desc, int tokens, const void* x, const void* packed,
+                          const float* alpha, const float* beta, int n_parts, const qalora_part* parts,
+                          void* y, int y_dtype, void* kept, void* ws, size_t ws_bytes, void* stream);
+int qalora_backward_shared(const qalora_desc* desc, int tokens, const void* dy, const void* x,
+                           const void* kept, const void* packed, const float* alpha, const float* beta,
+                           int n_parts, const qalora_part* parts, void* dx, int dx_dtype, int accumulate,
+                           void* ws, size_t ws_bytes, void* stream);
+
 /* Merge the adapter into the zero factors (Alg. 1 merge, App. B.3, in Eq. 1's
  * convention):  beta_out[l,j] = beta[l,j] + (s/g) * sum_k A[l,k] B[k,j].
  * Codes and alpha are untouched, so the merged layer is still N-bit.

@@ -32,6 +32,8 @@ EXPORTS = (
     "qalora_kept_bytes", "qalora_forward_keep", "qalora_backward_kept",
     "qalora_forward_noalloc", "qalora_profile_mfma_probe",
     "qalora_deployed_bytes", "qalora_deploy", "qalora_forward_deployed",
+    "qalora_shared_kept_bytes", "qalora_shared_workspace_bytes", "qalora_forward_shared",
+    "qalora_backward_shared",
 )
 
 
@@ -74,6 +76,12 @@ def load() -> ctypes.CDLL:
     lib.qalora_forward.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
     lib.qalora_backward.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, vp, i, vp, vp, i, vp, sz, vp]
     lib.qalora_merge.argtypes = [cp, vp, vp, vp, vp, vp]
+    lib.qalora_shared_kept_bytes.restype = sz
+    lib.qalora_shared_kept_bytes.argtypes = [cp, i, i, vp]
+    lib.qalora_shared_workspace_bytes.restype = sz
+    lib.qalora_shared_workspace_bytes.argtypes = [cp, i, i, i, vp]
+    lib.qalora_forward_shared.argtypes = [cp, i, vp, vp, vp, vp, i, vp, vp, i, vp, vp, sz, vp]
+    lib.qalora_backward_shared.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, i, vp, vp, i, i, vp, sz, vp]
     lib.qalora_deployed_bytes.restype = sz
     lib.qalora_deployed_bytes.argtypes = [cp]
     lib.qalora_deploy.argtypes = [cp, vp, vp, vp, vp, vp]
@@ -257,6 +265,88 @@ def forward_noalloc(desc: Desc, x, packed, alpha, beta, out_dtype=torch.float32,
                                        BF16 if y.dtype == torch.bfloat16 else F32, _stream())
     _check(rc, "qalora_forward_noalloc")
     return y
+
+
+class Part(ctypes.Structure):
+    """Mirror of ``qalora_part``."""
+    _fields_ = [("d_out", ctypes.c_int32), ("rank", ctypes.c_int32), ("s", ctypes.c_float),
+                ("A", ctypes.c_void_p), ("B", ctypes.c_void_p), ("dA", ctypes.c_void_p), ("dB", ctypes.c_void_p)]
+
+
+def _parts(desc, adapters, dev, grads=None):
+    """adapters: list of (A [L, rank], B [rank, d_out_p], s); grads: list of (dA, dB) or None."""
+    L = desc.d_in // max(desc.group, 1)
+    arr = (Part * len(adapters))()
+    for q, (A, B, s) in enumerate(adapters):
+        _need(A, f"A[{q}]", torch.float32, device=dev)
+        _need(B, f"B[{q}]", torch.float32, device=dev)
+        if A.dim() != 2 or B.dim() != 2 or A.shape[0] != L or A.shape[1] != B.shape[0]:
+            raise ValueError(f"part {q}: A {tuple(A.shape)}, B {tuple(B.shape)}, expected [{L}, r] and [r, d_out]")
+        arr[q].d_out, arr[q].rank, arr[q].s = int(B.shape[1]), int(A.shape[1]), float(s)
+        arr[q].A, arr[q].B = A.data_ptr(), B.data_ptr()
+        if grads is not None:
+            dA, dB = grads[q]
+            _need(dA, f"dA[{q}]", torch.float32, tuple(A.shape), device=dev)
+            _need(dB, f"dB[{q}]", torch.float32, tuple(B.shape), device=dev)
+            arr[q].dA, arr[q].dB = dA.data_ptr(), dB.data_ptr()
+    if sum(int(B.shape[1]) for _, B, _ in adapters) != desc.d_out:
+        raise ValueError("the parts' widths must add up to d_out")
+    return arr
+
+
+def forward_shared(desc: Desc, x, packed, alpha, beta, adapters, keep=False, out_dtype=torch.float32,
+                   ws=None, y=None, kept=None):
+    """Linears that share x as one wide layer (see qalora_forward_shared).  ``adapters`` is a
+    list of (A, B, s), one per part in column order.  Returns y, or (y, kept) with ``keep``."""
+    T, dev = _need_layer(desc, x, desc.d_in, packed, alpha, beta, None, None)
+    arr = _parts(desc, adapters, dev)
+    n = len(adapters)
+    if y is None:
+        y = torch.empty((T, desc.d_out), dtype=out_dtype, device=dev)
+    _need_out(y, "y", T, desc.d_out, dev)
+    if keep:
+        kb = int(load().qalora_shared_kept_bytes(ctypes.byref(desc), T, n, arr))
+        if kept is None:
+            kept = torch.empty(max(kb, 16), dtype=torch.uint8, device=dev)
+        _need(kept, "kept", nbytes=kb, device=dev)
+    if ws is None:
+        ws = torch.empty(max(int(load().qalora_shared_workspace_bytes(ctypes.byref(desc), T, OP_FORWARD, n, arr)), 16),
+                         dtype=torch.uint8, device=dev)
+    _need(ws, "ws", device=dev)
+    rc = load().qalora_forward_shared(ctypes.byref(desc), T, _p(x), _p(packed), _p(alpha), _p(beta), n, arr,
+                                      _p(y), BF16 if y.dtype == torch.bfloat16 else F32,
+                                      _p(kept) if keep else None, _p(ws), ws.numel() * ws.element_size(), _stream())
+    _check(rc, "qalora_forward_shared")
+    return (y, kept) if keep else y
+
+
+def backward_shared(desc: Desc, dy, x, kept, packed, alpha, beta, adapters, want_dx=True,
+                    dx_dtype=torch.float32, grads=None, accumulate=False, ws=None, dx=None):
+    """Backward of forward_shared: one dx over all parts, (dA, dB) per part.  Pass ``kept`` (from
+    forward_shared(keep=True)) or ``x``.  Returns (dx, [(dA, dB), ...])."""
+    T, dev = _need_layer(desc, dy, desc.d_out, packed, alpha, beta, None, None, x_name="dy")
+    if kept is None:
+        _need(x, "x", torch.bfloat16, (T, desc.d_in), device=dev)
+    if grads is None:
+        grads = [(torch.zeros_like(A), torch.zeros_like(B)) for A, B, _ in adapters]
+    arr = _parts(desc, adapters, dev, grads)
+    n = len(adapters)
+    if kept is not None:
+        _need(kept, "kept", nbytes=int(load().qalora_shared_kept_bytes(ctypes.byref(desc), T, n, arr)), device=dev)
+    if want_dx and dx is None:
+        dx = torch.empty((T, desc.d_in), dtype=dx_dtype, device=dev)
+    if dx is not None:
+        _need_out(dx, "dx", T, desc.d_in, dev)
+    if ws is None:
+        ws = torch.empty(max(int(load().qalora_shared_workspace_bytes(ctypes.byref(desc), T, OP_BACKWARD, n, arr)), 16),
+                         dtype=torch.uint8, device=dev)
+    _need(ws, "ws", device=dev)
+    dxd = BF16 if (dx is not None and dx.dtype == torch.bfloat16) else F32
+    rc = load().qalora_backward_shared(ctypes.byref(desc), T, _p(dy), _p(x) if kept is None else None, _p(kept),
+                                       _p(packed), _p(alpha), _p(beta), n, arr, _p(dx), dxd,
+                                       1 if accumulate else 0, _p(ws), ws.numel() * ws.element_size(), _stream())
+    _check(rc, "qalora_backward_shared")
+    return dx, grads
 
 
 def deploy(desc: Desc, packed, alpha, beta):

@@ -65,37 +65,44 @@ constexpr int ROWS_PER_BLOCK = 4;  // one wavefront each
 constexpr int ROW_BATCH = 8;       // 128-bit chunks per lane held in registers (4096 elements)
 constexpr int TR_TOK = 32;         // tokens per block of the transpose job
 
+// One linear's adapter among those that share the input x (a single layer is one part).
+struct FrontPart {
+  const float* A;       // [L, rank]
+  const float* B;       // [rank, d_out]
+  float s;
+  int rank;
+  int col0, d_out;      // its columns [col0, col0 + d_out) of the (wide) layer
+  float* u_keep;        // optional [T, rank]: s U in fp32, for a later launch's transpose job
+  const float* u_kept;  // transpose job: the [T, rank] rows an earlier launch kept
+  uint16_t* us_t;       // optional [2*rp, t_pad]
+  uint16_t* b_hl;       // backward: [2*rp, d_out]
+  int prep_block0;      // first block of its share of the prep job
+};
+
 struct FrontArgs {
   // rows job 1 (x)
   const uint16_t* x;
   int T, d_in;
   float2* rs_x;         // optional
   uint16_t* x16;        // optional, [T, d_in]
-  const float* A;       // optional: enables pooling and U
-  float s;
-  int g, rank;
+  int pool;             // rows job 1 also pools x and forms U = P A of every part
+  int g;
   float* P_out;         // optional [T, L]
-  uint16_t* us_t;       // optional [2*rp, t_pad]
   int t_pad;
-  float* u_keep;        // optional [T, rank]: s U in fp32, for a later launch's transpose job
-  // transpose job: us_t from the [T, rank] fp32 rows an earlier launch kept (then x is not needed)
-  const float* u_kept;
+  FrontPart part[MAX_PARTS];
+  int n_parts;
+  int tr_blocks;        // transpose job: blocks per part (t_pad / TR_TOK), or 0
   // rows job 2 (dy): scale + convert only
   const uint16_t* y;
   int Ty, d_y;
   float2* rs_y;
   uint16_t* y16;
-  // prep job
-  const float* B;
-  int d_out, L;
-  uint16_t* b_hl;       // backward: [2*rp, d_out]
   // factor job (see factor_block): the dense kernels' factor words
   const float* f_alpha; // [L, d_out]
   const float* f_beta;  // [L, d_out]
-  const float* f_A;     // [L, rank] or null: no adapter to fold in
-  const float* f_B;     // [rank, d_out]
-  float f_sg, f_mid;    // s / g; 2^(N-1)
-  int f_L, f_dout, f_rank, f_cols;  // f_cols: columns per block, a power of two <= 16
+  int f_fold;           // fold the parts' adapters in
+  float f_inv_g, f_mid; // 1 / g; 2^(N-1)
+  int f_L, f_dout, f_cols;  // f_cols: columns per block, a power of two <= 16
   int f_cw;             // columns per block of the adapter-free form: 32 or 64
   uint32_t* f_words;    // forward: [L, d_out] words at the per-column scale
   float* f_inv;         // forward: [d_out] 1 / S of each column
@@ -221,14 +228,22 @@ __device__ __forceinline__ void factor_block_plain(const FrontArgs& a, int bid, 
 }
 
 __device__ __forceinline__ void factor_block(const FrontArgs& a, int bid, float* lds, int tid) {
-  if (!a.f_A) {
+  if (!a.f_fold) {
     factor_block_plain(a, bid, lds, tid);
     return;
   }
   const int FC = a.f_cols, NLG = 256 / FC;
   const int c = tid & (FC - 1), lg = tid / FC;
-  const int L = a.f_L, dout = a.f_dout, rank = a.f_A ? a.f_rank : 0;
+  const int L = a.f_L, dout = a.f_dout;
   const int j0 = bid * FC, j = j0 + c;
+  // the part this block's columns belong to (part widths are multiples of the block's width)
+  int pi = 0;
+  for (int q = 1; q < a.n_parts; ++q)
+    if (j0 >= a.part[q].col0) pi = q;
+  const FrontPart& pt = a.part[pi];
+  const int rank = pt.rank, pj0 = j0 - pt.col0, pdout = pt.d_out;
+  const float* __restrict__ pA = pt.A;
+  const float sg = pt.s * a.f_inv_g;
   const bool col_ok = j < dout;
   const int bs = rank + 4;          // floats per staged column of B
   float* tile = lds;                // [L][FC]
@@ -236,7 +251,7 @@ __device__ __forceinline__ void factor_block(const FrontArgs& a, int bid, float*
   float* red = Bs + FC * bs;        // [256]
   for (int idx = tid; idx < FC * rank; idx += 256) {
     const int cc = idx & (FC - 1), k = idx / FC;
-    Bs[cc * bs + k] = (j0 + cc < dout) ? a.f_B[(size_t)k * dout + j0 + cc] : 0.0f;
+    Bs[cc * bs + k] = (pj0 + cc < pdout) ? pt.B[(size_t)k * pdout + pj0 + cc] : 0.0f;
   }
   __syncthreads();
   constexpr int GB = 4;  // groups per thread in flight
@@ -253,7 +268,7 @@ __device__ __forceinline__ void factor_block(const FrontArgs& a, int bid, float*
 #pragma unroll
         for (int i = 0; i < GB; ++i) {
           const int l = min(lb + i * NLG, L - 1);  // rows past the end repeat the last one, unused
-          const f32x4 av = *reinterpret_cast<const f32x4*>(a.f_A + (size_t)l * rank + k);
+          const f32x4 av = *reinterpret_cast<const f32x4*>(pA + (size_t)l * rank + k);
 #pragma unroll
           for (int q = 0; q < 4; ++q) acc[i] = __builtin_fmaf(av[q], b[q], acc[i]);
         }
@@ -264,7 +279,7 @@ __device__ __forceinline__ void factor_block(const FrontArgs& a, int bid, float*
 #pragma unroll
         for (int i = 0; i < GB; ++i) {
           const int l = min(lb + i * NLG, L - 1);
-          acc[i] = __builtin_fmaf(a.f_A[(size_t)l * rank + k], b, acc[i]);
+          acc[i] = __builtin_fmaf(pA[(size_t)l * rank + k], b, acc[i]);
         }
       }
     }
@@ -275,7 +290,7 @@ __device__ __forceinline__ void factor_block(const FrontArgs& a, int bid, float*
         float cst = 0.0f, bound = 0.0f;
         if (col_ok) {
           const float al = a.f_alpha[(size_t)l * dout + j];
-          const float bp = __builtin_fmaf(a.f_sg, acc[i], a.f_beta[(size_t)l * dout + j]);
+          const float bp = __builtin_fmaf(sg, acc[i], a.f_beta[(size_t)l * dout + j]);
           cst = __builtin_fmaf(a.f_mid, al, bp);
           bound = fabsf(cst) + a.f_mid * fabsf(al);
         }
@@ -403,58 +418,62 @@ __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
   if (bid < a.nb_rows1) {
     // ---- rows job 1: x ---------------------------------------------------------------
     const int t = bid * ROWS_PER_BLOCK + wave;
-    const int L = a.A ? a.d_in / a.g : 0;
-    const int rp = rank_pad32(a.rank);
-    float* P_s = a.A ? P_all + wave * L : nullptr;
+    const int L = a.pool ? a.d_in / a.g : 0;
+    float* P_s = a.pool ? P_all + wave * L : nullptr;
     float2 sc = float2{1.0f, 1.0f};
     if (t < a.T) {
       sc = process_row(a.x + (size_t)t * a.d_in, a.d_in,
                        a.x16 ? a.x16 + (size_t)t * a.d_in : nullptr, P_s, a.g, lane);
       if (lane == 0 && a.rs_x) a.rs_x[t] = sc;
-    } else if (a.A) {
+    } else if (a.pool) {
       for (int l = lane; l < L; l += 64) P_s[l] = 0.0f;
     }
-    if (!a.A) return;
+    if (!a.pool) return;
     __syncthreads();
     if (t < a.T && a.P_out)
       for (int l = lane; l < L; l += 64) a.P_out[(size_t)t * L + l] = P_s[l];
-    // U = P A for the block's 4 tokens, cooperatively: thread (k, q) covers a quarter of the
-    // groups for all 4 tokens (each A element is loaded once per block), then the quarters
-    // are added in fixed order.
+    // U = P A of every part for the block's 4 tokens, cooperatively: thread (k, q) covers a
+    // quarter of the groups for all 4 tokens (each A element is loaded once per block), then
+    // the quarters are added in fixed order.
     float* part = P_all + ROWS_PER_BLOCK * L;  // [4 quarters][4 tokens][128]
     const int lq0 = (L * wave) / 4, lq1 = (L * (wave + 1)) / 4;
-    for (int k = lane; k < a.rank; k += 64) {
-      float u[ROWS_PER_BLOCK] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int pi = 0; pi < a.n_parts; ++pi) {
+      const FrontPart& pt = a.part[pi];
+      const int rank = pt.rank, rp = rank_pad32(rank);
+      if (pi > 0) __syncthreads();  // the previous part's sums have been read
+      for (int k = lane; k < rank; k += 64) {
+        float u[ROWS_PER_BLOCK] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll 4
-      for (int l = lq0; l < lq1; ++l) {
-        const float av = a.A[(size_t)l * a.rank + k];
+        for (int l = lq0; l < lq1; ++l) {
+          const float av = pt.A[(size_t)l * rank + k];
 #pragma unroll
-        for (int r = 0; r < ROWS_PER_BLOCK; ++r) u[r] = __builtin_fmaf(P_all[r * L + l], av, u[r]);
-      }
+          for (int r = 0; r < ROWS_PER_BLOCK; ++r) u[r] = __builtin_fmaf(P_all[r * L + l], av, u[r]);
+        }
 #pragma unroll
-      for (int r = 0; r < ROWS_PER_BLOCK; ++r) part[(wave * ROWS_PER_BLOCK + r) * 128 + k] = u[r];
-    }
-    __syncthreads();
-    if (t < a.T) {
-      for (int k = lane; k < rp; k += 64) {
-        float u = 0.0f;
-        if (k < a.rank) {
-          u = ((part[(0 * ROWS_PER_BLOCK + wave) * 128 + k] + part[(1 * ROWS_PER_BLOCK + wave) * 128 + k]) +
-               part[(2 * ROWS_PER_BLOCK + wave) * 128 + k]) +
-              part[(3 * ROWS_PER_BLOCK + wave) * 128 + k];
-          u *= a.s;
-        }
-        uint16_t hi, lo;
-        if (a.u_keep && k < a.rank) a.u_keep[(size_t)t * a.rank + k] = u;
-        if (a.us_t) {
-          split_bf16(u, hi, lo);  // zero for the padding rows k >= rank
-          a.us_t[(size_t)k * a.t_pad + t] = hi;
-          a.us_t[(size_t)(rp + k) * a.t_pad + t] = lo;
-        }
+        for (int r = 0; r < ROWS_PER_BLOCK; ++r) part[(wave * ROWS_PER_BLOCK + r) * 128 + k] = u[r];
       }
-    } else if (a.us_t && t < a.t_pad) {
-      // token padding of the transposed operand must read as zero
-      for (int k = lane; k < 2 * rp; k += 64) a.us_t[(size_t)k * a.t_pad + t] = 0;
+      __syncthreads();
+      if (t < a.T) {
+        for (int k = lane; k < rp; k += 64) {
+          float u = 0.0f;
+          if (k < rank) {
+            u = ((part[(0 * ROWS_PER_BLOCK + wave) * 128 + k] + part[(1 * ROWS_PER_BLOCK + wave) * 128 + k]) +
+                 part[(2 * ROWS_PER_BLOCK + wave) * 128 + k]) +
+                part[(3 * ROWS_PER_BLOCK + wave) * 128 + k];
+            u *= pt.s;
+          }
+          uint16_t hi, lo;
+          if (pt.u_keep && k < rank) pt.u_keep[(size_t)t * rank + k] = u;
+          if (pt.us_t) {
+            split_bf16(u, hi, lo);  // zero for the padding rows k >= rank
+            pt.us_t[(size_t)k * a.t_pad + t] = hi;
+            pt.us_t[(size_t)(rp + k) * a.t_pad + t] = lo;
+          }
+        }
+      } else if (pt.us_t && t < a.t_pad) {
+        // token padding of the transposed operand must read as zero
+        for (int k = lane; k < 2 * rp; k += 64) pt.us_t[(size_t)k * a.t_pad + t] = 0;
+      }
     }
     return;
   }
@@ -476,7 +495,8 @@ __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
     // The loads go out in batches of eight per thread before any is used: the launch is
     // memory-saturated by the row jobs, and a round trip per element would outlast them.
     float* tile = P_all;  // [TR_TOK][rank + 1]
-    const int t0 = bid * TR_TOK, rank = a.rank, rp = rank_pad32(rank), ld = rank + 1;
+    const FrontPart& pt = a.part[bid / a.tr_blocks];
+    const int t0 = (bid % a.tr_blocks) * TR_TOK, rank = pt.rank, rp = rank_pad32(rank), ld = rank + 1;
     const int n = TR_TOK * rank;
     for (int e0 = 0; e0 < n; e0 += 8 * 256) {
       float r[8];
@@ -484,7 +504,7 @@ __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
       for (int j = 0; j < 8; ++j) {
         const int e = e0 + j * 256 + tid;
         const int t = e / rank;
-        r[j] = (e < n && t0 + t < a.T) ? a.u_kept[(size_t)t0 * rank + e] : 0.0f;
+        r[j] = (e < n && t0 + t < a.T) ? pt.u_kept[(size_t)t0 * rank + e] : 0.0f;
       }
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
@@ -498,27 +518,31 @@ __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
     for (int k = 2 * wave + (lane >> 5); k < rp; k += 8) {
       uint16_t hi, lo;
       split_bf16(k < rank ? tile[tl * ld + k] : 0.0f, hi, lo);  // zero for padding rows and tokens
-      a.us_t[(size_t)k * a.t_pad + t0 + tl] = hi;
-      a.us_t[(size_t)(rp + k) * a.t_pad + t0 + tl] = lo;
+      pt.us_t[(size_t)k * a.t_pad + t0 + tl] = hi;
+      pt.us_t[(size_t)(rp + k) * a.t_pad + t0 + tl] = lo;
     }
     return;
   }
   bid -= a.nb_tr;
-  // ---- prep job: hi/lo split of B for the dU product -------------------------------------
-  const size_t idx = (size_t)bid * 256 + tid;
-  const int rp = rank_pad32(a.rank);
-  const size_t nb = (size_t)2 * rp * a.d_out;
+  // ---- prep job: hi/lo split of every part's B for its dU product -----------------------
+  int pi = 0;
+  for (int q = 1; q < a.n_parts; ++q)
+    if (bid >= a.part[q].prep_block0) pi = q;
+  const FrontPart& pt = a.part[pi];
+  const size_t idx = (size_t)(bid - pt.prep_block0) * 256 + tid;
+  const int rp = rank_pad32(pt.rank);
+  const size_t nb = (size_t)2 * rp * pt.d_out;
   if (idx < nb) {
     // b_hl rows = hi(B) then lo(B) (rows padded to rp with zeros)
-    const int row = (int)(idx / a.d_out), j = (int)(idx % a.d_out);
+    const int row = (int)(idx / pt.d_out), j = (int)(idx % pt.d_out);
     const int k = row % rp;
     uint16_t v = 0;
-    if (k < a.rank) {
+    if (k < pt.rank) {
       uint16_t hi, lo;
-      split_bf16(a.B[(size_t)k * a.d_out + j], hi, lo);
+      split_bf16(pt.B[(size_t)k * pt.d_out + j], hi, lo);
       v = (row < rp) ? hi : lo;
     }
-    a.b_hl[idx] = v;
+    pt.b_hl[idx] = v;
   }
 }
 
@@ -570,31 +594,40 @@ static int factor_cols(int L) {
 }
 
 static hipError_t launch_front(FrontArgs a, hipStream_t st) {
-  if (a.x && !a.A && !a.y && !a.b_hl && !a.us_t && a.T <= kWideRows && a.d_in % 8 == 0 &&
+  const bool prep = a.n_parts > 0 && a.part[0].b_hl;
+  const bool transposes = a.n_parts > 0 && a.part[0].u_kept;
+  if (a.x && !a.pool && !a.y && !prep && !transposes && a.T <= kWideRows && a.d_in % 8 == 0 &&
       a.d_in <= 256 * 8 * WIDE_BATCH) {
     // few rows: a block per row; the factor job (if any) follows as a launch of its own
     front_wide_kernel<<<a.T, 256, 0, st>>>(a.x, a.d_in, a.rs_x, a.x16);
     if (hipError_t e = hipGetLastError(); e != hipSuccess || !a.f_alpha) return e;
     a.x = nullptr;
   }
-  a.nb_rows1 = a.x ? ceil_div(a.us_t ? a.t_pad : a.T, ROWS_PER_BLOCK) : 0;
+  int max_rank = 0;
+  for (int p = 0; p < a.n_parts; ++p) max_rank = a.part[p].rank > max_rank ? a.part[p].rank : max_rank;
+  a.nb_rows1 = a.x ? ceil_div((a.pool && a.part[0].us_t) ? a.t_pad : a.T, ROWS_PER_BLOCK) : 0;
   a.nb_rows2 = a.y ? ceil_div(a.Ty, ROWS_PER_BLOCK) : 0;
-  const size_t nprep = a.b_hl ? (size_t)2 * rank_pad32(a.rank) * a.d_out : 0;
-  a.nb_prep = (int)((nprep + 255) / 256);
-  a.nb_tr = a.u_kept ? a.t_pad / TR_TOK : 0;
+  a.nb_prep = 0;
+  if (prep)
+    for (int p = 0; p < a.n_parts; ++p) {
+      a.part[p].prep_block0 = a.nb_prep;
+      a.nb_prep += (int)(((size_t)2 * rank_pad32(a.part[p].rank) * a.part[p].d_out + 255) / 256);
+    }
+  a.tr_blocks = transposes ? a.t_pad / TR_TOK : 0;
+  a.nb_tr = a.tr_blocks * a.n_parts;
   size_t smem =
-      a.A ? ((size_t)ROWS_PER_BLOCK * (a.d_in / a.g) + 4 * ROWS_PER_BLOCK * 128) * sizeof(float) : 0;
-  const size_t tr_smem = (size_t)TR_TOK * (a.rank + 1) * sizeof(float);
+      (a.x && a.pool) ? ((size_t)ROWS_PER_BLOCK * (a.d_in / a.g) + 4 * ROWS_PER_BLOCK * 128) * sizeof(float) : 0;
+  const size_t tr_smem = (size_t)TR_TOK * (max_rank + 1) * sizeof(float);
   if (a.nb_tr > 0 && smem < tr_smem) smem = tr_smem;
   a.nb_fac = 0;
   if (a.f_alpha) {
     a.f_cols = factor_cols(a.f_L);
     // adapter-free form: the widest column tile that still leaves more blocks than compute units
     a.f_cw = a.f_dout / 64 >= 384 ? 64 : 32;
-    a.nb_fac = a.f_A ? ceil_div(a.f_dout, a.f_cols) : ceil_div(a.f_dout, a.f_cw);
+    a.nb_fac = a.f_fold ? ceil_div(a.f_dout, a.f_cols) : ceil_div(a.f_dout, a.f_cw);
     const size_t f_smem =
-        a.f_A ? ((size_t)a.f_L * a.f_cols + (size_t)a.f_cols * (a.f_rank + 4) + 256) * sizeof(float)
-              : 256 * sizeof(float);
+        a.f_fold ? ((size_t)a.f_L * a.f_cols + (size_t)a.f_cols * (max_rank + 4) + 256 + 4) * sizeof(float)
+                 : 256 * sizeof(float);
     if (smem < f_smem) smem = f_smem;
   }
   constexpr size_t kFrontLdsMax = 160 * 1024;  // a compute unit's LDS
@@ -611,15 +644,29 @@ static hipError_t launch_front(FrontArgs a, hipStream_t st) {
   return hipGetLastError();
 }
 
+static void set_parts(FrontArgs& a, const AdapterParts& ap) {
+  a.n_parts = ap.n;
+  for (int p = 0; p < ap.n; ++p) {
+    a.part[p].A = ap.A[p];
+    a.part[p].B = ap.B[p];
+    a.part[p].s = ap.s[p];
+    a.part[p].rank = ap.rank[p];
+    a.part[p].col0 = ap.col0[p];
+    a.part[p].d_out = ap.d_out[p];
+  }
+}
+
 static void set_factor_job(FrontArgs& a, const FactorJob& f) {
-  a.f_alpha = f.alpha; a.f_beta = f.beta; a.f_A = f.rank > 0 ? f.A : nullptr; a.f_B = f.B;
-  a.f_sg = f.s / (float)f.g; a.f_mid = (float)(1 << (f.bits - 1));
-  a.f_L = f.L; a.f_dout = f.d_out; a.f_rank = f.rank;
+  a.f_alpha = f.alpha; a.f_beta = f.beta; a.f_fold = f.parts.n > 0;
+  if (a.n_parts == 0) set_parts(a, f.parts);
+  a.f_inv_g = 1.0f / (float)f.g; a.f_mid = (float)(1 << (f.bits - 1));
+  a.f_L = f.L; a.f_dout = f.d_out;
   a.f_words = f.words; a.f_inv = f.inv_scale; a.f_const = f.cst; a.f_max = f.block_max;
   a.f_known = f.known_max;
 }
 
 int factor_job_blocks(int L, int d_out) { return ceil_div(d_out, factor_cols(L)); }
+int factor_job_cols(int L) { return factor_cols(L); }
 
 hipError_t launch_factor_job(const FactorJob& f, hipStream_t st) {
   FrontArgs a{};
@@ -628,32 +675,39 @@ hipError_t launch_factor_job(const FactorJob& f, hipStream_t st) {
 }
 
 hipError_t launch_front_forward(const uint16_t* x, int T, int d_in, float2* rs, uint16_t* x16,
-                                const float* A, float s, int g, int rank, float* P_keep,
-                                float* u_keep, const FactorJob& fac, hipStream_t st) {
+                                const AdapterParts& parts, int g, float* P_keep,
+                                float* const* u_keep, const FactorJob& fac, hipStream_t st) {
   FrontArgs a{};
-  a.x = x; a.T = T; a.d_in = d_in; a.rs_x = rs; a.x16 = x16;
-  if (A && rank > 0 && P_keep) {  // only a caller that keeps them needs P and s P A here
-    a.A = A; a.s = s; a.g = g; a.rank = rank;
+  a.x = x; a.T = T; a.d_in = d_in; a.rs_x = rs; a.x16 = x16; a.g = g;
+  if (parts.n > 0 && P_keep) {  // only a caller that keeps them needs P and s P A here
+    set_parts(a, parts);
+    a.pool = 1;
     a.P_out = P_keep;
-    a.u_keep = u_keep;
+    for (int p = 0; p < parts.n; ++p) a.part[p].u_keep = u_keep[p];
   }
   set_factor_job(a, fac);
   return launch_front(a, st);
 }
 
 hipError_t launch_front_backward(const uint16_t* dy, int T, int d_out, float2* rs_dy,
-                                 uint16_t* dy16, const uint16_t* x, int d_in, const float* A,
-                                 const float* B, float s, int g, int rank, float* P,
-                                 uint16_t* us_t, int t_pad, uint16_t* b_hl, const float* u_kept,
+                                 uint16_t* dy16, const uint16_t* x, int d_in,
+                                 const AdapterParts& parts, int g, float* P, uint16_t* const* us_t,
+                                 int t_pad, uint16_t* const* b_hl, const float* const* u_kept,
                                  const FactorJob& fac, hipStream_t st) {
   FrontArgs a{};
-  a.y = dy; a.Ty = T; a.d_y = d_out; a.rs_y = rs_dy; a.y16 = dy16;
-  if (A && rank > 0) {
-    a.x = u_kept ? nullptr : x;  // with the kept rows, P is the caller's and us_t is a transpose
-    a.u_kept = u_kept;
-    a.T = T; a.d_in = d_in; a.A = A; a.s = s; a.g = g; a.rank = rank;
-    a.P_out = P; a.us_t = us_t; a.t_pad = t_pad;
-    a.B = B; a.d_out = d_out; a.L = d_in / g; a.b_hl = b_hl;
+  a.y = dy; a.Ty = T; a.d_y = d_out; a.rs_y = rs_dy; a.y16 = dy16; a.g = g;
+  if (parts.n > 0) {
+    set_parts(a, parts);
+    const bool kept = u_kept != nullptr;
+    a.x = kept ? nullptr : x;  // with the kept rows, P is the caller's and us_t is a transpose
+    a.pool = kept ? 0 : 1;
+    a.T = T; a.d_in = d_in;
+    a.P_out = P; a.t_pad = t_pad;
+    for (int p = 0; p < parts.n; ++p) {
+      a.part[p].us_t = us_t[p];
+      a.part[p].b_hl = b_hl[p];
+      a.part[p].u_kept = kept ? u_kept[p] : nullptr;
+    }
   }
   if (fac.alpha) set_factor_job(a, fac);
   return launch_front(a, st);
@@ -716,7 +770,8 @@ constexpr int DB_DY_ROW = 136;  // bf16 per LDS row of the dy tile (128 + 8 pad)
 struct DbArgs {
   const uint16_t* us_t;  // bf16 [2*rp, t_pad]: hi rows, then lo rows, of (s U)^T
   int t_pad;
-  const uint16_t* dy;    // bf16 [T, d_out]
+  const uint16_t* dy;    // bf16 [T, d_out], rows dy_ld elements apart (a column slice of a wider dy)
+  int dy_ld;
   int T, d_out, rank, tsplit;
   float* part;           // [tsplit][rank, d_out]
 };
@@ -777,7 +832,7 @@ __device__ __forceinline__ void db_partial_block(const DbArgs& a, int bx, int z,
         const int idx = tid + 256 * q, row = idx >> 4, ch = idx & 15;
         const int t = t0 + row, j = j0 + 8 * ch;
         dy_r[q] = u32x4{0, 0, 0, 0};
-        if (t < T && j < d_out) dy_r[q] = *reinterpret_cast<const u32x4*>(dy + (size_t)t * d_out + j);
+        if (t < T && j < d_out) dy_r[q] = *reinterpret_cast<const u32x4*>(dy + (size_t)t * a.dy_ld + j);
       }
     }
     if (have) {
@@ -953,11 +1008,11 @@ __global__ __launch_bounds__(256, MT <= 4 ? 3 : 1) void adapter_grads_kernel(con
   }
 }
 
-hipError_t launch_adapter_grads(const uint16_t* us_t, int t_pad, const uint16_t* dy, int T, int d_out,
-                                int rank, int tsplit_b, float* db_part, const float* P,
+hipError_t launch_adapter_grads(const uint16_t* us_t, int t_pad, const uint16_t* dy, int dy_ld, int T,
+                                int d_out, int rank, int tsplit_b, float* db_part, const float* P,
                                 const float* raw, int ksplit, float s, int L, int tsplit_a,
                                 float* da_part, hipStream_t st) {
-  const DbArgs db{us_t, t_pad, dy, T, d_out, rank, tsplit_b, db_part};
+  const DbArgs db{us_t, t_pad, dy, dy_ld, T, d_out, rank, tsplit_b, db_part};
   const DaArgs da{P, raw, ksplit, s, T, L, rank, tsplit_a, da_part};
   const int db_bx = ceil_div(d_out, DB_BN), db_blocks = db_bx * tsplit_b;
   const int da_bx = ceil_div(L, 64), da_blocks = da_bx * tsplit_a;

@@ -23,9 +23,21 @@ struct FwdPlan {
   int gsplit;
   size_t rs, a16, fac, inv, gpart, total;
 };
+// One adapter among those sharing x (a single layer is one part over all columns).
+struct PartSpec {
+  int n;
+  AdapterParts ap;
+  float* dA[MAX_PARTS];
+  float* dB[MAX_PARTS];
+};
+struct BwdPartPlan {
+  int rp, ksplit, tsplit_b, tsplit_a;
+  size_t us_t, b_hl, du_raw, db_part, da_part;
+};
 struct BwdPlan {
-  int rp, t_pad, ksplit, tsplit_b, tsplit_a, gsplit, nmax;
-  size_t rs, a16, fac, cst, bmax, inv, P, us_t, b_hl, du_raw, db_part, da_part, gpart, total;
+  int t_pad, gsplit, nmax;
+  size_t rs, a16, fac, cst, bmax, inv, P, gpart, total;
+  BwdPartPlan part[MAX_PARTS];
 };
 
 // forward workspace: row scales, the fp16 copy of x, the factor words and their column scales,
@@ -49,10 +61,12 @@ FwdPlan plan_forward(const qalora_desc& d, int T) {
   return p;
 }
 
-BwdPlan plan_backward(const qalora_desc& d, int T) {
+// backward workspace: what the dx contraction needs (row scales, fp16 copy of dy, factor words
+// and their first stage), then P = pool(x) and per adapter part the operands and partial sums
+// of its gradient kernels.  n_parts = 0: adapter-free, only dx.
+BwdPlan plan_backward(const qalora_desc& d, int T, int n_parts, const int* part_rank, const int* part_dout) {
   BwdPlan p{};
   const int L = d.d_in / d.group;
-  p.rp = rank_pad32(d.rank);
   p.t_pad = round_up(T, 64);
   p.nmax = factor_job_blocks(L, d.d_out);
   size_t off = 0;
@@ -69,43 +83,51 @@ BwdPlan plan_backward(const qalora_desc& d, int T) {
   p.inv = take(16);
   p.gsplit = gemm_dq_ksplit(T, d.d_in, d.d_out);
   if (p.gsplit > 1) p.gpart = take((size_t)p.gsplit * T * d.d_in * 4);
-  if (d.rank <= 0) {  // adapter-free: only dx is produced
+  if (n_parts <= 0) {
     p.total = off;
     return p;
   }
-  // dU product: [T, 2rp] output tiles of plain_tile_rows x 128 (the taller tile pays when K is
-  // long: half the K steps per block for the same number of blocks); split K = d_out to fill
-  // the chip.
-  {
-    const int tiles = ceil_div(T, gemm_plain_tile_rows(d.d_out)) * ceil_div(2 * p.rp, 128);
-    const int nk = ceil_div(d.d_out, 64);
-    int ks = ceil_div(256, tiles);
-    ks = ks < 1 ? 1 : (ks > 16 ? 16 : ks);
-    const int by_steps = nk / 12;  // a slice shorter than about twelve K steps is all prologue
-    if (ks > by_steps) ks = by_steps < 1 ? 1 : by_steps;
-    p.ksplit = ks;
-  }
-  {
-    const int blocks = ceil_div(d.d_out, 128);
-    int ts = ceil_div(256, blocks);  // about one block per compute unit
-    ts = ts > 32 ? 32 : ts;
-    const int steps = p.t_pad / 64;
-    p.tsplit_b = ts > steps ? steps : ts;
-  }
-  {
-    // one 16-token chunk per block where possible: the work is tiny and latency-bound, so
-    // maximise the number of independent blocks
-    const int steps = ceil_div(T, 16);
-    p.tsplit_a = steps > 256 ? 256 : steps;
-  }
   p.P = take((size_t)T * L * 4);
-  p.us_t = take((size_t)2 * p.rp * p.t_pad * 2);
-  p.b_hl = take((size_t)2 * p.rp * d.d_out * 2);
-  p.du_raw = take((size_t)p.ksplit * T * 2 * p.rp * 4);
-  p.db_part = take((size_t)p.tsplit_b * d.rank * d.d_out * 4);
-  p.da_part = take((size_t)p.tsplit_a * L * d.rank * 4);
+  for (int q = 0; q < n_parts; ++q) {
+    BwdPartPlan& pp = p.part[q];
+    const int rank = part_rank[q], dout = part_dout[q];
+    pp.rp = rank_pad32(rank);
+    // dU product: [T, 2rp] output tiles of plain_tile_rows x 128 (the taller tile pays when K
+    // is long: half the K steps per block for the same number of blocks); split K = d_out to
+    // fill the chip.
+    {
+      const int tiles = ceil_div(T, gemm_plain_tile_rows(dout)) * ceil_div(2 * pp.rp, 128);
+      const int nk = ceil_div(dout, 64);
+      int ks = ceil_div(256, tiles);
+      ks = ks < 1 ? 1 : (ks > 16 ? 16 : ks);
+      const int by_steps = nk / 12;  // a slice shorter than about twelve K steps is all prologue
+      if (ks > by_steps) ks = by_steps < 1 ? 1 : by_steps;
+      pp.ksplit = ks;
+    }
+    {
+      const int blocks = ceil_div(dout, 128);
+      int ts = ceil_div(256, blocks);  // about one block per compute unit
+      ts = ts > 32 ? 32 : ts;
+      const int steps = p.t_pad / 64;
+      pp.tsplit_b = ts > steps ? steps : ts;
+    }
+    {
+      // one 16-token chunk per block where possible: the work is tiny and latency-bound, so
+      // maximise the number of independent blocks
+      const int steps = ceil_div(T, 16);
+      pp.tsplit_a = steps > 256 ? 256 : steps;
+    }
+    pp.us_t = take((size_t)2 * pp.rp * p.t_pad * 2);
+    pp.b_hl = take((size_t)2 * pp.rp * dout * 2);
+    pp.du_raw = take((size_t)pp.ksplit * T * 2 * pp.rp * 4);
+    pp.db_part = take((size_t)pp.tsplit_b * rank * dout * 4);
+    pp.da_part = take((size_t)pp.tsplit_a * L * rank * 4);
+  }
   p.total = off;
   return p;
+}
+BwdPlan plan_backward(const qalora_desc& d, int T) {
+  return plan_backward(d, T, d.rank > 0 ? 1 : 0, &d.rank, &d.d_out);
 }
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
@@ -140,6 +162,7 @@ inline size_t smallt_workspace(const qalora_desc& d, int tokens) {
   return ST_HEAD_BYTES + align_up((size_t)blocks * per_block * 4);
 }
 
+static_assert(MAX_PARTS == QALORA_MAX_PARTS, "the header documents this limit");
 static_assert(ST_STATUS_OFFSET == QALORA_WS_STATUS_OFFSET, "the header documents this offset");
 
 // Scratch of qalora_forward_noalloc: the streaming kernels' flags, status word and per-block
@@ -272,13 +295,17 @@ int qalora_pack(const qalora_desc* d, const uint8_t* codes, void* packed, void* 
 // What the forward leaves for the backward when asked to: P = pool_g(x) [T, L] and
 // s P A [T, rank], both fp32.
 struct KeptLayout {
-  size_t P, U, bmax, total;
+  size_t P, U[MAX_PARTS], bmax, total;
 };
-static KeptLayout kept_layout(const qalora_desc& d, int T) {
+static KeptLayout kept_layout(const qalora_desc& d, int T, int n_parts, const int* part_rank) {
   KeptLayout k{};
   k.P = 0;
-  k.U = align_up((size_t)T * (d.d_in / d.group) * 4);
-  k.bmax = k.U + align_up((size_t)T * d.rank * 4);
+  size_t off = align_up((size_t)T * (d.d_in / d.group) * 4);
+  for (int q = 0; q < n_parts; ++q) {
+    k.U[q] = off;
+    off += align_up((size_t)T * part_rank[q] * 4);
+  }
+  k.bmax = off;
   k.total = k.bmax + align_up((size_t)factor_job_blocks(d.d_in / d.group, d.d_out) * 4);
   return k;
 }
@@ -288,65 +315,157 @@ struct PreparedFactors {  // factor words and column scales made ahead of the ca
   const float* inv_scale;
 };
 static int forward_impl(const qalora_desc* d, int tokens, const void* x, const void* packed,
-                        const float* alpha, const float* beta, const float* A, const float* B, void* y,
-                        int y_dtype, void* kept, bool keep, void* ws, size_t ws_bytes, void* stream,
+                        const float* alpha, const float* beta, const PartSpec& ps, void* y, int y_dtype,
+                        void* kept, bool keep, void* ws, size_t ws_bytes, void* stream,
                         const PreparedFactors* pre = nullptr);
 static int backward_impl(const qalora_desc* d, int tokens, const void* dy, const void* x,
                          const void* kept, bool use_kept, const void* packed, const float* alpha,
-                         const float* beta, const float* A, const float* B, void* dx, int dx_dtype,
-                         float* dA, float* dB, int accumulate, void* ws, size_t ws_bytes, void* stream);
+                         const float* beta, const PartSpec& ps, void* dx, int dx_dtype, int accumulate,
+                         void* ws, size_t ws_bytes, void* stream);
+
+// A single layer as one part over all its columns; exactly one of A, B null is an error the
+// caller has checked for.
+static PartSpec single_part(const qalora_desc* d, const float* A, const float* B, float* dA, float* dB) {
+  PartSpec ps{};
+  if (d && A && B && d->rank > 0) {
+    ps.n = ps.ap.n = 1;
+    ps.ap.A[0] = A;
+    ps.ap.B[0] = B;
+    ps.ap.s[0] = d->s;
+    ps.ap.rank[0] = d->rank;
+    ps.ap.col0[0] = 0;
+    ps.ap.d_out[0] = d->d_out;
+    ps.dA[0] = dA;
+    ps.dB[0] = dB;
+  }
+  return ps;
+}
 
 int qalora_forward(const qalora_desc* d, int tokens, const void* x, const void* packed,
                    const float* alpha, const float* beta, const float* A, const float* B, void* y,
                    int y_dtype, void* ws, size_t ws_bytes, void* stream) {
-  return forward_impl(d, tokens, x, packed, alpha, beta, A, B, y, y_dtype, nullptr, false, ws, ws_bytes,
-                      stream);
+  if ((A == nullptr) != (B == nullptr)) return QALORA_EINVAL;
+  return forward_impl(d, tokens, x, packed, alpha, beta, single_part(d, A, B, nullptr, nullptr), y, y_dtype,
+                      nullptr, false, ws, ws_bytes, stream);
 }
 
 size_t qalora_kept_bytes(const qalora_desc* d, int tokens) {
   if (qalora_check_desc(d) != QALORA_OK || tokens <= 0 || d->rank <= 0) return 0;
-  return kept_layout(*d, tokens).total;
+  return kept_layout(*d, tokens, 1, &d->rank).total;
 }
 
 int qalora_forward_keep(const qalora_desc* d, int tokens, const void* x, const void* packed,
                         const float* alpha, const float* beta, const float* A, const float* B,
                         void* y, int y_dtype, void* kept, void* ws, size_t ws_bytes, void* stream) {
-  return forward_impl(d, tokens, x, packed, alpha, beta, A, B, y, y_dtype, kept, true, ws, ws_bytes,
-                      stream);
+  if (!A || !B || !kept || !d || d->rank <= 0) return QALORA_EINVAL;  // only an adapter has anything to keep
+  return forward_impl(d, tokens, x, packed, alpha, beta, single_part(d, A, B, nullptr, nullptr), y, y_dtype,
+                      kept, true, ws, ws_bytes, stream);
 }
 
 int qalora_backward(const qalora_desc* d, int tokens, const void* dy, const void* x,
                     const void* packed, const float* alpha, const float* beta, const float* A,
                     const float* B, void* dx, int dx_dtype, float* dA, float* dB, int accumulate,
                     void* ws, size_t ws_bytes, void* stream) {
-  return backward_impl(d, tokens, dy, x, nullptr, false, packed, alpha, beta, A, B, dx, dx_dtype, dA, dB,
-                       accumulate, ws, ws_bytes, stream);
+  if ((A == nullptr) != (B == nullptr)) return QALORA_EINVAL;
+  if (A && d && d->rank > 0 && (!dA || !dB || !x)) return QALORA_EINVAL;
+  return backward_impl(d, tokens, dy, x, nullptr, false, packed, alpha, beta, single_part(d, A, B, dA, dB),
+                       dx, dx_dtype, accumulate, ws, ws_bytes, stream);
 }
 
 int qalora_backward_kept(const qalora_desc* d, int tokens, const void* dy, const void* kept,
                          const void* packed, const float* alpha, const float* beta, const float* A,
                          const float* B, void* dx, int dx_dtype, float* dA, float* dB,
                          int accumulate, void* ws, size_t ws_bytes, void* stream) {
-  return backward_impl(d, tokens, dy, nullptr, kept, true, packed, alpha, beta, A, B, dx, dx_dtype, dA,
-                       dB, accumulate, ws, ws_bytes, stream);
+  if (!A || !B || !kept || !dA || !dB || !d || d->rank <= 0) return QALORA_EINVAL;
+  return backward_impl(d, tokens, dy, nullptr, kept, true, packed, alpha, beta, single_part(d, A, B, dA, dB),
+                       dx, dx_dtype, accumulate, ws, ws_bytes, stream);
+}
+
+// ---- several linears that share x, as one wide layer -----------------------------------
+static int shared_parts(const qalora_desc* d, int n_parts, const qalora_part* parts, bool backward,
+                        PartSpec& ps) {
+  const int rc = qalora_check_desc(d);
+  if (rc != QALORA_OK) return rc;
+  if (n_parts < 1 || n_parts > MAX_PARTS || !parts) return QALORA_EINVAL;
+  ps = PartSpec{};
+  int col = 0;
+  for (int q = 0; q < n_parts; ++q) {
+    const qalora_part& pt = parts[q];
+    if (pt.d_out <= 0 || pt.rank <= 0 || !pt.A || !pt.B) return QALORA_EINVAL;
+    if (backward && (!pt.dA || !pt.dB)) return QALORA_EINVAL;
+    if (misaligned(pt.A) || misaligned(pt.B) || misaligned(pt.dA) || misaligned(pt.dB)) return QALORA_EALIGN;
+    if (pt.rank > 128 || pt.d_out % 32 != 0) return QALORA_EUNSUPPORTED;
+    ps.ap.A[q] = pt.A;
+    ps.ap.B[q] = pt.B;
+    ps.ap.s[q] = pt.s;
+    ps.ap.rank[q] = pt.rank;
+    ps.ap.col0[q] = col;
+    ps.ap.d_out[q] = pt.d_out;
+    ps.dA[q] = pt.dA;
+    ps.dB[q] = pt.dB;
+    col += pt.d_out;
+  }
+  if (col != d->d_out) return QALORA_EINVAL;
+  ps.n = ps.ap.n = n_parts;
+  return QALORA_OK;
+}
+
+size_t qalora_shared_kept_bytes(const qalora_desc* d, int tokens, int n_parts, const qalora_part* parts) {
+  PartSpec ps;
+  if (tokens <= 0 || shared_parts(d, n_parts, parts, false, ps) != QALORA_OK) return 0;
+  return kept_layout(*d, tokens, ps.n, ps.ap.rank).total;
+}
+
+size_t qalora_shared_workspace_bytes(const qalora_desc* d, int tokens, int op, int n_parts,
+                                     const qalora_part* parts) {
+  PartSpec ps;
+  if (tokens <= 0 || shared_parts(d, n_parts, parts, false, ps) != QALORA_OK) return 0;
+  if (op == QALORA_OP_FORWARD) return plan_forward(*d, tokens).total;
+  if (op == QALORA_OP_BACKWARD) return plan_backward(*d, tokens, ps.n, ps.ap.rank, ps.ap.d_out).total;
+  return 0;
+}
+
+int qalora_forward_shared(const qalora_desc* d, int tokens, const void* x, const void* packed,
+                          const float* alpha, const float* beta, int n_parts, const qalora_part* parts,
+                          void* y, int y_dtype, void* kept, void* ws, size_t ws_bytes, void* stream) {
+  PartSpec ps;
+  if (const int rc = shared_parts(d, n_parts, parts, false, ps); rc != QALORA_OK) return rc;
+  return forward_impl(d, tokens, x, packed, alpha, beta, ps, y, y_dtype, kept, kept != nullptr, ws, ws_bytes,
+                      stream);
+}
+
+int qalora_backward_shared(const qalora_desc* d, int tokens, const void* dy, const void* x,
+                           const void* kept, const void* packed, const float* alpha, const float* beta,
+                           int n_parts, const qalora_part* parts, void* dx, int dx_dtype, int accumulate,
+                           void* ws, size_t ws_bytes, void* stream) {
+  PartSpec ps;
+  if (const int rc = shared_parts(d, n_parts, parts, true, ps); rc != QALORA_OK) return rc;
+  if (!kept && !x) return QALORA_EINVAL;
+  return backward_impl(d, tokens, dy, kept ? nullptr : x, kept, kept != nullptr, packed, alpha, beta, ps, dx,
+                       dx_dtype, accumulate, ws, ws_bytes, stream);
 }
 
 static int forward_impl(const qalora_desc* d, int tokens, const void* x, const void* packed,
-                        const float* alpha, const float* beta, const float* A, const float* B, void* y,
-                        int y_dtype, void* kept, bool keep, void* ws, size_t ws_bytes, void* stream,
+                        const float* alpha, const float* beta, const PartSpec& ps, void* y, int y_dtype,
+                        void* kept, bool keep, void* ws, size_t ws_bytes, void* stream,
                         const PreparedFactors* pre) {
   const int rc = qalora_check_desc(d);
   if (rc != QALORA_OK) return rc;
   if (tokens <= 0 || !x || !packed || !y) return QALORA_EINVAL;
   if (!pre && (!alpha || !beta)) return QALORA_EINVAL;
-  if ((A == nullptr) != (B == nullptr)) return QALORA_EINVAL;
   if (y_dtype != QALORA_F32 && y_dtype != QALORA_BF16) return QALORA_EINVAL;
-  if (keep && (!kept || !A || !B || d->rank <= 0)) return QALORA_EINVAL;  // only an adapter has anything to keep
-  if (misaligned(x) || misaligned(packed) || misaligned(alpha) || misaligned(beta) ||
-      misaligned(A) || misaligned(B) || misaligned(y) || misaligned(ws) || misaligned(kept))
+  const bool adapter = ps.n > 0;
+  if (keep && (!kept || !adapter)) return QALORA_EINVAL;  // only an adapter has anything to keep
+  if (misaligned(x) || misaligned(packed) || misaligned(alpha) || misaligned(beta) || misaligned(y) ||
+      misaligned(ws) || misaligned(kept))
     return QALORA_EALIGN;
+  for (int q = 0; q < ps.n; ++q)
+    if (misaligned(ps.ap.A[q]) || misaligned(ps.ap.B[q])) return QALORA_EALIGN;
   if (!addressable(*d, tokens)) return QALORA_EUNSUPPORTED;
-  const bool adapter = A && B && d->rank > 0;
+  // the folding job owns whole column blocks: every part's width must be a multiple of them
+  if (ps.n > 1)
+    for (int q = 0; q < ps.n; ++q)
+      if (ps.ap.d_out[q] % factor_job_cols(d->d_in / d->group) != 0) return QALORA_EUNSUPPORTED;
   if (!adapter && !pre && use_smallt(*d, tokens)) {
     // memory-bound regime: stream the weight once on the exact-operand path
     const size_t need = smallt_workspace(*d, tokens);
@@ -382,11 +501,8 @@ static int forward_impl(const qalora_desc* d, int tokens, const void* x, const v
   FactorJob fj{};
   fj.alpha = alpha;
   fj.beta = beta;
-  fj.A = adapter ? A : nullptr;
-  fj.B = adapter ? B : nullptr;
-  fj.s = d->s;
+  fj.parts = ps.ap;
   fj.g = d->group;
-  fj.rank = adapter ? d->rank : 0;
   fj.bits = d->bits;
   fj.L = L;
   fj.d_out = d->d_out;
@@ -394,17 +510,16 @@ static int forward_impl(const qalora_desc* d, int tokens, const void* x, const v
   fj.inv_scale = reinterpret_cast<float*>(w + plan.inv);
   if (pre) fj.alpha = nullptr;  // the words exist already: no factor job
   float* P_keep = nullptr;
-  float* u_keep = nullptr;
+  float* u_keep[MAX_PARTS] = {};
   if (keep) {
-    const KeptLayout k = kept_layout(*d, tokens);
+    const KeptLayout k = kept_layout(*d, tokens, ps.n, ps.ap.rank);
     P_keep = reinterpret_cast<float*>(static_cast<char*>(kept) + k.P);
-    u_keep = reinterpret_cast<float*>(static_cast<char*>(kept) + k.U);
+    for (int q = 0; q < ps.n; ++q) u_keep[q] = reinterpret_cast<float*>(static_cast<char*>(kept) + k.U[q]);
     // the bounds on |W~'| the factor job finds anyway: with them the backward knows its scale
     fj.block_max = reinterpret_cast<float*>(static_cast<char*>(kept) + k.bmax);
   }
-  if (launch_front_forward(static_cast<const uint16_t*>(x), tokens, d->d_in, rs, x16,
-                           adapter ? A : nullptr, d->s, d->group, d->rank, P_keep, u_keep, fj,
-                           st) != hipSuccess)
+  if (launch_front_forward(static_cast<const uint16_t*>(x), tokens, d->d_in, rs, x16, ps.ap, d->group,
+                           P_keep, u_keep, fj, st) != hipSuccess)
     return QALORA_EHIP;
 
   GemmArgs g{};
@@ -431,28 +546,33 @@ static int forward_impl(const qalora_desc* d, int tokens, const void* x, const v
 
 static int backward_impl(const qalora_desc* d, int tokens, const void* dy, const void* x,
                          const void* kept, bool use_kept, const void* packed, const float* alpha,
-                         const float* beta, const float* A, const float* B, void* dx, int dx_dtype,
-                         float* dA, float* dB, int accumulate, void* ws, size_t ws_bytes, void* stream) {
+                         const float* beta, const PartSpec& ps, void* dx, int dx_dtype, int accumulate,
+                         void* ws, size_t ws_bytes, void* stream) {
   const int rc = qalora_check_desc(d);
   if (rc != QALORA_OK) return rc;
   if (tokens <= 0 || !dy || !packed || !alpha || !beta) return QALORA_EINVAL;
-  if ((A == nullptr) != (B == nullptr)) return QALORA_EINVAL;
-  const bool adapter = A && B && d->rank > 0;
+  const bool adapter = ps.n > 0;
   if (use_kept && (!kept || !adapter)) return QALORA_EINVAL;
-  if (adapter && ((!use_kept && !x) || !dA || !dB)) return QALORA_EINVAL;
+  if (adapter && !use_kept && !x) return QALORA_EINVAL;
+  for (int q = 0; q < ps.n; ++q)
+    if (!ps.dA[q] || !ps.dB[q]) return QALORA_EINVAL;
   if (misaligned(kept)) return QALORA_EALIGN;
   if (dx && dx_dtype != QALORA_F32 && dx_dtype != QALORA_BF16) return QALORA_EINVAL;
   if (accumulate != 0 && accumulate != 1) return QALORA_EINVAL;
-  if (misaligned(dy) || misaligned(x) || misaligned(packed) || misaligned(alpha) ||
-      misaligned(beta) || misaligned(A) || misaligned(B) || misaligned(dx) || misaligned(dA) ||
-      misaligned(dB) || misaligned(ws))
+  if (misaligned(dy) || misaligned(x) || misaligned(packed) || misaligned(alpha) || misaligned(beta) ||
+      misaligned(dx) || misaligned(ws))
     return QALORA_EALIGN;
+  for (int q = 0; q < ps.n; ++q)
+    if (misaligned(ps.ap.A[q]) || misaligned(ps.ap.B[q]) || misaligned(ps.dA[q]) || misaligned(ps.dB[q]))
+      return QALORA_EALIGN;
   if (!addressable(*d, tokens)) return QALORA_EUNSUPPORTED;
-  qalora_desc dd = *d;
-  if (!adapter) dd.rank = 0;
-  const BwdPlan plan = plan_backward(dd, tokens);
-  if (adapter && (size_t)plan.ksplit * tokens * 2 * plan.rp * 4 >= kAddressable)
-    return QALORA_EUNSUPPORTED;  // the split-K partials of dU are read with 32-bit byte offsets
+  if (ps.n > 1)
+    for (int q = 0; q < ps.n; ++q)
+      if (ps.ap.d_out[q] % factor_job_cols(d->d_in / d->group) != 0) return QALORA_EUNSUPPORTED;
+  const BwdPlan plan = plan_backward(*d, tokens, ps.n, ps.ap.rank, ps.ap.d_out);
+  for (int q = 0; q < ps.n; ++q)
+    if ((size_t)plan.part[q].ksplit * tokens * 2 * plan.part[q].rp * 4 >= kAddressable)
+      return QALORA_EUNSUPPORTED;  // the split-K partials of dU are read with 32-bit byte offsets
   if (!ws || ws_bytes < plan.total) return QALORA_EWORKSPACE;
   hipStream_t st = as_stream(stream);
   char* w = static_cast<char*>(ws);
@@ -467,20 +587,18 @@ static int backward_impl(const qalora_desc* d, int tokens, const void* dy, const
   FactorJob fj{};
   uint32_t* words = reinterpret_cast<uint32_t*>(w + plan.fac);
   float* inv_scale = reinterpret_cast<float*>(w + plan.inv);
+  KeptLayout kl{};
+  if (use_kept) kl = kept_layout(*d, tokens, ps.n, ps.ap.rank);
   if (dx) {
     fj.alpha = alpha;
     fj.beta = beta;
-    fj.A = adapter ? A : nullptr;
-    fj.B = adapter ? B : nullptr;
-    fj.s = d->s;
+    fj.parts = ps.ap;
     fj.g = d->group;
-    fj.rank = adapter ? d->rank : 0;
     fj.bits = d->bits;
     fj.L = L;
     fj.d_out = d->d_out;
     if (use_kept) {  // the forward left the bounds: one stage
-      const KeptLayout k = kept_layout(*d, tokens);
-      fj.known_max = reinterpret_cast<const float*>(static_cast<const char*>(kept) + k.bmax);
+      fj.known_max = reinterpret_cast<const float*>(static_cast<const char*>(kept) + kl.bmax);
       fj.words = words;
       fj.inv_scale = inv_scale;
     } else {
@@ -489,26 +607,27 @@ static int backward_impl(const qalora_desc* d, int tokens, const void* dy, const
     }
   }
   float* P = nullptr;
-  uint16_t* us_t = nullptr;
-  uint16_t* b_hl = nullptr;
-  const float* u_kept = nullptr;
+  uint16_t* us_t[MAX_PARTS] = {};
+  uint16_t* b_hl[MAX_PARTS] = {};
+  const float* u_kept[MAX_PARTS] = {};
   if (adapter) {
     P = reinterpret_cast<float*>(w + plan.P);
-    us_t = reinterpret_cast<uint16_t*>(w + plan.us_t);
-    b_hl = reinterpret_cast<uint16_t*>(w + plan.b_hl);
+    for (int q = 0; q < ps.n; ++q) {
+      us_t[q] = reinterpret_cast<uint16_t*>(w + plan.part[q].us_t);
+      b_hl[q] = reinterpret_cast<uint16_t*>(w + plan.part[q].b_hl);
+    }
     if (use_kept) {  // written by the forward: the front launch below then skips x altogether
-      const KeptLayout k = kept_layout(*d, tokens);
       char* kp = const_cast<char*>(static_cast<const char*>(kept));
-      P = reinterpret_cast<float*>(kp + k.P);
-      u_kept = reinterpret_cast<const float*>(kp + k.U);
+      P = reinterpret_cast<float*>(kp + kl.P);
+      for (int q = 0; q < ps.n; ++q) u_kept[q] = reinterpret_cast<const float*>(kp + kl.U[q]);
     }
   }
   // row scales + fp16 copy of dy; first stage of the factor words; P = pool(x), sU^T hi/lo and
   // the hi/lo rows of B for the adapter gradients
   if (launch_front_backward(dy16, tokens, d->d_out, rs, dyh,
-                            (adapter && !use_kept) ? static_cast<const uint16_t*>(x) : nullptr,
-                            d->d_in, adapter ? A : nullptr, B, d->s, d->group, adapter ? d->rank : 0, P,
-                            us_t, plan.t_pad, b_hl, u_kept, fj, st) != hipSuccess)
+                            (adapter && !use_kept) ? static_cast<const uint16_t*>(x) : nullptr, d->d_in,
+                            ps.ap, d->group, P, us_t, plan.t_pad, b_hl, use_kept ? u_kept : nullptr, fj,
+                            st) != hipSuccess)
     return QALORA_EHIP;
   if (dx) {
     if (!use_kept && launch_factor_scale(alpha, fj.cst, fj.block_max, plan.nmax, (size_t)L * d->d_out,
@@ -535,28 +654,31 @@ static int backward_impl(const qalora_desc* d, int tokens, const void* dy, const
     g.partial = plan.gsplit > 1 ? reinterpret_cast<float*>(w + plan.gpart) : nullptr;
     if (launch_gemm_dq(d->bits, true, g, st) != hipSuccess) return QALORA_EHIP;
   }
-  if (adapter) {
-    float* du_raw = reinterpret_cast<float*>(w + plan.du_raw);
-    float* db_part = reinterpret_cast<float*>(w + plan.db_part);
-    float* da_part = reinterpret_cast<float*>(w + plan.da_part);
+  for (int q = 0; q < ps.n; ++q) {  // the adapter gradients of every part, on its columns of dy
+    const BwdPartPlan& pp = plan.part[q];
+    const int rank = ps.ap.rank[q], dout = ps.ap.d_out[q];
+    const uint16_t* dyq = dy16 + ps.ap.col0[q];
+    float* du_raw = reinterpret_cast<float*>(w + pp.du_raw);
+    float* db_part = reinterpret_cast<float*>(w + pp.db_part);
+    float* da_part = reinterpret_cast<float*>(w + pp.da_part);
     // dU = s dy B^T : plain bf16 product against the hi/lo rows of B, split over K = d_out
     GemmArgs g{};
-    g.a_tail = dy16;
+    g.a_tail = dyq;
     g.lda_tail = d->d_out;
-    g.b_tail = b_hl;
-    g.K_tail = d->d_out;
+    g.b_tail = b_hl[q];
+    g.K_tail = dout;
     g.out = du_raw;
     g.M = tokens;
-    g.N = 2 * plan.rp;
+    g.N = 2 * pp.rp;
     g.group = 1;
-    if (launch_gemm_plain(g, plan.ksplit, st) != hipSuccess) return QALORA_EHIP;
+    if (launch_gemm_plain(g, pp.ksplit, st) != hipSuccess) return QALORA_EHIP;
     // dB = (sU)^T dy and dA = P^T dU as partials over token slices, one launch; the dA job
     // finalises dU on the fly
-    if (launch_adapter_grads(us_t, plan.t_pad, dy16, tokens, d->d_out, d->rank, plan.tsplit_b, db_part,
-                             P, du_raw, plan.ksplit, d->s, L, plan.tsplit_a, da_part, st) != hipSuccess)
+    if (launch_adapter_grads(us_t[q], plan.t_pad, dyq, d->d_out, tokens, dout, rank, pp.tsplit_b, db_part, P,
+                             du_raw, pp.ksplit, ps.ap.s[q], L, pp.tsplit_a, da_part, st) != hipSuccess)
       return QALORA_EHIP;
-    if (launch_reduce2(da_part, plan.tsplit_a, (size_t)L * d->rank, dA, db_part, plan.tsplit_b,
-                       (size_t)d->rank * d->d_out, dB, accumulate, st) != hipSuccess)
+    if (launch_reduce2(da_part, pp.tsplit_a, (size_t)L * rank, ps.dA[q], db_part, pp.tsplit_b,
+                       (size_t)rank * dout, ps.dB[q], accumulate, st) != hipSuccess)
       return QALORA_EHIP;
   }
   return QALORA_OK;
@@ -671,8 +793,8 @@ int qalora_forward_deployed(const qalora_desc* d, int tokens, const void* x, con
     const DeployLayout l = deploy_layout(*d);
     const PreparedFactors pre{reinterpret_cast<const uint32_t*>(static_cast<const char*>(deployed) + l.words),
                               reinterpret_cast<const float*>(static_cast<const char*>(deployed) + l.inv)};
-    return forward_impl(d, tokens, x, packed, nullptr, nullptr, nullptr, nullptr, y, y_dtype, nullptr, false,
-                        ws, ws_bytes, stream, &pre);
+    return forward_impl(d, tokens, x, packed, nullptr, nullptr, PartSpec{}, y, y_dtype, nullptr, false, ws,
+                        ws_bytes, stream, &pre);
   }
   const size_t need = smallt_workspace(*d, tokens);
   if (!ws || ws_bytes < need) return QALORA_EWORKSPACE;

@@ -112,7 +112,19 @@ hipError_t launch_smallt4_f16(const SmallTArgs& a, hipStream_t st);  // the 16-b
 // Rows of the hi (and of the lo) section of a bf16 hi/lo split of a [rank, *] matrix.
 __host__ __device__ inline int rank_pad32(int rank) { return ((rank + 31) / 32) * 32; }
 
-// The factor job of a front launch: folds the adapter into the zero factors for this call,
+// The adapters of up to MAX_PARTS linears that share their input x and are evaluated as one
+// wide layer (q/k/v; gate/up): part p owns columns [col0, col0 + d_out) of it.  A single layer
+// is one part covering all columns; n = 0 means no adapter.
+constexpr int MAX_PARTS = 4;
+struct AdapterParts {
+  int n;
+  const float* A[MAX_PARTS];  // [L, rank]
+  const float* B[MAX_PARTS];  // [rank, d_out of the part]
+  float s[MAX_PARTS];
+  int rank[MAX_PARTS], col0[MAX_PARTS], d_out[MAX_PARTS];
+};
+
+// The factor job of a front launch: folds the adapters into the zero factors for this call,
 // beta' = beta + (s/g) A B (App. B.3), and writes the dense kernels' factor words
 // fp16(alpha S) | fp16((beta' + 2^(N-1) alpha) S) << 16.
 //   forward : words + inv_scale[d_out] (S per column, decided inside the job); optionally
@@ -124,10 +136,8 @@ __host__ __device__ inline int rank_pad32(int rank) { return ((rank + 31) / 32) 
 struct FactorJob {
   const float* alpha;   // [L, d_out]; null: no factor job in this launch
   const float* beta;    // [L, d_out]
-  const float* A;       // [L, rank] or null
-  const float* B;       // [rank, d_out] or null
-  float s;
-  int g, rank, bits, L, d_out;
+  AdapterParts parts;   // what to fold in (n = 0: nothing)
+  int g, bits, L, d_out;
   uint32_t* words;      // forward
   float* inv_scale;     // forward
   float* cst;           // backward, two-stage form
@@ -135,34 +145,36 @@ struct FactorJob {
   const float* known_max;  // backward, one-stage form
 };
 int factor_job_blocks(int L, int d_out);
+int factor_job_cols(int L);  // columns per block of the folding job: part widths must be multiples
 hipError_t launch_factor_job(const FactorJob& f, hipStream_t st);  // the job as a launch of its own
 hipError_t launch_factor_scale(const float* alpha, const float* cst, const float* block_max, int nmax,
                                size_t n, uint32_t* words, float* inv_scale, hipStream_t st);
 
 // Forward front launch: x -> rs (row scales), x16 = fp16(x * scale), the factor job, and, when
-// given, P_keep fp32 [T, L] = pool_g(x) and u_keep fp32 [T, rank] = s pool_g(x) A, from which the
-// backward front launch below can work without x (its u_kept argument).
+// given, P_keep fp32 [T, L] = pool_g(x) and per part u_keep fp32 [T, rank] = s pool_g(x) A, from
+// which the backward front launch below can work without x (its u_kept argument).
 hipError_t launch_front_forward(const uint16_t* x, int T, int d_in, float2* rs, uint16_t* x16,
-                                const float* A, float s, int g, int rank, float* P_keep,
-                                float* u_keep, const FactorJob& fac, hipStream_t st);
-// Backward front launch: dy -> rs_dy, dy16; the factor job (first stage); and with an adapter
-//   P       fp32 [T, L]          = pool_g(x)
+                                const AdapterParts& parts, int g, float* P_keep,
+                                float* const* u_keep, const FactorJob& fac, hipStream_t st);
+// Backward front launch: dy -> rs_dy, dy16; the factor job (first stage); and per adapter part
+//   P       fp32 [T, L]          = pool_g(x)  (shared by the parts)
 //   us_t    bf16 [2*rp, t_pad]   = rows hi(sU)^T then lo(sU)^T (token-contiguous, zero padded)
 //   b_hl    bf16 [2*rp, d_out]   = hi(B) rows then lo(B) rows
 // With u_kept (the forward's u_keep) x is not read: P is not written (the caller passes the
 // forward's P_keep on to the gradient kernels) and us_t is transposed from u_kept.
 hipError_t launch_front_backward(const uint16_t* dy, int T, int d_out, float2* rs_dy,
-                                 uint16_t* dy16, const uint16_t* x, int d_in, const float* A,
-                                 const float* B, float s, int g, int rank, float* P,
-                                 uint16_t* us_t, int t_pad, uint16_t* b_hl, const float* u_kept,
+                                 uint16_t* dy16, const uint16_t* x, int d_in,
+                                 const AdapterParts& parts, int g, float* P, uint16_t* const* us_t,
+                                 int t_pad, uint16_t* const* b_hl, const float* const* u_kept,
                                  const FactorJob& fac, hipStream_t st);
 // Both adapter-gradient jobs in one launch (neither depends on the other):
 //   dB partials over token slices: db_part[z][rank][d_out] = sum_{t in slice z} sU[t,:]^T dy[t,:]
+//   (dy: rows dy_ld elements apart, so that a part's columns of a wider dy can be passed)
 //   dA partials over token slices: da_part[z][L][rank] = sum_{t in slice z} P[t,:]^T dU[t,:], with
 //   dU = s * sum_q (raw[q][:, :rp] + raw[q][:, rp:]) rebuilt from the split-K partials of the dU
 //   product
-hipError_t launch_adapter_grads(const uint16_t* us_t, int t_pad, const uint16_t* dy, int T, int d_out,
-                                int rank, int tsplit_b, float* db_part, const float* P,
+hipError_t launch_adapter_grads(const uint16_t* us_t, int t_pad, const uint16_t* dy, int dy_ld, int T,
+                                int d_out, int rank, int tsplit_b, float* db_part, const float* P,
                                 const float* raw, int ksplit, float s, int L, int tsplit_a,
                                 float* da_part, hipStream_t st);
 // out = (accumulate ? out : 0) + sum_z part[z], fixed order, for two outputs in one launch
