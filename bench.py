@@ -183,6 +183,52 @@ class MlpBlock:
         return dx1.add_(dx2)
 
 
+class MlpBlockShared(MlpBlock):
+    """The same block with gate and up evaluated as one 4096 x 22016 layer (they share x): one
+    front pass and one dense launch forward, and dx of both as one contraction over K = 22016."""
+
+    def __init__(self, api, torch, synth, odt):
+        self.api = api
+        cg, cu = synth.CONFIGS["c3_gate"], synth.CONFIGS["c3_up"]
+        g, u = synth.make_inputs(cg), synth.make_inputs(cu)
+        dev = "cuda"
+        W = torch.from_numpy(np.concatenate([g["W"], u["W"]], axis=1)).to(dev)
+        self.desc = api.make_desc(cg.d_in, cg.d_out + cu.d_out, cg.bits, cg.group)
+        self.packed, self.alpha, self.beta = api.quantize(self.desc, W)
+        del W
+        self.adapters = [(torch.from_numpy(d["A"]).to(dev), torch.from_numpy(d["B"]).to(dev), c.s)
+                         for c, d in ((cg, g), (cu, u))]
+        self.grads = [(torch.zeros_like(A), torch.zeros_like(B)) for A, B, _ in self.adapters]
+        self.gate_cfg, self.up_cfg = cg, cu
+        self.down = Layer(api, torch, synth.CONFIGS["c3_down"], odt)
+        self.down.drop_w()
+        self.x = torch.from_numpy(g["x"]).to(dev).to(torch.bfloat16)
+        self.dy = self.down.dy
+        T = cg.tokens
+        self.gu = torch.empty((T, self.desc.d_out), dtype=odt, device=dev)      # [gate | up]
+        self.dgu = torch.empty_like(self.gu)
+        self.h = torch.empty((T, cg.d_out), dtype=odt, device=dev)
+        self.dx = torch.empty((T, cg.d_in), dtype=odt, device=dev)
+        lib, arr = api.load(), api._parts(self.desc, self.adapters, self.x.device)
+        import ctypes
+        self.kept = torch.empty(lib.qalora_shared_kept_bytes(ctypes.byref(self.desc), T, 2, arr), dtype=torch.uint8, device=dev)
+        self.ws_f = torch.empty(lib.qalora_shared_workspace_bytes(ctypes.byref(self.desc), T, api.OP_FORWARD, 2, arr),
+                                dtype=torch.uint8, device=dev)
+        self.ws_b = torch.empty(lib.qalora_shared_workspace_bytes(ctypes.byref(self.desc), T, api.OP_BACKWARD, 2, arr),
+                                dtype=torch.uint8, device=dev)
+
+    def step(self):
+        api, down, n = self.api, self.down, self.gate_cfg.d_out
+        w = (self.packed, self.alpha, self.beta, self.adapters)
+        api.forward_shared(self.desc, self.x, *w, keep=True, ws=self.ws_f, y=self.gu, kept=self.kept)
+        api.swiglu_forward_strided(self.gu, n, out=self.h)
+        down.forward(self.h)
+        dh, _, _ = down.backward(self.dy, self.h)
+        api.swiglu_backward_strided(dh, self.gu, n, out=self.dgu)
+        dx, _ = api.backward_shared(self.desc, self.dgu, None, self.kept, *w, grads=self.grads, ws=self.ws_b, dx=self.dx)
+        return dx
+
+
 def timed(torch, fn, n=20, warm=2):
     for _ in range(warm):
         fn()
@@ -387,6 +433,8 @@ def main():
     ap.add_argument("--tokens", type=int, default=16, help="c5: tokens per call")
     ap.add_argument("--factors16", action="store_true",
                     help="c5: alpha, beta of the merged layers stored as fp16 pairs (the configuration itself has fp32)")
+    ap.add_argument("--shared", action="store_true",
+                    help="c3: gate and up as one wide layer (they share x): qalora_forward_shared / backward_shared")
     ap.add_argument("--no-deployed", action="store_true",
                     help="c5, up to four tokens: read the training layout instead of the deployment stream")
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
@@ -487,15 +535,17 @@ def main():
     elif args.workload == "c3":
         if odt != torch.bfloat16:
             sys.exit("bench.py: workload c3 chains layers through bf16 activations; use --out-dtype bf16")
-        blk = MlpBlock(api, torch, synth, odt)
-        gate, up, down, step = blk.gate, blk.up, blk.down, blk.step
+        blk = (MlpBlockShared if args.shared else MlpBlock)(api, torch, synth, odt)
+        down, step = blk.down, blk.step
 
         ms_per_step, kms, clk = run_steps(torch, api, step, args.steps, args.warmup)
-        fls = [layer_flops(l.cfg) for l in (gate, up, down)]
+        fls = [layer_flops(c) for c in (synth.CONFIGS["c3_gate"], synth.CONFIGS["c3_up"], synth.CONFIGS["c3_down"])]
         total_flops = sum(f["fwd"] + f["bwd"] for f in fls)
         # armed events catch the first contraction of each direction: gate forward, down backward
         kf, kb = kms[0], kms[1]
-        cands = [("fwd 4096x11008", kf, fls[0]["fwd_kernel"]), ("bwd 11008x4096", kb, fls[2]["bwd_kernel"])]
+        # (shared: the first forward contraction is the wide gate|up layer, twice the flops)
+        cands = [("fwd 4096x22016", kf, fls[0]["fwd_kernel"] + fls[1]["fwd_kernel"]) if args.shared
+                 else ("fwd 4096x11008", kf, fls[0]["fwd_kernel"]), ("bwd 11008x4096", kb, fls[2]["bwd_kernel"])]
         dom = max(cands, key=lambda c: c[1])
         achieved = dom[2] / (dom[1] * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": f"gemm_dq_kernel<4,{dom[0]}>", "achieved": round(achieved, 2),
@@ -506,13 +556,14 @@ def main():
         roofline.update(clock_fields(clk[0 if dom[0].startswith("fwd") else 1], achieved))
         workload = ("c3: LLaMA-7B SwiGLU MLP block fwd+bwd, T=4096, gate/up 4096x11008 + down 11008x4096, "
                     f"INT4 g=32, rank 64, s=0.25, bf16 activations, outputs {args.out_dtype}; SwiGLU glue fused (one kernel each way)")
-        cfg = gate.cfg
+        cfg = synth.CONFIGS["c3_gate"]
+        if args.shared:
+            workload = workload.replace("c3:", "c3 (gate and up as one wide layer sharing x):")
         if not args.no_cpu_baseline:
             import oracle
-            d = gate.host
+            d = synth.make_inputs(cfg)
             n = min(256, cfg.tokens)
-            codes = api.unpack(gate.desc, gate.packed).cpu().numpy()
-            al, be = gate.alpha.cpu().numpy(), gate.beta.cpu().numpy()
+            codes, al, be = oracle.quantize(d["W"], cfg.bits, cfg.group)
             cpu_baseline = cpu_oracle_baseline(
                 [(lambda: oracle.forward(d["x"][:n], codes, al, be, cfg.group, d["A"], d["B"], cfg.s),
                   fls[0]["fwd"] * n / cfg.tokens),

@@ -381,6 +381,12 @@ int qalora_profile_mfma_probe(int shape, int lds_reads, int valu_per_mfma, int i
 int qalora_swiglu_forward(const void* gate, const void* up, void* h, size_t n, void* stream);
 int qalora_swiglu_backward(const void* dh, const void* gate, const void* up, void* dgate,
                            void* dup, size_t n, void* stream);
+/* The same glue on gu = [gate | up], one bf16 tensor [rows, 2 cols] as a wide gate/up layer
+ * (qalora_forward_shared) produces it: h [rows, cols]; dgu = [dgate | dup] [rows, 2 cols], which
+ * is the dy of qalora_backward_shared.  cols a multiple of 8. */
+int qalora_swiglu_forward_wide(const void* gu, void* h, size_t rows, size_t cols, void* stream);
+int qalora_swiglu_backward_wide(const void* dh, const void* gu, void* dgu, size_t rows, size_t cols,
+                                void* stream);
 
 #ifdef __cplusplus
 }

@@ -33,7 +33,7 @@ EXPORTS = (
     "qalora_forward_noalloc", "qalora_profile_mfma_probe",
     "qalora_deployed_bytes", "qalora_deploy", "qalora_forward_deployed",
     "qalora_shared_kept_bytes", "qalora_shared_workspace_bytes", "qalora_forward_shared",
-    "qalora_backward_shared",
+    "qalora_backward_shared", "qalora_swiglu_forward_wide", "qalora_swiglu_backward_wide",
 )
 
 
@@ -82,6 +82,8 @@ def load() -> ctypes.CDLL:
     lib.qalora_shared_workspace_bytes.argtypes = [cp, i, i, i, vp]
     lib.qalora_forward_shared.argtypes = [cp, i, vp, vp, vp, vp, i, vp, vp, i, vp, vp, sz, vp]
     lib.qalora_backward_shared.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, i, vp, vp, i, i, vp, sz, vp]
+    lib.qalora_swiglu_forward_wide.argtypes = [vp, vp, sz, sz, vp]
+    lib.qalora_swiglu_backward_wide.argtypes = [vp, vp, vp, sz, sz, vp]
     lib.qalora_deployed_bytes.restype = sz
     lib.qalora_deployed_bytes.argtypes = [cp]
     lib.qalora_deploy.argtypes = [cp, vp, vp, vp, vp, vp]
@@ -615,6 +617,32 @@ def swiglu_backward(dh, gate, up, dgate=None, dup=None):
     _check(load().qalora_swiglu_backward(_p(dh), _p(gate), _p(up), _p(dgate), _p(dup), gate.numel(),
                                          _stream()), "qalora_swiglu_backward")
     return dgate, dup
+
+
+def swiglu_forward_strided(gu, cols, out=None):
+    """Harness glue on gu = [gate | up] ([rows, 2 cols] bf16): h = silu(gate) * up."""
+    _need(gu, "gu", torch.bfloat16)
+    rows = gu.shape[0]
+    _need(gu, "gu", shape=(rows, 2 * cols))
+    if out is None:
+        out = torch.empty((rows, cols), dtype=torch.bfloat16, device=gu.device)
+    _need(out, "out", torch.bfloat16, (rows, cols), device=gu.device)
+    _check(load().qalora_swiglu_forward_wide(_p(gu), _p(out), rows, cols, _stream()), "qalora_swiglu_forward_wide")
+    return out
+
+
+def swiglu_backward_strided(dh, gu, cols, out=None):
+    """Harness glue: dgu = [dgate | dup] of h = silu(gate) * up on gu = [gate | up]."""
+    _need(gu, "gu", torch.bfloat16)
+    rows = gu.shape[0]
+    _need(gu, "gu", shape=(rows, 2 * cols))
+    _need(dh, "dh", torch.bfloat16, (rows, cols), device=gu.device)
+    if out is None:
+        out = torch.empty_like(gu)
+    _need(out, "out", torch.bfloat16, (rows, 2 * cols), device=gu.device)
+    _check(load().qalora_swiglu_backward_wide(_p(dh), _p(gu), _p(out), rows, cols, _stream()),
+           "qalora_swiglu_backward_wide")
+    return out
 
 
 class KernelTimer:

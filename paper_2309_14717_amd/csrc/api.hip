@@ -1032,4 +1032,18 @@ int qalora_swiglu_backward(const void* dh, const void* gate, const void* up, voi
              : QALORA_EHIP;
 }
 
+int qalora_swiglu_forward_wide(const void* gu, void* h, size_t rows, size_t cols, void* stream) {
+  if (!gu || !h || rows == 0 || cols == 0 || cols % 8 != 0) return QALORA_EINVAL;
+  if (misaligned(gu) || misaligned(h)) return QALORA_EALIGN;
+  return launch_swiglu_forward_wide(gu, h, rows, cols, as_stream(stream)) == hipSuccess ? QALORA_OK : QALORA_EHIP;
+}
+
+int qalora_swiglu_backward_wide(const void* dh, const void* gu, void* dgu, size_t rows, size_t cols,
+                                void* stream) {
+  if (!dh || !gu || !dgu || rows == 0 || cols == 0 || cols % 8 != 0) return QALORA_EINVAL;
+  if (misaligned(dh) || misaligned(gu) || misaligned(dgu)) return QALORA_EALIGN;
+  return launch_swiglu_backward_wide(dh, gu, dgu, rows, cols, as_stream(stream)) == hipSuccess ? QALORA_OK
+                                                                                              : QALORA_EHIP;
+}
+
 }  // extern "C"

@@ -14,12 +14,17 @@ __device__ __forceinline__ float hi_f(uint32_t w) { return __uint_as_float(w & 0
 __device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + __expf(-v)); }
 }  // namespace
 
+// Element i of the flat index space is 16-byte piece i % c8 of row i / c8; gate, up (and their
+// gradients) have rows ld8 pieces apart, h (and dh) c8: ld8 = c8 for separate tensors, 2 c8 for
+// the two halves of one [gate | up] tensor.
 __global__ __launch_bounds__(256) void swiglu_fwd_kernel(const u32x4* __restrict__ gate,
                                                          const u32x4* __restrict__ up,
-                                                         u32x4* __restrict__ h, size_t n8) {
+                                                         u32x4* __restrict__ h, size_t n8, size_t c8,
+                                                         size_t ld8) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n8; i += stride) {
-    const u32x4 g = gate[i], u = up[i];
+    const size_t gi = (i / c8) * ld8 + i % c8;
+    const u32x4 g = gate[gi], u = up[gi];
     u32x4 o;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -35,10 +40,12 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const u32x4* __restrict
                                                          const u32x4* __restrict__ gate,
                                                          const u32x4* __restrict__ up,
                                                          u32x4* __restrict__ dgate,
-                                                         u32x4* __restrict__ dup, size_t n8) {
+                                                         u32x4* __restrict__ dup, size_t n8, size_t c8,
+                                                         size_t ld8) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n8; i += stride) {
-    const u32x4 d = dh[i], g = gate[i], u = up[i];
+    const size_t gi = (i / c8) * ld8 + i % c8;
+    const u32x4 d = dh[i], g = gate[gi], u = up[gi];
     u32x4 og, ou;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -55,8 +62,8 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const u32x4* __restrict
       og[e] = pack_bf16x2(dg[0], dg[1]);
       ou[e] = pack_bf16x2(du[0], du[1]);
     }
-    dgate[i] = og;
-    dup[i] = ou;
+    dgate[gi] = og;
+    dup[gi] = ou;
   }
 }
 
@@ -64,7 +71,7 @@ hipError_t launch_swiglu_forward(const void* gate, const void* up, void* h, size
   const size_t n8 = n / 8;
   const unsigned blocks = (unsigned)((n8 + 255) / 256 < 4096 ? (n8 + 255) / 256 : 4096);
   swiglu_fwd_kernel<<<blocks, 256, 0, st>>>(static_cast<const u32x4*>(gate), static_cast<const u32x4*>(up),
-                                            static_cast<u32x4*>(h), n8);
+                                            static_cast<u32x4*>(h), n8, n8, n8);
   return hipGetLastError();
 }
 
@@ -74,7 +81,27 @@ hipError_t launch_swiglu_backward(const void* dh, const void* gate, const void* 
   const unsigned blocks = (unsigned)((n8 + 255) / 256 < 4096 ? (n8 + 255) / 256 : 4096);
   swiglu_bwd_kernel<<<blocks, 256, 0, st>>>(static_cast<const u32x4*>(dh), static_cast<const u32x4*>(gate),
                                             static_cast<const u32x4*>(up), static_cast<u32x4*>(dgate),
-                                            static_cast<u32x4*>(dup), n8);
+                                            static_cast<u32x4*>(dup), n8, n8, n8);
+  return hipGetLastError();
+}
+
+// The same on one [rows, 2 cols] tensor gu = [gate | up] (what a wide gate/up layer produces),
+// with the gradients written to dgu = [dgate | dup].
+hipError_t launch_swiglu_forward_wide(const void* gu, void* h, size_t rows, size_t cols, hipStream_t st) {
+  const size_t c8 = cols / 8, n8 = rows * c8;
+  const unsigned blocks = (unsigned)((n8 + 255) / 256 < 4096 ? (n8 + 255) / 256 : 4096);
+  const u32x4* g = static_cast<const u32x4*>(gu);
+  swiglu_fwd_kernel<<<blocks, 256, 0, st>>>(g, g + c8, static_cast<u32x4*>(h), n8, c8, 2 * c8);
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu_backward_wide(const void* dh, const void* gu, void* dgu, size_t rows, size_t cols,
+                                       hipStream_t st) {
+  const size_t c8 = cols / 8, n8 = rows * c8;
+  const unsigned blocks = (unsigned)((n8 + 255) / 256 < 4096 ? (n8 + 255) / 256 : 4096);
+  const u32x4* g = static_cast<const u32x4*>(gu);
+  u32x4* dg = static_cast<u32x4*>(dgu);
+  swiglu_bwd_kernel<<<blocks, 256, 0, st>>>(static_cast<const u32x4*>(dh), g, g + c8, dg, dg + c8, n8, c8, 2 * c8);
   return hipGetLastError();
 }
 

@@ -220,5 +220,9 @@ hipError_t launch_mfma_probe(int shape, int lds_reads, int valu_per_mfma, float*
 hipError_t launch_swiglu_forward(const void* gate, const void* up, void* h, size_t n, hipStream_t st);
 hipError_t launch_swiglu_backward(const void* dh, const void* gate, const void* up, void* dgate,
                                   void* dup, size_t n, hipStream_t st);
+// the same on gu = [gate | up] of shape [rows, 2 cols], gradients to dgu = [dgate | dup]
+hipError_t launch_swiglu_forward_wide(const void* gu, void* h, size_t rows, size_t cols, hipStream_t st);
+hipError_t launch_swiglu_backward_wide(const void* dh, const void* gu, void* dgu, size_t rows, size_t cols,
+                                       hipStream_t st);
 
 }  // namespace qalora

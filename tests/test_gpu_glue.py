@@ -43,3 +43,17 @@ def test_swiglu_rejects_ragged_length(gpu_api):
     gate, up, _ = bf16_inputs(16, seed=1)
     with pytest.raises(Exception):
         gpu_api.swiglu_forward(gate.cuda()[:12], up.cuda()[:12])
+
+
+def test_swiglu_wide_layout_matches_separate_tensors(gpu_api):
+    """[gate | up] in one tensor (the output of a wide gate/up layer): same values as the
+    two-tensor form, bit for bit."""
+    rows, cols = 37, 264
+    gate, up, dh = bf16_inputs(rows * cols, seed=9)
+    gate, up, dh = (t.view(rows, cols).cuda() for t in (gate, up, dh))
+    gu = torch.cat([gate, up], dim=1).contiguous()
+    h = gpu_api.swiglu_forward_strided(gu, cols)
+    assert torch.equal(h, gpu_api.swiglu_forward(gate.contiguous(), up.contiguous()))
+    dgu = gpu_api.swiglu_backward_strided(dh.contiguous(), gu, cols)
+    dg, du = gpu_api.swiglu_backward(dh.contiguous(), gate.contiguous(), up.contiguous())
+    assert torch.equal(dgu[:, :cols], dg) and torch.equal(dgu[:, cols:], du)
