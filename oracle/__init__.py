@@ -76,6 +76,26 @@ def quantize(W, bits: int, group: int):
     return codes, alpha, beta
 
 
+def quantize_compensated(W, U, bits: int, group: int, block: int = 128):
+    """Error-compensated code selection (the post-training quantizer's role, Sec. 4.1 /
+    App. B.1): rows quantized in order, each row's error spread over the later rows through
+    U, the upper Cholesky factor of the inverse input Hessian (H^-1 = U^T U); lazy updates per
+    ``block`` rows.  Same outputs as ``quantize``."""
+    W, U = _f32(W), _f32(U)
+    d_in, d_out = W.shape
+    if U.shape != (d_in, d_in):
+        raise ValueError("oracle.quantize_compensated: U must be [d_in, d_in]")
+    L = d_in // group
+    codes = np.empty((d_in, d_out), np.uint8)
+    alpha = np.empty((L, d_out), np.float32)
+    beta = np.empty((L, d_out), np.float32)
+    rc = _load().qo_quantize_compensated(_ptr(W), d_in, d_out, bits, group, _ptr(U), block, _ptr(codes),
+                                         _ptr(alpha), _ptr(beta))
+    if rc != 0:
+        raise ValueError("oracle.quantize_compensated: bad arguments")
+    return codes, alpha, beta
+
+
 def dequantize(codes, alpha, beta, group: int):
     """W~ = alpha * codes + beta per group (Eq. 1), fp64."""
     codes = np.ascontiguousarray(codes, np.uint8)

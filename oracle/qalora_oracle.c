@@ -112,6 +112,92 @@ int qo_quantize(const float* W, int d_in, int d_out, int bits, int g,
   return 0;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Error-compensated code selection: the role the post-training quantizer of   */
+/* the paper's experiments plays (Sec. 4.1, quantization settings; App. B.1:   */
+/* the layer takes whatever (codes, scales, zeros) that quantizer produced).    */
+/* The published procedure, restated: the input rows of W are quantized one     */
+/* after the other, and the error each row leaves is spread over the rows not   */
+/* yet quantized, weighted by the upper Cholesky factor U of the inverse of the */
+/* layer's input Hessian H (H^-1 = U^T U), so that the OUTPUT error under the   */
+/* calibration inputs, tr((W - W~)^T H (W - W~)), is reduced.  Per column j:    */
+/*   at the first row of a group: beta, alpha from the group's CURRENT rows,    */
+/*                                by the recipe of qo_quantize                   */
+/*   c   = clamp(rint((w_i - beta) / alpha), 0, 2^N - 1)                          */
+/*   e   = (w_i - (alpha c + beta)) / U[i,i]                                      */
+/*   w_r -= U[i,r] e     for the rows r > i                                       */
+/* with the updates of rows beyond the current block of `block` rows applied    */
+/* lazily, once per block, as the published procedure does.  fp32 throughout,   */
+/* every sum in ascending row order, products fused (fmaf): this order IS the   */
+/* definition both sides implement, so codes can be compared bit for bit.       */
+/* `block` must be a multiple of g.  U = identity gives qo_quantize exactly.     */
+/* Returns 0, or -1 on bad arguments.                                           */
+/* ------------------------------------------------------------------------- */
+int qo_quantize_compensated(const float* W, int d_in, int d_out, int bits, int g, const float* U,
+                            int block, uint8_t* codes, float* alpha, float* beta) {
+  if (!W || !U || !codes || !alpha || !beta) return -1;
+  if (d_in <= 0 || d_out <= 0 || bits < 1 || bits > 8 || g <= 0 || d_in % g) return -1;
+  if (block <= 0 || block % g) return -1;
+  const int qmax = (1 << bits) - 1;
+  const float levels = (float)qmax;
+  float* work = (float*)malloc((size_t)d_in * d_out * sizeof(float));
+  float* err = (float*)malloc((size_t)block * d_out * sizeof(float));
+  if (!work || !err) {
+    free(work);
+    free(err);
+    return -1;
+  }
+  memcpy(work, W, (size_t)d_in * d_out * sizeof(float));
+  for (int i1 = 0; i1 < d_in; i1 += block) {
+    const int i2 = i1 + block < d_in ? i1 + block : d_in;
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < d_out; ++j) {  /* columns are independent */
+      for (int i = i1; i < i2; ++i) {
+        const int l = i / g;
+        if (i % g == 0) {
+          float mn = work[(size_t)i * d_out + j];
+          float mx = mn;
+          for (int q = i + 1; q < i + g; ++q) {
+            const float w = work[(size_t)q * d_out + j];
+            if (w < mn) mn = w;
+            if (w > mx) mx = w;
+          }
+          float a = (mx - mn) / levels;
+          if (!(a > 0.0f)) a = 0x1p-60f;
+          alpha[(size_t)l * d_out + j] = a;
+          beta[(size_t)l * d_out + j] = mn;
+        }
+        const float a = alpha[(size_t)l * d_out + j], b = beta[(size_t)l * d_out + j];
+        const float w = work[(size_t)i * d_out + j];
+        const float d = w - b;
+        const float q = d / a;
+        float rq = rintf(q);
+        if (!(rq >= 0.0f)) rq = 0.0f;  /* clamp before the conversion (also catches NaN) */
+        if (rq > levels) rq = levels;
+        const int c = (int)rq;
+        codes[(size_t)i * d_out + j] = (uint8_t)c;
+        const float wq = fmaf(a, (float)c, b);
+        const float e = (w - wq) / U[(size_t)i * d_in + i];
+        err[(size_t)(i - i1) * d_out + j] = e;
+        for (int r = i + 1; r < i2; ++r)
+          work[(size_t)r * d_out + j] = fmaf(-U[(size_t)i * d_in + r], e, work[(size_t)r * d_out + j]);
+      }
+    }
+#pragma omp parallel for schedule(static)
+    for (int r = i2; r < d_in; ++r) {  /* the block's errors, onto the rows behind it */
+      for (int j = 0; j < d_out; ++j) {
+        float acc = 0.0f;
+        for (int i = i1; i < i2; ++i)
+          acc = fmaf(U[(size_t)i * d_in + r], err[(size_t)(i - i1) * d_out + j], acc);
+        work[(size_t)r * d_out + j] -= acc;
+      }
+    }
+  }
+  free(work);
+  free(err);
+  return 0;
+}
+
 /* W~[i,j] = alpha[i/g, j] * code[i,j] + beta[i/g, j]      (Eq. 1)             */
 /* lrow = (i / g) * d_out is the offset of row i's group in alpha / beta.         */
 static inline double wtilde(const uint8_t* codes, const float* alpha, const float* beta,
