@@ -517,6 +517,17 @@ def main():
                 "post_merge_fwd_ms": round(timed(torch, L.forward_merged), 4),
             }
             if args.workload == "c2":
+                # error-compensated code selection of the same layer under a seeded synthetic
+                # Hessian (factorised by the framework: the library takes the factor)
+                gen = torch.Generator(device="cuda").manual_seed(77)
+                X = torch.randn((2 * cfg.d_in, cfg.d_in), generator=gen, device="cuda", dtype=torch.float64)
+                H = X.T @ X / X.shape[0]
+                H += 0.01 * torch.diag(H).mean() * torch.eye(cfg.d_in, device="cuda", dtype=torch.float64)
+                U = torch.linalg.cholesky(torch.linalg.inv(H), upper=True).float().contiguous()
+                del X, H
+                extras["quantize_compensated_ms"] = round(
+                    timed(torch, lambda: api.quantize_compensated(L.desc, L.W, U), 3, 1), 3)
+                del U
                 L.drop_w()
                 extras["adamw_step_decoder_layer"] = adamw_layer_timing(torch, api)
                 extras["small_token_post_merge_forward"] = small_token_table(torch, api, synth, odt)

@@ -82,7 +82,8 @@ enum qalora_op {
   QALORA_OP_FORWARD = 1,
   QALORA_OP_BACKWARD = 2,
   QALORA_OP_MERGE = 3,
-  QALORA_OP_FORWARD_FACTORS16 = 4
+  QALORA_OP_FORWARD_FACTORS16 = 4,
+  QALORA_OP_QUANTIZE_COMPENSATED = 5
 };
 
 /* Human-readable name of a status code (static string, host). */
@@ -113,6 +114,25 @@ size_t qalora_workspace_bytes(const qalora_desc* desc, int tokens, int op);
  * rank and s of the descriptor are ignored.  Non-finite W gives unspecified codes. */
 int qalora_quantize(const qalora_desc* desc, const float* W, void* packed, float* alpha,
                     float* beta, void* ws, size_t ws_bytes, void* stream);
+
+/* Error-compensated code selection, the role the post-training quantizer plays in the paper's
+ * experiments (Sec. 4.1, quantization settings; App. B.1): same outputs as qalora_quantize, but
+ * the codes are chosen to reduce the layer's OUTPUT error tr((W - W~)^T H (W - W~)) under a given
+ * input Hessian H instead of rounding every weight to its nearest level.
+ * in : W fp32 [d_in, d_out]; hinv_chol fp32 [d_in, d_in] row-major, the upper-triangular
+ *      Cholesky factor U of the inverse Hessian (H^-1 = U^T U; only the upper triangle is read).
+ *      Computing H from calibration inputs and factorising it is the caller's business.
+ * The input rows are quantized in order; at the first row of a group beta = min and
+ * alpha = (max - min) / (2^N - 1) are taken from the group's rows as they then stand (Eq. 1's
+ * recipe); code = clamp(rint((w - beta) / alpha)); e = (w - (alpha code + beta)) / U[i,i]; every
+ * later row r receives w_r -= U[i,r] e, rows beyond the current block of 128 in one lazy
+ * update per block (sums in ascending row order, fused multiply-adds, fp32): with this order
+ * fixed the result is reproducible bit for bit.  U = identity gives qalora_quantize's result.
+ * group must divide 128 (QALORA_EUNSUPPORTED otherwise).
+ * Workspace: qalora_workspace_bytes(.., QALORA_OP_QUANTIZE_COMPENSATED) = 5 bytes per weight. */
+int qalora_quantize_compensated(const qalora_desc* desc, const float* W, const float* hinv_chol,
+                                void* packed, float* alpha, float* beta, void* ws, size_t ws_bytes,
+                                void* stream);
 
 /* packed -> canonical codes, uint8 [d_in, d_out] row-major, one code per byte.
  * This is the definition of the packed format ("bit-exact codes" means equal here). */

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libqalora_hip.so")
 
 OK, EINVAL, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
-OP_QUANTIZE, OP_FORWARD, OP_BACKWARD, OP_MERGE, OP_FORWARD_FACTORS16 = 0, 1, 2, 3, 4
+OP_QUANTIZE, OP_FORWARD, OP_BACKWARD, OP_MERGE, OP_FORWARD_FACTORS16, OP_QUANTIZE_COMPENSATED = 0, 1, 2, 3, 4, 5
 
 EXPORTS = (
     "qalora_status_string", "qalora_check_desc", "qalora_packed_bytes", "qalora_workspace_bytes",
@@ -33,6 +33,7 @@ EXPORTS = (
     "qalora_forward_noalloc", "qalora_profile_mfma_probe",
     "qalora_deployed_bytes", "qalora_deploy", "qalora_forward_deployed",
     "qalora_shared_kept_bytes", "qalora_shared_workspace_bytes", "qalora_forward_shared",
+    "qalora_quantize_compensated",
     "qalora_backward_shared", "qalora_swiglu_forward_wide", "qalora_swiglu_backward_wide",
 )
 
@@ -71,6 +72,7 @@ def load() -> ctypes.CDLL:
     lib.qalora_workspace_bytes.restype = sz
     lib.qalora_workspace_bytes.argtypes = [cp, i, i]
     lib.qalora_quantize.argtypes = [cp, vp, vp, vp, vp, vp, sz, vp]
+    lib.qalora_quantize_compensated.argtypes = [cp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.qalora_unpack.argtypes = [cp, vp, vp, vp]
     lib.qalora_pack.argtypes = [cp, vp, vp, vp]
     lib.qalora_forward.argtypes = [cp, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
@@ -223,6 +225,24 @@ def quantize(desc: Desc, W: torch.Tensor):
     rc = load().qalora_quantize(ctypes.byref(desc), _p(W), _p(packed), _p(alpha), _p(beta), None, 0,
                                 _stream())
     _check(rc, "qalora_quantize")
+    return packed, alpha, beta
+
+
+def quantize_compensated(desc: Desc, W: torch.Tensor, hinv_chol: torch.Tensor):
+    """Error-compensated code selection under an inverse-Hessian Cholesky factor U [d_in, d_in]
+    (upper triangular, H^-1 = U^T U).  Returns (packed, alpha, beta) like quantize()."""
+    _need(W, "W", torch.float32)
+    if check_desc(desc) == OK:
+        _need(W, "W", shape=(desc.d_in, desc.d_out))
+        _need(hinv_chol, "hinv_chol", torch.float32, (desc.d_in, desc.d_in), device=W.device)
+    L = desc.d_in // max(desc.group, 1)
+    packed = torch.empty(packed_bytes(desc), dtype=torch.uint8, device=W.device)
+    alpha = torch.empty((L, desc.d_out), dtype=torch.float32, device=W.device)
+    beta = torch.empty_like(alpha)
+    ws = torch.empty(max(workspace_bytes(desc, 1, OP_QUANTIZE_COMPENSATED), 16), dtype=torch.uint8, device=W.device)
+    rc = load().qalora_quantize_compensated(ctypes.byref(desc), _p(W), _p(hinv_chol), _p(packed), _p(alpha),
+                                            _p(beta), _p(ws), ws.numel(), _stream())
+    _check(rc, "qalora_quantize_compensated")
     return packed, alpha, beta
 
 

@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqalora_hip.so")
 SOURCES = ["api.hip", "quantize.hip", "gemm_dq.hip", "adapter.hip", "smallt.hip", "smallt4.hip", "smallt4_f16.hip",
-           "glue.hip", "optim.hip", "probe.hip"]
+           "glue.hip", "optim.hip", "probe.hip", "compensate.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

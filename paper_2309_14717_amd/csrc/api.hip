@@ -238,6 +238,10 @@ size_t qalora_workspace_bytes(const qalora_desc* d, int tokens, int op) {
   switch (op) {
     case QALORA_OP_QUANTIZE:
     case QALORA_OP_MERGE: return 0;
+    case QALORA_OP_QUANTIZE_COMPENSATED: {
+      const size_t n = (size_t)d->d_in * d->d_out;
+      return align_up(n * 4) + align_up(n);
+    }
     case QALORA_OP_FORWARD: {
       if (tokens <= 0) return 0;
       size_t need = plan_forward(*d, tokens).total;
@@ -271,6 +275,27 @@ int qalora_quantize(const qalora_desc* d, const float* W, void* packed, float* a
   if (misaligned(W) || misaligned(packed) || misaligned(alpha) || misaligned(beta))
     return QALORA_EALIGN;
   launch_quantize(d->bits, W, packed, alpha, beta, d->d_in, d->d_out, d->group, as_stream(stream));
+  return hipGetLastError() == hipSuccess ? QALORA_OK : QALORA_EHIP;
+}
+
+int qalora_quantize_compensated(const qalora_desc* d, const float* W, const float* hinv_chol, void* packed,
+                                float* alpha, float* beta, void* ws, size_t ws_bytes, void* stream) {
+  const int rc = qalora_check_desc(d);
+  if (rc != QALORA_OK) return rc;
+  if (!W || !hinv_chol || !packed || !alpha || !beta) return QALORA_EINVAL;
+  if (misaligned(W) || misaligned(hinv_chol) || misaligned(packed) || misaligned(alpha) || misaligned(beta) ||
+      misaligned(ws))
+    return QALORA_EALIGN;
+  if (128 % d->group != 0) return QALORA_EUNSUPPORTED;  // groups must not straddle the lazy blocks
+  const size_t n = (size_t)d->d_in * d->d_out;
+  if (!ws || ws_bytes < align_up(n * 4) + align_up(n)) return QALORA_EWORKSPACE;
+  float* work = static_cast<float*>(ws);
+  uint8_t* codes = static_cast<uint8_t*>(ws) + align_up(n * 4);
+  if (launch_compensate(W, hinv_chol, d->d_in, d->d_out, d->bits, d->group, work, codes, alpha, beta,
+                        as_stream(stream)) != hipSuccess)
+    return QALORA_EHIP;
+  // the codes enter the packed format the way any other quantizer's would
+  launch_pack(d->bits, codes, packed, d->d_in, d->d_out, as_stream(stream));
   return hipGetLastError() == hipSuccess ? QALORA_OK : QALORA_EHIP;
 }
 

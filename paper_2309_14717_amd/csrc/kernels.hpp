@@ -17,6 +17,11 @@ hipError_t launch_unpack_factors(const void* fac16, float* alpha, float* beta, s
 void launch_pack(int bits, const uint8_t* codes, void* packed, int d_in, int d_out,
                  hipStream_t st);
 
+// --- compensate.hip: error-compensated code selection on a given inverse-Hessian factor ------
+// work: d_in * d_out fp32 scratch; codes: canonical, one code per byte.  g must divide 128.
+hipError_t launch_compensate(const float* W, const float* U, int d_in, int d_out, int bits, int g,
+                             float* work, uint8_t* codes, float* alpha, float* beta, hipStream_t st);
+
 // --- gemm_dq.hip --------------------------------------------------------------------
 struct GemmArgs {
   const uint16_t* a_main;  // fp16 [M, K_main]: x (forward) or dy (backward), each row already
