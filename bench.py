@@ -67,7 +67,7 @@ def read_traffic(name, key="traffic_bytes_per_launch"):
     try:
         for line in open(path):
             if line.startswith(key + ":"):
-                return float(line.split(":", 1)[1])
+                return float(line.split(":", 1)[1].split()[0])
     except OSError:
         pass
     return None
@@ -563,7 +563,9 @@ def main():
                     "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_TFLOPS, 4),
                     "avg_kernel_ms": round(dom[1], 4), "gate_fwd_kernel_ms": round(kf, 4),
                     "down_bwd_kernel_ms": round(kb, 4),
-                    **traffic_fields("gemm_dq_c3_pmc.txt", "traffic_bytes_per_launch_" + dom[0][:3])}
+                    **(traffic_fields("gemm_dq_c3_shared_pmc.txt", "traffic_bytes_per_launch_fwd_wide")
+                       if dom[0] == "fwd 4096x22016" else
+                       traffic_fields("gemm_dq_c3_pmc.txt", "traffic_bytes_per_launch_" + dom[0][:3]))}
         roofline.update(clock_fields(clk[0 if dom[0].startswith("fwd") else 1], achieved))
         workload = ("c3: LLaMA-7B SwiGLU MLP block fwd+bwd, T=4096, gate/up 4096x11008 + down 11008x4096, "
                     f"INT4 g=32, rank 64, s=0.25, bf16 activations, outputs {args.out_dtype}; SwiGLU glue fused (one kernel each way)")
