@@ -268,6 +268,9 @@ def settle(torch, step, chunk=10, tol=0.015, max_chunks=40):
     return n
 
 
+BLOCK_TIMELINE = {}
+
+
 def run_steps(torch, api, step, steps, warmup, directions=(0, 1), arm_every=None):
     """Warm up, then time exactly `steps` steps; per-direction kernel times from events armed
     around the dense kernel on every `arm_every`-th step of the timed region (an armed launch
@@ -297,6 +300,16 @@ def run_steps(torch, api, step, steps, warmup, directions=(0, 1), arm_every=None
                            "samples": int(ms.size), "block_cycles": t.block_cycles()}
     clk = {d: t.shader_clock_ghz() for d, t in timers.items()}
     for t in timers.values():
+        t.close()
+    # outside the timed region: one more step whose armed kernels lay their blocks out on a time line
+    extra = {d: api.KernelTimer(d, 1) for d in directions}
+    for t in extra.values():
+        t.arm()
+        t.arm_blocks()
+    step()
+    torch.cuda.synchronize()
+    for d, t in extra.items():
+        BLOCK_TIMELINE[d] = t.block_timeline()
         t.close()
     return (t1 - t0) * 1e3 / steps, kms, clk
 
@@ -376,12 +389,14 @@ def probe_report(torch, api):
     library's plain product (torch.matmul) at two sizes."""
     rows = []
     for blocks in (16, 256):
-        for shape, lds, nv in ((0, 0, 0), (0, 1, 0), (0, 1, 2), (0, 1, 4), (0, 1, 6), (0, 1, 8),
+        for shape, lds, nv in ((0, 0, 0), (0, 1, 0), (0, 1, 1), (0, 1, 2), (0, 1, 3), (0, 1, 4), (0, 1, 6), (0, 1, 8),
+                               (0, 1, 102), (0, 1, 104),   # 2 / 4 per MFMA, issued as one burst per K-16 slice
                                (1, 0, 0), (1, 1, 0), (1, 1, 2), (1, 1, 4), (1, 1, 6), (1, 1, 8),
                                (2, 0, 0), (2, 1, 0), (2, 1, 2), (2, 1, 4)):
             cyc, ghz, tf = api.mfma_probe(shape, bool(lds), nv, iters=2000, blocks=blocks)
             rows.append({"blocks": blocks, "wavefronts_x_tiles": ("8 x (4x2)", "4 x (4x4)", "8 x (4x2) AGPR acc")[shape],
-                         "lds_fragment_reads": bool(lds), "valu_per_mfma": nv,
+                         "lds_fragment_reads": bool(lds), "valu_per_mfma": nv % 100,
+                         "valu_issued": "burst per slice" if nv >= 100 else "behind each MFMA",
                          "cycles_per_mfma_per_simd": round(cyc, 2), "shader_clock_ghz": round(ghz, 3),
                          "TFLOP/s": round(tf, 1), "frac_of_peak": round(tf / PEAK_MFMA_TFLOPS, 4)})
     vendor = []
@@ -502,6 +517,8 @@ def main():
             roofline.update({"kernel_ms_median": st["median_ms"], "kernel_ms_min": st["min_ms"],
                              "kernel_samples": st["samples"],
                              "first_block_shader_cycles": st["block_cycles"]})
+        if BLOCK_TIMELINE.get(0 if dom[0] == "fwd" else 1):
+            roofline["block_timeline"] = BLOCK_TIMELINE[0 if dom[0] == "fwd" else 1]
         workload = (f"{cfg.name}: QA-LoRA linear fwd+bwd, T={cfg.tokens}, {cfg.d_in}x{cfg.d_out}, "
                     f"INT{cfg.bits} g={cfg.group}, rank {cfg.rank}, s={cfg.s}, x/dy bf16, outputs {args.out_dtype}")
         if not args.no_extras:

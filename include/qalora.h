@@ -364,6 +364,14 @@ int qalora_profile_arm(int direction, void* start_event, void* stop_event);
  * over that block's life -- under load well below the nominal 2.4 GHz that the published
  * matrix-core peak assumes.  The small-token kernel does not report.  NULL disarms. */
 int qalora_profile_arm_clock(int direction, void* counts);
+
+/* Measurement aid: the time line of a launch.  Call after qalora_profile_arm for the same
+ * direction: every block b < capacity of the armed dense contraction kernel then stores four
+ * 64-bit values to times[4b .. 4b+3] (device, 32 * capacity bytes, 16-byte aligned): wall-clock
+ * ticks when it started, when it left the K loop and when it ended, and the id (0..7) of the
+ * XCD it ran on.  Blocks >= capacity store nothing; slices of a split-K launch other than the
+ * first store nothing.  NULL disarms; capacity <= 0 with a buffer is QALORA_EINVAL. */
+int qalora_profile_arm_blocks(int direction, void* times, int capacity);
 int qalora_profile_wall_clock_khz(int* khz /* host */);
 
 /* Create / time / destroy timing events for qalora_profile_arm (thin wrappers over
@@ -383,8 +391,10 @@ int qalora_profile_copy(void* dst, const void* src, size_t bytes, void* stream);
  * v_mfma_f32_32x32x16_f16 on register accumulators, with (lds_reads = 1) or without the operand
  * fragment reads from LDS, and valu_per_mfma ordinary vector instructions behind every matrix
  * instruction.  shape 0: eight wavefronts of 4 x 2 tiles per block (valu_per_mfma in
- * {0,2,4,6,8}; 0 only without LDS reads); shape 1: four wavefronts of 4 x 4 tiles (same
- * choices); shape 2: shape 0 with the accumulators held in AGPRs (valu in {0,2,4}).  Other combinations return QALORA_EINVAL.  Block b stores its shader cycles and
+ * {0,1,2,3,4,6,8}, and 102 / 104: two / four per matrix instruction issued as one burst behind
+ * the eight matrix instructions of a K-16 slice; 0 only without LDS reads); shape 1: four
+ * wavefronts of 4 x 4 tiles (valu in {0,2,4,6,8}); shape 2: shape 0 with the accumulators held
+ * in AGPRs (valu in {0,2,4}).  Other combinations return QALORA_EINVAL.  Block b stores its shader cycles and
  * wall-clock ticks over the loop to counts[2b], counts[2b+1] (device, 16 * blocks bytes); sink
  * is device scratch of 2048 * blocks bytes.  A block issues iters * 32 (shape 0: per wavefront,
  * two wavefronts per SIMD; shape 1: iters * 64, one wavefront per SIMD) matrix instructions per

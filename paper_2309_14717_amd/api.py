@@ -25,7 +25,7 @@ EXPORTS = (
     "qalora_merge", "qalora_profile_arm", "qalora_profile_event_create",
     "qalora_profile_event_elapsed_ms", "qalora_profile_event_destroy", "qalora_profile_copy",
     "qalora_swiglu_forward", "qalora_swiglu_backward",
-    "qalora_profile_arm_clock", "qalora_profile_wall_clock_khz",
+    "qalora_profile_arm_clock", "qalora_profile_arm_blocks", "qalora_profile_wall_clock_khz",
     "qalora_beta_from_zero_point", "qalora_zero_point_from_beta",
     "qalora_pack_factors16", "qalora_forward_factors16",
     "qalora_adamw_workspace_bytes", "qalora_adamw_step",
@@ -103,6 +103,7 @@ def load() -> ctypes.CDLL:
     lib.qalora_profile_copy.argtypes = [vp, vp, sz, vp]
     lib.qalora_swiglu_forward.argtypes = [vp, vp, vp, sz, vp]
     lib.qalora_profile_arm_clock.argtypes = [ctypes.c_int, vp]
+    lib.qalora_profile_arm_blocks.argtypes = [ctypes.c_int, vp, ctypes.c_int]
     lib.qalora_profile_wall_clock_khz.argtypes = [ctypes.POINTER(ctypes.c_int)]
     lib.qalora_swiglu_backward.argtypes = [vp, vp, vp, vp, vp, sz, vp]
     lib.qalora_pack_factors16.argtypes = [cp, vp, vp, vp, vp]
@@ -687,6 +688,28 @@ class KernelTimer:
         _check(load().qalora_profile_arm_clock(self.direction, _p(self.counts[self.used])),
                "profile_arm_clock")
         self.used += 1
+
+    def arm_blocks(self, capacity=4096):
+        """Call right after arm(): the armed kernel's blocks also report their time line."""
+        self.block_times = torch.zeros((capacity, 4), dtype=torch.int64, device="cuda")
+        _check(load().qalora_profile_arm_blocks(self.direction, _p(self.block_times), capacity),
+               "profile_arm_blocks")
+
+    def block_timeline(self):
+        """Summary of the last arm_blocks() launch, in microseconds from the first block's start."""
+        khz = ctypes.c_int()
+        _check(load().qalora_profile_wall_clock_khz(ctypes.byref(khz)), "wall_clock_khz")
+        c = self.block_times.cpu().numpy()
+        c = c[c[:, 0] > 0]
+        if len(c) == 0:
+            return None
+        import numpy as np
+        us = lambda v: (v - c[:, 0].min()) / khz.value * 1e3
+        st, kend, en, xcd = us(c[:, 0]), us(c[:, 1]), us(c[:, 2]), c[:, 3]
+        q = lambda v: [round(float(x), 1) for x in (v.min(), np.median(v), v.max())]
+        return {"blocks": int(len(c)), "start_us_min_med_max": q(st), "k_loop_end_us_min_med_max": q(kend),
+                "end_us_min_med_max": q(en), "epilogue_us_median": round(float(np.median(en - kend)), 1),
+                "end_us_median_by_xcd": {int(x): round(float(np.median(en[xcd == x])), 1) for x in sorted(set(xcd.tolist()))}}
 
     def shader_clock_ghz(self):
         """Average shader clock over the life of the armed kernels' first blocks (None when the

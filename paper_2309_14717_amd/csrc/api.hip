@@ -979,7 +979,15 @@ int qalora_adamw_step(const qalora_adamw* hp, int step, int n_tensors, float* co
 int qalora_profile_arm(int direction, void* start_event, void* stop_event) {
   if (direction != 0 && direction != 1) return QALORA_EINVAL;
   g_profile_hook[direction] = ProfileHook{static_cast<hipEvent_t>(start_event),
-                                          static_cast<hipEvent_t>(stop_event), nullptr};
+                                          static_cast<hipEvent_t>(stop_event), nullptr, nullptr, 0};
+  return QALORA_OK;
+}
+
+int qalora_profile_arm_blocks(int direction, void* times, int capacity) {
+  if (direction != 0 && direction != 1) return QALORA_EINVAL;
+  if (times && (misaligned(times) || capacity <= 0)) return times && capacity <= 0 ? QALORA_EINVAL : QALORA_EALIGN;
+  g_profile_hook[direction].block_times = static_cast<unsigned long long*>(times);
+  g_profile_hook[direction].block_times_cap = times ? capacity : 0;
   return QALORA_OK;
 }
 

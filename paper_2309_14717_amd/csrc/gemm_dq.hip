@@ -187,6 +187,14 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     p.clock_probe[0] = (unsigned long long)clock64();
     p.clock_probe[1] = (unsigned long long)wall_clock64();
   }
+  // measurement aid: every block reports when it started, left the K loop and ended, and on
+  // which XCD (register XCC_ID, bits 3:0), so that the launch can be laid out on a time line
+  const bool timeline = HAS_MAIN && p.block_times != nullptr && blockIdx.y == 0 && tid == 0 &&
+                        (int)blockIdx.x < p.block_times_cap;
+  if (timeline) {
+    p.block_times[4 * blockIdx.x + 0] = (unsigned long long)wall_clock64();
+    p.block_times[4 * blockIdx.x + 3] = (unsigned long long)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));
+  }
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -710,6 +718,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
   // memory sees 16-byte stores covering whole 512- or 1024-byte rows of the tile.  The row
   // scales are fetched once into LDS first.  (Thread coordinates are re-derived here so that
   // nothing but the accumulators has to stay live across the K loop.)
+  if (timeline) p.block_times[4 * blockIdx.x + 1] = (unsigned long long)wall_clock64();
   int e_tid = threadIdx.x;
   asm volatile("" : "+v"(e_tid));
   const int e_lane = e_tid & 63, e_wave = e_tid >> 6;
@@ -790,6 +799,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     p.clock_probe[2] = (unsigned long long)clock64();
     p.clock_probe[3] = (unsigned long long)wall_clock64();
   }
+  if (timeline) p.block_times[4 * blockIdx.x + 2] = (unsigned long long)wall_clock64();
 }
 
 template <int NBITS, bool BWD, int BM, int BN, int WAVES_M, int WAVES_N, bool HAS_MAIN, bool FAST>
@@ -889,8 +899,10 @@ hipError_t launch_gemm_dq(int bits, bool bwd, const GemmArgs& args, hipStream_t 
     a.out_bf16 = 0;
   }
   ProfileHook hook = g_profile_hook[bwd ? 1 : 0];
-  g_profile_hook[bwd ? 1 : 0] = ProfileHook{nullptr, nullptr, nullptr};
+  g_profile_hook[bwd ? 1 : 0] = ProfileHook{nullptr, nullptr, nullptr, nullptr, 0};
   a.clock_probe = hook.clock_probe;
+  a.block_times = hook.block_times;
+  a.block_times_cap = hook.block_times_cap;
   // without a split the events ride on the dispatch itself; with one they bracket both launches
   const bool ride = !split && hook.start && hook.stop;
   if (hook.start && !ride) (void)hipEventRecord(hook.start, st);

@@ -46,6 +46,9 @@ struct GemmArgs {
   int d_in, d_out, group;
   unsigned long long* clock_probe;  // measurement aid (may be null): block 0 stores its shader
                                     // cycle and wall-clock tick counts at start and end, [4]
+  unsigned long long* block_times;  // measurement aid (may be null): block b < block_times_cap
+  int block_times_cap;              // stores wall-clock ticks at start, K loop end and end, and
+                                    // the id of the XCD it ran on, [4 b .. 4 b + 3]
 };
 hipError_t launch_gemm_dq(int bits, bool bwd, const GemmArgs& a, hipStream_t st);
 // K slices the dequantising product should use for an [M x K_main] x [K_main x N] problem.
@@ -54,6 +57,8 @@ int gemm_dq_ksplit(int M, int N, int K_main);
 struct ProfileHook {
   hipEvent_t start, stop;
   unsigned long long* clock_probe;  // device, 4 x u64, or null
+  unsigned long long* block_times;  // device, 4 x u64 per block, or null
+  int block_times_cap;
 };
 extern ProfileHook g_profile_hook[2];
 hipError_t launch_gemm_plain(const GemmArgs& a, int ksplit, hipStream_t st);

@@ -22,7 +22,8 @@ typedef uint32_t pu32x4 __attribute__((ext_vector_type(4)));
 //   (8, 4, 2): the contraction kernel's shape, two wavefronts per SIMD, 6 fragment reads per 8 MFMAs
 //   (4, 4, 4): one wavefront per SIMD, 8 fragment reads per 16 MFMAs
 // LDS : fetch the fragments of the next K-16 slice from LDS under the current slice's MFMAs
-// NV  : vector instructions (v_and_or_b32 on private registers) issued behind every MFMA
+// NV  : vector instructions (v_and_or_b32 on private registers) issued behind every MFMA;
+//       100 + n: n per MFMA, issued as one burst behind the MFMAs of a K-16 slice
 // ACC : keep the accumulators in the accumulation registers (AGPRs).  With eight wavefronts per
 //       block the compiler otherwise keeps them in ordinary vector registers.
 template <int WAVES, int TM, int TN, bool LDS, int NV, bool ACC = false>
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_probe_kernel(float* sink, uns
           acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, af[a]),
                                                              __builtin_bit_cast(f16x8, bf[b]), acc[a][b], 0, 0, 0);
 #pragma unroll
-          for (int v = 0; v < NV; ++v)
+          for (int v = 0; v < NV % 100; ++v)
             asm volatile("v_and_or_b32 %0, %1, %2, %3"
                          : "=v"(jj[v & 7])
                          : "v"(jj[(v + 1) & 7]), "s"(0x0f0f0f0f), "v"(jj[(v + 3) & 7]));
@@ -94,11 +95,17 @@ __global__ __launch_bounds__(WAVES * 64) void mfma_probe_kernel(float* sink, uns
         for (int a = 0; a < TM; ++a) af[a] = na[a];
 #pragma unroll
         for (int b = 0; b < TN; ++b) bf[b] = nb[b];
+        if constexpr (NV >= 100) {  // all matrix instructions of the slice, then all vector work
+          __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, (NV % 100) * TM * TN, 0);
+        } else {
 #pragma unroll
-        for (int i = 0; i < TM * TN; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
-          if constexpr (NV > 0) __builtin_amdgcn_sched_group_barrier(0x002, NV, 0);
+          for (int i = 0; i < TM * TN; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+            if constexpr (NV > 0) __builtin_amdgcn_sched_group_barrier(0x002, NV, 0);
+          }
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -142,7 +149,11 @@ hipError_t launch_mfma_probe(int shape, int lds_reads, int valu_per_mfma, float*
                                               : hipErrorInvalidValue;
     switch (valu_per_mfma) {
       case 0: return run<8, 4, 2, true, 0>(sink, counts, iters, blocks, st);
+      case 1: return run<8, 4, 2, true, 1>(sink, counts, iters, blocks, st);
       case 2: return run<8, 4, 2, true, 2>(sink, counts, iters, blocks, st);
+      case 3: return run<8, 4, 2, true, 3>(sink, counts, iters, blocks, st);
+      case 102: return run<8, 4, 2, true, 102>(sink, counts, iters, blocks, st);
+      case 104: return run<8, 4, 2, true, 104>(sink, counts, iters, blocks, st);
       case 4: return run<8, 4, 2, true, 4>(sink, counts, iters, blocks, st);
       case 6: return run<8, 4, 2, true, 6>(sink, counts, iters, blocks, st);
       case 8: return run<8, 4, 2, true, 8>(sink, counts, iters, blocks, st);
