@@ -149,8 +149,17 @@ int qalora_pack(const qalora_desc* desc, const uint8_t* codes, void* packed, voi
  * out: y [tokens, d_out], fp32 or bf16 per y_dtype (bf16 = round-to-nearest-even of the
  *      fp32 result).
  * Precision: x is used exactly (each token row is scaled by a power of two and converted to
- * fp16), W~ is rounded to fp16 (11 significant bits) before the matrix cores, accumulation
- * is fp32; the adapter branch is evaluated to about 2^-16 relative.  Without an adapter, for
+ * fp16); accumulation is fp32.  The adapter is folded into the zero factors for the call,
+ * beta' = beta + (s/g) A B (App. B.3, fp32), and the weight is rebuilt around the mid code
+ * mid = 2^(N-1) from two fp16 factors per (group, column), scaled by a power of two so that
+ * the conversion keeps 11 significant bits at any magnitude:
+ *     W~' = fp16(alpha) (code - mid) + fp16(beta' + mid alpha),
+ * so per element |error| <= 2^-11 (|beta' + mid alpha| + |alpha (code - mid)|).  For min-max
+ * triples (qalora_quantize, qalora_quantize_compensated) that is 2^-11 of the group's largest
+ * |W~|; for imported triples whose used codes sit far from the mid code (say codes all 0,
+ * alpha = 1, beta = v) the bound is what it says: 2^-11 |v + mid|, not 2^-11 |v|.  The
+ * adapter's contribution passes through the same constant: with alpha = beta = 0 it is
+ * evaluated to 2^-11 relative.  Without an adapter, for
  * tokens <= 16 (<= 32 for 4-bit codes), group 32/64/128 and d_in a multiple of 128, a
  * streaming kernel takes over (one column per lane for tokens <= 4 and for the 2- and 3-bit
  * codes, a sixteen-token tile -- two of them beyond sixteen tokens -- for 4-bit codes) whose
