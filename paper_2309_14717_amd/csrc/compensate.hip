@@ -75,6 +75,9 @@ __global__ __launch_bounds__(kThreads) void compensate_kernel(const float* __res
           alpha[o] = a;
           beta[o] = b;
         }
+        // every row lane has read the group's rows before any lane updates them below (the
+        // condition is uniform over the block)
+        __syncthreads();
       }
       const float w = tile[i * kCols + c];
       float rq = rintf(__fdiv_rn(__fsub_rn(w, b), a));
