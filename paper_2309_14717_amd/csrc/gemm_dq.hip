@@ -148,8 +148,11 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
   constexpr int A_STAGES = 3;  // LDS-DMA prefetch runs two K steps ahead
 
   extern __shared__ __align__(1024) uint16_t smem[];
-  uint16_t* As = smem;                      // [A_STAGES][BM][64] swizzled
-  uint16_t* Bs = smem + A_STAGES * A_TILE;  // [2][BN][64] swizzled
+  // The B stages sit at the bottom: their offsets then fit the 16-bit immediate of the LDS
+  // instructions for either parity, so the producer's writes and the operand reads of B need no
+  // address arithmetic in the loop (the A stage rotates through three, so its base is a register).
+  uint16_t* Bs = smem;               // [2][BN][64] swizzled
+  uint16_t* As = smem + 2 * B_TILE;  // [A_STAGES][BM][64] swizzled
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -620,33 +623,36 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     //      flight -- then barrier
     //   4. start the LDS-DMA of A(it+3) into the stage of A(it), which nobody reads any more
     //   5. slice 3, fetching the first fragments of step it+1
-    // Steps past the end issue the same number of loads, aimed outside the buffers.
     const int pb = it_begin, pe = it_end;
     // (The 3-bit backward producer of the 256-row tile holds two code planes and has no
     // registers left for a second set: it keeps ONE set and reloads it in slice 2, as soon as
     // the dequantisation has read it -- half a step of lead instead of a whole one.)
     constexpr bool kSingleSet = (NBITS == 3 && BWD && BM == 256);
-    auto step = [&](int it, int slot, auto par) {
+    // Steps past the end of the K range still issue their loads (the waits count them).  On the
+    // fast path they re-read the last step, which is valid memory and never used; elsewhere they
+    // are aimed outside the buffers.
+    auto at = [&](int i) { return FAST ? min(i, pe - 1) : i; };
+    auto live = [&](int i) { return FAST ? true : i < pe; };
+    // a_cur / a_next / a_dma2: the A stages holding steps it, it+1 and it+2 (the caller rotates them)
+    auto step = [&](int it, uint16_t* a_cur, uint16_t* a_next, uint16_t* a_dma2, auto par) {
       constexpr int kPar = decltype(par)::value;
       using SetCur = std::integral_constant<int, kSingleSet ? 0 : kPar>;
       using SetNext = std::integral_constant<int, kSingleSet ? 0 : (kPar ^ 1)>;
-      const int sa = slot % 3, sa1 = (slot + 1) % 3;
-      uint16_t* a_cur = As + sa * A_TILE;
       with_step_regions(
-          As + ((slot + 2) % 3) * A_TILE, a_cur, As + sa1 * A_TILE, Bs + kPar * B_TILE,
+          a_dma2, a_cur, a_next, Bs + kPar * B_TILE,
           Bs + (kPar ^ 1) * B_TILE,
           [&](uint16_t*, const uint16_t* a_rd, const uint16_t* a_nx, const uint16_t* b_rd,
               uint16_t* b_wr) {
-            if constexpr (!kSingleSet) gload_b(MainK{}, it + 2, SetCur{}, it + 2 < pe);
+            if constexpr (!kSingleSet) gload_b(MainK{}, at(it + 2), SetCur{}, live(it + 2));
             __builtin_amdgcn_sched_barrier(0);
             compute_main(
                 a_rd, b_rd, a_nx, b_wr,
                 [&](auto kk) {
                   store_b(MainK{}, it + 1, b_wr, SetNext{}, kk);
                   if constexpr (kSingleSet && decltype(kk)::value == 2)
-                    gload_b(MainK{}, it + 2, SetCur{}, it + 2 < pe);
+                    gload_b(MainK{}, at(it + 2), SetCur{}, live(it + 2));
                 },
-                [&]() { issue_a(MainK{}, it + 3, a_cur, it + 3 < pe); });
+                [&]() { issue_a(MainK{}, at(it + 3), a_cur, live(it + 3)); });
           });
     };
     if (pe > pb) {
@@ -654,23 +660,28 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
       // loading; B(pb) dequantised into stage 0
       issue_a(MainK{}, pb, As, true);
       gload_b(MainK{}, pb, Set0{}, true);
-      issue_a(MainK{}, pb + 1, As + A_TILE, pb + 1 < pe);
-      if constexpr (!kSingleSet) gload_b(MainK{}, pb + 1, Set1{}, pb + 1 < pe);
-      issue_a(MainK{}, pb + 2, As + 2 * A_TILE, pb + 2 < pe);
+      issue_a(MainK{}, at(pb + 1), As + A_TILE, live(pb + 1));
+      if constexpr (!kSingleSet) gload_b(MainK{}, at(pb + 1), Set1{}, live(pb + 1));
+      issue_a(MainK{}, at(pb + 2), As + 2 * A_TILE, live(pb + 2));
       __builtin_amdgcn_sched_barrier(0);
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * A_LOADS + (kSingleSet ? 0 : kBLoadsMain))
                    : "memory");
       store_b(MainK{}, pb, Bs, Set0{}, AllPieces{});
-      if constexpr (kSingleSet) gload_b(MainK{}, pb + 1, Set0{}, pb + 1 < pe);
+      if constexpr (kSingleSet) gload_b(MainK{}, at(pb + 1), Set0{}, live(pb + 1));
       asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
       load_frags_main(As, Bs, 0, Set0{});
-      int it = pb, slot = 0;
+      int it = pb;
+      uint16_t *a0 = As, *a1 = As + A_TILE, *a2 = As + 2 * A_TILE;  // stages of it, it+1, it+2
 #pragma nounroll
-      for (; it + 1 < pe; it += 2, slot += 2) {  // hot loop: two steps, one per parity
-        step(it, slot, Set0{});
-        step(it + 1, slot + 1, Set1{});
+      for (; it + 1 < pe; it += 2) {  // hot loop: two steps, one per parity
+        step(it, a0, a1, a2, Set0{});
+        step(it + 1, a1, a2, a0, Set1{});
+        uint16_t* t = a0;  // two steps on: the stage of it+2 is the current one
+        a0 = a2;
+        a2 = a1;
+        a1 = t;
       }
-      if (it < pe) step(it, slot, Set0{});
+      if (it < pe) step(it, a0, a1, a2, Set0{});
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the out-of-range loads of the last steps
     }
   } else {
