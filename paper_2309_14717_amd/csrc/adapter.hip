@@ -249,13 +249,78 @@ __device__ __forceinline__ void factor_block(const FrontArgs& a, int bid, float*
   float* tile = lds;                // [L][FC]
   float* Bs = tile + (size_t)L * FC;  // [FC][bs]
   float* red = Bs + FC * bs;        // [256]
+  float m = 0.0f;
+  // what a thread does with one element of A B once it has it: the constant of the factor word
+  // into the LDS tile, its bound into the thread's running maximum
+  auto finish = [&](int l, float ab, float al, float be) {
+    float cst = 0.0f, bound = 0.0f;
+    if (col_ok) {
+      const float bp = __builtin_fmaf(sg, ab, be);
+      cst = __builtin_fmaf(a.f_mid, al, bp);
+      bound = fabsf(cst) + a.f_mid * fabsf(al);
+    }
+    tile[(size_t)l * FC + c] = cst;
+    m = fmaxf(m, bound);
+  };
+  if (FC == 16) {
+    // 16 columns: A B on the matrix cores in fp32 (v_mfma_f32_16x16x4_f32), a 16-group tile per
+    // wavefront at a time.  Lane (n, kb) = (lane % 16, lane / 16) supplies row n of the A tile and
+    // column n of B for the k values kb kq .. kb kq + kq - 1 (kq = a quarter of the rank, rounded
+    // up: the instruction's four k slots are four contiguous runs of k, so a lane's operands are
+    // contiguous in memory), and receives rows 4 kb .. 4 kb + 3 of column n -- the thread's
+    // column c, as in the plain form.
+    const int lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, kb = lane >> 4;
+    const int kq = (rank + 3) >> 2;  // <= 32
+    const bool vec4 = (rank & 3) == 0 && (kq & 3) == 0;
+    const int kbase = kb * kq;
+    const uint32_t bcol = (uint32_t)kbase * (uint32_t)pdout + (uint32_t)(pj0 + n);  // element index in B
+    const bool bcol_ok = pj0 + n < pdout;
+    // operands in chunks of eight k values (whole fragments in registers would cost the row jobs
+    // of the same launch their occupancy; the other wavefronts of the unit cover the latency)
+    constexpr int KC = 8;
+    for (int l0 = 16 * wave; l0 < L; l0 += 64) {
+      const uint32_t arow = (uint32_t)min(l0 + n, L - 1) * (uint32_t)rank + (uint32_t)kbase;  // rows past the end repeat the last one, unused
+      // alpha and beta of the four elements this lane will receive: requested now, used after
+      // the product
+      float al4[4], be4[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const size_t o = (size_t)min(l0 + 4 * kb + r, L - 1) * dout + (col_ok ? j : 0);
+        al4[r] = a.f_alpha[o];
+        be4[r] = a.f_beta[o];
+      }
+      f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+      for (int i0 = 0; i0 < kq; i0 += KC) {
+        float av[KC], bv[KC];
+        if (vec4 && i0 + KC <= kq) {
+          const f32x4 v0 = *reinterpret_cast<const f32x4*>(pA + arow + i0);
+          const f32x4 v1 = *reinterpret_cast<const f32x4*>(pA + arow + i0 + 4);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) av[q] = v0[q], av[4 + q] = v1[q];
+        } else {
+#pragma unroll
+          for (int q = 0; q < KC; ++q) av[q] = (i0 + q < kq && kbase + i0 + q < rank) ? pA[arow + i0 + q] : 0.0f;
+        }
+#pragma unroll
+        for (int q = 0; q < KC; ++q)
+          bv[q] = (bcol_ok && i0 + q < kq && kbase + i0 + q < rank) ? pt.B[bcol + (uint32_t)(i0 + q) * (uint32_t)pdout] : 0.0f;
+#pragma unroll
+        for (int q = 0; q < KC; ++q) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q], bv[q], acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int l = l0 + 4 * kb + r;
+        if (l < L) finish(l, acc[r], al4[r], be4[r]);
+      }
+    }
+  } else {
   for (int idx = tid; idx < FC * rank; idx += 256) {
     const int cc = idx & (FC - 1), k = idx / FC;
     Bs[cc * bs + k] = (pj0 + cc < pdout) ? pt.B[(size_t)k * pdout + pj0 + cc] : 0.0f;
   }
   __syncthreads();
   constexpr int GB = 4;  // groups per thread in flight
-  float m = 0.0f;
   const bool vec = (rank & 3) == 0;
   for (int lb = lg; lb < L; lb += NLG * GB) {
     float acc[GB];
@@ -287,17 +352,11 @@ __device__ __forceinline__ void factor_block(const FrontArgs& a, int bid, float*
     for (int i = 0; i < GB; ++i) {
       const int l = lb + i * NLG;
       if (l < L) {
-        float cst = 0.0f, bound = 0.0f;
-        if (col_ok) {
-          const float al = a.f_alpha[(size_t)l * dout + j];
-          const float bp = __builtin_fmaf(sg, acc[i], a.f_beta[(size_t)l * dout + j]);
-          cst = __builtin_fmaf(a.f_mid, al, bp);
-          bound = fabsf(cst) + a.f_mid * fabsf(al);
-        }
-        tile[(size_t)l * FC + c] = cst;
-        m = fmaxf(m, bound);
+        const size_t o = (size_t)l * dout + (col_ok ? j : 0);
+        finish(l, acc[i], a.f_alpha[o], a.f_beta[o]);
       }
     }
+  }
   }
   red[tid] = m;
   __syncthreads();
@@ -411,7 +470,12 @@ __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
   // the factor job's blocks come first: they are the longest-running ones, and started last
   // they would finish after everything else instead of under it
   if (bid < a.nb_fac) {
-    factor_block(a, bid, P_all, tid);
+    // Block ids are dealt round-robin to the 8 XCDs, each with its own L2.  The folding form
+    // works on 64-byte pieces of the 128-byte lines of alpha, beta and the words, so column
+    // blocks that share a line go to the same XCD: XCD x takes a contiguous run of them.
+    const int q = a.nb_fac >> 3, rem = a.nb_fac & 7, x = bid & 7;
+    const int fid = a.f_fold ? x * q + min(x, rem) + (bid >> 3) : bid;
+    factor_block(a, fid, P_all, tid);
     return;
   }
   bid -= a.nb_fac;
@@ -1083,6 +1147,12 @@ __global__ __launch_bounds__(256) void merge_kernel(const float* beta,  // may a
   const int l0 = blockIdx.y * GL;
   const int j = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (j >= d_out) return;  // d_out is a multiple of 8
+  // beta of this thread's elements is requested first and used last: its trip to HBM runs
+  // under the whole product
+  f32x4 bt[GL];
+#pragma unroll
+  for (int u = 0; u < GL; ++u)
+    bt[u] = *reinterpret_cast<const f32x4*>(beta + (size_t)min(l0 + u, L - 1) * d_out + j);
   f32x4 acc[GL];
 #pragma unroll
   for (int u = 0; u < GL; ++u) acc[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
@@ -1095,23 +1165,32 @@ __global__ __launch_bounds__(256) void merge_kernel(const float* beta,  // may a
       for (int c = 0; c < 4; ++c) acc[u][c] = __builtin_fmaf(av, b[c], acc[u][c]);
     }
   };
-  int k = 0;
-  for (; k + 8 <= rank; k += 8) {  // eight rows of B in flight
-    f32x4 b[8];
+  // rows of B in batches of eight, the next batch in flight while the current one is used
+  constexpr int KB = 8;
+  const int nb = rank / KB;
+  f32x4 cur[KB], nxt[KB];
+  auto fetch = [&](f32x4 (&dst)[KB], int k) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) b[q] = *reinterpret_cast<const f32x4*>(B + (size_t)(k + q) * d_out + j);
+    for (int q = 0; q < KB; ++q) dst[q] = *reinterpret_cast<const f32x4*>(B + (size_t)(k + q) * d_out + j);
+  };
+  if (nb > 0) fetch(cur, 0);
+  for (int ib = 0; ib < nb; ++ib) {
+    if (ib + 1 < nb) fetch(nxt, (ib + 1) * KB);
 #pragma unroll
-    for (int q = 0; q < 8; ++q) step(k + q, b[q]);
+    for (int q = 0; q < KB; ++q) step(ib * KB + q, cur[q]);
+    if (ib + 1 < nb) {
+#pragma unroll
+      for (int q = 0; q < KB; ++q) cur[q] = nxt[q];
+    }
   }
-  for (; k < rank; ++k) step(k, *reinterpret_cast<const f32x4*>(B + (size_t)k * d_out + j));
+  for (int k = nb * KB; k < rank; ++k) step(k, *reinterpret_cast<const f32x4*>(B + (size_t)k * d_out + j));
 #pragma unroll
   for (int u = 0; u < GL; ++u) {
     const int l = l0 + u;
     if (l >= L) break;
-    const f32x4 bt = *reinterpret_cast<const f32x4*>(beta + (size_t)l * d_out + j);
     f32x4 o;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) o[c] = __builtin_fmaf(scale, acc[u][c], bt[c]);
+    for (int c = 0; c < 4; ++c) o[c] = __builtin_fmaf(scale, acc[u][c], bt[u][c]);
     *reinterpret_cast<f32x4*>(beta_out + (size_t)l * d_out + j) = o;
   }
 }
