@@ -6,6 +6,8 @@
 // Small fp32 factors that must go through the bf16 matrix cores are split as hi + lo
 // (hi = bf16(v), lo = bf16(v - hi)); a product U.B is then evaluated as
 // hi.hi + lo.hi + hi.lo, which is accurate to about 2^-16.
+#include <algorithm>
+
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -62,7 +64,11 @@ __device__ __forceinline__ uint4 bf16x8_to_f16x8_scaled(uint4 v, float sc) {
 //   prep job   : hi/lo split of B into the operand layout of the dU product
 // ---------------------------------------------------------------------------------------
 constexpr int ROWS_PER_BLOCK = 4;  // one wavefront each
-constexpr int ROW_BATCH = 8;       // 128-bit chunks per lane held in registers (4096 elements)
+// 128-bit chunks per lane of a row that a wavefront holds in registers (64 lanes x 8 elements
+// each): 8 covers rows of 4096 elements.  The launch is built for 8, 16 and 28 and takes the
+// smallest that holds its longest row, so that rows up to 14336 elements are read once; the
+// larger forms cost the launch occupancy, which is why they are not the only one.
+constexpr int ROW_BATCH = 8;
 constexpr int TR_TOK = 32;         // tokens per block of the transpose job
 
 // One linear's adapter among those that share the input x (a single layer is one part).
@@ -403,6 +409,7 @@ __device__ __forceinline__ void factor_block(const FrontArgs& a, int bid, float*
 
 // One wavefront processes one bf16 row: returns the row scale; optionally writes the fp16
 // scaled copy and the group averages (to P_s, LDS, [L]).
+template <int RB>
 __device__ __forceinline__ float2 process_row(const uint16_t* __restrict__ src, int cols,
                                               uint16_t* __restrict__ dst16, float* P_s, int g,
                                               int lane) {
@@ -411,16 +418,16 @@ __device__ __forceinline__ float2 process_row(const uint16_t* __restrict__ src, 
   const bool butterfly = P_s && lpg <= 64 && (lpg & (lpg - 1)) == 0;
   const float inv_g = g > 0 ? 1.0f / (float)g : 0.0f;
   uint32_t amax = 0;
-  uint4 v[ROW_BATCH];
-  const bool resident = nch <= 64 * ROW_BATCH;  // whole row fits the register batch
-  for (int base = 0; base < nch; base += 64 * ROW_BATCH) {
+  uint4 v[RB];
+  const bool resident = nch <= 64 * RB;  // whole row fits the register batch
+  for (int base = 0; base < nch; base += 64 * RB) {
 #pragma unroll
-    for (int c = 0; c < ROW_BATCH; ++c) {
+    for (int c = 0; c < RB; ++c) {
       const int ch = base + c * 64 + lane;
       v[c] = ch < nch ? *reinterpret_cast<const uint4*>(src + 8 * ch) : uint4{0, 0, 0, 0};
     }
 #pragma unroll
-    for (int c = 0; c < ROW_BATCH; ++c) {
+    for (int c = 0; c < RB; ++c) {
       amax = max_abs_bits(v[c], amax);
       if (butterfly) {
         const int ch = base + c * 64 + lane;
@@ -441,7 +448,7 @@ __device__ __forceinline__ float2 process_row(const uint16_t* __restrict__ src, 
   if (dst16) {
     if (resident) {
 #pragma unroll
-      for (int c = 0; c < ROW_BATCH; ++c) {
+      for (int c = 0; c < RB; ++c) {
         const int ch = c * 64 + lane;
         if (ch < nch)
           *reinterpret_cast<uint4*>(dst16 + 8 * ch) = bf16x8_to_f16x8_scaled(v[c], sc.x);
@@ -463,6 +470,7 @@ __device__ __forceinline__ float2 process_row(const uint16_t* __restrict__ src, 
   return sc;
 }
 
+template <int RB>
 __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
   extern __shared__ float P_all[];  // [ROWS_PER_BLOCK][L] when pooling
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -486,7 +494,7 @@ __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
     float* P_s = a.pool ? P_all + wave * L : nullptr;
     float2 sc = float2{1.0f, 1.0f};
     if (t < a.T) {
-      sc = process_row(a.x + (size_t)t * a.d_in, a.d_in,
+      sc = process_row<RB>(a.x + (size_t)t * a.d_in, a.d_in,
                        a.x16 ? a.x16 + (size_t)t * a.d_in : nullptr, P_s, a.g, lane);
       if (lane == 0 && a.rs_x) a.rs_x[t] = sc;
     } else if (a.pool) {
@@ -546,7 +554,7 @@ __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
     // ---- rows job 2: dy -> scale + fp16 copy ----------------------------------------------
     const int t = bid * ROWS_PER_BLOCK + wave;
     if (t < a.Ty) {
-      const float2 sc = process_row(a.y + (size_t)t * a.d_y, a.d_y, a.y16 + (size_t)t * a.d_y,
+      const float2 sc = process_row<RB>(a.y + (size_t)t * a.d_y, a.d_y, a.y16 + (size_t)t * a.d_y,
                                     nullptr, 0, lane);
       if (lane == 0) a.rs_y[t] = sc;
     }
@@ -696,16 +704,32 @@ static hipError_t launch_front(FrontArgs a, hipStream_t st) {
   }
   constexpr size_t kFrontLdsMax = 160 * 1024;  // a compute unit's LDS
   if (smem > kFrontLdsMax) return hipErrorInvalidValue;
-  if (smem > 48 * 1024) {
-    static std::atomic<uint64_t> granted{0};
-    if (hipError_t e = grant_dynamic_lds(reinterpret_cast<const void*>(front_kernel), (int)kFrontLdsMax, granted);
-        e != hipSuccess)
-      return e;
-  }
   const int nblocks = a.nb_rows1 + a.nb_rows2 + a.nb_tr + a.nb_fac + a.nb_prep;
   if (nblocks == 0) return hipSuccess;
-  front_kernel<<<nblocks, 256, smem, st>>>(a);
-  return hipGetLastError();
+  // the register batch that holds the launch's longest row (two sweeps beyond 14336 elements)
+  const int longest = std::max(a.x ? a.d_in : 0, a.y ? a.d_y : 0);
+  auto launch = [&](auto rb) -> hipError_t {
+    constexpr int RB = decltype(rb)::value;
+    if (smem > 48 * 1024) {
+      static std::atomic<uint64_t> granted{0};  // per instantiation
+      if (hipError_t e = grant_dynamic_lds(reinterpret_cast<const void*>(front_kernel<RB>), (int)kFrontLdsMax,
+                                           granted);
+          e != hipSuccess)
+        return e;
+    }
+    front_kernel<RB><<<nblocks, 256, smem, st>>>(a);
+    return hipGetLastError();
+  };
+  // ... when the rows are most of the launch: the larger batches cost occupancy, which a launch
+  // whose factor job is the longer part pays back with interest (measured at 5120 x 13824 with
+  // 2048 tokens: 36.0 us with two sweeps, 40.9 us with one)
+  const size_t row_bytes = ((a.x ? (size_t)a.T * a.d_in : 0) + (a.y ? (size_t)a.Ty * a.d_y : 0)) * 4;
+  const size_t fac_bytes = a.f_alpha ? (size_t)a.f_L * a.f_dout * 12 : 0;
+  if (row_bytes >= 8 * fac_bytes) {
+    if (longest > 512 * 8 && longest <= 512 * 16) return launch(std::integral_constant<int, 16>{});
+    if (longest > 512 * 16 && longest <= 512 * 28) return launch(std::integral_constant<int, 28>{});
+  }
+  return launch(std::integral_constant<int, ROW_BATCH>{});
 }
 
 static void set_parts(FrontArgs& a, const AdapterParts& ap) {
