@@ -285,6 +285,10 @@ __device__ __forceinline__ void factor_block(const FrontArgs& a, int bid, float*
     // operands in chunks of eight k values (whole fragments in registers would cost the row jobs
     // of the same launch their occupancy; the other wavefronts of the unit cover the latency)
     constexpr int KC = 8;
+    float bres[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q)
+      bres[q] = (kq <= 16 && bcol_ok && q < kq && kbase + q < rank) ? pt.B[bcol + (uint32_t)q * (uint32_t)pdout] : 0.0f;
     for (int l0 = 16 * wave; l0 < L; l0 += 64) {
       const uint32_t arow = (uint32_t)min(l0 + n, L - 1) * (uint32_t)rank + (uint32_t)kbase;  // rows past the end repeat the last one, unused
       // alpha and beta of the four elements this lane will receive: requested now, used after
@@ -297,6 +301,27 @@ __device__ __forceinline__ void factor_block(const FrontArgs& a, int bid, float*
         be4[r] = a.f_beta[o];
       }
       f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (kq <= 16) {
+        // rank <= 64: the lane's share of B is sixteen values held for the whole block, its share
+        // of the tile's rows of A sixteen more, requested together with alpha and beta -- one
+        // round trip to memory per tile
+        float af[16];
+        if (vec4) {
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (4 * q4 < kq) v = *reinterpret_cast<const f32x4*>(pA + arow + 4 * q4);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) af[4 * q4 + q] = v[q];
+          }
+        } else {
+#pragma unroll
+          for (int q = 0; q < 16; ++q) af[q] = (q < kq && kbase + q < rank) ? pA[arow + q] : 0.0f;
+        }
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+          if (q < kq) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(af[q], bres[q], acc, 0, 0, 0);
+      } else
       for (int i0 = 0; i0 < kq; i0 += KC) {
         float av[KC], bv[KC];
         if (vec4 && i0 + KC <= kq) {
@@ -397,11 +422,22 @@ __device__ __forceinline__ void factor_block(const FrontArgs& a, int bid, float*
     } else if (lg == 0 && col_ok) {
       a.f_inv[j] = sc.y;
     }
-    if (col_ok)
-      for (int l = lg; l < L; l += NLG) {
-        const f32x2 v = {a.f_alpha[(size_t)l * dout + j] * sc.x, tile[(size_t)l * FC + c] * sc.x};
-        a.f_words[(size_t)l * dout + j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+    if (col_ok) {
+      constexpr int WB = 8;  // groups per batch: their alpha loads go out together
+      for (int lb = lg; lb < L; lb += NLG * WB) {
+        float al[WB];
+#pragma unroll
+        for (int q = 0; q < WB; ++q) al[q] = a.f_alpha[(size_t)min(lb + q * NLG, L - 1) * dout + j];
+#pragma unroll
+        for (int q = 0; q < WB; ++q) {
+          const int l = lb + q * NLG;
+          if (l < L) {
+            const f32x2 v = {al[q] * sc.x, tile[(size_t)l * FC + c] * sc.x};
+            a.f_words[(size_t)l * dout + j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+          }
+        }
       }
+    }
   } else if (col_ok) {
     for (int l = lg; l < L; l += NLG) a.f_const[(size_t)l * dout + j] = tile[(size_t)l * FC + c];
   }
@@ -475,8 +511,18 @@ __global__ __launch_bounds__(256) void front_kernel(const FrontArgs a) {
   extern __shared__ float P_all[];  // [ROWS_PER_BLOCK][L] when pooling
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int bid = blockIdx.x;
-  // the factor job's blocks come first: they are the longest-running ones, and started last
-  // they would finish after everything else instead of under it
+  // The factor job's blocks are the longest-running ones: started last they would finish after
+  // everything else instead of under it.  But all of them first would hold most of the chip's
+  // block slots while the row jobs, which carry the launch's memory traffic, wait; so the two
+  // kinds alternate until one runs out.
+  {
+    const int n_other = (int)gridDim.x - a.nb_fac;
+    const int m = min(a.nb_fac, n_other);
+    if (bid < 2 * m)
+      bid = (bid & 1) ? a.nb_fac + (bid >> 1) : (bid >> 1);
+    else
+      bid = (a.nb_fac > m) ? bid - m : bid;  // the rest of the longer kind, in order
+  }
   if (bid < a.nb_fac) {
     // Block ids are dealt round-robin to the 8 XCDs, each with its own L2.  The folding form
     // works on 64-byte pieces of the 128-byte lines of alpha, beta and the words, so column
