@@ -455,6 +455,10 @@ def main():
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
     ap.add_argument("--no-keep", action="store_true",
                     help="backward re-reads x instead of the pooled activations the forward kept")
+    ap.add_argument("--library", default=None,
+                    help="measure another build of the library (e.g. an ablation variant made by "
+                         "`python -m paper_2309_14717_amd.build --variant NAME -DQALORA_ABLATE=n`); "
+                         "the output carries its name")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
@@ -475,6 +479,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.library:   # a measurement build; the binding itself has no such switch
+        if not os.path.exists(args.library):
+            sys.exit(f"bench.py: {args.library} not found")
+        api.LIB_PATH = os.path.abspath(args.library)
     api.load()
     odt = torch.bfloat16 if args.out_dtype == "bf16" else torch.float32
     extras, cpu_baseline = {}, None
@@ -683,6 +691,8 @@ def main():
                                       ("pooled activations kept by the forward" if Layer.keep else "x"))},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "extras": extras,
     }
+    if args.library:
+        out["config"]["library"] = os.path.basename(args.library) + " (a measurement build: results may be wrong on purpose)"
     print(json.dumps(out))
 
 

@@ -65,17 +65,32 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
-    os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
-    tmp = LIB + ".tmp%d" % os.getpid()
+def build(verbose: bool = False, extra_flags=(), variant: str = "") -> str:
+    """Build the library.  `variant` names a measurement build (say, with -DQALORA_ABLATE=n in
+    `extra_flags`): it goes to libqalora_hip.<variant>.so with objects of its own, so the
+    library the tests and the product load is never replaced by it."""
+    global OBJ
+    lib = LIB if not variant else LIB[:-3] + "." + variant + ".so"
+    obj_dir = OBJ if not variant else OBJ + "_" + variant
+    os.makedirs(obj_dir, exist_ok=True)
+    saved, OBJ = OBJ, obj_dir
+    try:
+        with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+            objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
+    finally:
+        OBJ = saved
+    tmp = lib + ".tmp%d" % os.getpid()
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
-    os.replace(tmp, LIB)
+    os.replace(tmp, lib)
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", lib)
+    return lib
 
 
 if __name__ == "__main__":
-    build(verbose=True, extra_flags=sys.argv[1:])
+    # python -m paper_2309_14717_amd.build [--variant NAME] [compiler flags ...]
+    args = sys.argv[1:]
+    name = ""
+    if len(args) >= 2 and args[0] == "--variant":
+        name, args = args[1], args[2:]
+    build(verbose=True, extra_flags=args, variant=name)

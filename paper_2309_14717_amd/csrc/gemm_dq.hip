@@ -55,6 +55,21 @@ namespace qalora {
 constexpr int BK = 64;
 constexpr int NT = 512;  // threads per block
 
+// Measurement aid: -DQALORA_ABLATE=n builds the dequantising kernels with one part of their work
+// taken away, to see what that part costs.  The results are WRONG on purpose; every access stays
+// in bounds and every wait still ends.  (Such a build is for the benchmark's --library option,
+// never for the tests.)
+//   1  the producer dequantises every second column only (half the vector work, half the B writes)
+//   2  a quarter of the A tile's LDS-DMA loads
+//   3  the A tile always comes from the first 256 elements of K (served by L2 after the first pass)
+//   4  half of the A operand fragments are read from LDS, the others reuse them
+//   5  as 4, and one B fragment is read instead of all
+//   6  no block barrier in the K step
+//   7  no wait for the A tile in the K step
+#ifndef QALORA_ABLATE
+#define QALORA_ABLATE 0
+#endif
+
 // Raw buffer resources: loads through them return zero past `bytes`, which is how every
 // ragged edge (rows past M, patches past the matrix) is zero-filled without branches.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, size_t bytes) {
@@ -140,7 +155,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   constexpr int TM = WTM / 32, TN = WTN / 32;
   static_assert(TM >= 1 && TN >= 1, "wave tile must hold at least one 32x32 MFMA tile");
-  constexpr int A_LOADS = BM * 8 / NT;                           // LDS-DMA loads per thread
+  constexpr int A_LOADS = (QALORA_ABLATE == 2 && HAS_MAIN) ? 1 : BM * 8 / NT;  // LDS-DMA loads per thread
   constexpr int B_CHUNKS = (BN * 8 / NT) > 0 ? BN * 8 / NT : 1;  // plain B tile, per thread
   static_assert(A_LOADS >= 1, "BM too small for 512 threads");
   constexpr int A_TILE = BM * 64;  // 16-bit elements per A buffer
@@ -246,7 +261,8 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
       const uint32_t voff = a_voff_main | (live ? 0u : kOobOffset);
 #pragma unroll
       for (int q = 0; q < A_LOADS; ++q) {
-        const uint32_t soff = (uint32_t)k0 * 2u + (uint32_t)q * 64u * (uint32_t)p.lda_main * 2u;
+        const uint32_t soff = (uint32_t)(QALORA_ABLATE == 3 ? (k0 & 255) : k0) * 2u +
+                              (uint32_t)q * 64u * (uint32_t)p.lda_main * 2u;
         uint16_t* dst = a_dst + (q * 8 + wave) * 512;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a_main,
                                                  (__attribute__((address_space(3))) void*)dst, 16,
@@ -432,6 +448,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           if (piece >= 0 && (piece == 2 ? c < 2 : c != piece)) continue;  // columns {0}, {1}, {2, 3}
+          if (QALORA_ABLATE == 1 && (c & 1)) continue;
           const uint32_t w0s = w0[c] >> sh0;
           const uint32_t w1s = (NBITS == 3) ? (w1[c] >> sh1) : 0u;
           const f16x2 ab = ab_pair(fc[c]);
@@ -457,6 +474,11 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
           if (piece >= 0 && c / 4 != piece) continue;
+          if (QALORA_ABLATE == 1 && (c & 1)) {
+            wt[c][0] = wt[c - 1][0];
+            wt[c][1] = wt[c - 1][1];
+            continue;
+          }
           const uint32_t w0s = w0[c] >> sh0;
           const uint32_t w1s = (NBITS == 3) ? (w1[c] >> sh1) : 0u;
           const f16x2 ab = ab_pair(fc[c]);
@@ -562,10 +584,14 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     const int cx = (2 * kk + (lane >> 5)) << 4;
     const char* ap = reinterpret_cast<const char*>(a_src) + (a_lane ^ cx);
     const char* bp = reinterpret_cast<const char*>(b_src) + (b_lane ^ cx);
+    constexpr int kReadA = (QALORA_ABLATE == 4 || QALORA_ABLATE == 5) ? (TM + 1) / 2 : TM;
+    constexpr int kReadB = (QALORA_ABLATE == 5) ? 1 : TN;
 #pragma unroll
-    for (int a = 0; a < TM; ++a) maf[slot][a] = *reinterpret_cast<const uint4*>(ap + a * 4096);
+    for (int a = 0; a < TM; ++a)
+      maf[slot][a] = a < kReadA ? *reinterpret_cast<const uint4*>(ap + a * 4096) : maf[slot][a - kReadA];
 #pragma unroll
-    for (int b = 0; b < TN; ++b) mbf[slot][b] = *reinterpret_cast<const uint4*>(bp + b * 4096);
+    for (int b = 0; b < TN; ++b)
+      mbf[slot][b] = b < kReadB ? *reinterpret_cast<const uint4*>(bp + b * 4096) : mbf[slot][0];
   };
   auto compute_main = [&](const uint16_t* a_rd, const uint16_t* b_rd, const uint16_t* a_nx,
                           const uint16_t* b_nx, auto&& side, auto&& after_barrier) {
@@ -600,7 +626,12 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     // this wave's LDS writes (next B stage) and reads (fragments of slice 3) are done
     // ... and its share of A(it+1) has landed: the loads issued since (registers of it+2, A(it+2),
     // registers... see the step) may stay in flight
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(kMidKeep) : "memory");
+    if constexpr (QALORA_ABLATE == 6)
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kMidKeep) : "memory");
+    else if constexpr (QALORA_ABLATE == 7)
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(kMidKeep) : "memory");
     after_barrier();
     __builtin_amdgcn_sched_barrier(0);
     slice(std::integral_constant<int, 3>{});
