@@ -21,8 +21,10 @@
  *     never synchronises: work is enqueued on `stream` (a hipStream_t passed as void*;
  *     NULL = the default stream) and the results are ready when that stream reaches the
  *     end of the enqueued work.  No state that affects a result is kept between calls
- *     (the only process state is a call counter that tags flags in the workspace, and the
- *     events armed through qalora_profile_arm).
+ *     (the only process state is a call counter that tags flags in the workspace, one bit
+ *     per kernel and device noting that its dynamic-LDS attribute has been set, the device
+ *     address of qalora_forward_noalloc's built-in scratch array, and whatever the
+ *     qalora_profile_* measurement aids armed).
  *   - Scratch memory comes from the caller through (ws, ws_bytes); ask
  *     qalora_workspace_bytes for the size (forward and backward always need some, at least
  *     8 bytes per token).  ws contents are undefined afterwards.  Two calls that may run
