@@ -31,6 +31,26 @@ def test_compensated_bit_exact(gpu_api, bits, g, d_in, d_out):
     assert hessian_error(W, codes, a, b, g, H) < e_rtn
 
 
+def test_compensated_many_blocks_and_rerun(gpu_api):
+    """A layer of sixteen lazy row blocks and 128 column blocks (all compute units busy, two
+    block generations), bit for bit against the oracle, and twice: the row lanes of a column
+    live in different wavefronts, so an ordering mistake between them would show as a result
+    that differs between runs or from the oracle."""
+    bits, g, d_in, d_out = 4, 32, 2048, 2048
+    W = synth.make_inputs(synth.LayerConfig("t", 1, d_in, d_out, bits, g, 1, seed=61), want=("W",))["W"]
+    _, U = hessian(d_in, 2 * d_in, seed=9)
+    U32 = np.ascontiguousarray(U.astype(np.float32))
+    desc = gpu_api.make_desc(d_in, d_out, bits, g)
+    Wd, Ud = dev(W), dev(U32)
+    p1, a1, b1 = gpu_api.quantize_compensated(desc, Wd, Ud)
+    p2, a2, b2 = gpu_api.quantize_compensated(desc, Wd, Ud)
+    assert torch.equal(p1, p2) and torch.equal(a1, a2) and torch.equal(b1, b2)
+    c, a, b = oracle.quantize_compensated(W, U32, bits, g, block=128)
+    assert np.array_equal(gpu_api.unpack(desc, p1).cpu().numpy(), c)
+    assert np.array_equal(a1.cpu().numpy().view(np.uint32), a.view(np.uint32))
+    assert np.array_equal(b1.cpu().numpy().view(np.uint32), b.view(np.uint32))
+
+
 def test_compensated_identity_is_plain_quantize(gpu_api):
     d_in, d_out = 256, 64
     W = synth.make_inputs(synth.LayerConfig("t", 1, d_in, d_out, 4, 32, 1, seed=50), want=("W",))["W"]

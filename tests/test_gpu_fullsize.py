@@ -168,12 +168,24 @@ def test_config3_mlp_block_end_to_end(gpu_api):
     y and dx on sampled token rows (all columns), the three dA and the three dB in full."""
     import bench
 
-    blk = bench.MlpBlock(gpu_api, torch, synth, torch.bfloat16)
-    dx_gpu = blk.step().float().cpu().numpy()
-    y_gpu = blk.down.y.float().cpu().numpy()
-    grads_gpu = {n: (l.dA.cpu().numpy(), l.dB.cpu().numpy())
-                 for n, l in (("gate", blk.gate), ("up", blk.up), ("down", blk.down))}
-    torch.cuda.synchronize()
+    def run_block(shared):
+        """(y, dx, {linear: (dA, dB)}) of one step of the block as bench.py builds it: three
+        separate layers, or gate and up as one wide layer sharing x (--shared)."""
+        blk = (bench.MlpBlockShared if shared else bench.MlpBlock)(gpu_api, torch, synth, torch.bfloat16)
+        dx = blk.step().float().cpu().numpy()
+        y = blk.down.y.float().cpu().numpy()
+        if shared:
+            gr = {"gate": blk.grads[0], "up": blk.grads[1], "down": (blk.down.dA, blk.down.dB)}
+        else:
+            gr = {n: (l.dA, l.dB) for n, l in (("gate", blk.gate), ("up", blk.up), ("down", blk.down))}
+        gr = {n: (a.cpu().numpy(), b.cpu().numpy()) for n, (a, b) in gr.items()}
+        torch.cuda.synchronize()
+        return y, dx, gr
+
+    results = {"separate": run_block(False)}
+    torch.cuda.empty_cache()
+    results["shared"] = run_block(True)
+    torch.cuda.empty_cache()
 
     q, host = {}, {}
     for name in ("gate", "up", "down"):
@@ -206,11 +218,14 @@ def test_config3_mlp_block_end_to_end(gpu_api):
     dx2, _, _ = bwd("up", du[rows], x[rows], want_dAdB=False)
     dx_ref = _bf16(_bf16(dx1) + _bf16(dx2))
 
-    errs = dict(y=rel_err(y_gpu[rows], y_ref), dx=rel_err(dx_gpu[rows], dx_ref))
-    for name, (rA, rB) in (("gate", (dA_g, dB_g)), ("up", (dA_u, dB_u)), ("down", (dA_d, dB_d))):
-        errs["dA_" + name] = rel_err(grads_gpu[name][0], rA)
-        errs["dB_" + name] = rel_err(grads_gpu[name][1], rB)
-    record("fullsize c3 block end to end", **errs)
+    all_errs = {}
+    for kind, (y_gpu, dx_gpu, grads_gpu) in results.items():
+        errs = dict(y=rel_err(y_gpu[rows], y_ref), dx=rel_err(dx_gpu[rows], dx_ref))
+        for name, (rA, rB) in (("gate", (dA_g, dB_g)), ("up", (dA_u, dB_u)), ("down", (dA_d, dB_d))):
+            errs["dA_" + name] = rel_err(grads_gpu[name][0], rA)
+            errs["dB_" + name] = rel_err(grads_gpu[name][1], rB)
+        record(f"fullsize c3 block end to end ({kind})", **errs)
+        all_errs[kind] = errs
     # Bars of the chain.  Each contraction on the path to an output may be off by TOL of its own
     # maximum (the bar of a single layer), and each activation the block stores in bf16 by one
     # rounding, 2^-9 relative; both carry through the linear stages that follow at most
@@ -223,4 +238,6 @@ def test_config3_mlp_block_end_to_end(gpu_api):
     r = 2.0 ** -9
     bars = dict(y=2 * TOL + 3 * r, dx=3 * TOL + 5 * r, dA_gate=3 * TOL + 3 * r, dB_gate=3 * TOL + 3 * r,
                 dA_up=3 * TOL + 3 * r, dB_up=3 * TOL + 3 * r, dA_down=2 * TOL + 2 * r, dB_down=2 * TOL + 2 * r)
-    assert all(errs[k] <= bars[k] for k in bars), (errs, bars)
+    # (the shared form rounds dx once instead of dx1, dx2 and their sum: the same bar covers it)
+    for kind, errs in all_errs.items():
+        assert all(errs[k] <= bars[k] for k in bars), (kind, errs, bars)
