@@ -29,7 +29,8 @@
  *     qalora_workspace_bytes for the size (forward and backward always need some, at least
  *     8 bytes per token).  ws contents are undefined afterwards.  Two calls that may run
  *     at the same time (different streams) must not share a workspace.
- *   - Stream capture: forward, backward and merge may be captured into a HIP graph and
+ *   - Stream capture: forward, backward and merge -- and the _keep / _kept, _shared,
+ *     _deployed and _noalloc forms -- may be captured into a HIP graph and
  *     replayed (they enqueue kernels only: no memset, copy, allocation or event unless
  *     qalora_profile_arm armed one).  Make one eager call of the same shape first: the
  *     first use of a kernel sets its dynamic-LDS attribute, which is not stream work.  The
