@@ -242,6 +242,38 @@ def timed(torch, fn, n=20, warm=2):
     return s.elapsed_time(e) / n
 
 
+def capture(torch, fns):
+    """One HIP graph holding a call of each fn in order (each has run eagerly before: the first
+    use of a kernel sets its LDS attribute, which is not stream work)."""
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for fn in fns:
+            fn()
+    return g
+
+
+def timed_graph(torch, fns, n):
+    """Average time of one call over n calls that cycle through `fns`, launched as graph replays:
+    launches of 25 us kernels from Python are otherwise bound by the host (two argument-checked
+    ctypes calls take longer than the kernels they start on a slow host core), which is not what
+    a serving loop does either."""
+    for fn in fns:
+        fn()
+    torch.cuda.synchronize()
+    full = capture(torch, fns)
+    rem = capture(torch, fns[: n % len(fns)]) if n % len(fns) else None
+    for _ in range(2):
+        full.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n // len(fns)):
+        full.replay()
+    if rem is not None:
+        rem.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / n
+
+
 KERNEL_STATS = {}  # direction -> median / min / count of the armed kernel durations of the last run
 
 
@@ -347,8 +379,7 @@ def small_token_table(torch, api, synth, odt, n_sets=8, tokens=(1, 4, 16, 256), 
             x = sets[0].x[:T].contiguous()
             y = torch.empty((T, cfg.d_out), dtype=odt, device="cuda")
             ws = torch.empty(api.workspace_bytes(sets[0].desc, T, api.OP_FORWARD), dtype=torch.uint8, device="cuda")
-            it = iter(range(10 ** 9))
-            ms = timed(torch, lambda: sets[next(it) % n_sets].forward_merged(x=x, y=y, ws=ws), n=iters, warm=n_sets)
+            ms = timed_graph(torch, [(lambda L=L: L.forward_merged(x=x, y=y, ws=ws)) for L in sets], iters)
             by = forward_bytes(cfg, T, y.element_size())
             fl = 2.0 * T * cfg.d_in * cfg.d_out
             rows.append({"shape": f"{cfg.d_in}x{cfg.d_out}", "tokens": T,
@@ -375,8 +406,10 @@ def adamw_layer_timing(torch, api, d=4096, ff=11008, g=32, r=64):
     v = [torch.zeros_like(x) for x in p]
     hp = api.AdamW(2e-5, 0.9, 0.999, 1e-8, 0.0, 0.3)
     ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
-    it = iter(range(1, 10 ** 9))
-    ms = timed(torch, lambda: api.adamw_step(hp, next(it), p, gr, m, v, ws=ws), n=50, warm=5)
+    # (replayed as a graph: the two launches take 20 us, less than their launch from Python; the
+    # step number, a kernel argument, then stays at 2, which changes no timing)
+    api.adamw_step(hp, 1, p, gr, m, v, ws=ws)
+    ms = timed_graph(torch, [lambda: api.adamw_step(hp, 2, p, gr, m, v, ws=ws)] * 5, 50)
     n = sum(x.numel() for x in p)
     return {"parameters": n, "tensors": len(p), "us": round(ms * 1e3, 2), "GB/s": round(32.0 * n / ms / 1e6, 1),
             "frac_hbm": round(32.0 * n / ms / 1e6 / PEAK_HBM_GBS, 4)}
@@ -633,12 +666,37 @@ def main():
             ups[i].forward_merged(x=xu, y=yu, ws=ws_u)      # arms catch this kernel (first forward of the step)
             downs[i].forward_merged(x=xd, y=yd, ws=ws_d)
 
-        ms_per_step, kms, clk = run_steps(torch, api, step, args.steps, max(args.warmup, n_sets), directions=(0,), arm_every=7)
+        streaming = T <= (32 if args.bits == 4 else 16)
+        if streaming:
+            # graph replays of whole rotations (see timed_graph); then a few eager steps with armed
+            # events for the event-bracketed figure
+            def one(i):
+                def f():
+                    ups[i].forward_merged(x=xu, y=yu, ws=ws_u)
+                    downs[i].forward_merged(x=xd, y=yd, ws=ws_d)
+                return f
+            for _ in range(max(args.warmup, n_sets)):
+                step()
+            torch.cuda.synchronize()
+            full = capture(torch, [one(i) for i in range(n_sets)])
+            rem = capture(torch, [one(i) for i in range(args.steps % n_sets)]) if args.steps % n_sets else None
+            SETTLE["steps"] = n_sets * settle(torch, full.replay)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps // n_sets):
+                full.replay()
+            if rem is not None:
+                rem.replay()
+            torch.cuda.synchronize()
+            ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+            _, kms, clk = run_steps(torch, api, step, 14, 0, directions=(0,), arm_every=7)
+        else:
+            ms_per_step, kms, clk = run_steps(torch, api, step, args.steps, max(args.warmup, n_sets), directions=(0,), arm_every=7)
         total_flops = 2.0 * T * (cfg_u.d_in * cfg_u.d_out + cfg_d.d_in * cfg_d.d_out)
         by_u = forward_bytes(cfg_u, T, yu.element_size(), fb)
         by_step = by_u + forward_bytes(cfg_d, T, yd.element_size(), fb)
         k = kms[0]
-        if T <= (32 if args.bits == 4 else 16):  # the streaming kernels' range
+        if streaming:  # the streaming kernels' range
             # A step is two launches of the streaming kernel with (to 0.1 %) the same algorithmic
             # bytes, back to back on one stream, so the average launch duration over the timed
             # region is half the step.  (An event pair around a single 30 us launch reads 3-5 us
