@@ -265,13 +265,15 @@ def timed_graph(torch, fns, n):
     for _ in range(2):
         full.replay()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s.record()
     for _ in range(n // len(fns)):
         full.replay()
     if rem is not None:
         rem.replay()
+    e.record()
     torch.cuda.synchronize()
-    return (time.perf_counter() - t0) * 1e3 / n
+    return s.elapsed_time(e) / n
 
 
 KERNEL_STATS = {}  # direction -> median / min / count of the armed kernel durations of the last run
@@ -371,7 +373,7 @@ def small_token_sets(torch, api, synth, name, n_sets, odt, bits=4, deployed=Fals
     return cfg, sets
 
 
-def small_token_table(torch, api, synth, odt, n_sets=8, tokens=(1, 4, 16, 256), iters=48):
+def small_token_table(torch, api, synth, odt, n_sets=8, tokens=(1, 4, 16, 256), iters=96):
     rows = []
     for name in ("c5_up", "c5_down"):
         cfg, sets = small_token_sets(torch, api, synth, name, n_sets, odt, deployed=True)
