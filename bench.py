@@ -303,6 +303,7 @@ def settle(torch, step, chunk=10, tol=0.015, max_chunks=40):
 
 
 BLOCK_TIMELINE = {}
+ARM_EVERY = [None]   # --arm-every
 
 
 def run_steps(torch, api, step, steps, warmup, directions=(0, 1), arm_every=None):
@@ -314,11 +315,12 @@ def run_steps(torch, api, step, steps, warmup, directions=(0, 1), arm_every=None
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    SETTLE["steps"] = settle(torch, step)
     if arm_every is None:
         arm_every = 2 if steps <= 50 else 4
+    # (the timers are made before the settling steps, so that nothing but the synchronisation
+    # lies between the last settling step and the timed region)
     timers = {d: api.KernelTimer(d, (steps + arm_every - 1) // arm_every) for d in directions}
-    torch.cuda.synchronize()
+    SETTLE["steps"] = settle(torch, step)
     t0 = time.perf_counter()
     for i in range(steps):
         if i % arm_every == 0:
@@ -494,6 +496,9 @@ def main():
                     help="measure another build of the library (e.g. an ablation variant made by "
                          "`python -m paper_2309_14717_amd.build --variant NAME -DQALORA_ABLATE=n`); "
                          "the output carries its name")
+    ap.add_argument("--arm-every", type=int, default=None,
+                    help="arm the kernel-timing events on every n-th timed step (default: 2 for runs of "
+                         "up to 50 steps, else 4; 0: never, then the roofline has no kernel time)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
@@ -507,6 +512,7 @@ def main():
               file=sys.stderr)
         sys.exit(2)
     Layer.keep = not args.no_keep
+    ARM_EVERY[0] = args.arm_every
 
     import torch
     from paper_2309_14717_amd import api, synth
@@ -543,7 +549,7 @@ def main():
             L.forward()
             L.backward()
 
-        ms_per_step, kms, clk = run_steps(torch, api, step, args.steps, args.warmup)
+        ms_per_step, kms, clk = run_steps(torch, api, step, args.steps, args.warmup, arm_every=ARM_EVERY[0])
         fl = layer_flops(cfg)
         total_flops = fl["fwd"] + fl["bwd"]
         kf, kb = kms[0], kms[1]
@@ -609,7 +615,7 @@ def main():
         blk = (MlpBlockShared if args.shared else MlpBlock)(api, torch, synth, odt)
         down, step = blk.down, blk.step
 
-        ms_per_step, kms, clk = run_steps(torch, api, step, args.steps, args.warmup)
+        ms_per_step, kms, clk = run_steps(torch, api, step, args.steps, args.warmup, arm_every=ARM_EVERY[0])
         fls = [layer_flops(c) for c in (synth.CONFIGS["c3_gate"], synth.CONFIGS["c3_up"], synth.CONFIGS["c3_down"])]
         total_flops = sum(f["fwd"] + f["bwd"] for f in fls)
         # armed events catch the first contraction of each direction: gate forward, down backward
