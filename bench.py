@@ -451,6 +451,49 @@ def probe_report(torch, api):
             "mfma_probe": rows, "vendor_gemm": vendor}
 
 
+def two_stream_backward(torch, api, synth):
+    """Can the adapter-gradient kernels hide under the dx contraction?  The backward of the c2
+    layer as two calls -- dx only (adapter-free: front pass and contraction) and gradients only
+    (front pass, dU product, gradient kernels, reduction) -- one after the other on one stream,
+    and at the same time on two streams of equal priority."""
+    cfg = synth.CONFIGS["c2"]
+    L = Layer(api, torch, cfg, torch.bfloat16)
+    L.drop_w()
+    d = L.desc
+    ws2 = torch.empty_like(L.ws_b)
+    dA2, dB2 = torch.zeros_like(L.A), torch.zeros_like(L.B)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def dx_only():
+        api.backward(d, L.dy, None, L.packed, L.alpha, L.beta, None, None, ws=L.ws_b, dx=L.dx)
+
+    def grads_only():
+        api.backward(d, L.dy, L.x, L.packed, L.alpha, L.beta, L.A, L.B, want_dx=False, dA=dA2, dB=dB2, ws=ws2)
+
+    def one_stream():
+        dx_only()
+        grads_only()
+
+    def two_streams():
+        with torch.cuda.stream(s2):
+            grads_only()
+        with torch.cuda.stream(s1):
+            dx_only()
+
+    def wall(fn, n=60):
+        for _ in range(20):
+            fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return round((time.perf_counter() - t) / n * 1e6, 1)
+
+    return {"dx_only_us": wall(dx_only), "gradients_only_us": wall(grads_only),
+            "both_on_one_stream_us": wall(one_stream), "both_on_two_streams_us": wall(two_streams)}
+
+
 def cpu_model():
     try:
         for line in open("/proc/cpuinfo"):
@@ -536,7 +579,9 @@ def main():
         del src, dst
 
     if args.workload == "probe":
-        print(json.dumps(probe_report(torch, api)))
+        rep = probe_report(torch, api)
+        rep["two_stream_backward_c2"] = two_stream_backward(torch, api, synth)
+        print(json.dumps(rep))
         return
 
     if args.workload in ("c1", "c2", "c4"):
