@@ -140,6 +140,18 @@ __device__ __forceinline__ void with_step_regions(uint16_t* __restrict__ a_dma,
   f(a_dma, a_rd, a_nx, b_rd, b_wr);
 }
 
+// A stages of the LDS-DMA pipeline.  Three (the tile of step it+3 is requested as soon as step it
+// has released its stage), except for the 64-row tile of the dequantising product: with two
+// stages its LDS is 80 KB, so that two blocks fit a compute unit and cover each other's waits
+// -- a K step of that tile is mostly producer work and synchronisation, not matrix work.
+constexpr int gemm_a_stages(int bm, bool has_main) { return (has_main && bm == 64) ? 2 : 3; }
+// wavefronts per SIMD the kernel is compiled for (two blocks of the 64-row tile: four, i.e. 128
+// registers; the 3-bit backward producer with per-step edge handling does not fit them and
+// stays at one block per unit)
+constexpr int gemm_min_waves(int bm, bool has_main, int nbits, bool bwd, bool fast) {
+  return (has_main && bm == 64 && !(nbits == 3 && bwd && !fast)) ? 4 : 1;
+}
+
 // HAS_MAIN = false: a plain bf16 x bf16^T product over the "tail" operands only (used for
 // dU = s dy B^T), optionally split along K over blockIdx.y.
 //
@@ -148,7 +160,7 @@ __device__ __forceinline__ void with_step_regions(uint16_t* __restrict__ a_dma,
 // constant and the K advance lives in scalar offsets, so the hot loop carries no vector
 // address arithmetic.  FAST = false keeps per-step, per-lane offsets with full edge handling.
 template <int NBITS, bool BWD, int BM, int BN, int WAVES_M, int WAVES_N, bool HAS_MAIN, bool FAST>
-__global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
+__global__ __launch_bounds__(NT, gemm_min_waves(BM, HAS_MAIN, NBITS, BWD, FAST)) void gemm_dq_kernel(const GemmArgs p) {
   static_assert(!FAST || HAS_MAIN, "the fast addressing path is for the dequantising product");
   static_assert(WAVES_M * WAVES_N == 8, "eight wavefronts per block");
   static_assert(!HAS_MAIN || BN == 256, "the dequantising producer assumes 256 columns");
@@ -160,7 +172,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
   static_assert(A_LOADS >= 1, "BM too small for 512 threads");
   constexpr int A_TILE = BM * 64;  // 16-bit elements per A buffer
   constexpr int B_TILE = BN * 64;
-  constexpr int A_STAGES = 3;  // LDS-DMA prefetch runs two K steps ahead
+  constexpr int A_STAGES = gemm_a_stages(BM, HAS_MAIN);  // LDS-DMA prefetch runs A_STAGES - 1 K steps ahead
 
   extern __shared__ __align__(1024) uint16_t smem[];
   // The B stages sit at the bottom: their offsets then fit the 16-bit immediate of the LDS
@@ -577,7 +589,8 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
   // from the stages that barrier has just published -- so a step starts on the matrix cores
   // at once instead of waiting for an LDS round trip.
   constexpr int kMainB = BWD ? (NBITS == 3 ? 6 : 4) : (NBITS == 3 ? 3 : 2);
-  constexpr int kMidKeep = kMainB + A_LOADS + kMainB;  // see the main step below
+  // see the main step below (two stages: only the registers of it+2 were requested after A(it+1))
+  constexpr int kMidKeep = A_STAGES == 2 ? kMainB : kMainB + A_LOADS + kMainB;
   uint4 maf[2][TM], mbf[2][TN];
   auto load_frags_main = [&](const uint16_t* a_src, const uint16_t* b_src, int kk, auto slot_c) {
     constexpr int slot = decltype(slot_c)::value;
@@ -683,7 +696,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
                   if constexpr (kSingleSet && decltype(kk)::value == 2)
                     gload_b(MainK{}, at(it + 2), SetCur{}, live(it + 2));
                 },
-                [&]() { issue_a(MainK{}, at(it + 3), a_cur, live(it + 3)); });
+                [&]() { issue_a(MainK{}, at(it + A_STAGES), a_cur, live(it + A_STAGES)); });
           });
     };
     if (pe > pb) {
@@ -693,26 +706,36 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
       gload_b(MainK{}, pb, Set0{}, true);
       issue_a(MainK{}, at(pb + 1), As + A_TILE, live(pb + 1));
       if constexpr (!kSingleSet) gload_b(MainK{}, at(pb + 1), Set1{}, live(pb + 1));
-      issue_a(MainK{}, at(pb + 2), As + 2 * A_TILE, live(pb + 2));
+      if constexpr (A_STAGES == 3) issue_a(MainK{}, at(pb + 2), As + 2 * A_TILE, live(pb + 2));
       __builtin_amdgcn_sched_barrier(0);
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * A_LOADS + (kSingleSet ? 0 : kBLoadsMain))
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((A_STAGES - 1) * A_LOADS + (kSingleSet ? 0 : kBLoadsMain))
                    : "memory");
       store_b(MainK{}, pb, Bs, Set0{}, AllPieces{});
       if constexpr (kSingleSet) gload_b(MainK{}, at(pb + 1), Set0{}, live(pb + 1));
       asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
       load_frags_main(As, Bs, 0, Set0{});
       int it = pb;
-      uint16_t *a0 = As, *a1 = As + A_TILE, *a2 = As + 2 * A_TILE;  // stages of it, it+1, it+2
+      if constexpr (A_STAGES == 3) {
+        uint16_t *a0 = As, *a1 = As + A_TILE, *a2 = As + 2 * A_TILE;  // stages of it, it+1, it+2
 #pragma nounroll
-      for (; it + 1 < pe; it += 2) {  // hot loop: two steps, one per parity
-        step(it, a0, a1, a2, Set0{});
-        step(it + 1, a1, a2, a0, Set1{});
-        uint16_t* t = a0;  // two steps on: the stage of it+2 is the current one
-        a0 = a2;
-        a2 = a1;
-        a1 = t;
+        for (; it + 1 < pe; it += 2) {  // hot loop: two steps, one per parity
+          step(it, a0, a1, a2, Set0{});
+          step(it + 1, a1, a2, a0, Set1{});
+          uint16_t* t = a0;  // two steps on: the stage of it+2 is the current one
+          a0 = a2;
+          a2 = a1;
+          a1 = t;
+        }
+        if (it < pe) step(it, a0, a1, a2, Set0{});
+      } else {  // two stages: they alternate with the parity
+        uint16_t *a0 = As, *a1 = As + A_TILE;
+#pragma nounroll
+        for (; it + 1 < pe; it += 2) {
+          step(it, a0, a1, Bs, Set0{});
+          step(it + 1, a1, a0, Bs, Set1{});
+        }
+        if (it < pe) step(it, a0, a1, Bs, Set0{});
       }
-      if (it < pe) step(it, a0, a1, a2, Set0{});
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the out-of-range loads of the last steps
     }
   } else {
@@ -786,7 +809,7 @@ __global__ __launch_bounds__(NT) void gemm_dq_kernel(const GemmArgs p) {
     constexpr bool kBf16 = decltype(as_bf16)::value;
     constexpr int ES = kBf16 ? 2 : 4;
     constexpr int ROW = BN * ES + 16;  // staged row stride (+16: spreads rows over banks)
-    constexpr int kLds = (3 * BM + 2 * BN) * 64 * 2;
+    constexpr int kLds = (A_STAGES * BM + 2 * BN) * 64 * 2;
     constexpr int kPasses = (BM * ROW + BM * 4 > kLds) ? 2 : 1;
     constexpr int RP = BM / kPasses;  // rows staged per pass
     static_assert(RP % WTM == 0 && RP * ROW + BM * 4 <= kLds, "a pass is whole wave row-bands");
@@ -848,7 +871,7 @@ template <int NBITS, bool BWD, int BM, int BN, int WAVES_M, int WAVES_N, bool HA
 static hipError_t launch_cfg(const GemmArgs& a, int ksplit, hipStream_t st, hipEvent_t ev_start = nullptr,
                              hipEvent_t ev_stop = nullptr) {
   auto kern = gemm_dq_kernel<NBITS, BWD, BM, BN, WAVES_M, WAVES_N, HAS_MAIN, FAST>;
-  const size_t smem = (size_t)(3 * BM + 2 * BN) * 64 * sizeof(uint16_t);
+  const size_t smem = (size_t)(gemm_a_stages(BM, HAS_MAIN) * BM + 2 * BN) * 64 * sizeof(uint16_t);
   static std::atomic<uint64_t> granted{0};  // per instantiation
   if (hipError_t e = grant_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, granted); e != hipSuccess)
     return e;
@@ -887,9 +910,9 @@ static hipError_t launch_dir(const GemmArgs& a, hipStream_t st, hipEvent_t e0, h
 // here and read again by the sum, priced at 4 TB/s against the ~2 us of a 256-row K step.
 // At least eight K steps per slice.
 int gemm_dq_ksplit(int M, int N, int K_main) {
-  constexpr int kUnits = 256;        // compute units = resident blocks
   constexpr double kBlockSteps = 7;  // prologue + epilogue of a block, in K steps
   const int bm = M > 128 ? 256 : (M > 64 ? 128 : 64);
+  const int kUnits = bm == 64 ? 512 : 256;  // resident blocks: one per compute unit, two of the 64-row tile
   const long tiles = (long)ceil_div(M, bm) * ceil_div(N, 256);
   const int nk = ceil_div(K_main, BK);
   const double step_us = 2.0 * bm / 256;
