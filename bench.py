@@ -375,7 +375,7 @@ def small_token_sets(torch, api, synth, name, n_sets, odt, bits=4, deployed=Fals
     return cfg, sets
 
 
-def small_token_table(torch, api, synth, odt, n_sets=8, tokens=(1, 4, 16, 256), iters=96):
+def small_token_table(torch, api, synth, odt, n_sets=8, tokens=(1, 4, 16, 256), iters=128):
     rows = []
     for name in ("c5_up", "c5_down"):
         cfg, sets = small_token_sets(torch, api, synth, name, n_sets, odt, deployed=True)
@@ -383,7 +383,9 @@ def small_token_table(torch, api, synth, odt, n_sets=8, tokens=(1, 4, 16, 256), 
             x = sets[0].x[:T].contiguous()
             y = torch.empty((T, cfg.d_out), dtype=odt, device="cuda")
             ws = torch.empty(api.workspace_bytes(sets[0].desc, T, api.OP_FORWARD), dtype=torch.uint8, device="cuda")
-            ms = timed_graph(torch, [(lambda L=L: L.forward_merged(x=x, y=y, ws=ws)) for L in sets], iters)
+            # four rotations of the weight sets per graph: the seam between two replays costs a few
+            # microseconds, which 8 launches of 25 us would carry visibly
+            ms = timed_graph(torch, [(lambda L=L: L.forward_merged(x=x, y=y, ws=ws)) for L in sets] * 4, iters)
             by = forward_bytes(cfg, T, y.element_size())
             fl = 2.0 * T * cfg.d_in * cfg.d_out
             rows.append({"shape": f"{cfg.d_in}x{cfg.d_out}", "tokens": T,
