@@ -32,12 +32,19 @@ def test_deployed_forward_small(gpu_api, group, d_in, d_out, tokens):
 
 @pytest.mark.parametrize("name", ["c5_up", "c5_down"])
 def test_deployed_forward_config5(gpu_api, name):
-    cfg = synth.CONFIGS[name].scaled(tokens=4)
+    cfg = synth.CONFIGS[name].scaled(tokens=256)
     L = layer_on_gpu(gpu_api, cfg)
     d = L["np"]
     beta_m = gpu_api.merge(L["desc"], L["g_beta"], L["A"], L["B"])
     dep = gpu_api.deploy(L["desc"], L["packed"], L["g_alpha"], beta_m)
-    ref4 = oracle.forward(d["x"], L["codes"], L["alpha"], beta_m.cpu().numpy(), cfg.group)
+    # 64 and 256 tokens (the 64-row tile with its finer K split, and the configuration's largest
+    # count): the dense kernel on the prepared factor words gives qalora_forward's bits, which
+    # the full-size test of the configuration holds to the oracle
+    for T in (64, 256):
+        x = L["x"][:T].contiguous()
+        yd = gpu_api.forward_deployed(L["desc"], x, dep, packed=L["packed"])
+        assert torch.equal(yd, gpu_api.forward(L["desc"], x, L["packed"], L["g_alpha"], beta_m))
+    ref4 = oracle.forward(d["x"][:4], L["codes"], L["alpha"], beta_m.cpu().numpy(), cfg.group)
     for T in (1, 4):
         x = L["x"][:T].contiguous()
         yd = gpu_api.forward_deployed(L["desc"], x, dep)

@@ -91,7 +91,7 @@ def test_config4_low_bit_sweep(gpu_api, bits, group):
 @pytest.mark.parametrize("name", ["c5_up", "c5_down"])
 def test_config5_post_merge_inference(gpu_api, name):
     """Merged model, adapter-free forward at T in {1, 4, 16} (streaming path, full oracle) and
-    T = 256 (matrix path, sampled rows)."""
+    T = 256, 128, 64 (matrix path at its three tile heights, sampled rows)."""
     cfg = synth.CONFIGS[name].scaled(tokens=256)
     L = layer_on_gpu(gpu_api, cfg)
     d = L["np"]
@@ -114,6 +114,13 @@ def test_config5_post_merge_inference(gpu_api, name):
     err = rel_err(y256[torch.from_numpy(rows).cuda()].cpu().numpy(), ref)
     record(f"fullsize {name} post-merge T=256", y=err)
     assert err <= TOL
+    # 64 and 128 tokens: the 64- and 128-row tiles with their own K splits (sampled rows)
+    for T in (64, 128):
+        r = rows[rows < T]
+        yT = gpu_api.forward(L["desc"], L["x"][:T].contiguous(), L["packed"], L["g_alpha"], beta_m)
+        err = rel_err(yT[torch.from_numpy(r).cuda()].cpu().numpy(), ref[: len(r)])
+        record(f"fullsize {name} post-merge T={T}", y=err)
+        assert err <= TOL
 
 
 @pytest.mark.parametrize("name,bits", [("c5_up", 2), ("c5_up", 3), ("c5_down", 3)])
